@@ -1,0 +1,187 @@
+/*
+ * mst.h -- C ABI of the MI355X (gfx950) library for the training step of the
+ * dynamically sparse fully-connected layers of Mixed Sparsity Training.
+ *
+ * A layer is W [O x I] (row-major, flat index f = o*I + i) with a binary mask M of
+ * the same shape (Sec. 3.2: "binary mask outlining the sparse network topology").
+ * Its effective weight is W (.) M (Algorithm 1, last line).  With X [T x I] the input
+ * and dY [T x O] the gradient at the output:
+ *
+ *   mst_sparse_fc_fwd         Y  = X (W.M)^T                   (App. "FLOP Calculation", Eq. (1))
+ *   mst_sparse_fc_bwd_input   dX = dY (W.M)                    (same App.: backward = 2 x forward)
+ *   mst_sparse_fc_bwd_weight  dW = (dY^T X) at active positions only
+ *   mst_mask_update           Algorithm 1 "Topology Evolution by MG"
+ *   mst_schedule_density      Sec. 3.1 "Sparsity Variation" + Sec. 3.2 update fraction
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory, owned by the caller, 16-byte aligned;
+ *     everything else is host memory.  The library allocates no device memory: the
+ *     caller hands it one backing buffer per layer (mst_layer_device_bytes) and a
+ *     workspace (mst_workspace_bytes) that may be shared by all layers used on a stream.
+ *   - Activations (X, dY) are row-major, fp32 or bfloat16 (mst_dtype); W, Y, dX, dW and
+ *     the dense gradient are fp32; accumulation is fp32.
+ *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  Calls return after enqueueing unless stated otherwise.
+ *   - Outputs are overwritten, never accumulated into.  Results are deterministic:
+ *     identical inputs give bit-identical outputs (no floating-point atomics).
+ *   - Return value: MST_OK or a negative mst_status.  Arguments are validated on the
+ *     host before anything is launched; on error nothing has been enqueued.
+ *   - Inputs must be finite; NaN / Inf give unspecified selections in mst_mask_update.
+ *   - Calls on the same layer or the same workspace must not overlap in time.
+ */
+#ifndef MST_H
+#define MST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mst_layer mst_layer_t;   /* opaque host object */
+typedef void* mst_stream_t;             /* hipStream_t */
+
+typedef enum { MST_F32 = 0, MST_BF16 = 1 } mst_dtype;
+
+typedef enum {
+    MST_OK = 0,
+    MST_ERR_ARG = -1,        /* null pointer, misaligned pointer, value out of range */
+    MST_ERR_SHAPE = -2,      /* dimension not supported / inconsistent */
+    MST_ERR_WORKSPACE = -3,  /* workspace or layer buffer too small */
+    MST_ERR_STATE = -4,      /* e.g. active count would exceed the layer's capacity */
+    MST_ERR_HIP = -5         /* a HIP runtime call failed; see mst_last_hip_error() */
+} mst_status;
+
+/* compute path of the three products: unstructured-sparse kernels, masked dense
+ * MFMA kernels (for the dense end of the warm-up / restoration phases), or chosen
+ * from the layer's density. */
+typedef enum { MST_PATH_AUTO = 0, MST_PATH_SPARSE = 1, MST_PATH_DENSE = 2 } mst_path;
+
+/* Hyper-parameters of Sec. 3.1 / 3.2 (Table "Private hyperparameters of MST"). */
+typedef struct {
+    double S_M;            /* maximum sparsity, in [0, 1] (paper: 0.96) */
+    int32_t N;             /* number of sparsity stages (5) */
+    int64_t Delta_W;       /* pruning frequency of the warm-up (2000); T_W = N * Delta_W */
+    int64_t T_U;           /* ultra-sparsification duration (100000) */
+    int64_t Delta_R;       /* growing frequency of the restoration (2000); T_R = N * Delta_R */
+    const double* zeta;    /* zeta_1 .. zeta_{N+1}: magnitude of each cosine period (host) */
+    int32_t n_zeta;        /* must equal N + 1 */
+} mst_schedule_cfg;
+
+/* What one mask update did (Algorithm 1, count lines). */
+typedef struct {
+    int64_t nnz_before, nnz_after;
+    int64_t n_prune, n_grow, n_rand, n_grad;
+} mst_update_stats;
+
+const char* mst_version(void);
+int mst_last_hip_error(void);           /* hipError_t of the last failing HIP call on this thread */
+
+/* ------------------------------------------------------------------ layers */
+
+/* Bytes of device memory a layer of shape [O x I] needs to hold up to nnz_capacity
+ * active weights (mask, values, both index views).  0 on invalid arguments. */
+size_t mst_layer_device_bytes(int O, int I, int64_t nnz_capacity);
+
+/* Bytes of workspace sufficient for every call below on a layer of this shape with
+ * up to T tokens.  0 on invalid arguments. */
+size_t mst_workspace_bytes(int O, int I, int64_t nnz_capacity, int T);
+
+/* Creates the host object over the caller's buffer (kept, not copied, never freed by
+ * the library).  The layer starts empty (no active weight). 1 <= O, I <= 65535. */
+int mst_layer_create(mst_layer_t** out, int O, int I, int64_t nnz_capacity,
+                     void* buf_dev, size_t buf_bytes);
+int mst_layer_destroy(mst_layer_t* layer);   /* frees the host object only */
+
+/* Loads W . M from dense arrays (W_dev [O*I] fp32, M_dev [O*I] bytes, non-zero = active)
+ * and builds the index views.  Synchronises `stream` once to learn the active count.
+ * MST_ERR_STATE if it exceeds the capacity. */
+int mst_layer_load_dense(mst_layer_t* layer, const float* W_dev, const uint8_t* M_dev,
+                         void* ws_dev, size_t ws_bytes, mst_stream_t stream);
+
+/* Writes W . M (zeros at inactive positions) and / or M; either pointer may be NULL. */
+int mst_layer_export_dense(const mst_layer_t* layer, float* W_dev, uint8_t* M_dev,
+                           mst_stream_t stream);
+
+/* The active weights as one fp32 vector in ascending flat-index order, for the caller's
+ * optimiser to update in place.  After changing them call mst_layer_sync_values. */
+int mst_layer_values(mst_layer_t* layer, float** vals_dev, int64_t* nnz);
+int mst_layer_sync_values(mst_layer_t* layer, mst_stream_t stream);
+
+/* Flat indices (ascending, int32) of the active positions, same order as the values. */
+int mst_layer_indices(const mst_layer_t* layer, int32_t* flat_dev, mst_stream_t stream);
+
+int mst_layer_set_path(mst_layer_t* layer, mst_path path);
+int64_t mst_layer_nnz(const mst_layer_t* layer);
+
+/* ------------------------------------------------------------- the products */
+
+/* Y_dev [T*O] = X_dev [T*I] (W.M)^T.  T >= 1. */
+int mst_sparse_fc_fwd(const mst_layer_t* layer, const void* X_dev, float* Y_dev, int T,
+                      mst_dtype act, mst_stream_t stream);
+
+/* dX_dev [T*I] = dY_dev [T*O] (W.M). */
+int mst_sparse_fc_bwd_input(const mst_layer_t* layer, const void* dY_dev, float* dX_dev, int T,
+                            mst_dtype act, mst_stream_t stream);
+
+/* dW_dev [nnz] = sum_t dY[t, o] X[t, i] for the active (o, i), ascending flat index. */
+int mst_sparse_fc_bwd_weight(const mst_layer_t* layer, const void* dY_dev, const void* X_dev,
+                             float* dW_dev, int T, mst_dtype act,
+                             void* ws_dev, size_t ws_bytes, mst_stream_t stream);
+
+/* G_dev [O*I] = dY^T X at every position (the score of gradient-based growth; Sec. 2,
+ * "infrequent full gradient calculation").  Runs on the matrix cores.  ws_dev may be
+ * NULL; with a workspace small outputs split the token range over more workgroups. */
+int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, int O, int I,
+                   mst_dtype act, void* ws_dev, size_t ws_bytes, mst_stream_t stream);
+
+/* ------------------------------------------------------------ topology update */
+
+/* Host arithmetic of Algorithm 1's count lines for a layer of n_total positions with
+ * nnz active: target count = floor(d*n_total + 0.5); N_prune = floor(zeta*nnz);
+ * N_grow = N_prune + (target - nnz), clamped so that 0 <= N_grow <= n_total - nnz and the
+ * layer lands exactly on the target; N_rand = floor(N_grow*R); N_grad = N_grow - N_rand. */
+int mst_update_counts(int64_t n_total, int64_t nnz, double target_density, double zeta,
+                      double rand_ratio, mst_update_stats* out);
+
+/* One Mixed-Growing update given the score buffer G_dev [O*I] (fp32):
+ *   prune  the N_prune active weights with the smallest (|w|, f);
+ *   grow   the N_grad inactive positions with the largest |G| (lowest f on ties), then
+ *          the N_rand inactive, not gradient-grown positions with the smallest
+ *          (SplitMix64(rng_seed)[f], f), where SplitMix64(s)[f] is the (f+1)-th output of
+ *          the SplitMix64 generator started at state s;
+ *   apply  pruned and grown weights are 0; kept weights keep their value; the index
+ *          views are rebuilt.  |.| compares fp32 bit patterns with the sign cleared.
+ * The new active count is known on return (host arithmetic); the device work is
+ * asynchronous.  stats_out (host) may be NULL. */
+int mst_mask_update_from_scores(mst_layer_t* layer, const float* G_dev,
+                                double target_density, double zeta, double rand_ratio,
+                                uint64_t rng_seed, void* ws_dev, size_t ws_bytes,
+                                mst_update_stats* stats_out, mst_stream_t stream);
+
+/* The same with the score computed inside: G = dY^T X on the matrix cores. */
+int mst_mask_update(mst_layer_t* layer, const void* dY_dev, const void* X_dev, int T,
+                    mst_dtype act, double target_density, double zeta, double rand_ratio,
+                    uint64_t rng_seed, void* ws_dev, size_t ws_bytes,
+                    mst_update_stats* stats_out, mst_stream_t stream);
+
+/* ------------------------------------------------------------------ schedule */
+
+/* Pure host.  Density d_t = 1 - S_t of Sec. 3.1 read with stage index
+ * k = min(N, floor(t_phase / Delta)):
+ *   warm-up      t <  T_W:            d = d_min + (1 - d_min)(1 - k/N)^3
+ *   ultra        t <  T_W + T_U:      d = d_min = 1 - S_M
+ *   restoration  t <  T_W + T_U + T_R: d = 1 + (d_min - 1)(1 - k/N)^3
+ *   afterwards                        d = 1
+ * and the update fraction of Sec. 3.2,
+ *   zeta_t = zeta_i / 2 (1 + cos(pi (t - T_{i-1}) / (T_i - T_{i-1}))),  t in [T_{i-1}, T_i),
+ *   T_0 = 0, T_1 = T_W + T_U, T_{j+1} = T_W + T_U + j Delta_R; 0 from T_{N+1} on.
+ * Either output pointer may be NULL. */
+int mst_schedule_density(const mst_schedule_cfg* cfg, int64_t step,
+                         double* density_out, double* zeta_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MST_H */

@@ -1,0 +1,125 @@
+// The C-ABI entry points that launch device work: argument checks on the host, then
+// dispatch to the sparse kernels or, for dense layers, to the masked dense MFMA path.
+#include "common.h"
+
+namespace mst {
+
+__global__ void k_gather_flat(const float* __restrict__ G, const int* __restrict__ flat, int64_t nnz,
+                              float* __restrict__ out) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < nnz) out[k] = G[flat[k]];
+}
+
+static int ensure_dense_copy(const mst_layer* L, hipStream_t s) {
+    if (L->Wd_valid) return MST_OK;
+    return refresh_dense_copy(const_cast<mst_layer*>(L), s);   // cache of vals[], not layer state
+}
+
+int dense_products_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s) {
+    int rc = ensure_dense_copy(L, s);
+    if (rc != MST_OK) return rc;
+    return gemm_mfma(GEMM_NT, X, act, L->Wd, MST_F32, Y, T, L->O, L->I, nullptr, 0, s);
+}
+
+int dense_products_bwd_input(const mst_layer* L, const void* dY, float* dX, int T, mst_dtype act, hipStream_t s) {
+    int rc = ensure_dense_copy(L, s);
+    if (rc != MST_OK) return rc;
+    return gemm_mfma(GEMM_NN, dY, act, L->Wd, MST_F32, dX, T, L->I, L->O, nullptr, 0, s);
+}
+
+int dense_products_bwd_weight(const mst_layer* L, const void* dY, const void* X, float* dW, int T,
+                              mst_dtype act, const Workspace& ws, hipStream_t s) {
+    int rc = gemm_mfma(GEMM_TN, dY, act, X, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s);
+    if (rc != MST_OK) return rc;
+    if (L->nnz > 0) {
+        k_gather_flat<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(ws.G, L->flat, L->nnz, dW);
+        MST_LAUNCH_CHECK();
+    }
+    return MST_OK;
+}
+
+static bool act_ok(mst_dtype a) { return a == MST_F32 || a == MST_BF16; }
+
+}  // namespace mst
+
+using namespace mst;
+
+extern "C" {
+
+int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int T, mst_dtype act,
+                      mst_stream_t stream) {
+    if (!L || !X_dev || !Y_dev || T < 1 || !act_ok(act) || !aligned16(X_dev) || !aligned16(Y_dev)) return MST_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (use_dense_path(L)) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
+    return spmm(L->row, X_dev, Y_dev, T, act, s);
+}
+
+int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_dev, int T, mst_dtype act,
+                            mst_stream_t stream) {
+    if (!L || !dY_dev || !dX_dev || T < 1 || !act_ok(act) || !aligned16(dY_dev) || !aligned16(dX_dev)) return MST_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (use_dense_path(L)) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
+    return spmm(L->col, dY_dev, dX_dev, T, act, s);
+}
+
+int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const void* X_dev, float* dW_dev, int T,
+                             mst_dtype act, void* ws_dev, size_t ws_bytes, mst_stream_t stream) {
+    if (!L || !dY_dev || !X_dev || !dW_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
+    if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dW_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
+    if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (use_dense_path(L)) return dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+    return sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+}
+
+int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, int O, int I, mst_dtype act,
+                   void* ws_dev, size_t ws_bytes, mst_stream_t stream) {
+    if (!dY_dev || !X_dev || !G_dev || T < 1 || O < 1 || I < 1 || !act_ok(act)) return MST_ERR_ARG;
+    if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(G_dev) || (ws_dev && !aligned16(ws_dev))) return MST_ERR_ARG;
+    return gemm_mfma(GEMM_TN, dY_dev, act, X_dev, act, G_dev, O, I, T, (float*)ws_dev,
+                     ws_dev ? (int64_t)(ws_bytes / 4) : 0, (hipStream_t)stream);
+}
+
+static int update_common(mst_layer_t* L, const float* G, double d, double zeta, double R, uint64_t seed,
+                         const Workspace& ws, mst_update_stats* stats_out, hipStream_t s,
+                         const mst_update_stats& st) {
+    if (stats_out) *stats_out = st;
+    if (st.n_prune == 0 && st.n_grow == 0) return MST_OK;     // nothing moves
+    (void)d; (void)zeta; (void)R;
+    return mask_update_device(L, G, st, seed, ws, s);
+}
+
+int mst_mask_update_from_scores(mst_layer_t* L, const float* G_dev, double target_density, double zeta,
+                                double rand_ratio, uint64_t rng_seed, void* ws_dev, size_t ws_bytes,
+                                mst_update_stats* stats_out, mst_stream_t stream) {
+    if (!L || !G_dev || !ws_dev || !aligned16(G_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    mst_update_stats st;
+    int rc = mst_update_counts(L->N, L->nnz, target_density, zeta, rand_ratio, &st);
+    if (rc != MST_OK) return rc;
+    if (st.nnz_after > L->cap) return MST_ERR_STATE;
+    const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, 1);
+    if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
+    return update_common(L, G_dev, target_density, zeta, rand_ratio, rng_seed, ws, stats_out, (hipStream_t)stream, st);
+}
+
+int mst_mask_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, int T, mst_dtype act,
+                    double target_density, double zeta, double rand_ratio, uint64_t rng_seed, void* ws_dev,
+                    size_t ws_bytes, mst_update_stats* stats_out, mst_stream_t stream) {
+    if (!L || !dY_dev || !X_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
+    if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    mst_update_stats st;
+    int rc = mst_update_counts(L->N, L->nnz, target_density, zeta, rand_ratio, &st);
+    if (rc != MST_OK) return rc;
+    if (st.nnz_after > L->cap) return MST_ERR_STATE;
+    const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, 1);
+    if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (st.n_grad > 0) {      // the gradient score is only needed when something grows by gradient
+        rc = gemm_mfma(GEMM_TN, dY_dev, act, X_dev, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s);
+        if (rc != MST_OK) return rc;
+    }
+    return update_common(L, ws.G, target_density, zeta, rand_ratio, rng_seed, ws, stats_out, s, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,223 @@
+// Dense fp32-accumulating GEMM on the CDNA matrix cores (v_mfma_f32_32x32x2f32).
+//
+// Used where a dense contraction really is the work: the dense weight gradient
+// G = dY^T X that scores gradient-based growth (Algorithm 1, ArgTopK of |grad|; Sec. 2
+// "infrequent full gradient calculation"), and the three products of a layer whose
+// density is high (start of warm-up / end of restoration, Sec. 3.1).
+//
+// C[M x N] = sum_k A'[k][m] B'[k][n].  Each operand is given either k-major (element
+// (k, m) at src[k*ld + m]) or m-major (src[m*ld + k]); both are staged k-major in LDS.
+// Workgroup tile 128 x 128 x 16, four wavefronts of 64 x 64 (2 x 2 MFMA tiles each).
+// Optional split of the k range over blockIdx.z into separate partial outputs that a
+// second kernel adds in a fixed order.
+#include "common.h"
+
+namespace mst {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 16, LDT = BM + 4;
+
+template <typename TIn>
+__device__ inline float to_f32(TIn v);
+template <>
+__device__ inline float to_f32<float>(float v) { return v; }
+template <>
+__device__ inline float to_f32<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+// four consecutive source elements; the 16-byte path needs all four in range and aligned
+template <typename TIn>
+__device__ inline void load4(const TIn* __restrict__ p, int n_valid, bool vec, float* v);
+template <>
+__device__ inline void load4<float>(const float* __restrict__ p, int n_valid, bool vec, float* v) {
+    if (vec && n_valid >= 4) {
+        const float4 q = *reinterpret_cast<const float4*>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = j < n_valid ? p[j] : 0.f;
+}
+template <>
+__device__ inline void load4<uint16_t>(const uint16_t* __restrict__ p, int n_valid, bool vec, float* v) {
+    if (vec && n_valid >= 4) {
+        const uint2 q = *reinterpret_cast<const uint2*>(p);
+        v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xFFFF0000u);
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = j < n_valid ? to_f32<uint16_t>(p[j]) : 0.f;
+}
+
+// fetch this thread's share (8 floats) of a [BK x 128] k-major tile
+template <typename TIn, bool KMAJOR>
+__device__ inline void fetch_tile(const TIn* __restrict__ src, int64_t ld, int k0, int m0, int Kdim, int Mdim,
+                                  int tid, bool vec, float (&v)[8]) {
+    if (KMAJOR) {
+        // 16 rows of 128: item = (k, group of 4 m); 512 items, 2 per thread
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int idx = it * 256 + tid;
+            const int k = k0 + (idx >> 5), m = m0 + ((idx & 31) << 2);
+            const int nv = (k < Kdim) ? max(0, min(4, Mdim - m)) : 0;
+            if (nv > 0) load4<TIn>(src + (int64_t)k * ld + m, nv, vec, &v[it * 4]);
+            else { v[it * 4] = v[it * 4 + 1] = v[it * 4 + 2] = v[it * 4 + 3] = 0.f; }
+        }
+    } else {
+        // 128 rows (m) of 16 k: item = (m, group of 4 k); 512 items, 2 per thread
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int idx = it * 256 + tid;
+            const int m = m0 + (idx >> 2), k = k0 + ((idx & 3) << 2);
+            const int nv = (m < Mdim) ? max(0, min(4, Kdim - k)) : 0;
+            if (nv > 0) load4<TIn>(src + (int64_t)m * ld + k, nv, vec, &v[it * 4]);
+            else { v[it * 4] = v[it * 4 + 1] = v[it * 4 + 2] = v[it * 4 + 3] = 0.f; }
+        }
+    }
+}
+
+template <bool KMAJOR>
+__device__ inline void stage_tile(float* lds, int tid, const float (&v)[8]) {
+    if (KMAJOR) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int idx = it * 256 + tid;
+            const int k = idx >> 5, m = (idx & 31) << 2;
+            *reinterpret_cast<float4*>(lds + k * LDT + m) =
+                make_float4(v[it * 4 + 0], v[it * 4 + 1], v[it * 4 + 2], v[it * 4 + 3]);
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int idx = it * 256 + tid;
+            const int m = idx >> 2, k = (idx & 3) << 2;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lds[(k + j) * LDT + m] = v[it * 4 + j];
+        }
+    }
+}
+
+template <typename TA, bool A_KMAJOR, typename TB, bool B_KMAJOR>
+__global__ __launch_bounds__(256) void k_gemm(const TA* __restrict__ A, int64_t lda,
+                                              const TB* __restrict__ B, int64_t ldb,
+                                              float* __restrict__ C, int M, int N, int Kdim, int k_per_split,
+                                              int64_t split_stride, int vec_a, int vec_b) {
+    __shared__ float As[BK * LDT];
+    __shared__ float Bs[BK * LDT];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = min(Kdim, kbeg + k_per_split);
+    float* Cz = C + (int64_t)blockIdx.z * split_stride;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    float ra[8], rb[8];
+    fetch_tile<TA, A_KMAJOR>(A, lda, kbeg, m0, kend, M, tid, vec_a != 0, ra);
+    fetch_tile<TB, B_KMAJOR>(B, ldb, kbeg, n0, kend, N, tid, vec_b != 0, rb);
+    const int lk = lane >> 5, lm = lane & 31;
+    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+        __syncthreads();                       // previous tile fully consumed
+        stage_tile<A_KMAJOR>(As, tid, ra);
+        stage_tile<B_KMAJOR>(Bs, tid, rb);
+        __syncthreads();
+        if (k0 + BK < kend) {                  // next tile travels while this one is multiplied
+            fetch_tile<TA, A_KMAJOR>(A, lda, k0 + BK, m0, kend, M, tid, vec_a != 0, ra);
+            fetch_tile<TB, B_KMAJOR>(B, ldb, k0 + BK, n0, kend, N, tid, vec_b != 0, rb);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            const float a0 = As[(kk + lk) * LDT + wm + lm];
+            const float a1 = As[(kk + lk) * LDT + wm + 32 + lm];
+            const float b0 = Bs[(kk + lk) * LDT + wn + lm];
+            const float b1 = Bs[(kk + lk) * LDT + wn + 32 + lm];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+    }
+
+    // D layout of the 32x32 MFMA: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                const int n = n0 + wn + j * 32 + lm;
+                if (m < M && n < N) Cz[(int64_t)m * N + n] = acc[i][j][v];
+            }
+}
+
+__global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, int nsplit,
+                                float* __restrict__ C, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int z = 0; z < nsplit; ++z) s += part[(int64_t)z * stride + i];
+    C[i] = s;
+}
+
+template <typename TA, bool AK, typename TB, bool BKM>
+static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
+                  float* split_ws, int64_t split_ws_floats, hipStream_t s) {
+    const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
+    const int64_t mn = (int64_t)M * N;
+    int nsplit = 1;
+    if (split_ws && (int64_t)gm * gn < 384) {
+        nsplit = (int)cdiv(512, (int64_t)gm * gn);
+        nsplit = (int)std::min<int64_t>(nsplit, std::min<int64_t>(16, Kdim / 256));
+        nsplit = (int)std::min<int64_t>(nsplit, split_ws_floats / mn);
+        if (nsplit < 1) nsplit = 1;
+    }
+    int kps = (int)(cdiv(cdiv(Kdim, nsplit), BK) * BK);
+    nsplit = (int)cdiv(Kdim, kps);
+    dim3 grid(gn, gm, nsplit);
+    float* dst = nsplit > 1 ? split_ws : C;
+    // 16-byte loads need every row start aligned: leading dimension a multiple of 4
+    // elements (the k ranges of the splits start at multiples of BK)
+    const int vec_a = (lda % 4 == 0) ? 1 : 0, vec_b = (ldb % 4 == 0) ? 1 : 0;
+    k_gemm<TA, AK, TB, BKM><<<grid, 256, 0, s>>>((const TA*)A, lda, (const TB*)B, ldb, dst, M, N, Kdim, kps, mn,
+                                                 vec_a, vec_b);
+    MST_LAUNCH_CHECK();
+    if (nsplit > 1) {
+        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
+        MST_LAUNCH_CHECK();
+    }
+    return MST_OK;
+}
+
+// TN: C[M x N] = A^T B, A [K x M], B [K x N]          (G = dY^T X)
+// NT: C[M x N] = A B^T, A [M x K], B [N x K] (fp32)   (Y = X Wd^T)
+// NN: C[M x N] = A B,   A [M x K], B [K x N] (fp32)   (dX = dY Wd)
+int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_dtype b_dt, float* C,
+              int M, int N, int Kdim, float* split_ws, int64_t split_ws_floats, hipStream_t s) {
+    const bool ab = a_dt == MST_BF16, bb = b_dt == MST_BF16;
+    switch (kind) {
+        case GEMM_TN:
+            if (ab != bb) return MST_ERR_ARG;
+            if (ab) return launch<uint16_t, true, uint16_t, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
+            return launch<float, true, float, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
+        case GEMM_NT:
+            if (bb) return MST_ERR_ARG;
+            if (ab) return launch<uint16_t, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, s);
+            return launch<float, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, s);
+        case GEMM_NN:
+            if (bb) return MST_ERR_ARG;
+            if (ab) return launch<uint16_t, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
+            return launch<float, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
+    }
+    return MST_ERR_ARG;
+}
+
+}  // namespace mst

@@ -1,0 +1,449 @@
+// Layer object, storage format and its construction on the device.
+//
+// Storage (not prescribed by the paper, which only names the binary mask M of
+// Sec. 3.2): the active weights are kept once in canonical order (ascending flat
+// index o*I + i) as vals[] / flat[], plus two "views" that the product kernels walk:
+//   row view  S = W    [O x I]  -> forward and weight gradient
+//   col view  S = W^T  [I x O]  -> input gradient
+// A view cuts the contraction index into chunks of KC and lists, for each
+// (chunk, row) segment, its entries {LDS byte offset of the operand row, weight}; every
+// segment is padded with zero-weight entries to a multiple of SEG_PAD so the kernels
+// can fetch entries four at a time.  perm[] maps a view entry back to its canonical slot.
+#include "common.h"
+
+namespace mst {
+
+thread_local int g_last_hip_error = 0;
+
+// worst case: every real segment carries SEG_PAD - 1 padding entries
+int64_t view_capacity(int64_t cap, int64_t nchunk, int64_t R) {
+    return cdiv(cap + (SEG_PAD - 1) * nchunk * R + ENT_TAIL, 64) * 64;
+}
+
+static int64_t nchunks(int K) { return cdiv(K, KC); }
+static int64_t rpad(int R) { return cdiv(R, ROW_ALIGN) * ROW_ALIGN; }
+
+bool use_dense_path(const mst_layer* L) {
+    if (L->path == MST_PATH_DENSE) return true;
+    if (L->path == MST_PATH_SPARSE) return false;
+    return (double)L->nnz > 0.30 * (double)L->N;      // measured cross-over, see the benchmark table
+}
+
+struct LayerCarve {
+    size_t mask, vals, flat, rowptr, Wd;
+    size_t rptr, rent, rperm, cptr, cent, cperm;
+    size_t total;
+};
+
+static LayerCarve carve_layer(int O, int I, int64_t cap) {
+    LayerCarve c{};
+    const int64_t N = (int64_t)O * I;
+    const int64_t nseg_r = nchunks(I) * rpad(O), nseg_c = nchunks(O) * rpad(I);
+    const int64_t capv_r = view_capacity(cap, nchunks(I), O), capv_c = view_capacity(cap, nchunks(O), I);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    c.mask = take((size_t)N);
+    c.vals = take((size_t)cap * 4);
+    c.flat = take((size_t)cap * 4);
+    c.rowptr = take((size_t)(O + 1) * 4);
+    c.Wd = take((size_t)N * 4);
+    c.rptr = take((size_t)(nseg_r + 1) * 4);
+    c.rent = take((size_t)capv_r * 8);
+    c.rperm = take((size_t)capv_r * 4);
+    c.cptr = take((size_t)(nseg_c + 1) * 4);
+    c.cent = take((size_t)capv_c * 8);
+    c.cperm = take((size_t)capv_c * 4);
+    c.total = off;
+    return c;
+}
+
+static bool shape_ok(int O, int I, int64_t cap) {
+    if (O < 1 || I < 1 || O > 65535 || I > 65535) return false;
+    const int64_t N = (int64_t)O * I;
+    if (N >= (int64_t)1 << 31) return false;
+    if (cap < 0 || cap > N) return false;
+    return true;
+}
+
+Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
+    Workspace w{};
+    const int64_t N = (int64_t)O * I;
+    const int64_t nseg_r = nchunks(I) * rpad(O), nseg_c = nchunks(O) * rpad(I);
+    const int64_t nseg = nseg_r > nseg_c ? nseg_r : nseg_c;
+    const int64_t capv_r = view_capacity(cap, nchunks(I), O);
+    const int64_t ntile = cdiv(T > 0 ? T : 1, TT);
+    char* b = static_cast<char*>(base);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return b ? b + o : nullptr; };
+    w.G = (float*)take((size_t)N * 4);
+    w.Wd = (float*)take((size_t)N * 4);
+    w.cidx = (int*)take((size_t)N * 4);
+    w.sel = (uint8_t*)take((size_t)N);
+    w.psel = (uint8_t*)take((size_t)(cap > 0 ? cap : 1));
+    w.segcnt = (int*)take((size_t)(nseg + 1) * 4);
+    w.rowcnt = (int*)take((size_t)(O + 1) * 4);
+    w.blk = (uint32_t*)take((size_t)(cdiv(N, SELECT_BLOCK) + 2) * 4);
+    w.sel_state = (uint64_t*)take((size_t)SEL_STATE_WORDS * 8);
+    w.gemm_floats = (size_t)GEMM_WS_SPLITS * (size_t)N;
+    w.gemm = (float*)take(w.gemm_floats * 4);
+    w.partial_floats = (size_t)ntile * (size_t)capv_r;
+    w.partial = (float*)take(w.partial_floats * 4);
+    w.total = off;
+    return w;
+}
+
+// ------------------------------------------------------------------ kernels
+
+// one block per row r of the mask: active count per chunk of columns and per row
+__global__ void k_count_row(const uint8_t* __restrict__ mask, int O, int I, int nchunk, int Rpad,
+                            int* __restrict__ segcnt, int* __restrict__ rowcnt) {
+    extern __shared__ int cnt[];   // [nchunk]
+    const int r = blockIdx.x;
+    for (int c = threadIdx.x; c < nchunk; c += blockDim.x) cnt[c] = 0;
+    __syncthreads();
+    const uint8_t* m = mask + (size_t)r * I;
+    int total = 0;
+    for (int i = threadIdx.x; i < I; i += blockDim.x) {
+        if (m[i]) { atomicAdd(&cnt[i / KC], 1); }
+    }
+    __syncthreads();
+    if (segcnt)
+        for (int c = threadIdx.x; c < nchunk; c += blockDim.x) segcnt[(size_t)c * Rpad + r] = cnt[c];
+    if (threadIdx.x == 0) {
+        for (int c = 0; c < nchunk; ++c) total += cnt[c];
+        rowcnt[r] = total;
+    }
+}
+
+// one thread per (column i, chunk c of rows): active count of mask[c*KC .. , i]
+__global__ void k_count_col(const uint8_t* __restrict__ mask, int O, int I, int Rpad,
+                            int* __restrict__ segcnt) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = blockIdx.y;
+    if (i >= I) return;
+    const int o0 = c * KC, o1 = min(O, o0 + KC);
+    int n = 0;
+    for (int o = o0; o < o1; ++o) n += mask[(size_t)o * I + i] != 0;
+    segcnt[(size_t)c * Rpad + i] = n;
+}
+
+// single-block exclusive scan: out[j] = sum_{j' < j} f(in[j']), out[n] = total,
+// f = round up to a multiple of `pad` (pad = 1: plain scan)
+__global__ void k_scan_excl(const int* in, int* out, int64_t n, int pad) {
+    __shared__ int wsum[16];
+    __shared__ int carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < n; base += blockDim.x) {
+        const int64_t j = base + tid;
+        int v = 0;
+        if (j < n) { v = in[j]; v = (v + pad - 1) / pad * pad; }
+        int x = v;                                   // inclusive scan inside the wave
+        for (int d = 1; d < 64; d <<= 1) {
+            int y = __shfl_up(x, d, 64);
+            if (lane >= d) x += y;
+        }
+        if (lane == 63) wsum[wave] = x;
+        __syncthreads();
+        int woff = 0;
+        for (int w = 0; w < wave; ++w) woff += wsum[w];
+        const int carry = carry_s;
+        if (j < n) out[j] = carry + woff + x - v;
+        __syncthreads();
+        if (tid == blockDim.x - 1) carry_s = carry + woff + x;
+        __syncthreads();
+    }
+    if (tid == 0) out[n] = carry_s;
+}
+
+// one wavefront per row: ordered compaction of the row into canonical arrays and the row view
+__global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __restrict__ W,
+                           int O, int I, int nchunk, int Rpad,
+                           const int* __restrict__ rowptr, const int* __restrict__ segcnt,
+                           const int* __restrict__ ptr,
+                           float* __restrict__ vals, int* __restrict__ flat, int* __restrict__ cidx,
+                           uint2* __restrict__ ent, int* __restrict__ perm) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (r >= O) return;
+    const uint8_t* m = mask + (size_t)r * I;
+    const float* w = W + (size_t)r * I;
+    int canon = rowptr[r];
+    for (int c = 0; c < nchunk; ++c) {
+        const int seg = ptr[(size_t)c * Rpad + r];
+        const int n = segcnt[(size_t)c * Rpad + r];
+        int run = 0;
+        const int i1 = min(I, (c + 1) * KC);
+        for (int i0 = c * KC; i0 < i1; i0 += 64) {
+            const int i = i0 + lane;
+            const bool on = i < i1 && m[i] != 0;
+            const unsigned long long b = __ballot(on);
+            if (on) {
+                const int before = __popcll(b & ((1ull << lane) - 1ull));
+                const int k = canon + run + before;
+                const int e = seg + run + before;
+                const float v = w[i];
+                vals[k] = v;
+                flat[k] = r * I + i;
+                cidx[(size_t)r * I + i] = k;
+                ent[e] = make_uint2(lds_off((uint32_t)(i - c * KC)), __float_as_uint(v));
+                perm[e] = k;
+            }
+            run += __popcll(b);
+        }
+        const int npad = (n + SEG_PAD - 1) / SEG_PAD * SEG_PAD - n;
+        if (lane < npad) {
+            ent[seg + n + lane] = make_uint2(0u, 0u);
+            perm[seg + n + lane] = -1;
+        }
+        canon += n;
+    }
+}
+
+// one thread per (column i, chunk c of rows): the col view's segment (c, i)
+__global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __restrict__ W,
+                           int O, int I, int Rpad, const int* __restrict__ ptr, const int* __restrict__ cidx,
+                           uint2* __restrict__ ent, int* __restrict__ perm) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = blockIdx.y;
+    if (i >= I) return;
+    const int o0 = c * KC, o1 = min(O, o0 + KC);
+    int e = ptr[(size_t)c * Rpad + i];
+    int n = 0;
+    for (int o = o0; o < o1; ++o) {
+        const size_t f = (size_t)o * I + i;
+        if (mask[f]) {
+            ent[e] = make_uint2(lds_off((uint32_t)(o - o0)), __float_as_uint(W[f]));
+            perm[e] = cidx[f];
+            ++e; ++n;
+        }
+    }
+    const int npad = (n + SEG_PAD - 1) / SEG_PAD * SEG_PAD - n;
+    for (int p = 0; p < npad; ++p) { ent[e] = make_uint2(0u, 0u); perm[e] = -1; ++e; }
+}
+
+// zero-weight readable tail after the last entry of a view
+__global__ void k_fill_tail(const int* __restrict__ ptr, int64_t nseg, uint2* __restrict__ ent,
+                            int* __restrict__ perm) {
+    const int e = ptr[nseg] + threadIdx.x;
+    if (threadIdx.x < ENT_TAIL) { ent[e] = make_uint2(0u, 0u); perm[e] = -1; }
+}
+
+__global__ void k_sync_view(const float* __restrict__ vals, const int* __restrict__ ptr, int64_t nseg,
+                            const int* __restrict__ perm, uint2* __restrict__ ent) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= ptr[nseg]) return;
+    const int p = perm[e];
+    if (p >= 0) ent[e].y = __float_as_uint(vals[p]);
+}
+
+__global__ void k_scatter_dense(const float* __restrict__ vals, const int* __restrict__ flat,
+                                int64_t nnz, float* __restrict__ Wd) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < nnz) Wd[flat[k]] = vals[k];
+}
+
+__global__ void k_fill_u32(uint32_t* __restrict__ dst, uint32_t value, int64_t n) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < n) dst[k] = value;
+}
+
+__global__ void k_copy_i32(const int* __restrict__ src, int* __restrict__ dst, int64_t n) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < n) dst[k] = src[k];
+}
+
+// ------------------------------------------------------------------ build
+
+// out[j] = sum of in[0 .. j), out[n] = total; in == out is allowed
+int scan_excl_i32(const int* in, int* out, int64_t n, hipStream_t s) {
+    k_scan_excl<<<1, 1024, 0, s>>>(in, out, n, 1);
+    MST_LAUNCH_CHECK();
+    return MST_OK;
+}
+
+// Clears device memory with a kernel (safe to record into a HIP graph, unlike a memset node).
+int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s) {
+    if (n_words <= 0) return MST_OK;
+    k_fill_u32<<<(unsigned)cdiv(n_words, 256), 256, 0, s>>>((uint32_t*)dst, value, n_words);
+    MST_LAUNCH_CHECK();
+    return MST_OK;
+}
+
+static int build_one_view(View& v, bool row_view, const mst_layer* L, const float* Wsrc,
+                          const Workspace& ws, hipStream_t s) {
+    const int O = L->O, I = L->I;
+    int rc = fill_u32(ws.segcnt, 0u, v.nseg + 1, s);      // rows >= R keep empty segments
+    if (rc != MST_OK) return rc;
+    if (row_view) {
+        k_count_row<<<O, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, v.Rpad, ws.segcnt, ws.rowcnt);
+        MST_LAUNCH_CHECK();
+        k_scan_excl<<<1, 1024, 0, s>>>(ws.rowcnt, L->rowptr, O, 1);
+        MST_LAUNCH_CHECK();
+        k_scan_excl<<<1, 1024, 0, s>>>(ws.segcnt, v.ptr, v.nseg, SEG_PAD);
+        MST_LAUNCH_CHECK();
+        k_fill_row<<<(unsigned)cdiv(O, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.Rpad, L->rowptr, ws.segcnt,
+                                                        v.ptr, L->vals, L->flat, ws.cidx, v.ent, v.perm);
+        MST_LAUNCH_CHECK();
+    } else {
+        dim3 g((unsigned)cdiv(I, 256), (unsigned)v.nchunk);
+        k_count_col<<<g, 256, 0, s>>>(L->mask, O, I, v.Rpad, ws.segcnt);
+        MST_LAUNCH_CHECK();
+        k_scan_excl<<<1, 1024, 0, s>>>(ws.segcnt, v.ptr, v.nseg, SEG_PAD);
+        MST_LAUNCH_CHECK();
+        k_fill_col<<<g, 256, 0, s>>>(L->mask, Wsrc, O, I, v.Rpad, v.ptr, ws.cidx, v.ent, v.perm);
+        MST_LAUNCH_CHECK();
+    }
+    k_fill_tail<<<1, 64, 0, s>>>(v.ptr, v.nseg, v.ent, v.perm);
+    MST_LAUNCH_CHECK();
+    return MST_OK;
+}
+
+// Rebuilds vals / flat / rowptr and both views from the layer's mask and a dense weight
+// array.  The col view needs the canonical indices the row view pass writes to ws.cidx.
+int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s) {
+    int rc = build_one_view(L->row, true, L, Wsrc, ws, s);
+    if (rc != MST_OK) return rc;
+    rc = build_one_view(L->col, false, L, Wsrc, ws, s);
+    L->Wd_valid = false;
+    return rc;
+}
+
+int refresh_dense_copy(mst_layer* L, hipStream_t s) {
+    int rc = fill_u32(L->Wd, 0u, L->N, s);
+    if (rc != MST_OK) return rc;
+    if (L->nnz > 0) {
+        k_scatter_dense<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(L->vals, L->flat, L->nnz, L->Wd);
+        MST_LAUNCH_CHECK();
+    }
+    L->Wd_valid = true;
+    return MST_OK;
+}
+
+}  // namespace mst
+
+using namespace mst;
+
+extern "C" {
+
+int mst_last_hip_error(void) { return g_last_hip_error; }
+
+size_t mst_layer_device_bytes(int O, int I, int64_t nnz_capacity) {
+    if (!shape_ok(O, I, nnz_capacity)) return 0;
+    return carve_layer(O, I, nnz_capacity).total;
+}
+
+size_t mst_workspace_bytes(int O, int I, int64_t nnz_capacity, int T) {
+    if (!shape_ok(O, I, nnz_capacity) || T < 1) return 0;
+    return carve_workspace(nullptr, O, I, nnz_capacity, T).total;
+}
+
+int mst_layer_create(mst_layer_t** out, int O, int I, int64_t nnz_capacity, void* buf_dev,
+                     size_t buf_bytes) {
+    if (!out || !buf_dev || !aligned16(buf_dev)) return MST_ERR_ARG;
+    if (!shape_ok(O, I, nnz_capacity)) return MST_ERR_SHAPE;
+    const LayerCarve c = carve_layer(O, I, nnz_capacity);
+    if (buf_bytes < c.total) return MST_ERR_WORKSPACE;
+    mst_layer* L = new (std::nothrow) mst_layer();
+    if (!L) return MST_ERR_STATE;
+    char* b = static_cast<char*>(buf_dev);
+    L->O = O; L->I = I; L->N = (int64_t)O * I; L->cap = nnz_capacity; L->nnz = 0;
+    L->buf = buf_dev; L->buf_bytes = buf_bytes;
+    L->mask = (uint8_t*)(b + c.mask);
+    L->vals = (float*)(b + c.vals);
+    L->flat = (int*)(b + c.flat);
+    L->rowptr = (int*)(b + c.rowptr);
+    L->Wd = (float*)(b + c.Wd);
+    L->row.R = O; L->row.K = I; L->row.nchunk = (int)nchunks(I); L->row.Rpad = (int)rpad(O);
+    L->row.nseg = nchunks(I) * rpad(O);
+    L->row.capv = view_capacity(nnz_capacity, nchunks(I), O);
+    L->row.ptr = (int*)(b + c.rptr); L->row.ent = (uint2*)(b + c.rent); L->row.perm = (int*)(b + c.rperm);
+    L->col.R = I; L->col.K = O; L->col.nchunk = (int)nchunks(O); L->col.Rpad = (int)rpad(I);
+    L->col.nseg = nchunks(O) * rpad(I);
+    L->col.capv = view_capacity(nnz_capacity, nchunks(O), I);
+    L->col.ptr = (int*)(b + c.cptr); L->col.ent = (uint2*)(b + c.cent); L->col.perm = (int*)(b + c.cperm);
+    *out = L;
+    return MST_OK;
+}
+
+int mst_layer_destroy(mst_layer_t* layer) {
+    delete layer;
+    return MST_OK;
+}
+
+int mst_layer_load_dense(mst_layer_t* L, const float* W_dev, const uint8_t* M_dev, void* ws_dev,
+                         size_t ws_bytes, mst_stream_t stream) {
+    if (!L || !W_dev || !M_dev || !ws_dev || !aligned16(W_dev) || !aligned16(M_dev) || !aligned16(ws_dev))
+        return MST_ERR_ARG;
+    const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, 1);
+    if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    // learn the active count first so that nothing is written when it does not fit
+    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(M_dev, L->O, L->I, L->row.nchunk, L->row.Rpad,
+                                                              nullptr, ws.rowcnt);
+    MST_LAUNCH_CHECK();
+    k_scan_excl<<<1, 1024, 0, s>>>(ws.rowcnt, L->rowptr, L->O, 1);   // rebuilt below anyway
+    MST_LAUNCH_CHECK();
+    int total = 0;
+    MST_HIP(hipMemcpyAsync(&total, L->rowptr + L->O, 4, hipMemcpyDeviceToHost, s));
+    MST_HIP(hipStreamSynchronize(s));
+    if ((int64_t)total > L->cap) return MST_ERR_STATE;
+    MST_HIP(hipMemcpyAsync(L->mask, M_dev, (size_t)L->N, hipMemcpyDeviceToDevice, s));
+    L->nnz = total;
+    return build_views(L, W_dev, ws, s);
+}
+
+int mst_layer_export_dense(const mst_layer_t* L, float* W_dev, uint8_t* M_dev, mst_stream_t stream) {
+    if (!L) return MST_ERR_ARG;
+    if ((W_dev && !aligned16(W_dev)) || (M_dev && !aligned16(M_dev))) return MST_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (W_dev) {
+        int rc = fill_u32(W_dev, 0u, L->N, s);
+        if (rc != MST_OK) return rc;
+        if (L->nnz > 0) {
+            k_scatter_dense<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(L->vals, L->flat, L->nnz, W_dev);
+            MST_LAUNCH_CHECK();
+        }
+    }
+    if (M_dev) MST_HIP(hipMemcpyAsync(M_dev, L->mask, (size_t)L->N, hipMemcpyDeviceToDevice, s));
+    return MST_OK;
+}
+
+int mst_layer_values(mst_layer_t* L, float** vals_dev, int64_t* nnz) {
+    if (!L) return MST_ERR_ARG;
+    if (vals_dev) *vals_dev = L->vals;
+    if (nnz) *nnz = L->nnz;
+    return MST_OK;
+}
+
+int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
+    if (!L) return MST_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    L->Wd_valid = false;
+    if (L->nnz == 0) return MST_OK;
+    for (View* v : {&L->row, &L->col}) {
+        const int64_t upper = L->nnz + (SEG_PAD - 1) * (int64_t)v->nchunk * v->R;
+        k_sync_view<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(L->vals, v->ptr, v->nseg, v->perm, v->ent);
+        MST_LAUNCH_CHECK();
+    }
+    return MST_OK;
+}
+
+int mst_layer_indices(const mst_layer_t* L, int32_t* flat_dev, mst_stream_t stream) {
+    if (!L || !flat_dev) return MST_ERR_ARG;
+    if (L->nnz == 0) return MST_OK;
+    k_copy_i32<<<(unsigned)cdiv(L->nnz, 256), 256, 0, (hipStream_t)stream>>>(L->flat, flat_dev, L->nnz);
+    MST_LAUNCH_CHECK();
+    return MST_OK;
+}
+
+int mst_layer_set_path(mst_layer_t* L, mst_path path) {
+    if (!L || path < MST_PATH_AUTO || path > MST_PATH_DENSE) return MST_ERR_ARG;
+    L->path = path;
+    return MST_OK;
+}
+
+int64_t mst_layer_nnz(const mst_layer_t* L) { return L ? L->nnz : -1; }
+
+}  // extern "C"

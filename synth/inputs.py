@@ -76,13 +76,14 @@ def powerlaw_row_lengths(seed: int, tensor_id: int, O: int, I: int, density: flo
                          alpha: float = 1.5) -> np.ndarray:
     """Per-row active counts with a Pareto tail (pdf ~ len^-alpha), summing exactly to the target.
 
-    raw_r = min(I, (1-u)^(-1/(alpha-1))); a scale c is found by bisection so that
-    sum_r min(I, c*raw_r) hits the target; floors are taken and the remainder goes
-    to the rows with the largest fractional parts (lowest row first on ties).
+    raw_r = (1-u)^(-1/(alpha-1)); a scale c is found by bisection so that
+    sum_r min(I, c*raw_r) hits the target (so the heaviest rows are completely full);
+    floors are taken and the remainder goes to the rows with the largest fractional
+    parts (lowest row first on ties).
     """
     total = active_count(O * I, density)
     u = _rng(seed, tensor_id).random(O)
-    raw = np.minimum(float(I), (1.0 - u) ** (-1.0 / (alpha - 1.0)))
+    raw = (1.0 - u) ** (-1.0 / (alpha - 1.0))
     lo, hi = 0.0, float(I)
     for _ in range(200):
         mid = 0.5 * (lo + hi)

@@ -1,0 +1,186 @@
+"""GPU parity of the three products and the dense gradient against the CPU oracle.
+
+Bar: max|gpu - oracle| / max|oracle| <= 1e-4 per output tensor (fp32 values)."""
+import numpy as np
+import pytest
+
+import paper_2408_11746_amd as mst
+import synth
+from oracle import products as opr
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from gpu_util import Rig, TOL, dev, rel_err, DEV  # noqa: E402
+
+
+def _case(seed, T, I, O, density, mask="uniform"):
+    W, M = synth.make_layer(seed, 1, I, O, density, mask)
+    X, dY = synth.make_activations(seed, 1, T, I, O)
+    return W, M, X, dY
+
+
+# (T, I, O, density): several token tiles, several chunks, ragged tails in every dimension
+SHAPES = [
+    (300, 200, 333, 0.10),      # nothing a multiple of 4 / 64 / 128
+    (129, 768, 768, 0.05),      # one token past a tile
+    (512, 768, 3072, 0.05),     # the 768 -> 3072 layer at 512 tokens
+    (640, 3072, 768, 0.02),     # long contraction (24 chunks)
+    (64, 130, 70, 0.5),
+    (1, 5, 3, 0.6),             # single token, tiny
+]
+
+
+@pytest.mark.parametrize("T,I,O,density", SHAPES)
+def test_products_match_oracle(T, I, O, density):
+    print("case", T, I, O, density, flush=True)
+    W, M, X, dY = _case(11, T, I, O, density)
+    rig = Rig(W, M, T)
+    assert rig.layer.nnz == int(M.sum())
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL
+    assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, W, M)) <= TOL
+    assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, M)) <= TOL
+
+
+def test_load_export_roundtrip_and_canonical_order():
+    W, M, _, _ = _case(3, 8, 200, 333, 0.1)
+    rig = Rig(W, M, 8)
+    We, Me = rig.export()
+    np.testing.assert_array_equal(Me, M)
+    np.testing.assert_array_equal(We, W * M)
+    np.testing.assert_array_equal(rig.indices(), np.flatnonzero(M.reshape(-1)))
+    np.testing.assert_array_equal(rig.layer.values().cpu().numpy(), W[M != 0])
+
+
+def test_garbage_behind_the_mask_is_ignored():
+    W, M, X, dY = _case(4, 70, 96, 80, 0.2)
+    W2 = W.copy()
+    W2[M == 0] = 1e6
+    rig = Rig(W2, M, 70)
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL
+    We, _ = rig.export()
+    np.testing.assert_array_equal(We, W * M)
+
+
+def test_powerlaw_rows_and_full_rows():
+    W, M, X, dY = _case(5, 256, 768, 768, 0.02, mask="powerlaw")
+    assert M.sum(axis=1).max() >= 500        # some nearly full rows
+    rig = Rig(W, M, 256)
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL
+    assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, W, M)) <= TOL
+    assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, M)) <= TOL
+
+
+def test_degenerate_layers():
+    T, I, O = 140, 136, 72
+    X, dY = synth.make_activations(6, 1, T, I, O)
+    W = synth.normal(6, 9, (O, I), 0.02)
+    # empty layer: outputs are exactly zero
+    rig = Rig(W, np.zeros((O, I), np.uint8), T)
+    assert rig.layer.nnz == 0
+    assert not rig.fwd(X).any() and not rig.bwd_input(dY).any()
+    assert rig.bwd_weight(dY, X).size == 0
+    # fully dense layer through the sparse kernels
+    ones = np.ones((O, I), np.uint8)
+    rig = Rig(W, ones, T, cap=O * I)
+    rig.layer.set_path(mst.MST_PATH_SPARSE)
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, ones)) <= TOL
+    assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, W, ones)) <= TOL
+    assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, ones)) <= TOL
+    # a single active weight
+    one = np.zeros((O, I), np.uint8)
+    one[71, 135] = 1
+    rig = Rig(W, one, T)
+    Y = rig.fwd(X)
+    assert rel_err(Y, opr.fc_fwd(X, W, one)) <= TOL and not Y[:, :71].any()
+    assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, one)) <= TOL
+
+
+def test_dense_path_matches_oracle():
+    T, I, O = 200, 136, 264
+    W, M, X, dY = _case(7, T, I, O, 0.6)
+    rig = Rig(W, M, T, cap=O * I)
+    rig.layer.set_path(mst.MST_PATH_DENSE)
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL
+    assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, W, M)) <= TOL
+    assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, M)) <= TOL
+    # auto picks the dense kernels at this density and must agree with the sparse ones
+    rig.layer.set_path(mst.MST_PATH_AUTO)
+    Ya = rig.fwd(X)
+    rig.layer.set_path(mst.MST_PATH_SPARSE)
+    assert rel_err(Ya, rig.fwd(X)) <= TOL
+
+
+@pytest.mark.parametrize("T,I,O", [(300, 200, 333), (1024, 768, 768), (130, 64, 2304)])
+def test_dense_grad_matches_oracle(T, I, O):
+    X, dY = synth.make_activations(8, 2, T, I, O)
+    G = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(mst.mst_workspace_bytes(O, I, 16, T), dtype=torch.uint8, device=DEV)
+    mst.mst_dense_grad(dev(dY), dev(X), G, T, O, I, mst.MST_F32, ws)
+    torch.cuda.synchronize()
+    ref = opr.dense_grad(dY, X)
+    assert rel_err(G.cpu().numpy(), ref) <= TOL
+    G2 = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
+    mst.mst_dense_grad(dev(dY), dev(X), G2, T, O, I, mst.MST_F32, None)     # no split workspace
+    torch.cuda.synchronize()
+    assert rel_err(G2.cpu().numpy(), ref) <= TOL
+
+
+def test_bf16_activations_fp32_accumulate():
+    T, I, O = 260, 1024, 512
+    W, M = synth.make_layer(9, 1, I, O, 0.05)
+    Xf, dYf, xb, yb = synth.make_activations(9, 1, T, I, O, "bf16")
+    rig = Rig(W, M, T)
+    xb_d, yb_d = dev(xb.view(np.int16)), dev(yb.view(np.int16))
+    Y = torch.empty((T, O), dtype=torch.float32, device=DEV)
+    dX = torch.empty((T, I), dtype=torch.float32, device=DEV)
+    dW = torch.empty(rig.layer.nnz, dtype=torch.float32, device=DEV)
+    G = torch.empty((O, I), dtype=torch.float32, device=DEV)
+    mst.mst_sparse_fc_fwd(rig.layer, xb_d, Y, T, mst.MST_BF16)
+    mst.mst_sparse_fc_bwd_input(rig.layer, yb_d, dX, T, mst.MST_BF16)
+    mst.mst_sparse_fc_bwd_weight(rig.layer, yb_d, xb_d, dW, T, rig.ws, mst.MST_BF16)
+    mst.mst_dense_grad(yb_d, xb_d, G, T, O, I, mst.MST_BF16, rig.ws)
+    torch.cuda.synchronize()
+    # the oracle sees exactly the bf16-rounded inputs, widened to fp64
+    assert rel_err(Y.cpu().numpy(), opr.fc_fwd(Xf, W, M)) <= TOL
+    assert rel_err(dX.cpu().numpy(), opr.fc_bwd_input(dYf, W, M)) <= TOL
+    assert rel_err(dW.cpu().numpy(), opr.fc_bwd_weight(dYf, Xf, M)) <= TOL
+    assert rel_err(G.cpu().numpy(), opr.dense_grad(dYf, Xf)) <= TOL
+
+
+def test_results_are_bit_reproducible():
+    W, M, X, dY = _case(10, 384, 256, 384, 0.1)
+    rig = Rig(W, M, 384)
+    a = (rig.fwd(X), rig.bwd_input(dY), rig.bwd_weight(dY, X))
+    b = (rig.fwd(X), rig.bwd_input(dY), rig.bwd_weight(dY, X))
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
+
+
+def test_sync_values_after_optimizer_step():
+    W, M, X, dY = _case(12, 200, 256, 192, 0.1)
+    rig = Rig(W, M, 200)
+    vals = rig.layer.values()
+    vals.mul_(0.5).add_(0.01)                     # caller's optimiser updates in place
+    rig.layer.sync_values()
+    W2 = W.copy()
+    W2[M != 0] = W[M != 0] * np.float32(0.5) + np.float32(0.01)
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W2, M)) <= TOL
+    assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, W2, M)) <= TOL
+
+
+def test_argument_errors_launch_nothing():
+    W, M, X, dY = _case(13, 16, 32, 32, 0.2)
+    rig = Rig(W, M, 16)
+    Y = torch.empty((16, 32), dtype=torch.float32, device=DEV)
+    with pytest.raises(mst.MstError):
+        mst.mst_sparse_fc_fwd(rig.layer, dev(X), Y, 0)                       # T < 1
+    small = torch.empty(64, dtype=torch.uint8, device=DEV)
+    dW = torch.empty(rig.layer.nnz, dtype=torch.float32, device=DEV)
+    with pytest.raises(mst.MstError) as e:
+        mst.mst_sparse_fc_bwd_weight(rig.layer, dev(dY), dev(X), dW, 16, small)
+    assert e.value.code == -3
+    with pytest.raises(mst.MstError) as e:                                    # capacity exceeded
+        tiny = mst.Layer(32, 32, 4, DEV)
+        tiny.load_dense(dev(W), dev(M), rig.ws)
+    assert e.value.code == -4
