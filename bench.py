@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse fully-connected training step on one MI355X.
+
+A step is one pass of the hot path over one batch: for every layer of the workload the
+forward product, the input gradient and the weight gradient at the active positions;
+every Delta_t-th step (Table "Private hyperparameters of MST": topology update interval
+100) each layer also runs one Mixed-Growing update (dense gradient on the matrix cores,
+prune / grow selection, rebuild of the index views).  Inputs are synthetic, seeded, and
+resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+ALU_FP32_PEAK_TFLOPS = 157.3   # fp32 vector peak (256 CUs x 4 SIMD x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz)
+MFMA_FP32_PEAK_TFLOPS = 157.3
+METRIC = "effective sparse TFLOP/s + HBM GB/s (% peak) per FC train step, 1 MI355X"
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=100)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    p.add_argument("--update-interval", type=int, default=100, help="Delta_t; 0 = never update")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--seed", type=int, default=2024)
+    return p.parse_args()
+
+
+class LayerRun:
+    """Device state of one layer of the workload."""
+
+    def __init__(self, mst, synth, torch, seed, lid, name, I, O, T, density, mask, act):
+        import numpy as np
+        self.name, self.I, self.O, self.T = name, I, O, T
+        W, M = synth.make_layer(seed, lid, I, O, density, mask)
+        self.W, self.M = W, M
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        if act == "f32":
+            X, dY = synth.make_activations(seed, lid, T, I, O)
+            self.X, self.dY, self.act = to(X), to(dY), mst.MST_F32
+            self.act_bytes = 4
+        else:
+            Xf, dYf, xb, yb = synth.make_activations(seed, lid, T, I, O, "bf16")
+            X, dY = Xf, dYf
+            self.X, self.dY, self.act = to(xb.view(np.int16)), to(yb.view(np.int16)), mst.MST_BF16
+            self.act_bytes = 2
+        self.X_host, self.dY_host = X, dY
+        self.nnz = int(M.sum())
+        cap = min(O * I, self.nnz + self.nnz // 2 + 64)
+        self.layer = mst.Layer(O, I, cap, "cuda:0")
+        self.ws = torch.empty(mst.mst_workspace_bytes(O, I, cap, T), dtype=torch.uint8, device="cuda:0")
+        self.layer.load_dense(to(W), to(M), self.ws)
+        self.Y = torch.empty((T, O), dtype=torch.float32, device="cuda:0")
+        self.dX = torch.empty((T, I), dtype=torch.float32, device="cuda:0")
+        self.dW = torch.empty(cap, dtype=torch.float32, device="cuda:0")
+        self.density = density
+
+    # algorithmic (compulsory) bytes and flops of each product
+    def bytes_fwd(self):
+        return self.act_bytes * self.T * self.I + 4 * self.T * self.O + 8 * self.nnz + 4 * (self.O + 1)
+
+    def bytes_bwd_input(self):
+        return self.act_bytes * self.T * self.O + 4 * self.T * self.I + 8 * self.nnz + 4 * (self.I + 1)
+
+    def bytes_bwd_weight(self):
+        return self.act_bytes * self.T * (self.I + self.O) + 8 * self.nnz + 4 * self.nnz
+
+    def flops_product(self):
+        return 2 * self.nnz * self.T
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2408_11746_amd as mst
+    import synth
+
+    cfg = synth.CONFIGS[args.config]
+    T, act, density = cfg["T"], cfg["act"], cfg["densities"][0]
+    layers = [LayerRun(mst, synth, torch, args.seed, lid + 1, name, I, O, T, density, cfg["mask"], act)
+              for lid, (name, I, O) in enumerate(cfg["layers"])]
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+
+    kinds = ("fwd", "bwd_input", "bwd_weight", "mask_update")
+    ev = {(L.name, k): [] for L in layers for k in kinds}
+
+    def run_step(t, record):
+        for L in layers:
+            for kind in ("fwd", "bwd_input", "bwd_weight"):
+                if record:
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                if kind == "fwd":
+                    mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
+                elif kind == "bwd_input":
+                    mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
+                else:
+                    mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+                if record:
+                    b.record(stream)
+                    ev[(L.name, kind)].append((a, b))
+        if args.update_interval and (t + 1) % args.update_interval == 0:
+            for li, L in enumerate(layers):
+                if record:
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                mst.mst_mask_update(L.layer, L.dY, L.X, T, density, cfg["zeta"], cfg["R"],
+                                    args.seed * 1000003 + t * 131 + li, L.ws, L.act, stream)
+                if record:
+                    b.record(stream)
+                    ev[(L.name, "mask_update")].append((a, b))
+
+    t = 0
+    for _ in range(args.warmup):
+        run_step(t, False)
+        t += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step(t, True)
+        t += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    n_updates = sum(len(ev[(L.name, "mask_update")]) for L in layers) // max(1, len(layers))
+    ms_per_step = 1e3 * elapsed / args.steps
+    sparse_flops_step = sum(3 * L.flops_product() for L in layers)
+    bytes_step = sum(L.bytes_fwd() + L.bytes_bwd_input() + L.bytes_bwd_weight() for L in layers)
+    value = sparse_flops_step / (elapsed / args.steps) / 1e12
+
+    # per-call device times from the events recorded inside the timed region
+    table, dominant = [], None
+    for L in layers:
+        for kind in kinds:
+            pairs = ev[(L.name, kind)]
+            if not pairs:
+                continue
+            ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+            row = dict(layer=L.name, call=kind, launches=len(pairs), avg_ms=round(ms, 5))
+            if kind != "mask_update":
+                by = getattr(L, "bytes_" + kind)()
+                fl = L.flops_product()
+                row.update(eff_tflops=round(fl / ms / 1e9, 3), hbm_gbs=round(by / ms / 1e6, 1),
+                           hbm_frac=round(by / ms / 1e6 / HBM_PEAK_GBS, 4),
+                           alu_frac=round(fl / ms / 1e9 / ALU_FP32_PEAK_TFLOPS, 4),
+                           alg_bytes=by, alg_flops=fl)
+                tot = ms * len(pairs)
+                if dominant is None or tot > dominant[0]:
+                    dominant = (tot, row, L)
+            else:
+                row.update(dense_grad_gflop=round(2 * T * L.O * L.I / 1e9, 2))
+            table.append(row)
+
+    _, drow, dL = dominant
+    t_hbm = drow["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_alu = drow["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
+    kernel = {"fwd": "k_spmm", "bwd_input": "k_spmm", "bwd_weight": "k_sddmm"}[drow["call"]]
+    if t_hbm >= t_alu:
+        roof = dict(bound="hbm", achieved=drow["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(drow["hbm_gbs"] / HBM_PEAK_GBS, 4))
+    else:
+        roof = dict(bound="alu", achieved=drow["eff_tflops"], peak=ALU_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(drow["eff_tflops"] / ALU_FP32_PEAK_TFLOPS, 4))
+    roof.update(traffic=None, kernel=kernel, call="%s/%s" % (dL.name, drow["call"]),
+                avg_launch_ms=drow["avg_ms"], alg_bytes_per_launch=drow["alg_bytes"],
+                alg_flops_per_launch=drow["alg_flops"], hbm_frac=drow["hbm_frac"], alu_frac=drow["alu_frac"])
+
+    out = {
+        "metric": METRIC, "value": round(value, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if act == "f32" else "bf16-in/f32-acc",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s FC set (%s), density %.2f %s mask, T=%d tokens, fwd+bwd_input+bwd_weight "
+                               "per layer, Mixed-Growing update every %d steps"
+                               % (args.config, "GPT-2-small block" if len(layers) > 1 else "single layer",
+                                  ", ".join("%s %d->%d" % (L.name, L.I, L.O) for L in layers), density,
+                                  cfg["mask"], T, args.update_interval),
+                   "nnz": {L.name: L.nnz for L in layers}, "mask_updates_in_timed_region": n_updates},
+        "hbm_gbs_step": round(bytes_step / (elapsed / args.steps) / 1e9, 1),
+        "hbm_frac_step": round(bytes_step / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": roof,
+        "calls": table,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, T)
+    print(json.dumps(out))
+
+
+def cpu_baseline(layers, T):
+    """The oracle as it stands (dense masked fp64 products with numpy) on the host cores."""
+    import numpy as np
+    from oracle import products as opr
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Ts = min(T, 8192)            # bounded sample of the same batch: the first Ts tokens
+    t0 = time.perf_counter()
+    flops, reps = 0, 0
+    while time.perf_counter() - t0 < 10.0 and reps < 50:      # about 10-30 s of CPU work
+        for L in layers:
+            X, dY = L.X_host[:Ts], L.dY_host[:Ts]
+            opr.fc_fwd(X, L.W, L.M)
+            opr.fc_bwd_input(dY, L.W, L.M)
+            opr.fc_bwd_weight(dY, X, L.M)
+            flops += 3 * 2 * L.nnz * Ts
+        reps += 1
+    dt = time.perf_counter() - t0
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "first %d of %d tokens, all layers, fwd+bwd_input+bwd_weight, %d repetitions (%.1f s); "
+                      "effective (nonzero-only) FLOPs over the oracle's dense masked fp64 numpy products"
+                      % (Ts, T, reps, dt)}
+
+
+if __name__ == "__main__":
+    main()
