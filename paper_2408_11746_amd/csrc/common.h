@@ -26,11 +26,11 @@ __host__ __device__ inline uint32_t lds_off(uint32_t k) {
     return (k << 9) | (((k >> 2) & 31u) << 3);
 }
 
-constexpr int ROW_ALIGN = 512;   // rows of a view are padded (with empty segments) to this
+constexpr int MAX_SLAB = 512;    // most rows one workgroup may own; views carry that many empty rows past R
 
 struct View {          // sparse matrix S [R x K] stored by (chunk of K, row, k)
     int R = 0, K = 0, nchunk = 0;
-    int Rpad = 0;          // R rounded up to ROW_ALIGN; rows >= R have empty segments
+    int Rpad = 0;          // row stride of ptr: >= R + MAX_SLAB; rows >= R have empty segments
     int64_t nseg = 0;      // nchunk * Rpad
     int64_t capv = 0;      // entries the arrays can hold (incl. padding and tail)
     int* ptr = nullptr;    // [nseg + 1] first entry of segment c*Rpad + r
@@ -106,7 +106,7 @@ int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s);
 
 // ---- internal entry points implemented across the .hip files ----
 int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s);
-int spmm(const View& v, const void* A, float* out, int T, mst_dtype act, hipStream_t s);
+int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype act, hipStream_t s);
 int sddmm(const mst_layer* L, const void* dY, const void* X, float* dW, int T, mst_dtype act,
           const Workspace& ws, hipStream_t s);
 // C[M x N] (fp32) = op(A) op(B) on the matrix cores; see gemm_mfma.hip

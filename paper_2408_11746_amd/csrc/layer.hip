@@ -21,7 +21,7 @@ int64_t view_capacity(int64_t cap, int64_t nchunk, int64_t R) {
 }
 
 static int64_t nchunks(int K) { return cdiv(K, KC); }
-static int64_t rpad(int R) { return cdiv(R, ROW_ALIGN) * ROW_ALIGN; }
+static int64_t rpad(int R) { return cdiv((int64_t)R + MAX_SLAB, 64) * 64; }
 
 bool use_dense_path(const mst_layer* L) {
     if (L->path == MST_PATH_DENSE) return true;
