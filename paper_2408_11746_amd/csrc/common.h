@@ -13,29 +13,37 @@ namespace mst {
 // The contraction dimension of a view is cut into chunks of KC indices; one chunk of
 // the dense operand for TT tokens is what a workgroup stages in LDS at a time.
 constexpr int KC = 128;          // contraction indices per chunk
-constexpr int TT = 128;          // tokens per LDS tile (two per lane of a wavefront)
-constexpr int SEG_PAD = 4;       // every (chunk, row) segment holds a multiple of 4 entries
-constexpr int ENT_TAIL = 16;     // readable entries past the last one (prefetch overrun)
+constexpr int TT = 128;          // tokens per LDS tile
+constexpr int RB = 16;           // rows per row block: 4 lane groups x 4 quads
+constexpr int MAX_WG_BLOCKS = 16;   // most row blocks one workgroup may own
+constexpr int PAIR_TAIL = 4;     // readable step pairs past the last one (prefetch overrun)
 
-// LDS tile layout: row k (one contraction index) holds TT tokens = 512 bytes as 64
-// token pairs of 8 bytes.  Lane l owns tokens 2l, 2l+1 and finds them at byte
-// lds_off(k) ^ (l << 3): the 5-bit swizzle (k >> 2) spreads the transposing stores of
-// the tile loader over all banks while a wavefront's read of one row stays a
-// permutation of that row (conflict-free).
+// LDS tile layout: row k (one contraction index) holds TT tokens = 512 bytes as 32
+// 16-byte slots of four consecutive tokens; slot u of tokens 4u..4u+3 sits at byte
+// (u >> 4) * 256 + ((u & 15) ^ ((k >> 2) & 15)) * 16.  Lane s (0..15) of a lane group
+// owns tokens 4s..4s+3 and 64+4s..64+4s+3 and finds them at lds_off(k) ^ (s << 4) and
+// 256 bytes further.  The XOR spreads the transposing stores of the tile loader over all
+// banks while the 16 lanes of a group still read one contiguous 256 bytes.
 __host__ __device__ inline uint32_t lds_off(uint32_t k) {
-    return (k << 9) | (((k >> 2) & 31u) << 3);
+    return (k << 9) | (((k >> 2) & 15u) << 4);
 }
 
-constexpr int MAX_SLAB = 512;    // most rows one workgroup may own; views carry that many empty rows past R
-
-struct View {          // sparse matrix S [R x K] stored by (chunk of K, row, k)
+// Sparse matrix S [R x K] as the product kernels walk it.  Rows are grouped in blocks of
+// RB = 16; row 16b + 4g + q belongs to lane group g and quad q of block b.  For every
+// (chunk c of K, block b, quad q) the four rows' entries inside the chunk are stored side
+// by side, padded with zero-weight entries to the longest of the four and to an even
+// count (an ELL slice of height 4): step j of the quad holds one entry per lane group.
+// Two steps form a pair = uint4[4]: element g is {off_j, w_j, off_j+1, w_j+1} of lane
+// group g, off = lds_off(k - c*KC), w = fp32 bits.
+struct View {
     int R = 0, K = 0, nchunk = 0;
-    int Rpad = 0;          // row stride of ptr: >= R + MAX_SLAB; rows >= R have empty segments
-    int64_t nseg = 0;      // nchunk * Rpad
-    int64_t capv = 0;      // entries the arrays can hold (incl. padding and tail)
-    int* ptr = nullptr;    // [nseg + 1] first entry of segment c*Rpad + r
-    uint2* ent = nullptr;  // [capv] {lds_off(k - c*KC), fp32 bits of the weight}
-    int* perm = nullptr;   // [capv] canonical index of the entry, -1 for padding
+    int NB = 0;            // row blocks: ceil(R / 16)
+    int NBpad = 0;         // block stride of ptr: NB + MAX_WG_BLOCKS (the extra blocks stay empty)
+    int64_t nseg = 0;      // nchunk * NBpad * 4 quad segments
+    int64_t cap_pairs = 0; // pairs the arrays can hold (incl. tail)
+    int* ptr = nullptr;    // [nseg + 1] first pair of segment (c*NBpad + b)*4 + q
+    uint4* ent = nullptr;  // [cap_pairs * 4]
+    int* perm = nullptr;   // [cap_pairs * 8] canonical index of entry slot (pair*4 + g)*2 + half, -1 = padding
 };
 
 }  // namespace mst
@@ -85,13 +93,14 @@ struct Workspace {
     int* cidx = nullptr;       // [N] canonical index of each active position
     uint8_t* sel = nullptr;    // [N] selection flags of the grow step
     uint8_t* psel = nullptr;   // [cap] selection flags of the prune step
-    int* segcnt = nullptr;     // [max(nseg_row, nseg_col) + 1]
+    int* segcnt = nullptr;     // active count per (chunk, row) of the view being built
+    int* qlen = nullptr;       // pairs per quad segment of the view being built
     int* rowcnt = nullptr;     // [O + 1]
     uint32_t* blk = nullptr;   // [select_blocks(N) + 1] per-block tie counts
     uint64_t* sel_state = nullptr;   // radix-select state + histogram
     float* gemm = nullptr;     // [GEMM_WS_SPLITS * N] split-k partial outputs of the dense GEMM
     size_t gemm_floats = 0;
-    float* partial = nullptr;  // SDDMM partial sums [ntile][capv_row]
+    float* partial = nullptr;  // SDDMM partial sums [ntile][entry slots of the row view]
     size_t partial_floats = 0;
     size_t total = 0;
 };
@@ -101,7 +110,7 @@ constexpr int GEMM_WS_SPLITS = 4;
 constexpr int SELECT_BLOCK = 2048;   // elements per block in the ordered tie pass
 constexpr int SEL_STATE_WORDS = 8 + 256;
 
-int64_t view_capacity(int64_t cap, int64_t nchunk, int64_t R);
+int64_t view_pair_capacity(int64_t cap, int64_t nchunk, int64_t R);
 int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s);
 
 // ---- internal entry points implemented across the .hip files ----

@@ -5,23 +5,26 @@
 // index o*I + i) as vals[] / flat[], plus two "views" that the product kernels walk:
 //   row view  S = W    [O x I]  -> forward and weight gradient
 //   col view  S = W^T  [I x O]  -> input gradient
-// A view cuts the contraction index into chunks of KC and lists, for each
-// (chunk, row) segment, its entries {LDS byte offset of the operand row, weight}; every
-// segment is padded with zero-weight entries to a multiple of SEG_PAD so the kernels
-// can fetch entries four at a time.  perm[] maps a view entry back to its canonical slot.
+// A view cuts the contraction index into chunks of KC and stores, per (chunk, block of
+// 16 rows, quad), an ELL slice of four rows (see View in common.h).  perm[] maps an
+// entry slot back to its canonical position, so that values can be refreshed after an
+// optimiser step and weight gradients can be returned in canonical order.
 #include "common.h"
 
 namespace mst {
 
 thread_local int g_last_hip_error = 0;
 
-// worst case: every real segment carries SEG_PAD - 1 padding entries
-int64_t view_capacity(int64_t cap, int64_t nchunk, int64_t R) {
-    return cdiv(cap + (SEG_PAD - 1) * nchunk * R + ENT_TAIL, 64) * 64;
-}
-
 static int64_t nchunks(int K) { return cdiv(K, KC); }
-static int64_t rpad(int R) { return cdiv((int64_t)R + MAX_SLAB, 64) * 64; }
+static int64_t nblocks(int R) { return cdiv(R, RB); }
+static int64_t nbpad(int R) { return nblocks(R) + MAX_WG_BLOCKS; }
+
+// A quad segment holds max(len of its four rows) steps rounded up to even, which is at
+// most (sum of the four lens) + 1; summed over all segments: steps <= nnz + #segments.
+int64_t view_pair_capacity(int64_t cap, int64_t nchunk, int64_t R) {
+    const int64_t nqs = nchunk * nblocks((int)R) * 4;
+    return cdiv((cap + nqs) / 2 + 1 + PAIR_TAIL, 8) * 8;
+}
 
 bool use_dense_path(const mst_layer* L) {
     if (L->path == MST_PATH_DENSE) return true;
@@ -38,8 +41,8 @@ struct LayerCarve {
 static LayerCarve carve_layer(int O, int I, int64_t cap) {
     LayerCarve c{};
     const int64_t N = (int64_t)O * I;
-    const int64_t nseg_r = nchunks(I) * rpad(O), nseg_c = nchunks(O) * rpad(I);
-    const int64_t capv_r = view_capacity(cap, nchunks(I), O), capv_c = view_capacity(cap, nchunks(O), I);
+    const int64_t nseg_r = nchunks(I) * nbpad(O) * 4, nseg_c = nchunks(O) * nbpad(I) * 4;
+    const int64_t cp_r = view_pair_capacity(cap, nchunks(I), O), cp_c = view_pair_capacity(cap, nchunks(O), I);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     c.mask = take((size_t)N);
@@ -48,11 +51,11 @@ static LayerCarve carve_layer(int O, int I, int64_t cap) {
     c.rowptr = take((size_t)(O + 1) * 4);
     c.Wd = take((size_t)N * 4);
     c.rptr = take((size_t)(nseg_r + 1) * 4);
-    c.rent = take((size_t)capv_r * 8);
-    c.rperm = take((size_t)capv_r * 4);
+    c.rent = take((size_t)cp_r * 64);
+    c.rperm = take((size_t)cp_r * 32);
     c.cptr = take((size_t)(nseg_c + 1) * 4);
-    c.cent = take((size_t)capv_c * 8);
-    c.cperm = take((size_t)capv_c * 4);
+    c.cent = take((size_t)cp_c * 64);
+    c.cperm = take((size_t)cp_c * 32);
     c.total = off;
     return c;
 }
@@ -68,9 +71,9 @@ static bool shape_ok(int O, int I, int64_t cap) {
 Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
     Workspace w{};
     const int64_t N = (int64_t)O * I;
-    const int64_t nseg_r = nchunks(I) * rpad(O), nseg_c = nchunks(O) * rpad(I);
-    const int64_t nseg = nseg_r > nseg_c ? nseg_r : nseg_c;
-    const int64_t capv_r = view_capacity(cap, nchunks(I), O);
+    // per-row-per-chunk counts of either view, rows padded to whole blocks
+    const int64_t cnt_r = nchunks(I) * nbpad(O) * RB, cnt_c = nchunks(O) * nbpad(I) * RB;
+    const int64_t nseg_r = nchunks(I) * nbpad(O) * 4, nseg_c = nchunks(O) * nbpad(I) * 4;
     const int64_t ntile = cdiv(T > 0 ? T : 1, TT);
     char* b = static_cast<char*>(base);
     size_t off = 0;
@@ -80,13 +83,14 @@ Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
     w.cidx = (int*)take((size_t)N * 4);
     w.sel = (uint8_t*)take((size_t)N);
     w.psel = (uint8_t*)take((size_t)(cap > 0 ? cap : 1));
-    w.segcnt = (int*)take((size_t)(nseg + 1) * 4);
+    w.segcnt = (int*)take((size_t)(std::max(cnt_r, cnt_c) + 1) * 4);
+    w.qlen = (int*)take((size_t)(std::max(nseg_r, nseg_c) + 1) * 4);
     w.rowcnt = (int*)take((size_t)(O + 1) * 4);
     w.blk = (uint32_t*)take((size_t)(cdiv(N, SELECT_BLOCK) + 2) * 4);
     w.sel_state = (uint64_t*)take((size_t)SEL_STATE_WORDS * 8);
     w.gemm_floats = (size_t)GEMM_WS_SPLITS * (size_t)N;
     w.gemm = (float*)take(w.gemm_floats * 4);
-    w.partial_floats = (size_t)ntile * (size_t)capv_r;
+    w.partial_floats = (size_t)ntile * (size_t)view_pair_capacity(cap, nchunks(I), O) * 8;
     w.partial = (float*)take(w.partial_floats * 4);
     w.total = off;
     return w;
@@ -127,9 +131,19 @@ __global__ void k_count_col(const uint8_t* __restrict__ mask, int O, int I, int 
     segcnt[(size_t)c * Rpad + i] = n;
 }
 
-// single-block exclusive scan: out[j] = sum_{j' < j} f(in[j']), out[n] = total,
-// f = round up to a multiple of `pad` (pad = 1: plain scan)
-__global__ void k_scan_excl(const int* in, int* out, int64_t n, int pad) {
+// pairs of one quad segment: longest of its four rows, rounded up to even, halved
+__global__ void k_quad_len(const int* __restrict__ segcnt, int64_t nseg, int* __restrict__ qlen) {
+    const int64_t sidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (c*NBpad + b)*4 + q
+    if (sidx >= nseg) return;
+    const int64_t cb = sidx >> 2;
+    const int q = (int)(sidx & 3);
+    const int* p = segcnt + cb * RB + q;          // rows 16(c*NBpad + b) + 4g + q
+    const int L = max(max(p[0], p[4]), max(p[8], p[12]));
+    qlen[sidx] = (L + 1) >> 1;
+}
+
+// single-block exclusive scan: out[j] = sum_{j' < j} in[j'], out[n] = total
+__global__ void k_scan_excl(const int* in, int* out, int64_t n) {
     __shared__ int wsum[16];
     __shared__ int carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -137,8 +151,7 @@ __global__ void k_scan_excl(const int* in, int* out, int64_t n, int pad) {
     __syncthreads();
     for (int64_t base = 0; base < n; base += blockDim.x) {
         const int64_t j = base + tid;
-        int v = 0;
-        if (j < n) { v = in[j]; v = (v + pad - 1) / pad * pad; }
+        const int v = (j < n) ? in[j] : 0;
         int x = v;                                   // inclusive scan inside the wave
         for (int d = 1; d < 64; d <<= 1) {
             int y = __shfl_up(x, d, 64);
@@ -157,83 +170,86 @@ __global__ void k_scan_excl(const int* in, int* out, int64_t n, int pad) {
     if (tid == 0) out[n] = carry_s;
 }
 
+// every pair up to the readable tail starts as padding: zero weight, offset 0, perm -1
+__global__ void k_clear_view(const int* __restrict__ ptr, int64_t nseg, uint4* __restrict__ ent,
+                             int* __restrict__ perm) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // uint4 index
+    const int64_t n = ((int64_t)ptr[nseg] + PAIR_TAIL) * 4;
+    if (e >= n) return;
+    ent[e] = make_uint4(0u, 0u, 0u, 0u);
+    perm[2 * e] = -1;
+    perm[2 * e + 1] = -1;
+}
+
+// entry slot (as index into ent viewed as uint2[], and into perm) of step j of a row
+__device__ inline int64_t entry_slot(int pair0, int g, int j) {
+    return (((int64_t)pair0 + (j >> 1)) * 4 + g) * 2 + (j & 1);
+}
+
 // one wavefront per row: ordered compaction of the row into canonical arrays and the row view
 __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __restrict__ W,
-                           int O, int I, int nchunk, int Rpad,
-                           const int* __restrict__ rowptr, const int* __restrict__ segcnt,
-                           const int* __restrict__ ptr,
+                           int O, int I, int nchunk, int NBpad,
+                           const int* __restrict__ rowptr, const int* __restrict__ ptr,
                            float* __restrict__ vals, int* __restrict__ flat, int* __restrict__ cidx,
                            uint2* __restrict__ ent, int* __restrict__ perm) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (r >= O) return;
+    const int b = r / RB, g = (r % RB) >> 2, q = r & 3;
     const uint8_t* m = mask + (size_t)r * I;
     const float* w = W + (size_t)r * I;
     int canon = rowptr[r];
     for (int c = 0; c < nchunk; ++c) {
-        const int seg = ptr[(size_t)c * Rpad + r];
-        const int n = segcnt[(size_t)c * Rpad + r];
+        const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
         int run = 0;
         const int i1 = min(I, (c + 1) * KC);
         for (int i0 = c * KC; i0 < i1; i0 += 64) {
             const int i = i0 + lane;
             const bool on = i < i1 && m[i] != 0;
-            const unsigned long long b = __ballot(on);
+            const unsigned long long bal = __ballot(on);
             if (on) {
-                const int before = __popcll(b & ((1ull << lane) - 1ull));
-                const int k = canon + run + before;
-                const int e = seg + run + before;
+                const int j = run + __popcll(bal & ((1ull << lane) - 1ull));
+                const int k = canon + j;
                 const float v = w[i];
                 vals[k] = v;
                 flat[k] = r * I + i;
                 cidx[(size_t)r * I + i] = k;
+                const int64_t e = entry_slot(pair0, g, j);
                 ent[e] = make_uint2(lds_off((uint32_t)(i - c * KC)), __float_as_uint(v));
                 perm[e] = k;
             }
-            run += __popcll(b);
+            run += __popcll(bal);
         }
-        const int npad = (n + SEG_PAD - 1) / SEG_PAD * SEG_PAD - n;
-        if (lane < npad) {
-            ent[seg + n + lane] = make_uint2(0u, 0u);
-            perm[seg + n + lane] = -1;
-        }
-        canon += n;
+        canon += run;
     }
 }
 
-// one thread per (column i, chunk c of rows): the col view's segment (c, i)
+// one thread per (column i, chunk c of rows): row i of the col view, chunk c
 __global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __restrict__ W,
-                           int O, int I, int Rpad, const int* __restrict__ ptr, const int* __restrict__ cidx,
+                           int O, int I, int NBpad, const int* __restrict__ ptr, const int* __restrict__ cidx,
                            uint2* __restrict__ ent, int* __restrict__ perm) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int c = blockIdx.y;
     if (i >= I) return;
+    const int b = i / RB, g = (i % RB) >> 2, q = i & 3;
+    const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
     const int o0 = c * KC, o1 = min(O, o0 + KC);
-    int e = ptr[(size_t)c * Rpad + i];
-    int n = 0;
+    int j = 0;
     for (int o = o0; o < o1; ++o) {
         const size_t f = (size_t)o * I + i;
         if (mask[f]) {
+            const int64_t e = entry_slot(pair0, g, j);
             ent[e] = make_uint2(lds_off((uint32_t)(o - o0)), __float_as_uint(W[f]));
             perm[e] = cidx[f];
-            ++e; ++n;
+            ++j;
         }
     }
-    const int npad = (n + SEG_PAD - 1) / SEG_PAD * SEG_PAD - n;
-    for (int p = 0; p < npad; ++p) { ent[e] = make_uint2(0u, 0u); perm[e] = -1; ++e; }
-}
-
-// zero-weight readable tail after the last entry of a view
-__global__ void k_fill_tail(const int* __restrict__ ptr, int64_t nseg, uint2* __restrict__ ent,
-                            int* __restrict__ perm) {
-    const int e = ptr[nseg] + threadIdx.x;
-    if (threadIdx.x < ENT_TAIL) { ent[e] = make_uint2(0u, 0u); perm[e] = -1; }
 }
 
 __global__ void k_sync_view(const float* __restrict__ vals, const int* __restrict__ ptr, int64_t nseg,
                             const int* __restrict__ perm, uint2* __restrict__ ent) {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= ptr[nseg]) return;
+    if (e >= (int64_t)ptr[nseg] * 8) return;
     const int p = perm[e];
     if (p >= 0) ent[e].y = __float_as_uint(vals[p]);
 }
@@ -258,7 +274,7 @@ __global__ void k_copy_i32(const int* __restrict__ src, int* __restrict__ dst, i
 
 // out[j] = sum of in[0 .. j), out[n] = total; in == out is allowed
 int scan_excl_i32(const int* in, int* out, int64_t n, hipStream_t s) {
-    k_scan_excl<<<1, 1024, 0, s>>>(in, out, n, 1);
+    k_scan_excl<<<1, 1024, 0, s>>>(in, out, n);
     MST_LAUNCH_CHECK();
     return MST_OK;
 }
@@ -274,28 +290,31 @@ int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s) {
 static int build_one_view(View& v, bool row_view, const mst_layer* L, const float* Wsrc,
                           const Workspace& ws, hipStream_t s) {
     const int O = L->O, I = L->I;
-    int rc = fill_u32(ws.segcnt, 0u, v.nseg + 1, s);      // rows >= R keep empty segments
+    const int Rpad = v.NBpad * RB;
+    int rc = fill_u32(ws.segcnt, 0u, (int64_t)v.nchunk * Rpad + 1, s);      // rows >= R count as empty
     if (rc != MST_OK) return rc;
+    dim3 gcol((unsigned)cdiv(I, 256), (unsigned)v.nchunk);
     if (row_view) {
-        k_count_row<<<O, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, v.Rpad, ws.segcnt, ws.rowcnt);
+        k_count_row<<<O, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
         MST_LAUNCH_CHECK();
-        k_scan_excl<<<1, 1024, 0, s>>>(ws.rowcnt, L->rowptr, O, 1);
-        MST_LAUNCH_CHECK();
-        k_scan_excl<<<1, 1024, 0, s>>>(ws.segcnt, v.ptr, v.nseg, SEG_PAD);
-        MST_LAUNCH_CHECK();
-        k_fill_row<<<(unsigned)cdiv(O, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.Rpad, L->rowptr, ws.segcnt,
-                                                        v.ptr, L->vals, L->flat, ws.cidx, v.ent, v.perm);
-        MST_LAUNCH_CHECK();
+        if ((rc = scan_excl_i32(ws.rowcnt, L->rowptr, O, s)) != MST_OK) return rc;
     } else {
-        dim3 g((unsigned)cdiv(I, 256), (unsigned)v.nchunk);
-        k_count_col<<<g, 256, 0, s>>>(L->mask, O, I, v.Rpad, ws.segcnt);
-        MST_LAUNCH_CHECK();
-        k_scan_excl<<<1, 1024, 0, s>>>(ws.segcnt, v.ptr, v.nseg, SEG_PAD);
-        MST_LAUNCH_CHECK();
-        k_fill_col<<<g, 256, 0, s>>>(L->mask, Wsrc, O, I, v.Rpad, v.ptr, ws.cidx, v.ent, v.perm);
+        k_count_col<<<gcol, 256, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
         MST_LAUNCH_CHECK();
     }
-    k_fill_tail<<<1, 64, 0, s>>>(v.ptr, v.nseg, v.ent, v.perm);
+    k_quad_len<<<(unsigned)cdiv(v.nseg, 256), 256, 0, s>>>(ws.segcnt, v.nseg, ws.qlen);
+    MST_LAUNCH_CHECK();
+    if ((rc = scan_excl_i32(ws.qlen, v.ptr, v.nseg, s)) != MST_OK) return rc;
+    k_clear_view<<<(unsigned)cdiv(v.cap_pairs * 4, 256), 256, 0, s>>>(v.ptr, v.nseg, v.ent, v.perm);
+    MST_LAUNCH_CHECK();
+    if (row_view) {
+        k_fill_row<<<(unsigned)cdiv(O, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.NBpad, L->rowptr, v.ptr,
+                                                        L->vals, L->flat, ws.cidx,
+                                                        reinterpret_cast<uint2*>(v.ent), v.perm);
+    } else {
+        k_fill_col<<<gcol, 256, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, ws.cidx,
+                                        reinterpret_cast<uint2*>(v.ent), v.perm);
+    }
     MST_LAUNCH_CHECK();
     return MST_OK;
 }
@@ -355,14 +374,14 @@ int mst_layer_create(mst_layer_t** out, int O, int I, int64_t nnz_capacity, void
     L->flat = (int*)(b + c.flat);
     L->rowptr = (int*)(b + c.rowptr);
     L->Wd = (float*)(b + c.Wd);
-    L->row.R = O; L->row.K = I; L->row.nchunk = (int)nchunks(I); L->row.Rpad = (int)rpad(O);
-    L->row.nseg = nchunks(I) * rpad(O);
-    L->row.capv = view_capacity(nnz_capacity, nchunks(I), O);
-    L->row.ptr = (int*)(b + c.rptr); L->row.ent = (uint2*)(b + c.rent); L->row.perm = (int*)(b + c.rperm);
-    L->col.R = I; L->col.K = O; L->col.nchunk = (int)nchunks(O); L->col.Rpad = (int)rpad(I);
-    L->col.nseg = nchunks(O) * rpad(I);
-    L->col.capv = view_capacity(nnz_capacity, nchunks(O), I);
-    L->col.ptr = (int*)(b + c.cptr); L->col.ent = (uint2*)(b + c.cent); L->col.perm = (int*)(b + c.cperm);
+    auto init_view = [&](View& v, int R, int K, size_t optr, size_t oent, size_t operm) {
+        v.R = R; v.K = K; v.nchunk = (int)nchunks(K); v.NB = (int)nblocks(R); v.NBpad = (int)nbpad(R);
+        v.nseg = (int64_t)v.nchunk * v.NBpad * 4;
+        v.cap_pairs = view_pair_capacity(nnz_capacity, v.nchunk, R);
+        v.ptr = (int*)(b + optr); v.ent = (uint4*)(b + oent); v.perm = (int*)(b + operm);
+    };
+    init_view(L->row, O, I, c.rptr, c.rent, c.rperm);
+    init_view(L->col, I, O, c.cptr, c.cent, c.cperm);
     *out = L;
     return MST_OK;
 }
@@ -380,11 +399,10 @@ int mst_layer_load_dense(mst_layer_t* L, const float* W_dev, const uint8_t* M_de
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     // learn the active count first so that nothing is written when it does not fit
-    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(M_dev, L->O, L->I, L->row.nchunk, L->row.Rpad,
-                                                              nullptr, ws.rowcnt);
+    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(M_dev, L->O, L->I, L->row.nchunk, 0, nullptr, ws.rowcnt);
     MST_LAUNCH_CHECK();
-    k_scan_excl<<<1, 1024, 0, s>>>(ws.rowcnt, L->rowptr, L->O, 1);   // rebuilt below anyway
-    MST_LAUNCH_CHECK();
+    int rcs = scan_excl_i32(ws.rowcnt, L->rowptr, L->O, s);          // rebuilt below anyway
+    if (rcs != MST_OK) return rcs;
     int total = 0;
     MST_HIP(hipMemcpyAsync(&total, L->rowptr + L->O, 4, hipMemcpyDeviceToHost, s));
     MST_HIP(hipStreamSynchronize(s));
@@ -423,8 +441,10 @@ int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
     L->Wd_valid = false;
     if (L->nnz == 0) return MST_OK;
     for (View* v : {&L->row, &L->col}) {
-        const int64_t upper = L->nnz + (SEG_PAD - 1) * (int64_t)v->nchunk * v->R;
-        k_sync_view<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(L->vals, v->ptr, v->nseg, v->perm, v->ent);
+        // every real entry slot lies below 4 * (nnz + #quad segments); the kernel stops at ptr[nseg] * 8
+        const int64_t upper = 4 * (L->nnz + (int64_t)v->nchunk * v->NB * 4);
+        k_sync_view<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(L->vals, v->ptr, v->nseg, v->perm,
+                                                              reinterpret_cast<uint2*>(v->ent));
         MST_LAUNCH_CHECK();
     }
     return MST_OK;

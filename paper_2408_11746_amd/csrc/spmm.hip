@@ -1,160 +1,134 @@
-// Row-split SpMM:  out[T x R] = A[T x K] * S^T  with S [R x K] unstructured-sparse.
+// SpMM:  out[T x R] = A[T x K] * S^T  with S [R x K] unstructured-sparse.
 // Serves the forward product (S = W, A = X; App. "FLOP Calculation" Eq. (1)) and the
 // input gradient (S = W^T, A = dY; the first half of the backward pass).
 //
-// One workgroup owns TT = 128 tokens and a slab of 8*rw rows of S.  It walks the
+// A workgroup owns TT = 128 tokens and a slab of 16 rows per wavefront.  It walks the
 // contraction index in chunks of KC: the chunk of A is staged (transposed) in LDS, then
-// each wavefront walks the entries of its RW rows in that chunk.  A lane keeps two
-// tokens; an entry costs one scalar-fetched {offset, weight}, one 8-byte LDS read and
-// two FMAs into the row's accumulator pair, which stays in registers for the whole K loop.
+// each wavefront walks its row block's ELL slices.  A wavefront is four lane groups of 16
+// lanes; in one step each lane group multiplies ONE entry (its own row of the quad)
+// with 128 tokens, 8 per lane: the entry {offset, weight} comes from one per-lane vector
+// load (the 16 lanes of a group read the same 16 bytes), the 8 activations from two
+// 16-byte LDS reads, then 8 FMAs into the accumulators of that row, which stay in
+// registers for the whole K loop.  Nothing in the inner loop needs the scalar unit or a
+// cross-lane operation.  The result tile leaves through LDS so that global stores are
+// whole rows of the slab.
 #include "tile_loader.h"
 
 namespace mst {
 
-// entries of one group against the staged tile, accumulated into one row's pair
-#define MST_SPMM_GROUP(E)                                                                     \
-    do {                                                                                      \
-        const float2 x0 = *reinterpret_cast<const float2*>(tb + (lane8 ^ (E).off0));          \
-        const float2 x1 = *reinterpret_cast<const float2*>(tb + (lane8 ^ (E).off1));          \
-        const float2 x2 = *reinterpret_cast<const float2*>(tb + (lane8 ^ (E).off2));          \
-        const float2 x3 = *reinterpret_cast<const float2*>(tb + (lane8 ^ (E).off3));          \
-        const float w0 = __uint_as_float((E).w0), w1 = __uint_as_float((E).w1);               \
-        const float w2 = __uint_as_float((E).w2), w3 = __uint_as_float((E).w3);               \
-        acc[r].x = fmaf(w0, x0.x, acc[r].x); acc[r].y = fmaf(w0, x0.y, acc[r].y);             \
-        acc[r].x = fmaf(w1, x1.x, acc[r].x); acc[r].y = fmaf(w1, x1.y, acc[r].y);             \
-        acc[r].x = fmaf(w2, x2.x, acc[r].x); acc[r].y = fmaf(w2, x2.y, acc[r].y);             \
-        acc[r].x = fmaf(w3, x3.x, acc[r].x); acc[r].y = fmaf(w3, x3.y, acc[r].y);             \
+#define MST_STEP(OFF, W, ACC)                                                        \
+    do {                                                                             \
+        const uint32_t a_ = lane16 ^ (OFF);                                          \
+        const float4 xa = *reinterpret_cast<const float4*>(tb + a_);                 \
+        const float4 xb = *reinterpret_cast<const float4*>(tb + a_ + 256);           \
+        const float w_ = __uint_as_float(W);                                         \
+        ACC[0] = fmaf(w_, xa.x, ACC[0]); ACC[1] = fmaf(w_, xa.y, ACC[1]);            \
+        ACC[2] = fmaf(w_, xa.z, ACC[2]); ACC[3] = fmaf(w_, xa.w, ACC[3]);            \
+        ACC[4] = fmaf(w_, xb.x, ACC[4]); ACC[5] = fmaf(w_, xb.y, ACC[5]);            \
+        ACC[6] = fmaf(w_, xb.z, ACC[6]); ACC[7] = fmaf(w_, xb.w, ACC[7]);            \
     } while (0)
 
-// NW wavefronts per workgroup; RWMAX bounds the accumulator registers; rw <= RWMAX (a
-// multiple of 4) is the number of rows a wavefront actually owns, chosen on the host so
-// that the grid fills the chip.  Two variants are built: 16 wavefronts x 12 rows at
-// <= 64 VGPRs (two workgroups = 32 wavefronts per CU hide the latency of the scalar entry
-// fetches), and 8 wavefronts x 32 rows for very sparse layers, where re-reading the
-// activation tile for many narrow slabs would cost more than the entry work.
-template <int NW, int RWMAX, int MINB, typename TIn>
-__global__ __launch_bounds__(NW * 64, MINB) void k_spmm(const TIn* __restrict__ A, const int* __restrict__ ptr,
-                                                        const Ent4* __restrict__ ent4, float* __restrict__ out,
-                                                        int T, int K, int R, int Rpad, int nchunk, int nslab,
-                                                        int ntile, int rw, int vec_ok, int vec_store) {
+template <typename TIn>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_spmm(const TIn* __restrict__ A, const int* __restrict__ ptr,
+                                                  const uint4* __restrict__ ent, float* __restrict__ out,
+                                                  int T, int K, int R, int NBpad, int nchunk, int nslab,
+                                                  int ntile, int vec_ok, int vec_store) {
     __shared__ float tile[KC * TT];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
     const int lane = tid & 63;
+    const int nw = nthreads >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
-    const int r0 = slab * (NW * rw) + wave * rw;
-    const uint32_t lane8 = (uint32_t)lane << 3;
+    const int blk = slab * nw + wave;                 // this wavefront's row block
+    const int g = lane >> 4, s = lane & 15;
+    const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
+    const uint4* entl = ent + g;                      // this lane group's 16 bytes of every pair
 
-    float2 acc[RWMAX];
+    float acc[4][8];
 #pragma unroll
-    for (int r = 0; r < RWMAX; ++r) acc[r] = make_float2(0.f, 0.f);
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
 
-    // lane r keeps the wavefront's segment pointer r of the current chunk
-    const int pl = r0 + min(lane, rw);
+    // lane q (0..4) keeps the first pair of quad q of the current chunk
+    const int pl = blk * 4 + min(lane, 4);
     int pv = ptr[pl];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
-        load_tile<TIn, NW * 64>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
-        const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * Rpad + pl] : 0;
-        // the wavefront's entries of this chunk are contiguous: one running group pointer,
-        // the next group is always in flight while the current one is multiplied
-        int g = __builtin_amdgcn_readlane(pv, 0) >> 2;
-        const Ent4* pe = ent4 + g;
-        Ent4 cur = pe[0];
+        load_tile<TIn>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid, nthreads);
+        const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
+        int p = __builtin_amdgcn_readlane(pv, 0);
+        uint4 cur = entl[(int64_t)p * 4];
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < RWMAX; ++r) {
-            if (r < rw) {
-                const int gend = __builtin_amdgcn_readlane(pv, r + 1) >> 2;
-                int n = gend - g;
-                g = gend;
-                for (; n >= 2; n -= 2) {           // two groups per trip
-                    const Ent4 other = pe[1];
-                    MST_SPMM_GROUP(cur);
-                    cur = pe[2];
-                    MST_SPMM_GROUP(other);
-                    pe += 2;
-                }
-                if (n > 0) {
-                    const Ent4 nxt = pe[1];
-                    MST_SPMM_GROUP(cur);
-                    cur = nxt;
-                    pe += 1;
-                }
+        for (int q = 0; q < 4; ++q) {
+            const int pend = __builtin_amdgcn_readlane(pv, q + 1);
+            for (; p < pend; ++p) {
+                const uint4 nxt = entl[(int64_t)(p + 1) * 4];      // next pair in flight
+                MST_STEP(cur.x, cur.y, acc[q]);
+                MST_STEP(cur.z, cur.w, acc[q]);
+                cur = nxt;
             }
         }
         pv = pv_next;
     }
 
-    // lane l holds tokens t0 + 2l and t0 + 2l + 1 for rows r0 .. r0 + rw - 1
-    const int ta = t0 + 2 * lane;
-    if (vec_store && r0 + rw <= R) {
+    // ---- epilogue: through LDS, 64 tokens at a time, so that each token's nw*16 outputs
+    // leave as one contiguous run.  Staging layout: token tl (0..63) owns 1 KB; the
+    // 16-byte chunk j (rows 4j..4j+3 of the slab) sits at slot j ^ ((tl >> 2) & 15).
+    const int row0 = slab * nw * RB;                  // first row of the slab
+    const int chunk = wave * 4 + g;                   // this lane's 16-byte chunk of a token row
+    float4* st = reinterpret_cast<float4*>(tile);
 #pragma unroll
-        for (int r = 0; r < RWMAX; r += 4) {
-            if (r < rw) {
-                if (ta < T)
-                    *reinterpret_cast<float4*>(out + (int64_t)ta * R + r0 + r) =
-                        make_float4(acc[r].x, acc[r + 1].x, acc[r + 2].x, acc[r + 3].x);
-                if (ta + 1 < T)
-                    *reinterpret_cast<float4*>(out + (int64_t)(ta + 1) * R + r0 + r) =
-                        make_float4(acc[r].y, acc[r + 1].y, acc[r + 2].y, acc[r + 3].y);
-            }
+    for (int h = 0; h < 2; ++h) {
+        __syncthreads();                              // tile / previous half no longer read
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int tl = 4 * s + e;
+            st[tl * 64 + (chunk ^ s)] = make_float4(acc[0][4 * h + e], acc[1][4 * h + e], acc[2][4 * h + e],
+                                                    acc[3][4 * h + e]);
         }
-    } else {
-#pragma unroll
-        for (int r = 0; r < RWMAX; ++r) {
-            if (r < rw && r0 + r < R) {
-                if (ta < T) out[(int64_t)ta * R + r0 + r] = acc[r].x;
-                if (ta + 1 < T) out[(int64_t)(ta + 1) * R + r0 + r] = acc[r].y;
+        __syncthreads();
+        const int nchunks16 = nw * 4;                 // 16-byte chunks per token row of the slab
+        for (int item = tid; item < 64 * nchunks16; item += nthreads) {
+            const int tl = item / nchunks16, j = item % nchunks16;
+            const int t = t0 + 64 * h + tl;
+            const int row = row0 + 4 * j;
+            if (t >= T || row >= R) continue;
+            const float4 v = st[tl * 64 + (j ^ ((tl >> 2) & 15))];
+            float* o = out + (int64_t)t * R + row;
+            if (vec_store && row + 3 < R) {
+                *reinterpret_cast<float4*>(o) = v;
+            } else {
+                o[0] = v.x;
+                if (row + 1 < R) o[1] = v.y;
+                if (row + 2 < R) o[2] = v.z;
+                if (row + 3 < R) o[3] = v.w;
             }
         }
     }
-}
-
-// Rows per wavefront (multiple of 4, <= rw_max).  The grid is ntile * ceil(R / (nw rw))
-// workgroups running two per CU; the model charges each round of 512 workgroups
-// rw units of entry work plus a fixed cost for staging the tile, and picks the minimum.
-int pick_rows_per_wave(int T, int R, int nw, int rw_max, double stage_cost) {
-    const int64_t ntile = cdiv(T, TT);
-    int best = 4;
-    double best_cost = 1e300;
-    for (int rw = 4; rw <= rw_max; rw += 4) {
-        const int64_t items = ntile * cdiv(R, nw * rw);
-        const double rounds = (double)cdiv(items, 512);
-        const double cost = rounds * (rw + stage_cost);
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = rw; }
-    }
-    return best;
 }
 
 template <typename TIn>
-static int launch_spmm(const View& v, const TIn* A, float* out, int T, int64_t nnz, hipStream_t s) {
+static int launch_spmm(const View& v, const TIn* A, float* out, int T, hipStream_t s) {
     const int ntile = (int)cdiv(T, TT);
+    const int nw = pick_waves(T, v.NB);
+    const int nslab = (int)cdiv(v.NB, nw);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int vec_store = (v.R % 4 == 0) ? 1 : 0;
-    const Ent4* e4 = reinterpret_cast<const Ent4*>(v.ent);
-    const double per_seg = (double)nnz / ((double)v.R * v.nchunk);      // entries per (row, chunk)
-    if (per_seg >= 4.0) {
-        const int rw = pick_rows_per_wave(T, v.R, 16, 12, 3.0);
-        const int nslab = (int)cdiv(v.R, 16 * rw);
-        k_spmm<16, 12, 2, TIn><<<grid_for(ntile, nslab), 1024, 0, s>>>(A, v.ptr, e4, out, T, v.K, v.R, v.Rpad,
-                                                                      v.nchunk, nslab, ntile, rw, vec_ok, vec_store);
-    } else {
-        const int rw = pick_rows_per_wave(T, v.R, 8, 32, 6.0);
-        const int nslab = (int)cdiv(v.R, 8 * rw);
-        k_spmm<8, 32, 1, TIn><<<grid_for(ntile, nslab), 512, 0, s>>>(A, v.ptr, e4, out, T, v.K, v.R, v.Rpad,
-                                                                    v.nchunk, nslab, ntile, rw, vec_ok, vec_store);
-    }
+    k_spmm<TIn><<<grid_for(ntile, nslab), nw * 64, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
+                                                          nslab, ntile, vec_ok, vec_store);
     MST_LAUNCH_CHECK();
     return MST_OK;
 }
 
 int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype act, hipStream_t s) {
-    if (act == MST_F32) return launch_spmm<float>(v, static_cast<const float*>(A), out, T, nnz, s);
-    return launch_spmm<uint16_t>(v, static_cast<const uint16_t*>(A), out, T, nnz, s);
+    (void)nnz;
+    if (act == MST_F32) return launch_spmm<float>(v, static_cast<const float*>(A), out, T, s);
+    return launch_spmm<uint16_t>(v, static_cast<const uint16_t*>(A), out, T, s);
 }
 
 }  // namespace mst
