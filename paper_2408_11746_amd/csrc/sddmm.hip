@@ -48,17 +48,17 @@ __device__ inline float load_act<uint16_t>(const uint16_t* p) { return bf16_to_f
         RES = row_sum_to_last(d_);                                                   \
     } while (0)
 
-template <typename TIn>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8)))
+template <typename TIn, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2)))
 void k_sddmm(const TIn* __restrict__ X, const TIn* __restrict__ dY, const int* __restrict__ ptr,
              const uint4* __restrict__ ent, float* __restrict__ partial, int64_t slots_stride, int T, int K,
              int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok) {
     __shared__ float tile[KC * TT];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
-    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int tid = threadIdx.x;
+    constexpr int nthreads = NW * 64, nw = NW;
     const int lane = tid & 63;
-    const int nw = nthreads >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
     const int blk = slab * nw + wave;
@@ -87,7 +87,7 @@ void k_sddmm(const TIn* __restrict__ X, const TIn* __restrict__ dY, const int* _
     int pv = ptr[pl];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
-        load_tile<TIn>(tile, X, K, t0, c * KC, T, K, vec_ok != 0, tid, nthreads);
+        load_tile<TIn, NW * 64>(tile, X, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
         uint4 cur = entl[(int64_t)p * 4];
@@ -130,8 +130,12 @@ static int launch_sddmm(const mst_layer* L, const TIn* dY, const TIn* X, float* 
     const int nslab = (int)cdiv(v.NB, nw);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int64_t stride = v.cap_pairs * 8;
-    k_sddmm<TIn><<<grid_for(ntile, nslab), nw * 64, 0, s>>>(X, dY, v.ptr, v.ent, ws.partial, stride, T, v.K, v.R,
-                                                           v.NBpad, v.nchunk, nslab, ntile, vec_ok);
+    if (nw == 16)
+        k_sddmm<TIn, 16><<<grid_for(ntile, nslab), 1024, 0, s>>>(X, dY, v.ptr, v.ent, ws.partial, stride, T, v.K, v.R,
+                                                                v.NBpad, v.nchunk, nslab, ntile, vec_ok);
+    else
+        k_sddmm<TIn, 8><<<grid_for(ntile, nslab), 512, 0, s>>>(X, dY, v.ptr, v.ent, ws.partial, stride, T, v.K, v.R,
+                                                              v.NBpad, v.nchunk, nslab, ntile, vec_ok);
     MST_LAUNCH_CHECK();
     const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
     k_sddmm_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, stride, ntile, v.ptr, v.nseg, v.perm, dW);

@@ -28,17 +28,17 @@ namespace mst {
         ACC[6] = fmaf(w_, xb.z, ACC[6]); ACC[7] = fmaf(w_, xb.w, ACC[7]);            \
     } while (0)
 
-template <typename TIn>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_spmm(const TIn* __restrict__ A, const int* __restrict__ ptr,
+template <typename TIn, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2))) void k_spmm(const TIn* __restrict__ A, const int* __restrict__ ptr,
                                                   const uint4* __restrict__ ent, float* __restrict__ out,
                                                   int T, int K, int R, int NBpad, int nchunk, int nslab,
                                                   int ntile, int vec_ok, int vec_store) {
     __shared__ float tile[KC * TT];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
-    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int tid = threadIdx.x;
+    constexpr int nthreads = NW * 64, nw = NW;
     const int lane = tid & 63;
-    const int nw = nthreads >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
     const int blk = slab * nw + wave;                 // this wavefront's row block
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     int pv = ptr[pl];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
-        load_tile<TIn>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid, nthreads);
+        load_tile<TIn, NW * 64>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
         uint4 cur = entl[(int64_t)p * 4];
@@ -119,8 +119,12 @@ static int launch_spmm(const View& v, const TIn* A, float* out, int T, hipStream
     const int nslab = (int)cdiv(v.NB, nw);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int vec_store = (v.R % 4 == 0) ? 1 : 0;
-    k_spmm<TIn><<<grid_for(ntile, nslab), nw * 64, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
-                                                          nslab, ntile, vec_ok, vec_store);
+    if (nw == 16)
+        k_spmm<TIn, 16><<<grid_for(ntile, nslab), 1024, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
+                                                               nslab, ntile, vec_ok, vec_store);
+    else
+        k_spmm<TIn, 8><<<grid_for(ntile, nslab), 512, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
+                                                             nslab, ntile, vec_ok, vec_store);
     MST_LAUNCH_CHECK();
     return MST_OK;
 }

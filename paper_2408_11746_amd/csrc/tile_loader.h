@@ -49,27 +49,34 @@ __device__ inline float4 load_quad<uint16_t>(const uint16_t* __restrict__ A, int
 
 // All threads of the workgroup fill tile[KC][TT] from A[t0 .. t0+TT) x [k0 .. k0+KC).
 // Work item = (token quad tq, index quad kq): four 16-byte row reads (consecutive lanes
-// read consecutive 16 bytes of a row), a 4x4 transpose in registers, four 16-byte LDS
-// stores.  1024 items per tile.
-template <typename TIn>
+// read consecutive 16 bytes of a row), transposed in registers two token rows at a time,
+// eight 8-byte LDS stores.  1024 items per tile.
+template <typename TIn, int NTHREADS>
 __device__ inline void load_tile(float* tile, const TIn* __restrict__ A, int64_t lda, int t0, int k0, int T,
-                                 int K, bool vec_ok, int tid, int nthreads) {
+                                 int K, bool vec_ok, int tid) {
+    constexpr int ITEMS = (TT / 4) * (KC / 4);
+    static_assert(ITEMS % NTHREADS == 0, "tile loader needs a thread count that divides 1024");
     char* base = reinterpret_cast<char*>(tile);
-    for (int item = tid; item < (TT / 4) * (KC / 4); item += nthreads) {
+#pragma unroll
+    for (int it = 0; it < ITEMS / NTHREADS; ++it) {
+        const int item = it * NTHREADS + tid;
         const int kq = item & (KC / 4 - 1);
         const int tq = item / (KC / 4);
         const int row = t0 + 4 * tq, k = k0 + 4 * kq;
-        const float4 a = load_quad<TIn>(A, lda, row + 0, k, T, K, vec_ok);
-        const float4 b = load_quad<TIn>(A, lda, row + 1, k, T, K, vec_ok);
-        const float4 c = load_quad<TIn>(A, lda, row + 2, k, T, K, vec_ok);
-        const float4 d = load_quad<TIn>(A, lda, row + 3, k, T, K, vec_ok);
         // rows 4kq .. 4kq+3 share the swizzle kq & 15
         const uint32_t slot = ((uint32_t)(tq >> 4) << 8) | ((uint32_t)((tq & 15) ^ (kq & 15)) << 4);
         const uint32_t kl = 4u * kq;
-        *reinterpret_cast<float4*>(base + (((kl + 0) << 9) | slot)) = make_float4(a.x, b.x, c.x, d.x);
-        *reinterpret_cast<float4*>(base + (((kl + 1) << 9) | slot)) = make_float4(a.y, b.y, c.y, d.y);
-        *reinterpret_cast<float4*>(base + (((kl + 2) << 9) | slot)) = make_float4(a.z, b.z, c.z, d.z);
-        *reinterpret_cast<float4*>(base + (((kl + 3) << 9) | slot)) = make_float4(a.w, b.w, c.w, d.w);
+        // two token rows at a time (8 live registers): 8-byte halves of the 16-byte slot
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float4 a = load_quad<TIn>(A, lda, row + 2 * h, k, T, K, vec_ok);
+            const float4 b = load_quad<TIn>(A, lda, row + 2 * h + 1, k, T, K, vec_ok);
+            const uint32_t sl = slot | (uint32_t)(h << 3);
+            *reinterpret_cast<float2*>(base + (((kl + 0) << 9) | sl)) = make_float2(a.x, b.x);
+            *reinterpret_cast<float2*>(base + (((kl + 1) << 9) | sl)) = make_float2(a.y, b.y);
+            *reinterpret_cast<float2*>(base + (((kl + 2) << 9) | sl)) = make_float2(a.z, b.z);
+            *reinterpret_cast<float2*>(base + (((kl + 3) << 9) | sl)) = make_float2(a.w, b.w);
+        }
     }
 }
 
@@ -89,18 +96,11 @@ __device__ inline bool block_to_tile(int nslab, int ntile, int& tile, int& slab)
 inline unsigned grid_for(int ntile, int nslab) { return (unsigned)(cdiv(ntile, 8) * 8 * nslab); }
 
 // Wavefronts per workgroup (each owns one row block of 16 rows; two workgroups share a
-// CU).  Picks the count whose grid wastes the least of its last round of 512 workgroups,
-// preferring wide slabs (fewer re-reads of the activation tile) on ties.
+// CU).  Sixteen (32 wavefronts per CU, fewest re-reads of the activation tile) unless that
+// grid could not give every CU a workgroup; then eight.
 inline int pick_waves(int T, int NB) {
     const int64_t ntile = cdiv(T, TT);
-    int best = 16;
-    double best_cost = 1e300;
-    for (int nw : {16, 12, 8}) {
-        const int64_t items = ntile * cdiv(NB, nw);
-        const double cost = (double)cdiv(items, 512) * (nw + 3.0);
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = nw; }
-    }
-    return best;
+    return (ntile * cdiv(NB, 16) >= 256) ? 16 : 8;
 }
 
 }  // namespace mst
