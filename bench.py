@@ -35,6 +35,8 @@ def parse():
     p.add_argument("--update-interval", type=int, default=100, help="Delta_t; 0 = never update")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--seed", type=int, default=2024)
+    p.add_argument("--pmc-probe", action="store_true",
+                   help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration), then each product twice")
     return p.parse_args()
 
 
@@ -98,6 +100,21 @@ def main():
               for lid, (name, I, O) in enumerate(cfg["layers"])]
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream()
+
+    if args.pmc_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                      # 1 GiB read + 1 GiB written per launch
+        for L in layers:
+            for _ in range(2):
+                mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
+                mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
+                mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "copy_bytes_each_way": 1 << 30,
+                          "layers": {L.name: dict(I=L.I, O=L.O, nnz=L.nnz) for L in layers}}))
+        return
 
     kinds = ("fwd", "bwd_input", "bwd_weight", "mask_update")
     ev = {(L.name, k): [] for L in layers for k in kinds}
@@ -179,7 +196,11 @@ def main():
     else:
         roof = dict(bound="alu", achieved=drow["eff_tflops"], peak=ALU_FP32_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=round(drow["eff_tflops"] / ALU_FP32_PEAK_TFLOPS, 4))
-    roof.update(traffic=None, kernel=kernel, call="%s/%s" % (dL.name, drow["call"]),
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % args.config.lower())
+    if os.path.exists(tpath):        # counter-based HBM bytes of this call, measured by the commands in profiles/
+        traffic = json.load(open(tpath)).get("calls", {}).get("%s/%s" % (dL.name, drow["call"]))
+    roof.update(traffic=traffic, kernel=kernel, call="%s/%s" % (dL.name, drow["call"]),
                 avg_launch_ms=drow["avg_ms"], alg_bytes_per_launch=drow["alg_bytes"],
                 alg_flops_per_launch=drow["alg_flops"], hbm_frac=drow["hbm_frac"], alu_frac=drow["alu_frac"])
 
