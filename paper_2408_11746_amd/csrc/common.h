@@ -16,7 +16,7 @@ constexpr int KC = 128;          // contraction indices per chunk
 constexpr int TT = 128;          // tokens per LDS tile
 constexpr int RB = 16;           // rows per row block: 4 lane groups x 4 quads
 constexpr int MAX_WG_BLOCKS = 16;   // most row blocks one workgroup may own
-constexpr int PAIR_TAIL = 4;     // readable step pairs past the last one (prefetch overrun)
+constexpr int PAIR_TAIL = 16;    // readable step pairs past the last one (a whole entry batch may be fetched there)
 
 // LDS tile layout: row k (one contraction index) holds TT tokens = 512 bytes as 32
 // 16-byte slots of four consecutive tokens; slot u of tokens 4u..4u+3 sits at byte

@@ -5,7 +5,8 @@
 // Same decomposition and lane mapping as the SpMM: a workgroup owns TT = 128 tokens and
 // 16 rows of the row view per wavefront, stages chunks of X in LDS and walks the ELL
 // slices.  A lane keeps dY of its 8 tokens for the 4 rows of its lane group in
-// registers; per step it reads its 8 X values of the entry's column from LDS, forms the
+// registers; entries reach the lanes through the same per-wavefront LDS buffer as in
+// the SpMM; per step a lane reads its 8 X values of the entry's column from LDS, forms the
 // 8-term dot product and the 16 lanes of the group add their parts with four DPP row
 // shifts -- all four lane groups (four entries) at once, no LDS traffic.  Lane 15 of
 // each group stores the per-(token tile, entry slot) partial sums; a second kernel adds
@@ -48,16 +49,20 @@ __device__ inline float load_act<uint16_t>(const uint16_t* p) { return bf16_to_f
         RES = row_sum_to_last(d_);                                                   \
     } while (0)
 
+template <int NW> struct EntryBatchS { static constexpr int BP = (NW == 16) ? 12 : 16; };
+
 template <typename TIn, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2)))
 void k_sddmm(const TIn* __restrict__ X, const TIn* __restrict__ dY, const int* __restrict__ ptr,
              const uint4* __restrict__ ent, float* __restrict__ partial, int64_t slots_stride, int T, int K,
              int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok) {
+    constexpr int BP = EntryBatchS<NW>::BP;
     __shared__ float tile[KC * TT];
+    __shared__ uint4 ebuf[NW][BP * 4];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
     const int tid = threadIdx.x;
-    constexpr int nthreads = NW * 64, nw = NW;
+    constexpr int nw = NW;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
@@ -65,7 +70,8 @@ void k_sddmm(const TIn* __restrict__ X, const TIn* __restrict__ dY, const int* _
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
-    const uint4* entl = ent + g;
+    uint4* eb = ebuf[wave];
+    const int ll = min(lane, BP * 4 - 1);
     // partial sums of this token tile, viewed as float2[] indexed by pair * 4 + g
     float2* pt = reinterpret_cast<float2*>(partial + (int64_t)tile_id * slots_stride);
 
@@ -90,18 +96,28 @@ void k_sddmm(const TIn* __restrict__ X, const TIn* __restrict__ dY, const int* _
         load_tile<TIn, NW * 64>(tile, X, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
-        uint4 cur = entl[(int64_t)p * 4];
+        const int ptot = __builtin_amdgcn_readlane(pv, 4);
+        uint4 stage = ent[(int64_t)p * 4 + ll];
+        int bend = p;
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int pend = __builtin_amdgcn_readlane(pv, q + 1);
-            for (; p < pend; ++p) {
-                const uint4 nxt = entl[(int64_t)(p + 1) * 4];
-                float r0, r1;
-                MST_DOT(cur.x, dy[q], r0);
-                MST_DOT(cur.z, dy[q], r1);
-                if (s == 15) pt[(int64_t)p * 4 + g] = make_float2(r0, r1);
-                cur = nxt;
+            while (p < pend) {
+                if (p == bend) {
+                    if (lane < BP * 4) eb[lane] = stage;
+                    bend = p + BP;
+                    if (bend < ptot) stage = ent[(int64_t)bend * 4 + ll];
+                }
+                const int lim = min(pend, bend);
+                const uint4* er = eb + (p - (bend - BP)) * 4 + g;
+                for (; p < lim; ++p, er += 4) {
+                    const uint4 cur = *er;
+                    float r0, r1;
+                    MST_DOT(cur.x, dy[q], r0);
+                    MST_DOT(cur.z, dy[q], r1);
+                    if (s == 15) pt[(int64_t)p * 4 + g] = make_float2(r0, r1);
+                }
             }
         }
         pv = pv_next;

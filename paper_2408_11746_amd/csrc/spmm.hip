@@ -6,11 +6,12 @@
 // contraction index in chunks of KC: the chunk of A is staged (transposed) in LDS, then
 // each wavefront walks its row block's ELL slices.  A wavefront is four lane groups of 16
 // lanes; in one step each lane group multiplies ONE entry (its own row of the quad)
-// with 128 tokens, 8 per lane: the entry {offset, weight} comes from one per-lane vector
-// load (the 16 lanes of a group read the same 16 bytes), the 8 activations from two
-// 16-byte LDS reads, then 8 FMAs into the accumulators of that row, which stay in
-// registers for the whole K loop.  Nothing in the inner loop needs the scalar unit or a
-// cross-lane operation.  The result tile leaves through LDS so that global stores are
+// with 128 tokens, 8 per lane: the entry {offset, weight} comes from a small
+// per-wavefront LDS buffer that the wavefront refills in batches with one coalesced
+// vector load (next batch in flight while the current one is consumed), the 8 activations
+// from two 16-byte LDS reads, then 8 FMAs into the accumulators of that row, which stay
+// in registers for the whole K loop.  Nothing in the inner loop touches global memory,
+// the scalar unit or another lane.  The result tile leaves through LDS so that global stores are
 // whole rows of the slab.
 #include "tile_loader.h"
 
@@ -28,12 +29,17 @@ namespace mst {
         ACC[6] = fmaf(w_, xb.z, ACC[6]); ACC[7] = fmaf(w_, xb.w, ACC[7]);            \
     } while (0)
 
+// pairs per refill of a wavefront's entry buffer (64 bytes each); 16 wavefronts x 12 pairs or
+// 8 x 16 keep two workgroups (tile + buffers) inside the 160 KB of LDS
+template <int NW> struct EntryBatch { static constexpr int BP = (NW == 16) ? 12 : 16; };
+
 template <typename TIn, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2))) void k_spmm(const TIn* __restrict__ A, const int* __restrict__ ptr,
-                                                  const uint4* __restrict__ ent, float* __restrict__ out,
-                                                  int T, int K, int R, int NBpad, int nchunk, int nslab,
-                                                  int ntile, int vec_ok, int vec_store) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2))) void k_spmm(
+    const TIn* __restrict__ A, const int* __restrict__ ptr, const uint4* __restrict__ ent, float* __restrict__ out,
+    int T, int K, int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_store) {
+    constexpr int BP = EntryBatch<NW>::BP;
     __shared__ float tile[KC * TT];
+    __shared__ uint4 ebuf[NW][BP * 4];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
     const int tid = threadIdx.x;
@@ -45,7 +51,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2,
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
-    const uint4* entl = ent + g;                      // this lane group's 16 bytes of every pair
+    uint4* eb = ebuf[wave];
+    const int ll = min(lane, BP * 4 - 1);             // this lane's 16 bytes of a batch
 
     float acc[4][8];
 #pragma unroll
@@ -61,16 +68,26 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2,
         load_tile<TIn, NW * 64>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
-        uint4 cur = entl[(int64_t)p * 4];
+        const int ptot = __builtin_amdgcn_readlane(pv, 4);   // end of this wavefront's pairs in the chunk
+        uint4 stage = ent[(int64_t)p * 4 + ll];               // first batch (reads past ptot stay in the tail)
+        int bend = p;                                         // end of the batch held in LDS
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int pend = __builtin_amdgcn_readlane(pv, q + 1);
-            for (; p < pend; ++p) {
-                const uint4 nxt = entl[(int64_t)(p + 1) * 4];      // next pair in flight
-                MST_STEP(cur.x, cur.y, acc[q]);
-                MST_STEP(cur.z, cur.w, acc[q]);
-                cur = nxt;
+            while (p < pend) {
+                if (p == bend) {       // refill: staged batch -> LDS, following batch -> registers
+                    if (lane < BP * 4) eb[lane] = stage;
+                    bend = p + BP;
+                    if (bend < ptot) stage = ent[(int64_t)bend * 4 + ll];
+                }
+                const int lim = min(pend, bend);
+                const uint4* er = eb + (p - (bend - BP)) * 4 + g;
+                for (; p < lim; ++p, er += 4) {
+                    const uint4 cur = *er;
+                    MST_STEP(cur.x, cur.y, acc[q]);
+                    MST_STEP(cur.z, cur.w, acc[q]);
+                }
             }
         }
         pv = pv_next;
