@@ -189,7 +189,8 @@ def main():
     _, drow, dL = dominant
     t_hbm = drow["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_alu = drow["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
-    kernel = {"fwd": "k_spmm", "bwd_input": "k_spmm", "bwd_weight": "k_sddmm"}[drow["call"]]
+    # fwd / bwd_input are one k_spmm launch; bwd_weight is k_sddmm followed by the small k_sddmm_reduce
+    kernel = {"fwd": "k_spmm", "bwd_input": "k_spmm", "bwd_weight": "k_sddmm+k_sddmm_reduce"}[drow["call"]]
     if t_hbm >= t_alu:
         roof = dict(bound="hbm", achieved=drow["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(drow["hbm_gbs"] / HBM_PEAK_GBS, 4))

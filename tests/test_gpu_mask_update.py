@@ -152,3 +152,36 @@ def test_fused_update_three_step_check(act):
     differ = int((Me != ref64["M"]).sum())
     print("positions differing from the oracle-score mask:", differ, "of", st["n_grow"], "grown")
     assert differ <= max(4, st["n_grow"] // 100)
+
+
+def test_schedule_sweep_chain_matches_oracle_and_switches_paths():
+    """Densities 1.0 -> 0.5 -> 0.1 -> 0.02 -> 0.1 -> 0.5, every transition produced by the
+    update itself (the large-model sweep at reduced width): masks stay bit-exact against the
+    oracle chain and the products stay within tolerance on the dense (MFMA) and sparse paths."""
+    T, I, O = 384, 320, 512
+    W = synth.normal(31, 1, (O, I), 0.02)
+    M = np.ones((O, I), np.uint8)
+    X, dY = synth.make_activations(31, 1, T, I, O)
+    G = opr.dense_grad(dY, X).astype(np.float32)
+    rig = Rig(W, M, T, cap=O * I)
+    Gd = dev(G)
+    Wc, Mc = W.copy(), M.copy()
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, Wc, Mc)) <= TOL            # dense start: MFMA path
+    for step, d in enumerate([0.5, 0.1, 0.02, 0.1, 0.5]):
+        st = mst.mst_mask_update_from_scores(rig.layer, Gd, d, 0.3, 0.25, 1000 + step, rig.ws)
+        ref = omg.update(Wc, Mc, G, d, 0.3, 0.25, 1000 + step)
+        torch.cuda.synchronize()
+        We, Me = rig.export()
+        np.testing.assert_array_equal(Me, ref["M"])
+        np.testing.assert_array_equal(We, ref["W"])
+        assert st["nnz_after"] == omg.target_count(O * I, d)
+        Wc, Mc = ref["W"], ref["M"]
+        # train the surviving and grown weights a little so later prunes see non-zero values
+        vals = rig.layer.values()
+        vals.add_(0.001 * (step + 1))
+        rig.layer.sync_values()
+        Wc = Wc.copy()
+        Wc[Mc != 0] += np.float32(0.001 * (step + 1))
+        assert rel_err(rig.fwd(X), opr.fc_fwd(X, Wc, Mc)) <= TOL
+        assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, Wc, Mc)) <= TOL
+        assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, Mc)) <= TOL
