@@ -1,4 +1,5 @@
-// Dense fp32-accumulating GEMM on the CDNA matrix cores (v_mfma_f32_32x32x2f32).
+// Dense fp32-accumulating GEMMs on the CDNA matrix cores: v_mfma_f32_32x32x2f32 for fp32
+// operands, v_mfma_f32_32x32x16_bf16 when both operands are bfloat16.
 //
 // Used where a dense contraction really is the work: the dense weight gradient
 // G = dY^T X that scores gradient-based growth (Algorithm 1, ArgTopK of |grad|; Sec. 2
@@ -159,6 +160,102 @@ __global__ __launch_bounds__(256) void k_gemm(const TA* __restrict__ A, int64_t 
             }
 }
 
+// ---- bf16 x bf16 -> fp32, both operands k-major (the dense gradient G = dY^T X with
+// bfloat16 activations).  v_mfma_f32_32x32x16_bf16 wants, per lane, 8 consecutive k of one
+// row; the k-major source is transposed on its way into LDS: a thread fetches an
+// [8 k x 2 m] patch with eight 4-byte loads (a wavefront reads 256 contiguous bytes per k),
+// interleaves the halves and stores two 16-byte rows [m][8 k].
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int BKH = 32;            // k per LDS tile
+constexpr int LDH = BKH + 8;       // row stride in bf16 elements (80 bytes: conflict-free 16-byte reads)
+
+__device__ inline void fetch_patch(const uint16_t* __restrict__ src, int64_t ld, int k0, int m0, int Kdim,
+                                   int Mdim, int tid, bool pair_ok, uint32_t (&d)[8]) {
+    const int mp = tid & 63, kg = tid >> 6;
+    const int m = m0 + 2 * mp;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const int k = k0 + 8 * kg + kk;
+        uint32_t v = 0;
+        if (k < Kdim && m < Mdim) {
+            const uint16_t* p = src + (int64_t)k * ld + m;
+            if (pair_ok && m + 1 < Mdim) v = *reinterpret_cast<const uint32_t*>(p);
+            else v = (uint32_t)p[0] | ((m + 1 < Mdim) ? ((uint32_t)p[1] << 16) : 0u);
+        }
+        d[kk] = v;
+    }
+}
+
+__device__ inline void stage_patch(uint16_t* lds, int tid, const uint32_t (&d)[8]) {
+    const int mp = tid & 63, kg = tid >> 6;
+    uint4 lo, hi;     // row m: low halves, row m+1: high halves, 8 consecutive k each
+    lo.x = (d[0] & 0xFFFFu) | (d[1] << 16); hi.x = (d[0] >> 16) | (d[1] & 0xFFFF0000u);
+    lo.y = (d[2] & 0xFFFFu) | (d[3] << 16); hi.y = (d[2] >> 16) | (d[3] & 0xFFFF0000u);
+    lo.z = (d[4] & 0xFFFFu) | (d[5] << 16); hi.z = (d[4] >> 16) | (d[5] & 0xFFFF0000u);
+    lo.w = (d[6] & 0xFFFFu) | (d[7] << 16); hi.w = (d[6] >> 16) | (d[7] & 0xFFFF0000u);
+    *reinterpret_cast<uint4*>(lds + (2 * mp) * LDH + 8 * kg) = lo;
+    *reinterpret_cast<uint4*>(lds + (2 * mp + 1) * LDH + 8 * kg) = hi;
+}
+
+__global__ __launch_bounds__(256) void k_gemm_tn_bf16(const uint16_t* __restrict__ A, int64_t lda,
+                                                      const uint16_t* __restrict__ B, int64_t ldb,
+                                                      float* __restrict__ C, int M, int N, int Kdim,
+                                                      int k_per_split, int64_t split_stride, int pair_a,
+                                                      int pair_b) {
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDH];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDH];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = min(Kdim, kbeg + k_per_split);
+    float* Cz = C + (int64_t)blockIdx.z * split_stride;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    uint32_t ra[8], rb[8];
+    fetch_patch(A, lda, kbeg, m0, kend, M, tid, pair_a != 0, ra);
+    fetch_patch(B, ldb, kbeg, n0, kend, N, tid, pair_b != 0, rb);
+    const int lk = lane >> 5, lm = lane & 31;
+    for (int k0 = kbeg; k0 < kend; k0 += BKH) {
+        __syncthreads();
+        stage_patch(As, tid, ra);
+        stage_patch(Bs, tid, rb);
+        __syncthreads();
+        if (k0 + BKH < kend) {
+            fetch_patch(A, lda, k0 + BKH, m0, kend, M, tid, pair_a != 0, ra);
+            fetch_patch(B, ldb, k0 + BKH, n0, kend, N, tid, pair_b != 0, rb);
+        }
+#pragma unroll
+        for (int ks = 0; ks < BKH; ks += 16) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(As + (wm + lm) * LDH + ks + 8 * lk);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(As + (wm + 32 + lm) * LDH + ks + 8 * lk);
+            const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(Bs + (wn + lm) * LDH + ks + 8 * lk);
+            const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(Bs + (wn + 32 + lm) * LDH + ks + 8 * lk);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                const int n = n0 + wn + j * 32 + lm;
+                if (m < M && n < N) Cz[(int64_t)m * N + n] = acc[i][j][v];
+            }
+}
+
 __global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, int nsplit,
                                 float* __restrict__ C, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -197,6 +294,32 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
     return MST_OK;
 }
 
+static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, int Kdim, float* split_ws,
+                          int64_t split_ws_floats, hipStream_t s) {
+    const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
+    const int64_t mn = (int64_t)M * N;
+    int nsplit = 1;
+    if (split_ws && (int64_t)gm * gn < 384) {
+        nsplit = (int)cdiv(512, (int64_t)gm * gn);
+        nsplit = (int)std::min<int64_t>(nsplit, std::min<int64_t>(16, Kdim / 512));
+        nsplit = (int)std::min<int64_t>(nsplit, split_ws_floats / mn);
+        if (nsplit < 1) nsplit = 1;
+    }
+    int kps = (int)(cdiv(cdiv(Kdim, nsplit), BKH) * BKH);
+    nsplit = (int)cdiv(Kdim, kps);
+    dim3 grid(gn, gm, nsplit);
+    float* dst = nsplit > 1 ? split_ws : C;
+    // 4-byte loads of element pairs need even leading dimensions (bases are 16-byte aligned)
+    k_gemm_tn_bf16<<<grid, 256, 0, s>>>((const uint16_t*)A, M, (const uint16_t*)B, N, dst, M, N, Kdim, kps, mn,
+                                        (M % 2 == 0) ? 1 : 0, (N % 2 == 0) ? 1 : 0);
+    MST_LAUNCH_CHECK();
+    if (nsplit > 1) {
+        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
+        MST_LAUNCH_CHECK();
+    }
+    return MST_OK;
+}
+
 // TN: C[M x N] = A^T B, A [K x M], B [K x N]          (G = dY^T X)
 // NT: C[M x N] = A B^T, A [M x K], B [N x K] (fp32)   (Y = X Wd^T)
 // NN: C[M x N] = A B,   A [M x K], B [K x N] (fp32)   (dX = dY Wd)
@@ -206,7 +329,7 @@ int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_d
     switch (kind) {
         case GEMM_TN:
             if (ab != bb) return MST_ERR_ARG;
-            if (ab) return launch<uint16_t, true, uint16_t, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
+            if (ab) return launch_tn_bf16(A, B, C, M, N, Kdim, split_ws, split_ws_floats, s);
             return launch<float, true, float, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
         case GEMM_NT:
             if (bb) return MST_ERR_ARG;
