@@ -90,7 +90,8 @@ Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
     w.sel_state = (uint64_t*)take((size_t)SEL_STATE_WORDS * 8);
     w.gemm_floats = (size_t)GEMM_WS_SPLITS * (size_t)N;
     w.gemm = (float*)take(w.gemm_floats * 4);
-    w.partial_floats = (size_t)ntile * (size_t)view_pair_capacity(cap, nchunks(I), O) * 8;
+    w.partial_floats = (size_t)ntile * 8 *
+                       (size_t)std::max(view_pair_capacity(cap, nchunks(I), O), view_pair_capacity(cap, nchunks(O), I));
     w.partial = (float*)take(w.partial_floats * 4);
     w.total = off;
     return w;

@@ -53,7 +53,8 @@ template <int NW> struct EntryBatchS { static constexpr int BP = (NW == 16) ? 12
 
 template <typename TIn, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2)))
-void k_sddmm(const TIn* __restrict__ X, const TIn* __restrict__ dY, const int* __restrict__ ptr,
+void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* __restrict__ dY /* register operand [T x R] */,
+             const int* __restrict__ ptr,
              const uint4* __restrict__ ent, float* __restrict__ partial, int64_t slots_stride, int T, int K,
              int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok) {
     constexpr int BP = EntryBatchS<NW>::BP;
@@ -137,21 +138,27 @@ __global__ void k_sddmm_reduce(const float* __restrict__ partial, int64_t slots_
     dW[p] = sum;
 }
 
+// The product is symmetric in its two dense operands: either view can drive it.  The view
+// with more rows is used (more workgroups, fewer chunks): the row view stages X and keeps
+// dY in registers, the col view stages dY and keeps X in registers.
 template <typename TIn>
 static int launch_sddmm(const mst_layer* L, const TIn* dY, const TIn* X, float* dW, int T,
                         const Workspace& ws, hipStream_t s) {
-    const View& v = L->row;
+    const bool use_col = L->I > L->O;
+    const View& v = use_col ? L->col : L->row;
+    const TIn* staged = use_col ? dY : X;
+    const TIn* inreg = use_col ? X : dY;
     const int ntile = (int)cdiv(T, TT);
     const int nw = pick_waves(T, v.NB);
     const int nslab = (int)cdiv(v.NB, nw);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int64_t stride = v.cap_pairs * 8;
     if (nw == 16)
-        k_sddmm<TIn, 16><<<grid_for(ntile, nslab), 1024, 0, s>>>(X, dY, v.ptr, v.ent, ws.partial, stride, T, v.K, v.R,
-                                                                v.NBpad, v.nchunk, nslab, ntile, vec_ok);
+        k_sddmm<TIn, 16><<<grid_for(ntile, nslab), 1024, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
+                                                                v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
     else
-        k_sddmm<TIn, 8><<<grid_for(ntile, nslab), 512, 0, s>>>(X, dY, v.ptr, v.ent, ws.partial, stride, T, v.K, v.R,
-                                                              v.NBpad, v.nchunk, nslab, ntile, vec_ok);
+        k_sddmm<TIn, 8><<<grid_for(ntile, nslab), 512, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
+                                                              v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
     MST_LAUNCH_CHECK();
     const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
     k_sddmm_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, stride, ntile, v.ptr, v.nseg, v.perm, dW);
