@@ -49,15 +49,16 @@ __device__ inline float load_act<uint16_t>(const uint16_t* p) { return bf16_to_f
         RES = row_sum_to_last(d_);                                                   \
     } while (0)
 
-template <int NW> struct EntryBatchS { static constexpr int BP = (NW == 16) ? 12 : 16; };
+constexpr int BP = 12;      // pairs per refill of a wavefront's entry buffer
+constexpr int NW = 16;      // wavefronts per workgroup
 
-template <typename TIn, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2)))
+// QW = quads per wavefront (4: a whole row block, 2: half of one), as in the SpMM
+template <typename TIn, int QW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* __restrict__ dY /* register operand [T x R] */,
              const int* __restrict__ ptr,
              const uint4* __restrict__ ent, float* __restrict__ partial, int64_t slots_stride, int T, int K,
              int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok) {
-    constexpr int BP = EntryBatchS<NW>::BP;
     __shared__ float tile[KC * TT];
     __shared__ uint4 ebuf[NW][BP * 4];
     int tile_id, slab;
@@ -67,7 +68,9 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
-    const int blk = slab * nw + wave;
+    constexpr int WPB = 4 / QW;
+    const int blk = (slab * nw + wave) / WPB;
+    const int q0 = (wave % WPB) * QW;
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
@@ -76,33 +79,33 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
     // partial sums of this token tile, viewed as float2[] indexed by pair * 4 + g
     float2* pt = reinterpret_cast<float2*>(partial + (int64_t)tile_id * slots_stride);
 
-    // dY of this lane's 8 tokens for rows 16 blk + 4 g + q
-    float dy[4][8];
-    const int rbase = blk * RB + g * 4;
+    // dY of this lane's 8 tokens for rows 16 blk + 4 g + q0 + q
+    float dy[QW][8];
+    const int rbase = blk * RB + g * 4 + q0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int t = t0 + lane_token(s, e);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < QW; ++q) {
             float v = 0.f;
             if (t < T && rbase + q < R) v = load_act<TIn>(dY + (int64_t)t * R + rbase + q);
             dy[q][e] = v;
         }
     }
 
-    const int pl = blk * 4 + min(lane, 4);
+    const int pl = blk * 4 + q0 + min(lane, QW);
     int pv = ptr[pl];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
         load_tile<TIn, NW * 64>(tile, X, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
-        const int ptot = __builtin_amdgcn_readlane(pv, 4);
+        const int ptot = __builtin_amdgcn_readlane(pv, QW);
         uint4 stage = ent[(int64_t)p * 4 + ll];
         int bend = p;
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < QW; ++q) {
             const int pend = __builtin_amdgcn_readlane(pv, q + 1);
             while (p < pend) {
                 if (p == bend) {
@@ -149,16 +152,16 @@ static int launch_sddmm(const mst_layer* L, const TIn* dY, const TIn* X, float* 
     const TIn* staged = use_col ? dY : X;
     const TIn* inreg = use_col ? X : dY;
     const int ntile = (int)cdiv(T, TT);
-    const int nw = pick_waves(T, v.NB);
-    const int nslab = (int)cdiv(v.NB, nw);
+    const int qw = pick_quads(T, v.NB);
+    const int nslab = (int)cdiv(v.NB, NW * qw / 4);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int64_t stride = v.cap_pairs * 8;
-    if (nw == 16)
-        k_sddmm<TIn, 16><<<grid_for(ntile, nslab), 1024, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
-                                                                v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
+    if (qw == 4)
+        k_sddmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
+                                                                  v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
     else
-        k_sddmm<TIn, 8><<<grid_for(ntile, nslab), 512, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
-                                                              v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
+        k_sddmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
+                                                                  v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
     MST_LAUNCH_CHECK();
     const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
     k_sddmm_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, stride, ntile, v.ptr, v.nseg, v.perm, dW);

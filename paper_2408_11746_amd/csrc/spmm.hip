@@ -29,15 +29,18 @@ namespace mst {
         ACC[6] = fmaf(w_, xb.z, ACC[6]); ACC[7] = fmaf(w_, xb.w, ACC[7]);            \
     } while (0)
 
-// pairs per refill of a wavefront's entry buffer (64 bytes each); 16 wavefronts x 12 pairs or
-// 8 x 16 keep two workgroups (tile + buffers) inside the 160 KB of LDS
-template <int NW> struct EntryBatch { static constexpr int BP = (NW == 16) ? 12 : 16; };
+// pairs per refill of a wavefront's entry buffer (64 bytes each): 16 wavefronts x 12 pairs
+// keep two workgroups (tile + buffers) inside the 160 KB of LDS
+constexpr int BP = 12;
+constexpr int NW = 16;
 
-template <typename TIn, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2, NW / 2))) void k_spmm(
+// QW = quads per wavefront: 4 (a wavefront owns a whole row block of 16 rows) or 2 (two
+// wavefronts share a block, 8 rows each) -- the latter doubles the number of wavefronts
+// when the output is too narrow to give every CU two full workgroups.
+template <typename TIn, int QW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_spmm(
     const TIn* __restrict__ A, const int* __restrict__ ptr, const uint4* __restrict__ ent, float* __restrict__ out,
     int T, int K, int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_store) {
-    constexpr int BP = EntryBatch<NW>::BP;
     __shared__ float tile[KC * TT];
     __shared__ uint4 ebuf[NW][BP * 4];
     int tile_id, slab;
@@ -47,33 +50,35 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2,
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
-    const int blk = slab * nw + wave;                 // this wavefront's row block
+    constexpr int WPB = 4 / QW;                        // wavefronts per row block
+    const int blk = (slab * nw + wave) / WPB;         // this wavefront's row block
+    const int q0 = (wave % WPB) * QW;                 // its first quad
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
     uint4* eb = ebuf[wave];
     const int ll = min(lane, BP * 4 - 1);             // this lane's 16 bytes of a batch
 
-    float acc[4][8];
+    float acc[QW][8];
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < QW; ++q)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
 
-    // lane q (0..4) keeps the first pair of quad q of the current chunk
-    const int pl = blk * 4 + min(lane, 4);
+    // lane q (0..QW) keeps the first pair of this wavefront's quad q of the current chunk
+    const int pl = blk * 4 + q0 + min(lane, QW);
     int pv = ptr[pl];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
         load_tile<TIn, NW * 64>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
-        const int ptot = __builtin_amdgcn_readlane(pv, 4);   // end of this wavefront's pairs in the chunk
+        const int ptot = __builtin_amdgcn_readlane(pv, QW);  // end of this wavefront's pairs in the chunk
         uint4 stage = ent[(int64_t)p * 4 + ll];               // first batch (reads past ptot stay in the tail)
         int bend = p;                                         // end of the batch held in LDS
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < QW; ++q) {
             const int pend = __builtin_amdgcn_readlane(pv, q + 1);
             while (p < pend) {
                 if (p == bend) {       // refill: staged batch -> LDS, following batch -> registers
@@ -93,29 +98,31 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2,
         pv = pv_next;
     }
 
-    // ---- epilogue: through LDS, 64 tokens at a time, so that each token's nw*16 outputs
-    // leave as one contiguous run.  Staging layout: token tl (0..63) owns 1 KB; the
-    // 16-byte chunk j (rows 4j..4j+3 of the slab) sits at slot j ^ ((tl >> 2) & 15).
-    const int row0 = slab * nw * RB;                  // first row of the slab
-    const int chunk = wave * 4 + g;                   // this lane's 16-byte chunk of a token row
-    float4* st = reinterpret_cast<float4*>(tile);
+    // ---- epilogue: through LDS, 64 tokens at a time, so that each token's outputs of the
+    // whole slab leave as one contiguous run.  Staging layout: token tl (0..63) owns 1 KB;
+    // the 16-byte chunk j (rows 4j..4j+3 of the slab) sits at slot j ^ ((tl >> 2) & 15).
+    constexpr int SLAB_ROWS = NW * QW * 4;
+    const int row0 = slab * SLAB_ROWS;                // first row of the slab
+    const int chunk = ((wave / WPB) * 4 + g);         // this lane's 16-byte chunk of a token row
+    float* stf = tile;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         __syncthreads();                              // tile / previous half no longer read
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int tl = 4 * s + e;
-            st[tl * 64 + (chunk ^ s)] = make_float4(acc[0][4 * h + e], acc[1][4 * h + e], acc[2][4 * h + e],
-                                                    acc[3][4 * h + e]);
+            float* dst = stf + (tl * 64 + (chunk ^ s)) * 4 + q0;
+#pragma unroll
+            for (int q = 0; q < QW; ++q) dst[q] = acc[q][4 * h + e];
         }
         __syncthreads();
-        const int nchunks16 = nw * 4;                 // 16-byte chunks per token row of the slab
-        for (int item = tid; item < 64 * nchunks16; item += nthreads) {
-            const int tl = item / nchunks16, j = item % nchunks16;
+        constexpr int NCH = SLAB_ROWS / 4;            // 16-byte chunks per token row of the slab
+        for (int item = tid; item < 64 * NCH; item += nthreads) {
+            const int tl = item / NCH, j = item % NCH;
             const int t = t0 + 64 * h + tl;
             const int row = row0 + 4 * j;
             if (t >= T || row >= R) continue;
-            const float4 v = st[tl * 64 + (j ^ ((tl >> 2) & 15))];
+            const float4 v = *reinterpret_cast<const float4*>(stf + (tl * 64 + (j ^ ((tl >> 2) & 15))) * 4);
             float* o = out + (int64_t)t * R + row;
             if (vec_store && row + 3 < R) {
                 *reinterpret_cast<float4*>(o) = v;
@@ -132,16 +139,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 2,
 template <typename TIn>
 static int launch_spmm(const View& v, const TIn* A, float* out, int T, hipStream_t s) {
     const int ntile = (int)cdiv(T, TT);
-    const int nw = pick_waves(T, v.NB);
-    const int nslab = (int)cdiv(v.NB, nw);
+    const int qw = pick_quads(T, v.NB);
+    const int nslab = (int)cdiv(v.NB, NW * qw / 4);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int vec_store = (v.R % 4 == 0) ? 1 : 0;
-    if (nw == 16)
-        k_spmm<TIn, 16><<<grid_for(ntile, nslab), 1024, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
-                                                               nslab, ntile, vec_ok, vec_store);
+    if (qw == 4)
+        k_spmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
+                                                                 nslab, ntile, vec_ok, vec_store);
     else
-        k_spmm<TIn, 8><<<grid_for(ntile, nslab), 512, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
-                                                             nslab, ntile, vec_ok, vec_store);
+        k_spmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
+                                                                 nslab, ntile, vec_ok, vec_store);
     MST_LAUNCH_CHECK();
     return MST_OK;
 }
