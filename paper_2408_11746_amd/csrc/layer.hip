@@ -128,7 +128,11 @@ __global__ void k_count_col(const uint8_t* __restrict__ mask, int O, int I, int 
     if (i >= I) return;
     const int o0 = c * KC, o1 = min(O, o0 + KC);
     int n = 0;
-    for (int o = o0; o < o1; ++o) n += mask[(size_t)o * I + i] != 0;
+    for (int ob = o0; ob < o1; ob += 16) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (ob + u < o1) n += mask[(size_t)(ob + u) * I + i] != 0;
+    }
     segcnt[(size_t)c * Rpad + i] = n;
 }
 
@@ -225,7 +229,8 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     }
 }
 
-// one thread per (column i, chunk c of rows): row i of the col view, chunk c
+// one thread per (column i, chunk c of rows): row i of the col view, chunk c.  The 128
+// mask bytes of the thread's column are fetched 16 at a time (independent loads in flight).
 __global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __restrict__ W,
                            int O, int I, int NBpad, const int* __restrict__ ptr, const int* __restrict__ cidx,
                            uint2* __restrict__ ent, int* __restrict__ perm) {
@@ -236,13 +241,19 @@ __global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __rest
     const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
     const int o0 = c * KC, o1 = min(O, o0 + KC);
     int j = 0;
-    for (int o = o0; o < o1; ++o) {
-        const size_t f = (size_t)o * I + i;
-        if (mask[f]) {
-            const int64_t e = entry_slot(pair0, g, j);
-            ent[e] = make_uint2(lds_off((uint32_t)(o - o0)), __float_as_uint(W[f]));
-            perm[e] = cidx[f];
-            ++j;
+    for (int ob = o0; ob < o1; ob += 16) {
+        uint8_t m[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) m[u] = (ob + u < o1) ? mask[(size_t)(ob + u) * I + i] : (uint8_t)0;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            if (m[u]) {
+                const size_t f = (size_t)(ob + u) * I + i;
+                const int64_t e = entry_slot(pair0, g, j);
+                ent[e] = make_uint2(lds_off((uint32_t)(ob + u - o0)), __float_as_uint(W[f]));
+                perm[e] = cidx[f];
+                ++j;
+            }
         }
     }
 }
@@ -294,13 +305,13 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     const int Rpad = v.NBpad * RB;
     int rc = fill_u32(ws.segcnt, 0u, (int64_t)v.nchunk * Rpad + 1, s);      // rows >= R count as empty
     if (rc != MST_OK) return rc;
-    dim3 gcol((unsigned)cdiv(I, 256), (unsigned)v.nchunk);
+    dim3 gcol((unsigned)cdiv(I, 64), (unsigned)v.nchunk);
     if (row_view) {
         k_count_row<<<O, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
         MST_LAUNCH_CHECK();
         if ((rc = scan_excl_i32(ws.rowcnt, L->rowptr, O, s)) != MST_OK) return rc;
     } else {
-        k_count_col<<<gcol, 256, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
+        k_count_col<<<gcol, 64, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
         MST_LAUNCH_CHECK();
     }
     k_quad_len<<<(unsigned)cdiv(v.nseg, 256), 256, 0, s>>>(ws.segcnt, v.nseg, ws.qlen);
@@ -313,7 +324,7 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
                                                         L->vals, L->flat, ws.cidx,
                                                         reinterpret_cast<uint2*>(v.ent), v.perm);
     } else {
-        k_fill_col<<<gcol, 256, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, ws.cidx,
+        k_fill_col<<<gcol, 64, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, ws.cidx,
                                         reinterpret_cast<uint2*>(v.ent), v.perm);
     }
     MST_LAUNCH_CHECK();

@@ -78,23 +78,32 @@ __global__ void k_select_hist(KS ks, int64_t n, uint64_t* __restrict__ state, in
 }
 
 // picks the digit that contains the k-th smallest key and clears the histogram
+// (256 threads: inclusive scan of the bins, the first bin whose running total reaches k)
 __global__ void k_select_pick(uint64_t* __restrict__ state, int shift) {
-    __shared__ uint32_t cum[256];
+    __shared__ uint32_t wsum[4];
+    __shared__ int pick_bin;
+    __shared__ uint32_t pick_before;
     uint32_t* hist = reinterpret_cast<uint32_t*>(state + 8);
-    const int t = threadIdx.x;
-    cum[t] = hist[t];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const uint32_t c = hist[t];
+    uint32_t x = c;
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    if (lane == 63) wsum[wave] = x;
+    if (t == 0) { pick_bin = 255; pick_before = 0; }
+    __syncthreads();
+    uint32_t incl = x;
+    for (int w = 0; w < wave; ++w) incl += wsum[w];
+    const uint64_t k = state[1];
+    // exactly one bin has (total before it) < k <= (total including it)
+    if ((uint64_t)(incl - c) < k && (uint64_t)incl >= k) { pick_bin = t; pick_before = incl - c; }
     __syncthreads();
     if (t == 0) {
-        uint64_t k = state[1], run = 0;
-        int b = 0;
-        for (; b < 255; ++b) {
-            if (run + cum[b] >= k) break;
-            run += cum[b];
-        }
-        state[0] |= (uint64_t)b << shift;
-        state[1] = k - run;
+        state[0] |= (uint64_t)pick_bin << shift;
+        state[1] = k - pick_before;
     }
-    __syncthreads();
     hist[t] = 0;
 }
 
