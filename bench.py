@@ -31,7 +31,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=100)
     p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    p.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     p.add_argument("--update-interval", type=int, default=100, help="Delta_t; 0 = never update")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--seed", type=int, default=2024)
@@ -95,6 +95,8 @@ def main():
     import synth
 
     cfg = synth.CONFIGS[args.config]
+    if args.config == "C5":
+        return sweep(args, cfg, mst, synth, torch)
     T, act, density = cfg["T"], cfg["act"], cfg["densities"][0]
     layers = [LayerRun(mst, synth, torch, args.seed, lid + 1, name, I, O, T, density, cfg["mask"], act)
               for lid, (name, I, O) in enumerate(cfg["layers"])]
@@ -224,6 +226,71 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, T)
+    print(json.dumps(out))
+
+
+def sweep(args, cfg, mst, synth, torch):
+    """Config C5: one GPT-2-large block (of 36 identical ones) swept through the densities
+    1.0, 0.5, 0.1, 0.02, 0.1, 0.5; every transition is produced by the fused mask update itself
+    and every step also runs one update at the current density (mask update every step)."""
+    import numpy as np
+    T = cfg["T"]
+    stream = torch.cuda.current_stream()
+    layers = []
+    for lid, (name, I, O) in enumerate(cfg["layers"]):
+        L = LayerRun.__new__(LayerRun)
+        L.name, L.I, L.O, L.T, L.act, L.act_bytes = name, I, O, T, mst.MST_F32, 4
+        W = synth.normal(args.seed, 1000 * (lid + 1) + 2, (O, I), 0.02)
+        M = np.ones((O, I), np.uint8)
+        X, dY = synth.make_activations(args.seed, lid + 1, T, I, O)
+        L.X, L.dY = torch.from_numpy(X).cuda(), torch.from_numpy(dY).cuda()
+        cap = O * I
+        L.layer = mst.Layer(O, I, cap, "cuda:0")
+        L.ws = torch.empty(mst.mst_workspace_bytes(O, I, cap, T), dtype=torch.uint8, device="cuda:0")
+        L.layer.load_dense(torch.from_numpy(W).cuda(), torch.from_numpy(M).cuda(), L.ws)
+        L.Y = torch.empty((T, O), dtype=torch.float32, device="cuda:0")
+        L.dX = torch.empty((T, I), dtype=torch.float32, device="cuda:0")
+        L.dW = torch.empty(cap, dtype=torch.float32, device="cuda:0")
+        layers.append(L)
+    torch.cuda.synchronize()
+    steps = max(1, args.steps // len(cfg["densities"]))
+    rows, tot_time, tot_flops, seed = [], 0.0, 0.0, args.seed * 7919
+
+    def one_step(d):
+        nonlocal seed
+        for L in layers:
+            mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
+            mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
+            mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+            seed += 1
+            mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, stream)
+
+    for d in cfg["densities"]:
+        for L in layers:                       # transition to this density (untimed)
+            seed += 1
+            mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, stream)
+        for _ in range(min(2, args.warmup)):
+            one_step(d)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one_step(d)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        flops = sum(6 * L.layer.nnz * T for L in layers)
+        rows.append(dict(density=d, ms_per_step=round(1e3 * dt, 4), eff_tflops=round(flops / dt / 1e12, 3),
+                         nnz={L.name: L.layer.nnz for L in layers},
+                         path="dense-mfma" if d > 0.30 else "sparse"))
+        tot_time += dt
+        tot_flops += flops
+    out = {"metric": METRIC, "value": round(tot_flops / tot_time / 1e12, 4), "unit": "TFLOP/s", "n_gpus": 1,
+           "steps": steps * len(cfg["densities"]), "warmup": args.warmup,
+           "ms_per_step": round(1e3 * tot_time / len(cfg["densities"]), 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "C5: one GPT-2-large block (1280/5120; 1 of 36 identical blocks), T=%d, densities %s "
+                                  "reached by the mask update itself, products + fused Mixed-Growing update every step"
+                                  % (T, cfg["densities"])},
+           "sweep": rows}
     print(json.dumps(out))
 
 

@@ -29,7 +29,10 @@ __host__ __device__ inline uint32_t lds_off(uint32_t k) {
 }
 
 // Sparse matrix S [R x K] as the product kernels walk it.  Rows are grouped in blocks of
-// RB = 16; row 16b + 4g + q belongs to lane group g and quad q of block b.  For every
+// RB = 16 consecutive rows.  Inside a block the rows are ranked by their total length
+// (longest first, lower index first on ties); the row of rank 4q + g belongs to quad q and
+// lane group g, so the four rows of a quad have similar lengths (little ELL padding even
+// when row lengths are very uneven).  rowmap[16b + rank] is that row.  For every
 // (chunk c of K, block b, quad q) the four rows' entries inside the chunk are stored side
 // by side, padded with zero-weight entries to the longest of the four and to an even
 // count (an ELL slice of height 4): step j of the quad holds one entry per lane group.
@@ -44,6 +47,8 @@ struct View {
     int* ptr = nullptr;    // [nseg + 1] first pair of segment (c*NBpad + b)*4 + q
     uint4* ent = nullptr;  // [cap_pairs * 4]
     int* perm = nullptr;   // [cap_pairs * 8] canonical index of entry slot (pair*4 + g)*2 + half, -1 = padding
+    int* rowmap = nullptr; // [NBpad * 16] rank inside the block -> row (identity in the empty blocks)
+    int* rowpos = nullptr; // [NBpad * 16] row -> rank inside its block
 };
 
 }  // namespace mst

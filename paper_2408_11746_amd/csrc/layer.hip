@@ -34,7 +34,7 @@ bool use_dense_path(const mst_layer* L) {
 
 struct LayerCarve {
     size_t mask, vals, flat, rowptr, Wd;
-    size_t rptr, rent, rperm, cptr, cent, cperm;
+    size_t rptr, rent, rperm, rmap, rpos, cptr, cent, cperm, cmap, cpos;
     size_t total;
 };
 
@@ -53,9 +53,13 @@ static LayerCarve carve_layer(int O, int I, int64_t cap) {
     c.rptr = take((size_t)(nseg_r + 1) * 4);
     c.rent = take((size_t)cp_r * 64);
     c.rperm = take((size_t)cp_r * 32);
+    c.rmap = take((size_t)nbpad(O) * RB * 4);
+    c.rpos = take((size_t)nbpad(O) * RB * 4);
     c.cptr = take((size_t)(nseg_c + 1) * 4);
     c.cent = take((size_t)cp_c * 64);
     c.cperm = take((size_t)cp_c * 32);
+    c.cmap = take((size_t)nbpad(I) * RB * 4);
+    c.cpos = take((size_t)nbpad(I) * RB * 4);
     c.total = off;
     return c;
 }
@@ -136,14 +140,42 @@ __global__ void k_count_col(const uint8_t* __restrict__ mask, int O, int I, int 
     segcnt[(size_t)c * Rpad + i] = n;
 }
 
+// one thread per row block: rank its 16 rows by total length over all chunks, longest
+// first, lower row first on ties (the empty padding blocks keep the identity)
+__global__ void k_block_rank(const int* __restrict__ segcnt, int nchunk, int Rpad, int NBpad,
+                             int* __restrict__ rowmap, int* __restrict__ rowpos) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= NBpad) return;
+    int len[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) len[j] = 0;
+    for (int c = 0; c < nchunk; ++c) {
+        const int* p = segcnt + (size_t)c * Rpad + b * RB;
+#pragma unroll
+        for (int j = 0; j < RB; ++j) len[j] += p[j];
+    }
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        int rank = 0;
+#pragma unroll
+        for (int u = 0; u < RB; ++u) rank += (len[u] > len[j]) || (len[u] == len[j] && u < j);
+        rowmap[b * RB + rank] = b * RB + j;
+        rowpos[b * RB + j] = rank;
+    }
+}
+
 // pairs of one quad segment: longest of its four rows, rounded up to even, halved
-__global__ void k_quad_len(const int* __restrict__ segcnt, int64_t nseg, int* __restrict__ qlen) {
+__global__ void k_quad_len(const int* __restrict__ segcnt, const int* __restrict__ rowmap, int Rpad, int NBpad,
+                           int64_t nseg, int* __restrict__ qlen) {
     const int64_t sidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (c*NBpad + b)*4 + q
     if (sidx >= nseg) return;
-    const int64_t cb = sidx >> 2;
     const int q = (int)(sidx & 3);
-    const int* p = segcnt + cb * RB + q;          // rows 16(c*NBpad + b) + 4g + q
-    const int L = max(max(p[0], p[4]), max(p[8], p[12]));
+    const int64_t cb = sidx >> 2;
+    const int b = (int)(cb % NBpad);
+    const int64_t c = cb / NBpad;
+    const int* cnt = segcnt + c * Rpad;
+    const int* rm = rowmap + b * RB + 4 * q;          // the quad's four rows (one per lane group)
+    const int L = max(max(cnt[rm[0]], cnt[rm[1]]), max(cnt[rm[2]], cnt[rm[3]]));
     qlen[sidx] = (L + 1) >> 1;
 }
 
@@ -195,12 +227,13 @@ __device__ inline int64_t entry_slot(int pair0, int g, int j) {
 __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __restrict__ W,
                            int O, int I, int nchunk, int NBpad,
                            const int* __restrict__ rowptr, const int* __restrict__ ptr,
+                           const int* __restrict__ rowpos,
                            float* __restrict__ vals, int* __restrict__ flat, int* __restrict__ cidx,
                            uint2* __restrict__ ent, int* __restrict__ perm) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (r >= O) return;
-    const int b = r / RB, g = (r % RB) >> 2, q = r & 3;
+    const int b = r / RB, rank = rowpos[r], g = rank & 3, q = rank >> 2;
     const uint8_t* m = mask + (size_t)r * I;
     const float* w = W + (size_t)r * I;
     int canon = rowptr[r];
@@ -232,12 +265,12 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
 // one thread per (column i, chunk c of rows): row i of the col view, chunk c.  The 128
 // mask bytes of the thread's column are fetched 16 at a time (independent loads in flight).
 __global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __restrict__ W,
-                           int O, int I, int NBpad, const int* __restrict__ ptr, const int* __restrict__ cidx,
-                           uint2* __restrict__ ent, int* __restrict__ perm) {
+                           int O, int I, int NBpad, const int* __restrict__ ptr, const int* __restrict__ rowpos,
+                           const int* __restrict__ cidx, uint2* __restrict__ ent, int* __restrict__ perm) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int c = blockIdx.y;
     if (i >= I) return;
-    const int b = i / RB, g = (i % RB) >> 2, q = i & 3;
+    const int b = i / RB, rank = rowpos[i], g = rank & 3, q = rank >> 2;
     const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
     const int o0 = c * KC, o1 = min(O, o0 + KC);
     int j = 0;
@@ -314,17 +347,19 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
         k_count_col<<<gcol, 64, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
         MST_LAUNCH_CHECK();
     }
-    k_quad_len<<<(unsigned)cdiv(v.nseg, 256), 256, 0, s>>>(ws.segcnt, v.nseg, ws.qlen);
+    k_block_rank<<<(unsigned)cdiv(v.NBpad, 64), 64, 0, s>>>(ws.segcnt, v.nchunk, Rpad, v.NBpad, v.rowmap, v.rowpos);
+    MST_LAUNCH_CHECK();
+    k_quad_len<<<(unsigned)cdiv(v.nseg, 256), 256, 0, s>>>(ws.segcnt, v.rowmap, Rpad, v.NBpad, v.nseg, ws.qlen);
     MST_LAUNCH_CHECK();
     if ((rc = scan_excl_i32(ws.qlen, v.ptr, v.nseg, s)) != MST_OK) return rc;
     k_clear_view<<<(unsigned)cdiv(v.cap_pairs * 4, 256), 256, 0, s>>>(v.ptr, v.nseg, v.ent, v.perm);
     MST_LAUNCH_CHECK();
     if (row_view) {
         k_fill_row<<<(unsigned)cdiv(O, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.NBpad, L->rowptr, v.ptr,
-                                                        L->vals, L->flat, ws.cidx,
+                                                        v.rowpos, L->vals, L->flat, ws.cidx,
                                                         reinterpret_cast<uint2*>(v.ent), v.perm);
     } else {
-        k_fill_col<<<gcol, 64, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, ws.cidx,
+        k_fill_col<<<gcol, 64, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, v.rowpos, ws.cidx,
                                         reinterpret_cast<uint2*>(v.ent), v.perm);
     }
     MST_LAUNCH_CHECK();
@@ -386,14 +421,15 @@ int mst_layer_create(mst_layer_t** out, int O, int I, int64_t nnz_capacity, void
     L->flat = (int*)(b + c.flat);
     L->rowptr = (int*)(b + c.rowptr);
     L->Wd = (float*)(b + c.Wd);
-    auto init_view = [&](View& v, int R, int K, size_t optr, size_t oent, size_t operm) {
+    auto init_view = [&](View& v, int R, int K, size_t optr, size_t oent, size_t operm, size_t omap, size_t opos) {
         v.R = R; v.K = K; v.nchunk = (int)nchunks(K); v.NB = (int)nblocks(R); v.NBpad = (int)nbpad(R);
         v.nseg = (int64_t)v.nchunk * v.NBpad * 4;
         v.cap_pairs = view_pair_capacity(nnz_capacity, v.nchunk, R);
         v.ptr = (int*)(b + optr); v.ent = (uint4*)(b + oent); v.perm = (int*)(b + operm);
+        v.rowmap = (int*)(b + omap); v.rowpos = (int*)(b + opos);
     };
-    init_view(L->row, O, I, c.rptr, c.rent, c.rperm);
-    init_view(L->col, I, O, c.cptr, c.cent, c.cperm);
+    init_view(L->row, O, I, c.rptr, c.rent, c.rperm, c.rmap, c.rpos);
+    init_view(L->col, I, O, c.cptr, c.cent, c.cperm, c.cmap, c.cpos);
     *out = L;
     return MST_OK;
 }

@@ -57,7 +57,7 @@ template <typename TIn, int QW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* __restrict__ dY /* register operand [T x R] */,
              const int* __restrict__ ptr,
-             const uint4* __restrict__ ent, float* __restrict__ partial, int64_t slots_stride, int T, int K,
+             const uint4* __restrict__ ent, const int* __restrict__ rowmap, float* __restrict__ partial, int64_t slots_stride, int T, int K,
              int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok) {
     __shared__ float tile[KC * TT];
     __shared__ uint4 ebuf[NW][BP * 4];
@@ -79,16 +79,18 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
     // partial sums of this token tile, viewed as float2[] indexed by pair * 4 + g
     float2* pt = reinterpret_cast<float2*>(partial + (int64_t)tile_id * slots_stride);
 
-    // dY of this lane's 8 tokens for rows 16 blk + 4 g + q0 + q
+    // dY of this lane's 8 tokens for the rows of rank 4 (q0 + q) + g of the block
     float dy[QW][8];
-    const int rbase = blk * RB + g * 4 + q0;
+    int rsel[QW];
+#pragma unroll
+    for (int q = 0; q < QW; ++q) rsel[q] = rowmap[blk * RB + 4 * (q0 + q) + g];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int t = t0 + lane_token(s, e);
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             float v = 0.f;
-            if (t < T && rbase + q < R) v = load_act<TIn>(dY + (int64_t)t * R + rbase + q);
+            if (t < T && rsel[q] < R) v = load_act<TIn>(dY + (int64_t)t * R + rsel[q]);
             dy[q][e] = v;
         }
     }
@@ -157,10 +159,10 @@ static int launch_sddmm(const mst_layer* L, const TIn* dY, const TIn* X, float* 
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int64_t stride = v.cap_pairs * 8;
     if (qw == 4)
-        k_sddmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
+        k_sddmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, v.rowmap, ws.partial, stride, T,
                                                                   v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
     else
-        k_sddmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, ws.partial, stride, T,
+        k_sddmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, v.rowmap, ws.partial, stride, T,
                                                                   v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
     MST_LAUNCH_CHECK();
     const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);

@@ -39,7 +39,8 @@ constexpr int NW = 16;
 // when the output is too narrow to give every CU two full workgroups.
 template <typename TIn, int QW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_spmm(
-    const TIn* __restrict__ A, const int* __restrict__ ptr, const uint4* __restrict__ ent, float* __restrict__ out,
+    const TIn* __restrict__ A, const int* __restrict__ ptr, const uint4* __restrict__ ent,
+    const int* __restrict__ rowmap, float* __restrict__ out,
     int T, int K, int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_store) {
     __shared__ float tile[KC * TT];
     __shared__ uint4 ebuf[NW][BP * 4];
@@ -98,12 +99,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
         pv = pv_next;
     }
 
+    // rows of this lane's accumulators: rank 4 (q0 + q) + g of the block
+    int rloc[QW];
+#pragma unroll
+    for (int q = 0; q < QW; ++q) rloc[q] = rowmap[blk * RB + 4 * (q0 + q) + g];
+
     // ---- epilogue: through LDS, 64 tokens at a time, so that each token's outputs of the
     // whole slab leave as one contiguous run.  Staging layout: token tl (0..63) owns 1 KB;
     // the 16-byte chunk j (rows 4j..4j+3 of the slab) sits at slot j ^ ((tl >> 2) & 15).
     constexpr int SLAB_ROWS = NW * QW * 4;
     const int row0 = slab * SLAB_ROWS;                // first row of the slab
-    const int chunk = ((wave / WPB) * 4 + g);         // this lane's 16-byte chunk of a token row
+#pragma unroll
+    for (int q = 0; q < QW; ++q) rloc[q] -= row0;     // position inside the slab's token row
     float* stf = tile;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -111,9 +118,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int tl = 4 * s + e;
-            float* dst = stf + (tl * 64 + (chunk ^ s)) * 4 + q0;
 #pragma unroll
-            for (int q = 0; q < QW; ++q) dst[q] = acc[q][4 * h + e];
+            for (int q = 0; q < QW; ++q)
+                stf[(tl * 64 + ((rloc[q] >> 2) ^ s)) * 4 + (rloc[q] & 3)] = acc[q][4 * h + e];
         }
         __syncthreads();
         constexpr int NCH = SLAB_ROWS / 4;            // 16-byte chunks per token row of the slab
@@ -144,10 +151,10 @@ static int launch_spmm(const View& v, const TIn* A, float* out, int T, hipStream
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int vec_store = (v.R % 4 == 0) ? 1 : 0;
     if (qw == 4)
-        k_spmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
+        k_spmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, v.rowmap, out, T, v.K, v.R, v.NBpad, v.nchunk,
                                                                  nslab, ntile, vec_ok, vec_store);
     else
-        k_spmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, out, T, v.K, v.R, v.NBpad, v.nchunk,
+        k_spmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, v.rowmap, out, T, v.K, v.R, v.NBpad, v.nchunk,
                                                                  nslab, ntile, vec_ok, vec_store);
     MST_LAUNCH_CHECK();
     return MST_OK;
