@@ -28,6 +28,7 @@ SHAPES = [
     (640, 3072, 768, 0.02),     # long contraction (24 chunks)
     (64, 130, 70, 0.5),
     (1, 5, 3, 0.6),             # single token, tiny
+    (2100, 200, 3850, 0.05),    # ragged everywhere and large enough for whole-block wavefronts
 ]
 
 
