@@ -95,3 +95,16 @@ def test_size_queries_and_argument_errors():
     assert L.mst_sparse_fc_fwd(None, None, None, 4, 0, None) == -1
     assert L.mst_layer_load_dense(None, None, None, None, 0, None) == -1
     assert L.mst_mask_update(None, None, None, 4, 0, 0.1, 0.3, 0.25, 1, None, 0, None, None) == -1
+
+
+def test_product_package_never_imports_the_oracle():
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r); import paper_2408_11746_amd as m; m.lib(); "
+            "bad = [k for k in sys.modules if k == 'oracle' or k.startswith('oracle.')]; "
+            "assert not bad, bad; print('clean')" % ROOT)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True)
+    assert out.returncode == 0 and "clean" in out.stdout, out.stderr
+    for name in ("binding.py", "build.py", "__init__.py"):
+        src = open(os.path.join(ROOT, "paper_2408_11746_amd", name)).read()
+        assert "oracle" not in src
