@@ -51,7 +51,7 @@ int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int
     if (!L || !X_dev || !Y_dev || T < 1 || !act_ok(act) || !aligned16(X_dev) || !aligned16(Y_dev)) return MST_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_path(L)) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
-    return spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
+    return spmm(L->row, X_dev, Y_dev, T, act, s);
 }
 
 int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_dev, int T, mst_dtype act,
@@ -59,7 +59,7 @@ int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_
     if (!L || !dY_dev || !dX_dev || T < 1 || !act_ok(act) || !aligned16(dY_dev) || !aligned16(dX_dev)) return MST_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_path(L)) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
-    return spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
+    return spmm(L->col, dY_dev, dX_dev, T, act, s);
 }
 
 int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const void* X_dev, float* dW_dev, int T,
@@ -81,12 +81,10 @@ int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, i
                      ws_dev ? (int64_t)(ws_bytes / 4) : 0, (hipStream_t)stream);
 }
 
-static int update_common(mst_layer_t* L, const float* G, double d, double zeta, double R, uint64_t seed,
-                         const Workspace& ws, mst_update_stats* stats_out, hipStream_t s,
-                         const mst_update_stats& st) {
+static int update_common(mst_layer_t* L, const float* G, uint64_t seed, const Workspace& ws,
+                         mst_update_stats* stats_out, hipStream_t s, const mst_update_stats& st) {
     if (stats_out) *stats_out = st;
     if (st.n_prune == 0 && st.n_grow == 0) return MST_OK;     // nothing moves
-    (void)d; (void)zeta; (void)R;
     return mask_update_device(L, G, st, seed, ws, s);
 }
 
@@ -100,7 +98,7 @@ int mst_mask_update_from_scores(mst_layer_t* L, const float* G_dev, double targe
     if (st.nnz_after > L->cap) return MST_ERR_STATE;
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, 1);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
-    return update_common(L, G_dev, target_density, zeta, rand_ratio, rng_seed, ws, stats_out, (hipStream_t)stream, st);
+    return update_common(L, G_dev, rng_seed, ws, stats_out, (hipStream_t)stream, st);
 }
 
 int mst_mask_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, int T, mst_dtype act,
@@ -119,7 +117,7 @@ int mst_mask_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, int T
         rc = gemm_mfma(GEMM_TN, dY_dev, act, X_dev, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s);
         if (rc != MST_OK) return rc;
     }
-    return update_common(L, ws.G, target_density, zeta, rand_ratio, rng_seed, ws, stats_out, s, st);
+    return update_common(L, ws.G, rng_seed, ws, stats_out, s, st);
 }
 
 }  // extern "C"

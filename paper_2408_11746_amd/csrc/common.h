@@ -120,7 +120,7 @@ int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s);
 
 // ---- internal entry points implemented across the .hip files ----
 int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s);
-int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype act, hipStream_t s);
+int spmm(const View& v, const void* A, float* out, int T, mst_dtype act, hipStream_t s);
 int sddmm(const mst_layer* L, const void* dY, const void* X, float* dW, int T, mst_dtype act,
           const Workspace& ws, hipStream_t s);
 // C[M x N] (fp32) = op(A) op(B) on the matrix cores; see gemm_mfma.hip

@@ -3,8 +3,9 @@
 // backward = 2 x forward).
 //
 // Same decomposition and lane mapping as the SpMM: a workgroup owns TT = 128 tokens and
-// 16 rows of the row view per wavefront, stages chunks of X in LDS and walks the ELL
-// slices.  A lane keeps dY of its 8 tokens for the 4 rows of its lane group in
+// a row block (or half of one) of the driving view per wavefront, stages chunks of one
+// dense operand in LDS and walks the ELL slices (written below for the row view: X is
+// staged, dY sits in registers; the col view swaps the two).  A lane keeps dY of its 8 tokens for the 4 rows of its lane group in
 // registers; entries reach the lanes through the same per-wavefront LDS buffer as in
 // the SpMM; per step a lane reads its 8 X values of the entry's column from LDS, forms the
 // 8-term dot product and the 16 lanes of the group add their parts with four DPP row

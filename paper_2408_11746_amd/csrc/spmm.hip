@@ -2,7 +2,8 @@
 // Serves the forward product (S = W, A = X; App. "FLOP Calculation" Eq. (1)) and the
 // input gradient (S = W^T, A = dY; the first half of the backward pass).
 //
-// A workgroup owns TT = 128 tokens and a slab of 16 rows per wavefront.  It walks the
+// A workgroup of 16 wavefronts owns TT = 128 tokens and a slab of 256 rows (a row block of
+// 16 rows per wavefront) or 128 rows (half a block per wavefront).  It walks the
 // contraction index in chunks of KC: the chunk of A is staged (transposed) in LDS, then
 // each wavefront walks its row block's ELL slices.  A wavefront is four lane groups of 16
 // lanes; in one step each lane group multiplies ONE entry (its own row of the quad)
@@ -11,8 +12,8 @@
 // vector load (next batch in flight while the current one is consumed), the 8 activations
 // from two 16-byte LDS reads, then 8 FMAs into the accumulators of that row, which stay
 // in registers for the whole K loop.  Nothing in the inner loop touches global memory,
-// the scalar unit or another lane.  The result tile leaves through LDS so that global stores are
-// whole rows of the slab.
+// the scalar unit or another lane.  The result tile leaves through LDS so that global
+// stores are contiguous runs of the slab's columns.
 #include "tile_loader.h"
 
 namespace mst {
@@ -160,8 +161,7 @@ static int launch_spmm(const View& v, const TIn* A, float* out, int T, hipStream
     return MST_OK;
 }
 
-int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype act, hipStream_t s) {
-    (void)nnz;
+int spmm(const View& v, const void* A, float* out, int T, mst_dtype act, hipStream_t s) {
     if (act == MST_F32) return launch_spmm<float>(v, static_cast<const float*>(A), out, T, s);
     return launch_spmm<uint16_t>(v, static_cast<const uint16_t*>(A), out, T, s);
 }
