@@ -6,8 +6,8 @@
 // a row block (or half of one) of the driving view per wavefront, stages chunks of one
 // dense operand in LDS and walks the ELL slices (written below for the row view: X is
 // staged, dY sits in registers; the col view swaps the two).  A lane keeps dY of its 8 tokens for the 4 rows of its lane group in
-// registers; entries reach the lanes through the same per-wavefront LDS buffer as in
-// the SpMM; per step a lane reads its 8 X values of the entry's column from LDS, forms the
+// registers; entries reach the lanes as in the SpMM (batches of four pairs, handed round
+// the groups of four lanes through DPP operands); per step a lane reads its 8 X values of the entry's column from LDS, forms the
 // 8-term dot product and the 16 lanes of the group add their parts with four DPP row
 // shifts -- all four lane groups (four entries) at once, no LDS traffic.  Lane 15 of
 // each group stores the per-(token tile, entry slot) partial sums; a second kernel adds
@@ -38,9 +38,15 @@ __device__ inline float load_act<float>(const float* p) { return *p; }
 template <>
 __device__ inline float load_act<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
 
-#define MST_DOT(OFF, DY, RES)                                                        \
+// value of v in lane JJ of this lane's aligned group of four lanes
+template <int JJ>
+__device__ inline uint32_t quad_bcast(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, JJ * 0x55, 0xf, 0xf, true);
+}
+
+#define MST_DOT(JJ, OFF, DY, RES)                                                    \
     do {                                                                             \
-        const uint32_t a_ = lane16 ^ (OFF);                                          \
+        const uint32_t a_ = lane16 ^ quad_bcast<JJ>(OFF);                                        \
         const float4 xa = *reinterpret_cast<const float4*>(tb + a_);                 \
         const float4 xb = *reinterpret_cast<const float4*>(tb + a_ + 256);           \
         float d_ = DY[0] * xa.x;                                                     \
@@ -50,7 +56,15 @@ __device__ inline float load_act<uint16_t>(const uint16_t* p) { return bf16_to_f
         RES = row_sum_to_last(d_);                                                   \
     } while (0)
 
-constexpr int BP = 12;      // pairs per refill of a wavefront's entry buffer
+// partial sums of the pair held by lane JJ of each group of four lanes
+#define MST_DOT_PAIR(JJ, DY, P)                                                      \
+    do {                                                                             \
+        float r0, r1;                                                                \
+        MST_DOT(JJ, cur.x, DY, r0);                                                  \
+        MST_DOT(JJ, cur.z, DY, r1);                                                  \
+        if (s == 15) pt[(int64_t)(P) * 4 + g] = make_float2(r0, r1);                 \
+    } while (0)
+
 constexpr int NW = 16;      // wavefronts per workgroup
 
 // QW = quads per wavefront (4: a whole row block, 2: half of one), as in the SpMM
@@ -61,7 +75,6 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
              const uint4* __restrict__ ent, const int* __restrict__ rowmap, float* __restrict__ partial, int64_t slots_stride, int T, int K,
              int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok) {
     __shared__ float tile[KC * TT];
-    __shared__ uint4 ebuf[NW][BP * 4];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
     const int tid = threadIdx.x;
@@ -75,8 +88,7 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
-    uint4* eb = ebuf[wave];
-    const int ll = min(lane, BP * 4 - 1);
+    const int eoff = (lane & 3) * 4 + g;              // this lane's 16 bytes of a batch of four pairs
     // partial sums of this token tile, viewed as float2[] indexed by pair * 4 + g
     float2* pt = reinterpret_cast<float2*>(partial + (int64_t)tile_id * slots_stride);
 
@@ -103,28 +115,24 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
         load_tile<TIn, NW * 64>(tile, X, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
-        const int ptot = __builtin_amdgcn_readlane(pv, QW);
-        uint4 stage = ent[(int64_t)p * 4 + ll];
-        int bend = p;
+        uint4 nxt = ent[(int64_t)p * 4 + eoff];
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             const int pend = __builtin_amdgcn_readlane(pv, q + 1);
             while (p < pend) {
-                if (p == bend) {
-                    if (lane < BP * 4) eb[lane] = stage;
-                    bend = p + BP;
-                    if (bend < ptot) stage = ent[(int64_t)bend * 4 + ll];
+                const uint4 cur = nxt;
+                const int pn = min(p + 4, pend);
+                nxt = ent[(int64_t)pn * 4 + eoff];
+                MST_DOT_PAIR(0, dy[q], p);
+                if (p + 1 < pend) {
+                    MST_DOT_PAIR(1, dy[q], p + 1);
+                    if (p + 2 < pend) {
+                        MST_DOT_PAIR(2, dy[q], p + 2);
+                        if (p + 3 < pend) MST_DOT_PAIR(3, dy[q], p + 3);
+                    }
                 }
-                const int lim = min(pend, bend);
-                const uint4* er = eb + (p - (bend - BP)) * 4 + g;
-                for (; p < lim; ++p, er += 4) {
-                    const uint4 cur = *er;
-                    float r0, r1;
-                    MST_DOT(cur.x, dy[q], r0);
-                    MST_DOT(cur.z, dy[q], r1);
-                    if (s == 15) pt[(int64_t)p * 4 + g] = make_float2(r0, r1);
-                }
+                p = pn;
             }
         }
         pv = pv_next;

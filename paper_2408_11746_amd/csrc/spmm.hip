@@ -18,22 +18,43 @@
 
 namespace mst {
 
-#define MST_STEP(OFF, W, ACC)                                                        \
+// value of v in lane JJ of this lane's aligned group of four lanes
+template <int JJ>
+__device__ inline uint32_t quad_bcast(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, JJ * 0x55, 0xf, 0xf, true);
+}
+
+// Four FMAs whose common factor W comes from lane JJ of the group of four lanes through the
+// DPP operand of v_fmac_f32 (no separate broadcast move).  The leading s_nop covers the two
+// wait states a DPP read needs after a VALU write of its source, whatever was scheduled
+// in front of the block.
+#define MST_FMA4_BC(JJ, A0, A1, A2, A3, W, X)                                                   \
+    asm("s_nop 1\n\t"                                                                           \
+        "v_fmac_f32_dpp %0, %4, %5 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+        "v_fmac_f32_dpp %1, %4, %6 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+        "v_fmac_f32_dpp %2, %4, %7 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+        "v_fmac_f32_dpp %3, %4, %8 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1"     \
+        : "+v"(A0), "+v"(A1), "+v"(A2), "+v"(A3)                                                \
+        : "v"(W), "v"(X.x), "v"(X.y), "v"(X.z), "v"(X.w))
+
+// one step: entry {OFF, W} as held by lane JJ of the group of four lanes
+#define MST_STEP(JJ, OFF, W, ACC)                                                    \
     do {                                                                             \
-        const uint32_t a_ = lane16 ^ (OFF);                                          \
+        const uint32_t a_ = lane16 ^ quad_bcast<JJ>(OFF);                            \
         const float4 xa = *reinterpret_cast<const float4*>(tb + a_);                 \
         const float4 xb = *reinterpret_cast<const float4*>(tb + a_ + 256);           \
-        const float w_ = __uint_as_float(W);                                         \
-        ACC[0] = fmaf(w_, xa.x, ACC[0]); ACC[1] = fmaf(w_, xa.y, ACC[1]);            \
-        ACC[2] = fmaf(w_, xa.z, ACC[2]); ACC[3] = fmaf(w_, xa.w, ACC[3]);            \
-        ACC[4] = fmaf(w_, xb.x, ACC[4]); ACC[5] = fmaf(w_, xb.y, ACC[5]);            \
-        ACC[6] = fmaf(w_, xb.z, ACC[6]); ACC[7] = fmaf(w_, xb.w, ACC[7]);            \
+        MST_FMA4_BC(JJ, ACC[0], ACC[1], ACC[2], ACC[3], W, xa);                      \
+        MST_FMA4_BC(JJ, ACC[4], ACC[5], ACC[6], ACC[7], W, xb);                      \
     } while (0)
 
-// pairs per refill of a wavefront's entry buffer (64 bytes each): 16 wavefronts x 12 pairs
-// keep two workgroups (tile + buffers) inside the 160 KB of LDS
-constexpr int BP = 12;
-constexpr int NW = 16;
+// the pair held by lane JJ of each group of four lanes: both of its steps
+#define MST_PAIR(JJ, ACC)                                                            \
+    do {                                                                             \
+        MST_STEP(JJ, cur.x, cur.y, ACC);                                             \
+        MST_STEP(JJ, cur.z, cur.w, ACC);                                             \
+    } while (0)
+
+constexpr int NW = 16;      // wavefronts per workgroup
 
 // QW = quads per wavefront: 4 (a wavefront owns a whole row block of 16 rows) or 2 (two
 // wavefronts share a block, 8 rows each) -- the latter doubles the number of wavefronts
@@ -44,7 +65,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const int* __restrict__ rowmap, float* __restrict__ out,
     int T, int K, int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_store) {
     __shared__ float tile[KC * TT];
-    __shared__ uint4 ebuf[NW][BP * 4];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
     const int tid = threadIdx.x;
@@ -58,8 +78,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
-    uint4* eb = ebuf[wave];
-    const int ll = min(lane, BP * 4 - 1);             // this lane's 16 bytes of a batch
+    // a batch is four consecutive pairs: lane (g, j = lane & 3) holds lane group g's
+    // 16 bytes of pair j of the batch, the four lanes of a group of four hand them round
+    const int eoff = (lane & 3) * 4 + g;
 
     float acc[QW][8];
 #pragma unroll
@@ -75,26 +96,26 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
         load_tile<TIn, NW * 64>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
-        const int ptot = __builtin_amdgcn_readlane(pv, QW);  // end of this wavefront's pairs in the chunk
-        uint4 stage = ent[(int64_t)p * 4 + ll];               // first batch (reads past ptot stay in the tail)
-        int bend = p;                                         // end of the batch held in LDS
+        uint4 nxt = ent[(int64_t)p * 4 + eoff];               // (reads past ptot stay in the tail)
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             const int pend = __builtin_amdgcn_readlane(pv, q + 1);
             while (p < pend) {
-                if (p == bend) {       // refill: staged batch -> LDS, following batch -> registers
-                    if (lane < BP * 4) eb[lane] = stage;
-                    bend = p + BP;
-                    if (bend < ptot) stage = ent[(int64_t)bend * 4 + ll];
+                // batch = pairs p .. p+3 of this slice; the following batch starts at p + 4
+                // or, when the slice ends before that, at the first pair of the next slice
+                const uint4 cur = nxt;
+                const int pn = min(p + 4, pend);
+                nxt = ent[(int64_t)pn * 4 + eoff];            // (at most 4 pairs past ptot: next block or tail)
+                MST_PAIR(0, acc[q]);
+                if (p + 1 < pend) {
+                    MST_PAIR(1, acc[q]);
+                    if (p + 2 < pend) {
+                        MST_PAIR(2, acc[q]);
+                        if (p + 3 < pend) MST_PAIR(3, acc[q]);
+                    }
                 }
-                const int lim = min(pend, bend);
-                const uint4* er = eb + (p - (bend - BP)) * 4 + g;
-                for (; p < lim; ++p, er += 4) {
-                    const uint4 cur = *er;
-                    MST_STEP(cur.x, cur.y, acc[q]);
-                    MST_STEP(cur.z, cur.w, acc[q]);
-                }
+                p = pn;
             }
         }
         pv = pv_next;
