@@ -115,6 +115,14 @@ int mst_layer_indices(const mst_layer_t* layer, int32_t* flat_dev, mst_stream_t 
 int mst_layer_set_path(mst_layer_t* layer, mst_path path);
 int64_t mst_layer_nnz(const mst_layer_t* layer);
 
+/* Launch shape of the sparse products' SpMM kernel: tokens per workgroup (128 or 64) and
+ * quads of four rows per wavefront (2 or 4 with 128 tokens; 2, 3, 4, 6 or 8 with 64).  By
+ * default the library chooses per call from T, the layer's shape and its density; every
+ * shape gives bit-identical results.  This call pins one shape for all later calls of the
+ * process (tests and tuning); (0, 0) returns to the automatic choice.  Not thread-safe.
+ * MST_ERR_ARG for a combination that does not exist. */
+int mst_spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront);
+
 /* ------------------------------------------------------------- the products */
 
 /* Y_dev [T*O] = X_dev [T*I] (W.M)^T.  T >= 1. */

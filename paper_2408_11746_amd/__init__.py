@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     mst_mask_update,
     mst_mask_update_from_scores,
     mst_dense_grad,
+    mst_spmm_force_shape,
     MST_F32,
     MST_BF16,
     MST_PATH_AUTO,

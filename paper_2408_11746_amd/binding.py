@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         "mst_layer_sync_values": (i32, [vp, vp]),
         "mst_layer_indices": (i32, [vp, vp, vp]),
         "mst_layer_set_path": (i32, [vp, i32]),
+        "mst_spmm_force_shape": (i32, [i32, i32]),
         "mst_layer_nnz": (i64, [vp]),
         "mst_sparse_fc_fwd": (i32, [vp, vp, vp, i32, i32, vp]),
         "mst_sparse_fc_bwd_input": (i32, [vp, vp, vp, i32, i32, vp]),
@@ -86,7 +87,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_workspace_bytes",
            "mst_layer_create", "mst_layer_destroy", "mst_layer_load_dense", "mst_layer_export_dense",
-           "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path",
+           "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_spmm_force_shape",
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
            "mst_schedule_density"]
@@ -167,10 +168,11 @@ class Layer:
         h = C.c_void_p()
         _check("mst_layer_create", lib().mst_layer_create(C.byref(h), O, I, nnz_capacity, self.buf.data_ptr(), nbytes))
         self.h = h
+        self._destroy = lib().mst_layer_destroy      # kept for __del__ at interpreter shutdown
 
     def close(self):
         if getattr(self, "h", None):
-            lib().mst_layer_destroy(self.h)
+            self._destroy(self.h)
             self.h = None
 
     __del__ = close
@@ -205,6 +207,10 @@ class Layer:
 
 
 # ------------------------------------------------------------------ device calls
+
+def mst_spmm_force_shape(tokens_per_workgroup: int = 0, quads_per_wavefront: int = 0):
+    _check("mst_spmm_force_shape", lib().mst_spmm_force_shape(tokens_per_workgroup, quads_per_wavefront))
+
 
 def mst_sparse_fc_fwd(layer: Layer, X, Y, T: int, act: int = MST_F32, stream=None):
     _check("mst_sparse_fc_fwd", lib().mst_sparse_fc_fwd(layer.h, _ptr(X), _ptr(Y), T, act, _stream(stream)))

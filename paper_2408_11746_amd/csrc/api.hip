@@ -46,12 +46,16 @@ using namespace mst;
 
 extern "C" {
 
+int mst_spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront) {
+    return spmm_force_shape(tokens_per_workgroup, quads_per_wavefront);
+}
+
 int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int T, mst_dtype act,
                       mst_stream_t stream) {
     if (!L || !X_dev || !Y_dev || T < 1 || !act_ok(act) || !aligned16(X_dev) || !aligned16(Y_dev)) return MST_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_path(L)) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
-    return spmm(L->row, X_dev, Y_dev, T, act, s);
+    return spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
 }
 
 int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_dev, int T, mst_dtype act,
@@ -59,7 +63,7 @@ int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_
     if (!L || !dY_dev || !dX_dev || T < 1 || !act_ok(act) || !aligned16(dY_dev) || !aligned16(dX_dev)) return MST_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_path(L)) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
-    return spmm(L->col, dY_dev, dX_dev, T, act, s);
+    return spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
 }
 
 int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const void* X_dev, float* dW_dev, int T,

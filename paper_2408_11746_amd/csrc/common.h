@@ -15,7 +15,7 @@ namespace mst {
 constexpr int KC = 128;          // contraction indices per chunk
 constexpr int TT = 128;          // tokens per LDS tile
 constexpr int RB = 16;           // rows per row block: 4 lane groups x 4 quads
-constexpr int MAX_WG_BLOCKS = 16;   // most row blocks one workgroup may own
+constexpr int MAX_WG_BLOCKS = 32;   // most row blocks one workgroup may own
 constexpr int PAIR_TAIL = 16;    // readable step pairs past the last one (a whole entry batch may be fetched there)
 
 // LDS tile layout: row k (one contraction index) holds TT tokens = 512 bytes as 32
@@ -120,7 +120,8 @@ int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s);
 
 // ---- internal entry points implemented across the .hip files ----
 int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s);
-int spmm(const View& v, const void* A, float* out, int T, mst_dtype act, hipStream_t s);
+int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype act, hipStream_t s);
+int spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront);
 int sddmm(const mst_layer* L, const void* dY, const void* X, float* dW, int T, mst_dtype act,
           const Workspace& ws, hipStream_t s);
 // C[M x N] (fp32) = op(A) op(B) on the matrix cores; see gemm_mfma.hip

@@ -96,7 +96,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
         load_tile<TIn, NW * 64>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
-        uint4 nxt = ent[(int64_t)p * 4 + eoff];               // (reads past ptot stay in the tail)
+        uint4 nxt = ent[(int64_t)p * 4 + eoff];               // (reads past the end stay in the tail)
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
                 // or, when the slice ends before that, at the first pair of the next slice
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = ent[(int64_t)pn * 4 + eoff];            // (at most 4 pairs past ptot: next block or tail)
+                nxt = ent[(int64_t)pn * 4 + eoff];            // (at most 4 pairs past the end: next block or tail)
                 MST_PAIR(0, acc[q]);
                 if (p + 1 < pend) {
                     MST_PAIR(1, acc[q]);
@@ -153,26 +153,235 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
             if (t >= T || row >= R) continue;
             const float4 v = *reinterpret_cast<const float4*>(stf + (tl * 64 + (j ^ ((tl >> 2) & 15))) * 4);
             float* o = out + (int64_t)t * R + row;
+            // streaming stores: the output is not read again by this kernel and should not
+            // push the activation tiles out of the L2
             if (vec_store && row + 3 < R) {
-                *reinterpret_cast<float4*>(o) = v;
+                typedef float f4 __attribute__((ext_vector_type(4)));
+                f4 vv = {v.x, v.y, v.z, v.w};
+                __builtin_nontemporal_store(vv, reinterpret_cast<f4*>(o));
             } else {
-                o[0] = v.x;
-                if (row + 1 < R) o[1] = v.y;
-                if (row + 2 < R) o[2] = v.z;
-                if (row + 3 < R) o[3] = v.w;
+                __builtin_nontemporal_store(v.x, o);
+                if (row + 1 < R) __builtin_nontemporal_store(v.y, o + 1);
+                if (row + 2 < R) __builtin_nontemporal_store(v.z, o + 2);
+                if (row + 3 < R) __builtin_nontemporal_store(v.w, o + 3);
             }
         }
     }
 }
 
+// ---- 64-token variant.  Same walk with half as many tokens per lane (one 16-byte LDS read
+// and four FMAs per step); a wavefront owns QW consecutive quads, which may cross row
+// blocks, so a workgroup's slab is 64 QW rows (128 .. 512).  Twice as many token tiles and
+// the free choice of QW let the grid match the chip where the 128-token kernel leaves
+// CUs idle, and a wide slab re-reads the activations less often.  The tile uses the first
+// 256 bytes of every 512-byte row of the 128-token layout, so the entries' stored offsets
+// serve both kernels.
+#define MST_STEP64(JJ, OFF, W, ACC)                                                  \
+    do {                                                                             \
+        const uint32_t a_ = lane16 ^ quad_bcast<JJ>(OFF);                            \
+        const float4 xa = *reinterpret_cast<const float4*>(tb + a_);                 \
+        MST_FMA4_BC(JJ, ACC[0], ACC[1], ACC[2], ACC[3], W, xa);                      \
+    } while (0)
+#define MST_PAIR64(JJ, ACC)                                                          \
+    do {                                                                             \
+        MST_STEP64(JJ, cur.x, cur.y, ACC);                                           \
+        MST_STEP64(JJ, cur.z, cur.w, ACC);                                           \
+    } while (0)
+
+constexpr int TT64 = 64;
+
+// 64 tokens x KC indices into the first half of each tile row.  Work item = (token quad,
+// index quad, row pair): two 16-byte row reads, four 8-byte LDS stores; 1024 items.
 template <typename TIn>
-static int launch_spmm(const View& v, const TIn* A, float* out, int T, hipStream_t s) {
+__device__ inline void load_tile64(float* tile, const TIn* __restrict__ A, int64_t lda, int t0, int k0, int T,
+                                   int K, bool vec_ok, int tid) {
+    char* base = reinterpret_cast<char*>(tile);
+    const int kq = tid & 31, h = (tid >> 5) & 1, tq = tid >> 6;
+    const int row = t0 + 4 * tq + 2 * h, k = k0 + 4 * kq;
+    float4 a, b;
+    if (vec_ok && t0 + TT64 <= T && k0 + KC <= K) {       // uniform: tile wholly inside the matrix
+        const TIn* p = A + (int64_t)row * lda + k;
+        a = load_quad_fast<TIn>(p);
+        b = load_quad_fast<TIn>(p + lda);
+    } else {
+        a = load_quad<TIn>(A, lda, row, k, T, K, vec_ok);
+        b = load_quad<TIn>(A, lda, row + 1, k, T, K, vec_ok);
+    }
+    const uint32_t sl = ((uint32_t)(tq ^ (kq & 15)) << 4) | (uint32_t)(h << 3);
+    const uint32_t kl = 4u * kq;
+    *reinterpret_cast<float2*>(base + (((kl + 0) << 9) | sl)) = make_float2(a.x, b.x);
+    *reinterpret_cast<float2*>(base + (((kl + 1) << 9) | sl)) = make_float2(a.y, b.y);
+    *reinterpret_cast<float2*>(base + (((kl + 2) << 9) | sl)) = make_float2(a.z, b.z);
+    *reinterpret_cast<float2*>(base + (((kl + 3) << 9) | sl)) = make_float2(a.w, b.w);
+}
+
+template <typename TIn, int QW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_spmm64(
+    const TIn* __restrict__ A, const int* __restrict__ ptr, const uint4* __restrict__ ent,
+    const int* __restrict__ rowmap, float* __restrict__ out,
+    int T, int K, int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_store) {
+    __shared__ float tile[KC * TT];
+    int tile_id, slab;
+    if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
+    const int tid = threadIdx.x;
+    constexpr int nthreads = NW * 64;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int t0 = tile_id * TT64;
+    const int fq = (slab * NW + wave) * QW;           // this wavefront's first quad (4 * block + quad)
+    const int g = lane >> 4, s = lane & 15;
+    const uint32_t lane16 = (uint32_t)s << 4;
+    const char* tb = reinterpret_cast<const char*>(tile);
+    const int eoff = (lane & 3) * 4 + g;
+
+    float acc[QW][4];
+#pragma unroll
+    for (int q = 0; q < QW; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[q][e] = 0.f;
+
+    const int pl = fq + min(lane, QW);
+    int pv = ptr[pl];
+    for (int c = 0; c < nchunk; ++c) {
+        if (c > 0) __syncthreads();
+        load_tile64<TIn>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
+        const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
+        int p = __builtin_amdgcn_readlane(pv, 0);
+        uint4 nxt = ent[(int64_t)p * 4 + eoff];
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < QW; ++q) {
+            const int pend = __builtin_amdgcn_readlane(pv, q + 1);
+            while (p < pend) {
+                const uint4 cur = nxt;
+                const int pn = min(p + 4, pend);
+                nxt = ent[(int64_t)pn * 4 + eoff];
+                MST_PAIR64(0, acc[q]);
+                if (p + 1 < pend) {
+                    MST_PAIR64(1, acc[q]);
+                    if (p + 2 < pend) {
+                        MST_PAIR64(2, acc[q]);
+                        if (p + 3 < pend) MST_PAIR64(3, acc[q]);
+                    }
+                }
+                p = pn;
+            }
+        }
+        pv = pv_next;
+    }
+
+    // ---- epilogue: through LDS in passes of 256 slab rows; as in the 128-token kernel a
+    // token owns 1 KB of staging and chunk j (rows 4j..4j+3 of the pass) sits at slot
+    // j ^ ((token >> 2) & 15)
+    constexpr int SLAB_ROWS = NW * QW * 4;
+    constexpr int NPASS = (SLAB_ROWS + 255) / 256;
+    const int row0 = slab * SLAB_ROWS;
+    int rloc[QW];
+#pragma unroll
+    for (int q = 0; q < QW; ++q) rloc[q] = rowmap[(fq + q) * 4 + g] - row0;
+    float* stf = tile;
+#pragma unroll
+    for (int h = 0; h < NPASS; ++h) {
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < QW; ++q) {
+            if (NPASS > 1 && ((wave * QW + q) >> 6) != h) continue;      // quad's block lies in another pass
+            const int rl = rloc[q] - 256 * h;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                stf[((4 * s + e) * 64 + ((rl >> 2) ^ s)) * 4 + (rl & 3)] = acc[q][e];
+        }
+        __syncthreads();
+        const int NCH = (SLAB_ROWS - 256 * h < 256 ? SLAB_ROWS - 256 * h : 256) / 4;   // constant after unrolling
+        for (int item = tid; item < 64 * NCH; item += nthreads) {
+            const int tl = item / NCH, j = item % NCH;
+            const int t = t0 + tl;
+            const int row = row0 + 256 * h + 4 * j;
+            if (t >= T || row >= R) continue;
+            const float4 v = *reinterpret_cast<const float4*>(stf + (tl * 64 + (j ^ ((tl >> 2) & 15))) * 4);
+            float* o = out + (int64_t)t * R + row;
+            if (vec_store && row + 3 < R) {
+                typedef float f4 __attribute__((ext_vector_type(4)));
+                f4 vv = {v.x, v.y, v.z, v.w};
+                __builtin_nontemporal_store(vv, reinterpret_cast<f4*>(o));
+            } else {
+                __builtin_nontemporal_store(v.x, o);
+                if (row + 1 < R) __builtin_nontemporal_store(v.y, o + 1);
+                if (row + 2 < R) __builtin_nontemporal_store(v.z, o + 2);
+                if (row + 3 < R) __builtin_nontemporal_store(v.w, o + 3);
+            }
+        }
+    }
+}
+
+template <typename TIn, int QW>
+static void launch64(const View& v, const TIn* A, float* out, int T, hipStream_t s) {
+    const int ntile = (int)cdiv(T, TT64);
+    const int nslab = (int)cdiv((int64_t)v.NB * 4, NW * QW);
+    k_spmm64<TIn, QW><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, v.rowmap, out, T, v.K, v.R, v.NBpad,
+                                                                v.nchunk, nslab, ntile, (v.K % 4 == 0) ? 1 : 0,
+                                                                (v.R % 4 == 0) ? 1 : 0);
+}
+
+// Launch shape: tokens per workgroup (128 or 64) and quads per wavefront.  Every candidate
+// computes the same sums in the same order, so the choice changes speed only.  The cost of a
+// candidate is the cost of one workgroup -- walk (proportional to its entries x tokens),
+// activation staging (tokens x K) and output (tokens x rows) -- times the number of
+// rounds its grid needs on 256 CUs x 2 workgroups; a last round that leaves every CU at
+// most one workgroup costs less than a full one.  The constants were fitted to timings
+// of GPT-2 small/medium/large layer shapes at densities 0.02 .. 0.10 on MI355X.
+struct SpmmShape {
+    int tt, qw;
+};
+static SpmmShape g_forced = {0, 0};
+
+static SpmmShape pick_shape(int T, int R, int K, double density) {
+    if (g_forced.tt != 0) return g_forced;
+    static const SpmmShape cand[] = {{128, 2}, {128, 4}, {64, 2}, {64, 3}, {64, 4}, {64, 6}, {64, 8}};
+    const double kWalk = 2.92e-5, kStage = 1.92e-5, kOut = 5.19e-4, kChunk = 1.87;
+    const double kLoneTail = 0.60, kLoneOnly = 0.71, k64 = 0.967;
+    const int64_t nchunk = cdiv(K, KC);
+    SpmmShape best = cand[0];
+    double best_cost = 0.0;
+    for (const SpmmShape& c : cand) {
+        const int rows = NW * c.qw * 4;
+        const int64_t nslab = cdiv(R, rows), ntile = cdiv(T, c.tt), nwg = ntile * nslab;
+        const double rows_eff = (double)R / (double)nslab;
+        const double wg = c.tt * (rows_eff * density * K * kWalk * (c.tt == 64 ? k64 : 1.0) +
+                                  (double)nchunk * KC * kStage + rows * kOut) + kChunk * (double)nchunk;
+        const int64_t full = nwg / 512, rest = nwg % 512;
+        double rounds;
+        if (full == 0) rounds = rest <= 256 ? kLoneOnly : 1.0;
+        else rounds = (double)full + (rest == 0 ? 0.0 : rest <= 256 ? kLoneTail : 1.0);
+        const double cost = wg * rounds;
+        if (best_cost == 0.0 || cost < best_cost) {
+            best_cost = cost;
+            best = c;
+        }
+    }
+    return best;
+}
+
+template <typename TIn>
+static int launch_spmm(const View& v, const TIn* A, float* out, int T, int64_t nnz, hipStream_t s) {
+    const double density = (double)nnz / ((double)v.R * (double)v.K);
+    const SpmmShape sh = pick_shape(T, v.R, v.K, density);
+    if (sh.tt == 64) {
+        switch (sh.qw) {
+            case 2: launch64<TIn, 2>(v, A, out, T, s); break;
+            case 3: launch64<TIn, 3>(v, A, out, T, s); break;
+            case 4: launch64<TIn, 4>(v, A, out, T, s); break;
+            case 6: launch64<TIn, 6>(v, A, out, T, s); break;
+            default: launch64<TIn, 8>(v, A, out, T, s); break;
+        }
+        MST_LAUNCH_CHECK();
+        return MST_OK;
+    }
     const int ntile = (int)cdiv(T, TT);
-    const int qw = pick_quads(T, v.NB);
-    const int nslab = (int)cdiv(v.NB, NW * qw / 4);
+    const int nslab = (int)cdiv(v.NB, NW * sh.qw / 4);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int vec_store = (v.R % 4 == 0) ? 1 : 0;
-    if (qw == 4)
+    if (sh.qw == 4)
         k_spmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, v.rowmap, out, T, v.K, v.R, v.NBpad, v.nchunk,
                                                                  nslab, ntile, vec_ok, vec_store);
     else
@@ -182,9 +391,21 @@ static int launch_spmm(const View& v, const TIn* A, float* out, int T, hipStream
     return MST_OK;
 }
 
-int spmm(const View& v, const void* A, float* out, int T, mst_dtype act, hipStream_t s) {
-    if (act == MST_F32) return launch_spmm<float>(v, static_cast<const float*>(A), out, T, s);
-    return launch_spmm<uint16_t>(v, static_cast<const uint16_t*>(A), out, T, s);
+int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype act, hipStream_t s) {
+    if (act == MST_F32) return launch_spmm<float>(v, static_cast<const float*>(A), out, T, nnz, s);
+    return launch_spmm<uint16_t>(v, static_cast<const uint16_t*>(A), out, T, nnz, s);
+}
+
+int spmm_force_shape(int tt, int qw) {
+    if (tt == 0 && qw == 0) {
+        g_forced = {0, 0};
+        return MST_OK;
+    }
+    const bool ok = (tt == 128 && (qw == 2 || qw == 4)) ||
+                    (tt == 64 && (qw == 2 || qw == 3 || qw == 4 || qw == 6 || qw == 8));
+    if (!ok) return MST_ERR_ARG;
+    g_forced = {tt, qw};
+    return MST_OK;
 }
 
 }  // namespace mst

@@ -47,16 +47,33 @@ __device__ inline float4 load_quad<uint16_t>(const uint16_t* __restrict__ A, int
     return v;
 }
 
+// unchecked 16-byte (fp32) / 8-byte (bf16) read of A[row, k .. k+3]
+template <typename TIn>
+__device__ inline float4 load_quad_fast(const TIn* __restrict__ p);
+template <>
+__device__ inline float4 load_quad_fast<float>(const float* __restrict__ p) {
+    return *reinterpret_cast<const float4*>(p);
+}
+template <>
+__device__ inline float4 load_quad_fast<uint16_t>(const uint16_t* __restrict__ p) {
+    const uint2 u = *reinterpret_cast<const uint2*>(p);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u),
+                       __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
+}
+
 // All threads of the workgroup fill tile[KC][TT] from A[t0 .. t0+TT) x [k0 .. k0+KC).
 // Work item = (token quad tq, index quad kq): four 16-byte row reads (consecutive lanes
-// read consecutive 16 bytes of a row), transposed in registers two token rows at a time,
-// eight 8-byte LDS stores.  1024 items per tile.
+// read consecutive 16 bytes of a row), transposed in registers, eight 8-byte LDS stores.
+// 1024 items per tile.  A tile that lies wholly inside the matrix (and rows that allow
+// vector reads) takes the branch-free path: all four reads of an item are in flight at
+// once, one memory round trip per tile.  Edge tiles take the checked path.
 template <typename TIn, int NTHREADS>
 __device__ inline void load_tile(float* tile, const TIn* __restrict__ A, int64_t lda, int t0, int k0, int T,
                                  int K, bool vec_ok, int tid) {
     constexpr int ITEMS = (TT / 4) * (KC / 4);
     static_assert(ITEMS % NTHREADS == 0, "tile loader needs a thread count that divides 1024");
     char* base = reinterpret_cast<char*>(tile);
+    const bool interior = vec_ok && t0 + TT <= T && k0 + KC <= K;     // uniform over the workgroup
 #pragma unroll
     for (int it = 0; it < ITEMS / NTHREADS; ++it) {
         const int item = it * NTHREADS + tid;
@@ -66,6 +83,18 @@ __device__ inline void load_tile(float* tile, const TIn* __restrict__ A, int64_t
         // rows 4kq .. 4kq+3 share the swizzle kq & 15
         const uint32_t slot = ((uint32_t)(tq >> 4) << 8) | ((uint32_t)((tq & 15) ^ (kq & 15)) << 4);
         const uint32_t kl = 4u * kq;
+        if (interior) {
+            const TIn* p = A + (int64_t)row * lda + k;
+            const float4 r0 = load_quad_fast<TIn>(p);
+            const float4 r1 = load_quad_fast<TIn>(p + lda);
+            const float4 r2 = load_quad_fast<TIn>(p + 2 * lda);
+            const float4 r3 = load_quad_fast<TIn>(p + 3 * lda);
+            *reinterpret_cast<float4*>(base + (((kl + 0) << 9) | slot)) = make_float4(r0.x, r1.x, r2.x, r3.x);
+            *reinterpret_cast<float4*>(base + (((kl + 1) << 9) | slot)) = make_float4(r0.y, r1.y, r2.y, r3.y);
+            *reinterpret_cast<float4*>(base + (((kl + 2) << 9) | slot)) = make_float4(r0.z, r1.z, r2.z, r3.z);
+            *reinterpret_cast<float4*>(base + (((kl + 3) << 9) | slot)) = make_float4(r0.w, r1.w, r2.w, r3.w);
+            continue;
+        }
         // two token rows at a time (8 live registers): 8-byte halves of the 16-byte slot
 #pragma unroll
         for (int h = 0; h < 2; ++h) {

@@ -43,6 +43,38 @@ def test_products_match_oracle(T, I, O, density):
     assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, M)) <= TOL
 
 
+SPMM_SHAPES = [(128, 2), (128, 4), (64, 2), (64, 3), (64, 4), (64, 6), (64, 8)]
+
+
+@pytest.mark.parametrize("tokens,quads", SPMM_SHAPES)
+def test_every_spmm_launch_shape_matches_oracle_and_each_other(tokens, quads):
+    """Each launch shape of the SpMM kernel, pinned, on inputs ragged in every dimension
+    (tokens past a tile, rows past a slab of every width, a partial last chunk); all
+    shapes add a row's entries in the same order, so they agree bit for bit."""
+    T, I, O, density = 333, 410, 1100, 0.08
+    print("case", tokens, quads, T, I, O, density, flush=True)
+    W, M, X, dY = _case(21, T, I, O, density)
+    rig = Rig(W, M, T)
+    try:
+        mst.mst_spmm_force_shape(128, 4)
+        y_ref, dx_ref = rig.fwd(X), rig.bwd_input(dY)
+        mst.mst_spmm_force_shape(tokens, quads)
+        y, dx = rig.fwd(X), rig.bwd_input(dY)
+    finally:
+        mst.mst_spmm_force_shape(0, 0)
+    assert rel_err(y, opr.fc_fwd(X, W, M)) <= TOL
+    assert rel_err(dx, opr.fc_bwd_input(dY, W, M)) <= TOL
+    np.testing.assert_array_equal(y, y_ref)
+    np.testing.assert_array_equal(dx, dx_ref)
+
+
+def test_spmm_force_shape_rejects_unknown_shapes():
+    for tokens, quads in [(128, 3), (64, 5), (32, 4), (0, 4), (64, 0)]:
+        with pytest.raises(mst.MstError):
+            mst.mst_spmm_force_shape(tokens, quads)
+    mst.mst_spmm_force_shape(0, 0)
+
+
 def test_load_export_roundtrip_and_canonical_order():
     W, M, _, _ = _case(3, 8, 200, 333, 0.1)
     rig = Rig(W, M, 8)
