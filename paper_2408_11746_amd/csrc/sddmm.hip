@@ -22,21 +22,18 @@ __device__ inline float dpp_add(float x) {
     return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
 }
 
-// sum over each row of 16 lanes, valid in the row's last lane
-__device__ inline float row_sum_to_last(float x) {
-    x = dpp_add<0x111>(x);   // row_shr:1
-    x = dpp_add<0x112>(x);   // row_shr:2
-    x = dpp_add<0x114>(x);   // row_shr:4
-    x = dpp_add<0x118>(x);   // row_shr:8
-    return x;
+// Sums of a and b over each row of 16 lanes with six adds / selects instead of eight:
+// after the first exchange the lower eight lanes go on with a, the upper eight with b.
+// The sum of a ends up in lanes 0..7 of the row, the sum of b in lanes 8..15.
+__device__ inline float row_sum_pair(float a, float b, bool upper_half) {
+    a = dpp_add<0x128>(a);                 // row_ror:8   lane s += lane s ^ 8
+    b = dpp_add<0x128>(b);
+    float c = upper_half ? b : a;
+    c = dpp_add<0x141>(c);                 // row_half_mirror   lane s += lane 7 - s of its half
+    c = dpp_add<0xB1>(c);                  // quad_perm:[1,0,3,2]
+    c = dpp_add<0x4E>(c);                  // quad_perm:[2,3,0,1]
+    return c;
 }
-
-template <typename TIn>
-__device__ inline float load_act(const TIn* p);
-template <>
-__device__ inline float load_act<float>(const float* p) { return *p; }
-template <>
-__device__ inline float load_act<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
 
 // value of v in lane JJ of this lane's aligned group of four lanes
 template <int JJ>
@@ -44,74 +41,95 @@ __device__ inline uint32_t quad_bcast(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, JJ * 0x55, 0xf, 0xf, true);
 }
 
+// this lane's share (8 tokens) of the dot product of one entry
 #define MST_DOT(JJ, OFF, DY, RES)                                                    \
     do {                                                                             \
-        const uint32_t a_ = lane16 ^ quad_bcast<JJ>(OFF);                                        \
+        const uint32_t a_ = lane16 ^ quad_bcast<JJ>(OFF);                            \
         const float4 xa = *reinterpret_cast<const float4*>(tb + a_);                 \
         const float4 xb = *reinterpret_cast<const float4*>(tb + a_ + 256);           \
         float d_ = DY[0] * xa.x;                                                     \
         d_ = fmaf(DY[1], xa.y, d_); d_ = fmaf(DY[2], xa.z, d_); d_ = fmaf(DY[3], xa.w, d_); \
         d_ = fmaf(DY[4], xb.x, d_); d_ = fmaf(DY[5], xb.y, d_);                      \
         d_ = fmaf(DY[6], xb.z, d_); d_ = fmaf(DY[7], xb.w, d_);                      \
-        RES = row_sum_to_last(d_);                                                   \
+        RES = d_;                                                                    \
     } while (0)
 
-// partial sums of the pair held by lane JJ of each group of four lanes
+// partial sums of the pair held by lane JJ of each group of four lanes: lane 0 of a lane
+// group stores the first entry's sum, lane 8 the second's
 #define MST_DOT_PAIR(JJ, DY, P)                                                      \
     do {                                                                             \
         float r0, r1;                                                                \
         MST_DOT(JJ, cur.x, DY, r0);                                                  \
         MST_DOT(JJ, cur.z, DY, r1);                                                  \
-        if (s == 15) pt[(int64_t)(P) * 4 + g] = make_float2(r0, r1);                 \
+        const float r_ = row_sum_pair(r0, r1, upper);                                \
+        if (storer) pt[(int64_t)(P) * 8 + pslot] = r_;                               \
     } while (0)
 
 constexpr int NW = 16;      // wavefronts per workgroup
 
-// QW = quads per wavefront (4: a whole row block, 2: half of one), as in the SpMM
+// QW = quads per wavefront (consecutive quads, which may cross row blocks): the slab of a
+// workgroup is 64 QW rows of the driving view
 template <typename TIn, int QW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* __restrict__ dY /* register operand [T x R] */,
              const int* __restrict__ ptr,
              const uint4* __restrict__ ent, const int* __restrict__ rowmap, float* __restrict__ partial, int64_t slots_stride, int T, int K,
-             int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok) {
+             int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_reg) {
     __shared__ float tile[KC * TT];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
     const int tid = threadIdx.x;
-    constexpr int nw = NW;
+    constexpr int nthreads = NW * 64;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
-    constexpr int WPB = 4 / QW;
-    const int blk = (slab * nw + wave) / WPB;
-    const int q0 = (wave % WPB) * QW;
+    const int fq = (slab * NW + wave) * QW;           // this wavefront's first quad (4 * block + quad)
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
     const int eoff = (lane & 3) * 4 + g;              // this lane's 16 bytes of a batch of four pairs
-    // partial sums of this token tile, viewed as float2[] indexed by pair * 4 + g
-    float2* pt = reinterpret_cast<float2*>(partial + (int64_t)tile_id * slots_stride);
+    const bool upper = (s & 8) != 0;
+    const bool storer = (s & 7) == 0;
+    const int pslot = g * 2 + (s >> 3);               // slot of this lane's sum inside a pair's eight
+    // partial sums of this token tile: eight per pair, (lane group, step of the pair)
+    float* pt = partial + (int64_t)tile_id * slots_stride;
 
-    // dY of this lane's 8 tokens for the rows of rank 4 (q0 + q) + g of the block
+    // ---- register operand: dY of this lane's 8 tokens for the row of each of its quads.
+    // It comes in through LDS, 64 tokens at a time: the workgroup reads the slab's columns
+    // of 64 token rows as whole contiguous runs into the staging layout the SpMM epilogue
+    // uses (token tl owns 1 KB, the 16-byte chunk j of rows 4j..4j+3 at slot
+    // j ^ ((tl >> 2) & 15)), then every lane picks its rows' values.
+    constexpr int SLAB_ROWS = NW * QW * 4;
+    constexpr int NCH = SLAB_ROWS / 4;
+    const int row0 = slab * SLAB_ROWS;
     float dy[QW][8];
-    int rsel[QW];
+    int rloc[QW];
 #pragma unroll
-    for (int q = 0; q < QW; ++q) rsel[q] = rowmap[blk * RB + 4 * (q0 + q) + g];
+    for (int q = 0; q < QW; ++q) rloc[q] = rowmap[(fq + q) * 4 + g] - row0;
+    float* stf = tile;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int t = t0 + lane_token(s, e);
-#pragma unroll
-        for (int q = 0; q < QW; ++q) {
-            float v = 0.f;
-            if (t < T && rsel[q] < R) v = load_act<TIn>(dY + (int64_t)t * R + rsel[q]);
-            dy[q][e] = v;
+    for (int h = 0; h < 2; ++h) {
+        if (h) __syncthreads();
+        for (int item = tid; item < 64 * NCH; item += nthreads) {
+            const int tl = item / NCH, j = item % NCH;
+            const int t = t0 + 64 * h + tl;
+            const int row = row0 + 4 * j;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < T && row < R) v = load_quad<TIn>(dY, R, t, row, T, R, vec_reg != 0);
+            *reinterpret_cast<float4*>(stf + (tl * 64 + (j ^ ((tl >> 2) & 15))) * 4) = v;
         }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < QW; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                dy[q][4 * h + e] = stf[((4 * s + e) * 64 + ((rloc[q] >> 2) ^ s)) * 4 + (rloc[q] & 3)];
     }
 
-    const int pl = blk * 4 + q0 + min(lane, QW);
+    const int pl = fq + min(lane, QW);
     int pv = ptr[pl];
     for (int c = 0; c < nchunk; ++c) {
-        if (c > 0) __syncthreads();
+        __syncthreads();
         load_tile<TIn, NW * 64>(tile, X, K, t0, c * KC, T, K, vec_ok != 0, tid);
         const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
@@ -152,6 +170,47 @@ __global__ void k_sddmm_reduce(const float* __restrict__ partial, int64_t slots_
     dW[p] = sum;
 }
 
+// Quads per wavefront (2, 3 or 4: slabs of 128, 192 or 256 rows), by the cost model of the
+// SpMM launch shapes: the cost of one workgroup (walk, staging of both dense operands,
+// per-chunk overhead) times the rounds the grid needs on 256 CUs x 2 workgroups, a last
+// round with at most one workgroup per CU costing less.  Constants fitted to timings of
+// GPT-2 small / medium / large layer shapes at densities 0.02 .. 0.10 on MI355X.  Every
+// choice adds the same terms in the same order.
+static int pick_sddmm_quads(int T, int R, int K, double density) {
+    const double kWalk = 3.71e-5, kStage = 3.0e-5, kReg = 9.96e-4, kChunk = 1.57;
+    const double kLoneTail = 0.51, kLoneOnly = 0.58;
+    const int64_t nchunk = cdiv(K, KC), ntile = cdiv(T, TT);
+    int best = 4;
+    double best_cost = 0.0;
+    for (int qw = 2; qw <= 4; ++qw) {
+        const int rows = NW * qw * 4;
+        const int64_t nslab = cdiv(R, rows), nwg = ntile * nslab;
+        const double rows_eff = (double)R / (double)nslab;
+        const double wg = TT * (rows_eff * density * K * kWalk + (double)nchunk * KC * kStage + rows * kReg) +
+                          kChunk * (double)nchunk;
+        const int64_t full = nwg / 512, rest = nwg % 512;
+        double rounds;
+        if (full == 0) rounds = rest <= 256 ? kLoneOnly : 1.0;
+        else rounds = (double)full + (rest == 0 ? 0.0 : rest <= 256 ? kLoneTail : 1.0);
+        const double cost = wg * rounds;
+        if (best_cost == 0.0 || cost < best_cost) {
+            best_cost = cost;
+            best = qw;
+        }
+    }
+    return best;
+}
+
+template <typename TIn, int QW>
+static void launch_k(const View& v, const TIn* staged, const TIn* inreg, float* partial, int64_t stride, int T,
+                     hipStream_t s) {
+    const int ntile = (int)cdiv(T, TT);
+    const int nslab = (int)cdiv((int64_t)v.NB * 4, NW * QW);
+    k_sddmm<TIn, QW><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, v.rowmap, partial, stride, T,
+                                                               v.K, v.R, v.NBpad, v.nchunk, nslab, ntile,
+                                                               (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0);
+}
+
 // The product is symmetric in its two dense operands: either view can drive it.  The view
 // with more rows is used (more workgroups, fewer chunks): the row view stages X and keeps
 // dY in registers, the col view stages dY and keeps X in registers.
@@ -163,16 +222,11 @@ static int launch_sddmm(const mst_layer* L, const TIn* dY, const TIn* X, float* 
     const TIn* staged = use_col ? dY : X;
     const TIn* inreg = use_col ? X : dY;
     const int ntile = (int)cdiv(T, TT);
-    const int qw = pick_quads(T, v.NB);
-    const int nslab = (int)cdiv(v.NB, NW * qw / 4);
-    const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
+    const int qw = pick_sddmm_quads(T, v.R, v.K, (double)L->nnz / ((double)v.R * (double)v.K));
     const int64_t stride = v.cap_pairs * 8;
-    if (qw == 4)
-        k_sddmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, v.rowmap, ws.partial, stride, T,
-                                                                  v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
-    else
-        k_sddmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, v.rowmap, ws.partial, stride, T,
-                                                                  v.K, v.R, v.NBpad, v.nchunk, nslab, ntile, vec_ok);
+    if (qw == 4) launch_k<TIn, 4>(v, staged, inreg, ws.partial, stride, T, s);
+    else if (qw == 3) launch_k<TIn, 3>(v, staged, inreg, ws.partial, stride, T, s);
+    else launch_k<TIn, 2>(v, staged, inreg, ws.partial, stride, T, s);
     MST_LAUNCH_CHECK();
     const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
     k_sddmm_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, stride, ntile, v.ptr, v.nseg, v.perm, dW);

@@ -124,12 +124,4 @@ __device__ inline bool block_to_tile(int nslab, int ntile, int& tile, int& slab)
 }
 inline unsigned grid_for(int ntile, int nslab) { return (unsigned)(cdiv(ntile, 8) * 8 * nslab); }
 
-// Quads per wavefront (workgroups are 16 wavefronts, two per CU): a whole row block (4)
-// unless that grid could not give every CU a workgroup; then half a block (2), which
-// doubles the workgroups at the price of re-reading the activation tile twice as often.
-inline int pick_quads(int T, int NB) {
-    const int64_t ntile = cdiv(T, TT);
-    return (ntile * cdiv(NB, 16) >= 256) ? 4 : 2;
-}
-
 }  // namespace mst
