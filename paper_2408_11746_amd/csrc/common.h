@@ -111,7 +111,7 @@ struct Workspace {
 };
 Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T);
 
-constexpr int GEMM_WS_SPLITS = 4;
+constexpr int GEMM_WS_SPLITS = 8;
 constexpr int SELECT_BLOCK = 2048;   // elements per block in the ordered tie pass
 constexpr int SEL_STATE_WORDS = 8 + 256;
 

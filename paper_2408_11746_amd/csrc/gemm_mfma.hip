@@ -269,6 +269,32 @@ __global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, 
     C[i] = s;
 }
 
+// Number of k ranges (blockIdx.z) a GEMM of `tiles` output tiles is split into.  A CU holds
+// four workgroups; the grid should fill 256 x 4 places a whole number of times.  Cost of a
+// choice = (k steps per workgroup x step_us + wg_us) x rounds, a last partial round
+// counting 0.44 / 0.63 / 0.84 / 1 by quarters of the places it fills (fitted to timings
+// of the dense gradient at GPT-2 small / medium / large shapes), plus the pass that adds
+// the partial outputs.
+static int pick_nsplit(int64_t tiles, int Kdim, int bk, double step_us, double wg_us, int64_t max_split) {
+    const int64_t places = 1024;
+    int best = 1;
+    double best_cost = 0.0;
+    const int64_t hi = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, max_split), Kdim / 256));
+    for (int ns = 1; ns <= hi; ++ns) {
+        const int64_t n = tiles * ns, full = n / places, rest = n % places;
+        const double steps = (double)cdiv(cdiv(Kdim, ns), bk);
+        const double frac = (double)rest / (double)places;
+        const double last = rest == 0 ? 0.0 : frac <= 0.25 ? 0.44 : frac <= 0.5 ? 0.63 : frac <= 0.75 ? 0.84 : 1.0;
+        const double cost = (steps * step_us + wg_us) * ((double)full + last) +
+                            (ns > 1 ? 5e-7 * (double)ns * (double)tiles * 128.0 * 128.0 : 0.0);
+        if (best_cost == 0.0 || cost < best_cost) {
+            best_cost = cost;
+            best = ns;
+        }
+    }
+    return best;
+}
+
 template <typename TA, bool AK, typename TB, bool BKM>
 static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
                   float* split_ws, int64_t split_ws_floats, hipStream_t s) {
@@ -276,15 +302,9 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
     const int tm = 128;
     const int gm = (int)cdiv(M, tm), gn = (int)cdiv(N, 128);
     const int64_t mn = (int64_t)M * N;
-    int nsplit = 1;
-    if (split_ws && (int64_t)gm * gn < 384) {
-        nsplit = (int)cdiv(512, (int64_t)gm * gn);
-        nsplit = (int)std::min<int64_t>(nsplit, std::min<int64_t>(16, Kdim / 256));
-        nsplit = (int)std::min<int64_t>(nsplit, split_ws_floats / mn);
-        if (nsplit < 1) nsplit = 1;
-    }
-    int kps = (int)(cdiv(cdiv(Kdim, nsplit), BK) * BK);
-    nsplit = (int)cdiv(Kdim, kps);
+    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, BK, 4.63, 10.7, split_ws_floats / mn) : 1;
+    const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), BK) * BK);
+    const int nsplit = (int)cdiv(Kdim, kps);
     dim3 grid(gn, gm, nsplit);
     float* dst = nsplit > 1 ? split_ws : C;
     // 16-byte loads need every row start aligned: leading dimension a multiple of 4
@@ -304,15 +324,9 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
                           int64_t split_ws_floats, hipStream_t s) {
     const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
     const int64_t mn = (int64_t)M * N;
-    int nsplit = 1;
-    if (split_ws && (int64_t)gm * gn < 384) {
-        nsplit = (int)cdiv(512, (int64_t)gm * gn);
-        nsplit = (int)std::min<int64_t>(nsplit, std::min<int64_t>(16, Kdim / 512));
-        nsplit = (int)std::min<int64_t>(nsplit, split_ws_floats / mn);
-        if (nsplit < 1) nsplit = 1;
-    }
-    int kps = (int)(cdiv(cdiv(Kdim, nsplit), BKH) * BKH);
-    nsplit = (int)cdiv(Kdim, kps);
+    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, BKH, 4.63, 10.7, split_ws_floats / mn) : 1;
+    const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), BKH) * BKH);
+    const int nsplit = (int)cdiv(Kdim, kps);
     dim3 grid(gn, gm, nsplit);
     float* dst = nsplit > 1 ? split_ws : C;
     // 4-byte loads of element pairs need even leading dimensions (bases are 16-byte aligned)
