@@ -65,8 +65,9 @@ struct mst_layer {
     int* rowptr = nullptr;     // [O + 1] canonical CSR row pointers
     float* Wd = nullptr;       // [N] dense W . M, maintained only while the dense path is in use
     bool Wd_valid = false;
-    mst::View row;             // S = W   [O x I], used by fwd and bwd_weight
+    mst::View row;             // S = W   [O x I], used by fwd (and bwd_weight)
     mst::View col;             // S = W^T [I x O], used by bwd_input
+    int* sddmm_view = nullptr; // device flag: view that drives bwd_weight (0 row, 1 col), set when the views are built
 };
 
 namespace mst {

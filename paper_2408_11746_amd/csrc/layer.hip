@@ -34,7 +34,7 @@ bool use_dense_path(const mst_layer* L) {
 
 struct LayerCarve {
     size_t mask, vals, flat, rowptr, Wd;
-    size_t rptr, rent, rperm, rmap, rpos, cptr, cent, cperm, cmap, cpos;
+    size_t rptr, rent, rperm, rmap, rpos, cptr, cent, cperm, cmap, cpos, choice;
     size_t total;
 };
 
@@ -60,6 +60,7 @@ static LayerCarve carve_layer(int O, int I, int64_t cap) {
     c.cperm = take((size_t)cp_c * 32);
     c.cmap = take((size_t)nbpad(I) * RB * 4);
     c.cpos = take((size_t)nbpad(I) * RB * 4);
+    c.choice = take(16);
     c.total = off;
     return c;
 }
@@ -368,12 +369,28 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
 
 // Rebuilds vals / flat / rowptr and both views from the layer's mask and a dense weight
 // array.  The col view needs the canonical indices the row view pass writes to ws.cidx.
+// The weight gradient can walk either view.  The one with clearly fewer pairs (less ELL
+// padding: with very uneven row lengths one view is far cheaper than the other) drives
+// it; otherwise the one with more rows.
+__global__ void k_choose_view(const int* __restrict__ row_ptr, int64_t row_nseg, const int* __restrict__ col_ptr,
+                              int64_t col_nseg, int prefer_col, int* __restrict__ choice) {
+    const int64_t pr = row_ptr[row_nseg], pc = col_ptr[col_nseg];
+    int c = prefer_col;
+    if (prefer_col && pr * 10 < pc * 9) c = 0;
+    if (!prefer_col && pc * 10 < pr * 9) c = 1;
+    *choice = c;
+}
+
 int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s) {
     int rc = build_one_view(L->row, true, L, Wsrc, ws, s);
     if (rc != MST_OK) return rc;
     rc = build_one_view(L->col, false, L, Wsrc, ws, s);
+    if (rc != MST_OK) return rc;
+    k_choose_view<<<1, 1, 0, s>>>(L->row.ptr, L->row.nseg, L->col.ptr, L->col.nseg, L->I > L->O ? 1 : 0,
+                                  L->sddmm_view);
+    MST_LAUNCH_CHECK();
     L->Wd_valid = false;
-    return rc;
+    return MST_OK;
 }
 
 int refresh_dense_copy(mst_layer* L, hipStream_t s) {
@@ -421,6 +438,7 @@ int mst_layer_create(mst_layer_t** out, int O, int I, int64_t nnz_capacity, void
     L->flat = (int*)(b + c.flat);
     L->rowptr = (int*)(b + c.rowptr);
     L->Wd = (float*)(b + c.Wd);
+    L->sddmm_view = (int*)(b + c.choice);
     auto init_view = [&](View& v, int R, int K, size_t optr, size_t oent, size_t operm, size_t omap, size_t opos) {
         v.R = R; v.K = K; v.nchunk = (int)nchunks(K); v.NB = (int)nblocks(R); v.NBpad = (int)nbpad(R);
         v.nseg = (int64_t)v.nchunk * v.NBpad * 4;

@@ -74,8 +74,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* __restrict__ dY /* register operand [T x R] */,
              const int* __restrict__ ptr,
              const uint4* __restrict__ ent, const int* __restrict__ rowmap, float* __restrict__ partial, int64_t slots_stride, int T, int K,
-             int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_reg) {
+             int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_reg, const int* __restrict__ choice, int me) {
     __shared__ float tile[KC * TT];
+    if (*choice != me) return;                        // the other view drives this layer's weight gradient
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
     const int tid = threadIdx.x;
@@ -160,7 +161,8 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
 // dW[perm[e]] = sum over token tiles of partial[tile][e], tiles added in ascending order
 __global__ void k_sddmm_reduce(const float* __restrict__ partial, int64_t slots_stride, int ntile,
                                const int* __restrict__ ptr, int64_t nseg, const int* __restrict__ perm,
-                               float* __restrict__ dW) {
+                               float* __restrict__ dW, const int* __restrict__ choice, int me) {
+    if (*choice != me) return;
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (int64_t)ptr[nseg] * 8) return;
     const int p = perm[e];
@@ -203,34 +205,38 @@ static int pick_sddmm_quads(int T, int R, int K, double density) {
 
 template <typename TIn, int QW>
 static void launch_k(const View& v, const TIn* staged, const TIn* inreg, float* partial, int64_t stride, int T,
-                     hipStream_t s) {
+                     const int* choice, int me, hipStream_t s) {
     const int ntile = (int)cdiv(T, TT);
     const int nslab = (int)cdiv((int64_t)v.NB * 4, NW * QW);
     k_sddmm<TIn, QW><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, v.rowmap, partial, stride, T,
                                                                v.K, v.R, v.NBpad, v.nchunk, nslab, ntile,
-                                                               (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0);
+                                                               (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0, choice, me);
 }
 
-// The product is symmetric in its two dense operands: either view can drive it.  The view
-// with more rows is used (more workgroups, fewer chunks): the row view stages X and keeps
-// dY in registers, the col view stages dY and keeps X in registers.
+// The product is symmetric in its two dense operands: either view can drive it.  The row
+// view stages X and keeps dY in registers, the col view stages dY and keeps X in registers.
+// Which one is a device-side flag set when the views were built (the host does not know the
+// views' padded sizes without a synchronisation): both are launched, the workgroups of
+// the one not chosen leave at once.
 template <typename TIn>
 static int launch_sddmm(const mst_layer* L, const TIn* dY, const TIn* X, float* dW, int T,
                         const Workspace& ws, hipStream_t s) {
-    const bool use_col = L->I > L->O;
-    const View& v = use_col ? L->col : L->row;
-    const TIn* staged = use_col ? dY : X;
-    const TIn* inreg = use_col ? X : dY;
     const int ntile = (int)cdiv(T, TT);
-    const int qw = pick_sddmm_quads(T, v.R, v.K, (double)L->nnz / ((double)v.R * (double)v.K));
-    const int64_t stride = v.cap_pairs * 8;
-    if (qw == 4) launch_k<TIn, 4>(v, staged, inreg, ws.partial, stride, T, s);
-    else if (qw == 3) launch_k<TIn, 3>(v, staged, inreg, ws.partial, stride, T, s);
-    else launch_k<TIn, 2>(v, staged, inreg, ws.partial, stride, T, s);
-    MST_LAUNCH_CHECK();
-    const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
-    k_sddmm_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, stride, ntile, v.ptr, v.nseg, v.perm, dW);
-    MST_LAUNCH_CHECK();
+    for (int me = 0; me < 2; ++me) {
+        const View& v = me ? L->col : L->row;
+        const TIn* staged = me ? dY : X;
+        const TIn* inreg = me ? X : dY;
+        const int qw = pick_sddmm_quads(T, v.R, v.K, (double)L->nnz / ((double)v.R * (double)v.K));
+        const int64_t stride = v.cap_pairs * 8;
+        if (qw == 4) launch_k<TIn, 4>(v, staged, inreg, ws.partial, stride, T, L->sddmm_view, me, s);
+        else if (qw == 3) launch_k<TIn, 3>(v, staged, inreg, ws.partial, stride, T, L->sddmm_view, me, s);
+        else launch_k<TIn, 2>(v, staged, inreg, ws.partial, stride, T, L->sddmm_view, me, s);
+        MST_LAUNCH_CHECK();
+        const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
+        k_sddmm_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, stride, ntile, v.ptr, v.nseg, v.perm, dW,
+                                                                  L->sddmm_view, me);
+        MST_LAUNCH_CHECK();
+    }
     return MST_OK;
 }
 
