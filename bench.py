@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 ALU_FP32_PEAK_TFLOPS = 157.3   # fp32 vector peak (256 CUs x 4 SIMD x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz)
 MFMA_FP32_PEAK_TFLOPS = 157.3
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA peak
 METRIC = "effective sparse TFLOP/s + HBM GB/s (% peak) per FC train step, 1 MI355X"
 
 
@@ -193,7 +194,15 @@ def main():
     t_alu = drow["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
     # fwd / bwd_input are one k_spmm launch; bwd_weight is k_sddmm followed by the small k_sddmm_reduce
     kernel = {"fwd": "k_spmm", "bwd_input": "k_spmm", "bwd_weight": "k_sddmm+k_sddmm_reduce"}[drow["call"]]
-    if t_hbm >= t_alu:
+    # with bfloat16 activations the library computes the weight gradient as the full MFMA
+    # product dY^T X read at the active positions from a density of 0.045 on (T >= 2048)
+    mfma_bww = drow["call"] == "bwd_weight" and act == "bf16" and density > 0.045 and T >= 2048
+    if mfma_bww:
+        kernel = "k_gemm_tn_bf16+k_splitk_reduce+k_gather_flat"
+        dense_tf = 2.0 * T * dL.O * dL.I / drow["avg_ms"] / 1e9
+        roof = dict(bound="mfma", achieved=round(dense_tf, 1), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(dense_tf / MFMA_BF16_PEAK_TFLOPS, 4))
+    elif t_hbm >= t_alu:
         roof = dict(bound="hbm", achieved=drow["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(drow["hbm_gbs"] / HBM_PEAK_GBS, 4))
     else:

@@ -73,7 +73,7 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const voi
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    if (use_dense_path(L)) return dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+    if (use_dense_weight_grad(L, act, T)) return dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
     return sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
 }
 

@@ -32,6 +32,17 @@ bool use_dense_path(const mst_layer* L) {
     return (double)L->nnz > 0.30 * (double)L->N;      // measured cross-over, see the benchmark table
 }
 
+// The weight gradient alone has a second cross-over: with bfloat16 activations both operands
+// of G = dY^T X are bfloat16, the MFMA kernel runs at 300-440 TFLOP/s and computing all of
+// G, then reading the active positions, beats the SDDMM (about 17 effective TFLOP/s) from a
+// density of about 0.045 on (measured at T >= 8192; short batches keep the common threshold).
+bool use_dense_weight_grad(const mst_layer* L, mst_dtype act, int T) {
+    if (L->path == MST_PATH_DENSE) return true;
+    if (L->path == MST_PATH_SPARSE) return false;
+    const double thr = (act == MST_BF16 && T >= 2048) ? 0.045 : 0.30;
+    return (double)L->nnz > thr * (double)L->N;
+}
+
 struct LayerCarve {
     size_t mask, vals, flat, rowptr, Wd;
     size_t rptr, rent, rperm, rmap, rpos, cptr, cent, cperm, cmap, cpos, choice;
