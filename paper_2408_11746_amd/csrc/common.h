@@ -15,7 +15,8 @@ namespace mst {
 constexpr int KC = 128;          // contraction indices per chunk
 constexpr int TT = 128;          // tokens per LDS tile
 constexpr int RB = 16;           // rows per row block: 4 lane groups x 4 quads
-constexpr int MAX_WG_BLOCKS = 32;   // most row blocks one workgroup may own
+constexpr int MAX_WG_BLOCKS = 32;
+constexpr int SPREAD_FLAG = 1 << 30;   // in rowmap / rowpos: the quad holds ONE row spread over its four lane groups   // most row blocks one workgroup may own
 constexpr int PAIR_TAIL = 16;    // readable step pairs past the last one (a whole entry batch may be fetched there)
 
 // LDS tile layout: row k (one contraction index) holds TT tokens = 512 bytes as 32
@@ -38,6 +39,12 @@ __host__ __device__ inline uint32_t lds_off(uint32_t k) {
 // count (an ELL slice of height 4): step j of the quad holds one entry per lane group.
 // Two steps form a pair = uint4[4]: element g is {off_j, w_j, off_j+1, w_j+1} of lane
 // group g, off = lds_off(k - c*KC), w = fp32 bits.
+// A very long row can take a whole quad ("spread"): its entries are dealt to the four lane
+// groups in turn (entry j of a chunk: lane group j & 3, step j >> 2), the kernels add the
+// four lane groups' sums at the end.  The other three places of such a quad are given to
+// three EMPTY rows of the block (they own the output positions, which receive zero), so a
+// block spreads at most as many rows as it has triples of empty rows.  All four rowmap
+// entries of a spread quad and the rowpos entry of the spread row carry SPREAD_FLAG.
 struct View {
     int R = 0, K = 0, nchunk = 0;
     int NB = 0;            // row blocks: ceil(R / 16)

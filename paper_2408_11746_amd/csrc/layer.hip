@@ -152,8 +152,11 @@ __global__ void k_count_col(const uint8_t* __restrict__ mask, int O, int I, int 
     segcnt[(size_t)c * Rpad + i] = n;
 }
 
-// one thread per row block: rank its 16 rows by total length over all chunks, longest
-// first, lower row first on ties (the empty padding blocks keep the identity)
+// one thread per row block: order its 16 rows by total length over all chunks, longest
+// first, lower row first on ties (the empty padding blocks keep the identity).  With h rows
+// spread over whole quads (h <= #empty rows / 3) the quads cost about
+//   sum_{j<h} ceil(len_j / 4)  +  sum over the quads of the other rows of their longest row,
+// h is the value that minimises it (0 for every mask without empty rows).
 __global__ void k_block_rank(const int* __restrict__ segcnt, int nchunk, int Rpad, int NBpad,
                              int* __restrict__ rowmap, int* __restrict__ rowpos) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -166,17 +169,44 @@ __global__ void k_block_rank(const int* __restrict__ segcnt, int nchunk, int Rpa
 #pragma unroll
         for (int j = 0; j < RB; ++j) len[j] += p[j];
     }
+    int order[RB], sorted[RB];        // sorted position -> row, its length
+    int nzero = 0;
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
         int rank = 0;
 #pragma unroll
         for (int u = 0; u < RB; ++u) rank += (len[u] > len[j]) || (len[u] == len[j] && u < j);
-        rowmap[b * RB + rank] = b * RB + j;
-        rowpos[b * RB + j] = rank;
+#pragma unroll
+        for (int u = 0; u < RB; ++u)
+            if (u == rank) { order[u] = j; sorted[u] = len[j]; }
+        nzero += len[j] == 0;
+    }
+    int h = 0, best = sorted[0] + sorted[4] + sorted[8] + sorted[12];
+    for (int hh = 1; hh <= 4 && 3 * hh <= nzero; ++hh) {
+        int cost = 0;
+        for (int j = 0; j < hh; ++j) cost += (sorted[j] + 3) >> 2;
+        for (int p = hh; p < RB - 3 * hh; p += 4) {
+            int v = 0;
+#pragma unroll
+            for (int u = 0; u < RB; ++u) if (u == p) v = sorted[u];
+            cost += v;
+        }
+        if (cost < best) { best = cost; h = hh; }
+    }
+#pragma unroll
+    for (int p = 0; p < RB; ++p) {
+        int slot, flag_row = 0;
+        if (p < h) { slot = 4 * p; flag_row = SPREAD_FLAG; }                 // spread row: lane group 0 of quad p
+        else if (p < RB - 3 * h) slot = 4 * h + (p - h);                     // ordinary rows fill the other quads
+        else { const int e = p - (RB - 3 * h); slot = 4 * (e / 3) + 1 + e % 3; }   // empty rows own the rest
+        const int flag_quad = (slot >> 2) < h ? SPREAD_FLAG : 0;
+        rowmap[b * RB + slot] = (b * RB + order[p]) | flag_quad;
+        rowpos[b * RB + order[p]] = slot | flag_row;
     }
 }
 
-// pairs of one quad segment: longest of its four rows, rounded up to even, halved
+// pairs of one quad segment: longest of its four rows (a spread row: a quarter of it),
+// rounded up to even, halved
 __global__ void k_quad_len(const int* __restrict__ segcnt, const int* __restrict__ rowmap, int Rpad, int NBpad,
                            int64_t nseg, int* __restrict__ qlen) {
     const int64_t sidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (c*NBpad + b)*4 + q
@@ -187,7 +217,9 @@ __global__ void k_quad_len(const int* __restrict__ segcnt, const int* __restrict
     const int64_t c = cb / NBpad;
     const int* cnt = segcnt + c * Rpad;
     const int* rm = rowmap + b * RB + 4 * q;          // the quad's four rows (one per lane group)
-    const int L = max(max(cnt[rm[0]], cnt[rm[1]]), max(cnt[rm[2]], cnt[rm[3]]));
+    int L;
+    if (rm[0] & SPREAD_FLAG) L = (cnt[rm[0] & ~SPREAD_FLAG] + 3) >> 2;
+    else L = max(max(cnt[rm[0]], cnt[rm[1]]), max(cnt[rm[2]], cnt[rm[3]]));
     qlen[sidx] = (L + 1) >> 1;
 }
 
@@ -245,7 +277,8 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (r >= O) return;
-    const int b = r / RB, rank = rowpos[r], g = rank & 3, q = rank >> 2;
+    const int b = r / RB, rp = rowpos[r], rank = rp & ~SPREAD_FLAG, g = rank & 3, q = rank >> 2;
+    const bool spread = (rp & SPREAD_FLAG) != 0;
     const uint8_t* m = mask + (size_t)r * I;
     const float* w = W + (size_t)r * I;
     int canon = rowptr[r];
@@ -264,7 +297,7 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
                 vals[k] = v;
                 flat[k] = r * I + i;
                 cidx[(size_t)r * I + i] = k;
-                const int64_t e = entry_slot(pair0, g, j);
+                const int64_t e = spread ? entry_slot(pair0, j & 3, j >> 2) : entry_slot(pair0, g, j);
                 ent[e] = make_uint2(lds_off((uint32_t)(i - c * KC)), __float_as_uint(v));
                 perm[e] = k;
             }
@@ -282,7 +315,8 @@ __global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __rest
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int c = blockIdx.y;
     if (i >= I) return;
-    const int b = i / RB, rank = rowpos[i], g = rank & 3, q = rank >> 2;
+    const int b = i / RB, rp = rowpos[i], rank = rp & ~SPREAD_FLAG, g = rank & 3, q = rank >> 2;
+    const bool spread = (rp & SPREAD_FLAG) != 0;
     const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
     const int o0 = c * KC, o1 = min(O, o0 + KC);
     int j = 0;
@@ -294,7 +328,7 @@ __global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __rest
         for (int u = 0; u < 16; ++u) {
             if (m[u]) {
                 const size_t f = (size_t)(ob + u) * I + i;
-                const int64_t e = entry_slot(pair0, g, j);
+                const int64_t e = spread ? entry_slot(pair0, j & 3, j >> 2) : entry_slot(pair0, g, j);
                 ent[e] = make_uint2(lds_off((uint32_t)(ob + u - o0)), __float_as_uint(W[f]));
                 perm[e] = cidx[f];
                 ++j;
@@ -380,12 +414,27 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
 
 // Rebuilds vals / flat / rowptr and both views from the layer's mask and a dense weight
 // array.  The col view needs the canonical indices the row view pass writes to ws.cidx.
-// The weight gradient can walk either view.  The one with clearly fewer pairs (less ELL
-// padding: with very uneven row lengths one view is far cheaper than the other) drives
-// it; otherwise the one with more rows.
-__global__ void k_choose_view(const int* __restrict__ row_ptr, int64_t row_nseg, const int* __restrict__ col_ptr,
-                              int64_t col_nseg, int prefer_col, int* __restrict__ choice) {
-    const int64_t pr = row_ptr[row_nseg], pc = col_ptr[col_nseg];
+// The weight gradient can walk either view.  A workgroup of the SDDMM owns about 16
+// consecutive row blocks and waits at every chunk for its longest wavefront, so the time of
+// a view goes with  sum over (chunk, group of 16 blocks) of the most pairs of a block  --
+// with uneven row lengths far more than its pairs / 16.  The view with the clearly smaller
+// sum drives the product, else the one with more rows.
+__global__ void k_view_cost(const int* __restrict__ ptr, int nchunk, int NBpad, int NB,
+                            unsigned long long* __restrict__ cost) {
+    const int ngroup = (NB + 15) / 16;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)nchunk * ngroup) return;
+    const int c = (int)(idx / ngroup), grp = (int)(idx % ngroup);
+    int worst = 0;
+    for (int b = grp * 16; b < min(NB, grp * 16 + 16); ++b) {
+        const int64_t sidx = ((int64_t)c * NBpad + b) * 4;
+        worst = max(worst, ptr[sidx + 4] - ptr[sidx]);
+    }
+    if (worst) atomicAdd(cost, (unsigned long long)worst);
+}
+
+__global__ void k_choose_view(const unsigned long long* __restrict__ cost, int prefer_col, int* __restrict__ choice) {
+    const unsigned long long pr = cost[0], pc = cost[1];
     int c = prefer_col;
     if (prefer_col && pr * 10 < pc * 9) c = 0;
     if (!prefer_col && pc * 10 < pr * 9) c = 1;
@@ -397,8 +446,15 @@ int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_
     if (rc != MST_OK) return rc;
     rc = build_one_view(L->col, false, L, Wsrc, ws, s);
     if (rc != MST_OK) return rc;
-    k_choose_view<<<1, 1, 0, s>>>(L->row.ptr, L->row.nseg, L->col.ptr, L->col.nseg, L->I > L->O ? 1 : 0,
-                                  L->sddmm_view);
+    unsigned long long* cost = reinterpret_cast<unsigned long long*>(ws.sel_state);
+    if ((rc = fill_u32(cost, 0u, 4, s)) != MST_OK) return rc;
+    for (int me = 0; me < 2; ++me) {
+        const View& v = me ? L->col : L->row;
+        const int64_t n = (int64_t)v.nchunk * cdiv(v.NB, 16);
+        k_view_cost<<<(unsigned)cdiv(n, 256), 256, 0, s>>>(v.ptr, v.nchunk, v.NBpad, v.NB, cost + me);
+        MST_LAUNCH_CHECK();
+    }
+    k_choose_view<<<1, 1, 0, s>>>(cost, L->I > L->O ? 1 : 0, L->sddmm_view);
     MST_LAUNCH_CHECK();
     L->Wd_valid = false;
     return MST_OK;

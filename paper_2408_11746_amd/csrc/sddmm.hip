@@ -106,7 +106,11 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
     float dy[QW][8];
     int rloc[QW];
 #pragma unroll
-    for (int q = 0; q < QW; ++q) rloc[q] = rowmap[(fq + q) * 4 + g] - row0;
+    for (int q = 0; q < QW; ++q) {
+        // a spread quad: all four lane groups work on the row of lane group 0
+        const int rm = rowmap[(fq + q) * 4 + g], rm0 = rowmap[(fq + q) * 4];
+        rloc[q] = (((rm & SPREAD_FLAG) ? rm0 : rm) & ~SPREAD_FLAG) - row0;
+    }
     float* stf = tile;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {

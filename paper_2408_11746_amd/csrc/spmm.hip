@@ -56,6 +56,21 @@ __device__ inline uint32_t quad_bcast(uint32_t v) {
 
 constexpr int NW = 16;      // wavefronts per workgroup
 
+// A spread quad (one long row dealt over the four lane groups): lane group 0 takes the sum
+// of the four lane groups' accumulators, the others -- whose output positions belong to
+// empty rows -- take zero.  `spread` is the same in every lane of the wavefront.
+template <int NACC>
+__device__ inline void fold_spread(float (&acc)[NACC], int spread, int g) {
+    if (!__builtin_amdgcn_readfirstlane(spread)) return;
+#pragma unroll
+    for (int e = 0; e < NACC; ++e) {
+        float v = acc[e];
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+        acc[e] = (g == 0) ? v : 0.f;
+    }
+}
+
 // QW = quads per wavefront: 4 (a wavefront owns a whole row block of 16 rows) or 2 (two
 // wavefronts share a block, 8 rows each) -- the latter doubles the number of wavefronts
 // when the output is too narrow to give every CU two full workgroups.
@@ -124,7 +139,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     // rows of this lane's accumulators: rank 4 (q0 + q) + g of the block
     int rloc[QW];
 #pragma unroll
-    for (int q = 0; q < QW; ++q) rloc[q] = rowmap[blk * RB + 4 * (q0 + q) + g];
+    for (int q = 0; q < QW; ++q) {
+        const int rm = rowmap[blk * RB + 4 * (q0 + q) + g];
+        fold_spread(acc[q], rm & SPREAD_FLAG, g);
+        rloc[q] = rm & ~SPREAD_FLAG;
+    }
 
     // ---- epilogue: through LDS, 64 tokens at a time, so that each token's outputs of the
     // whole slab leave as one contiguous run.  Staging layout: token tl (0..63) owns 1 KB;
@@ -278,7 +297,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const int row0 = slab * SLAB_ROWS;
     int rloc[QW];
 #pragma unroll
-    for (int q = 0; q < QW; ++q) rloc[q] = rowmap[(fq + q) * 4 + g] - row0;
+    for (int q = 0; q < QW; ++q) {
+        const int rm = rowmap[(fq + q) * 4 + g];
+        fold_spread(acc[q], rm & SPREAD_FLAG, g);
+        rloc[q] = (rm & ~SPREAD_FLAG) - row0;
+    }
     float* stf = tile;
 #pragma unroll
     for (int h = 0; h < NPASS; ++h) {

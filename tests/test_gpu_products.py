@@ -75,6 +75,49 @@ def test_spmm_force_shape_rejects_unknown_shapes():
     mst.mst_spmm_force_shape(0, 0)
 
 
+def test_long_rows_spread_over_a_quad():
+    """Blocks of 16 rows built by hand so that the format spreads 1, 4, 1 (too few empty
+    rows for the second long row) and 0 long rows over whole quads, next to ordinary
+    blocks; all products and the layer round trip against the oracle."""
+    rng = np.random.default_rng(5)
+    T, I, O = 200, 300, 80
+    M = (rng.random((O, I)) < 0.04).astype(np.uint8)
+    M[0:16] = 0
+    M[3] = 1                                   # block 0: one full row, a few short rows, many empty
+    M[5, ::7] = 1
+    M[9, 10:14] = 1
+    M[16:32] = 0
+    for r in (17, 20, 22, 31):                 # block 1: four long rows, twelve empty
+        M[r, rng.random(I) < 0.7] = 1
+    M[32:48] = (rng.random((16, I)) < 0.05)
+    M[33] = 1
+    M[40, : I // 2] = 1                        # block 2: two long rows, exactly four empty rows
+    M[[34, 35, 36, 37]] = 0
+    M[48:64] = (rng.random((16, I)) < 0.05)    # block 3: a full row, no empty row
+    M[50] = 1
+    M[48:64, 0] = 1
+    W = (synth.normal(9, 77, (O, I), 0.02) * M).astype(np.float32)
+    X, dY = synth.make_activations(9, 1, T, I, O)
+    rig = Rig(W, M, T)
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL
+    assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, W, M)) <= TOL
+    assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, M)) <= TOL
+    for shape in ((128, 2), (64, 3), (64, 8)):
+        try:
+            mst.mst_spmm_force_shape(*shape)
+            assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL, shape
+        finally:
+            mst.mst_spmm_force_shape(0, 0)
+    We, Me = rig.export()
+    np.testing.assert_array_equal(Me, M)
+    np.testing.assert_array_equal(We, W)
+    # the transposed problem puts the long rows into the col view
+    rigT = Rig(np.ascontiguousarray(W.T), np.ascontiguousarray(M.T), T)
+    Xt, dYt = synth.make_activations(9, 2, T, O, I)
+    assert rel_err(rigT.bwd_input(dYt), opr.fc_bwd_input(dYt, W.T, M.T)) <= TOL
+    assert rel_err(rigT.bwd_weight(dYt, Xt), opr.fc_bwd_weight(dYt, Xt, M.T)) <= TOL
+
+
 def test_load_export_roundtrip_and_canonical_order():
     W, M, _, _ = _case(3, 8, 200, 333, 0.1)
     rig = Rig(W, M, 8)
