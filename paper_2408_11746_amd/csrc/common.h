@@ -111,7 +111,7 @@ struct Workspace {
     int* qlen = nullptr;       // pairs per quad segment of the view being built
     int* rowcnt = nullptr;     // [O + 1]
     uint32_t* blk = nullptr;   // [select_blocks(N) + 1] per-block tie counts
-    uint64_t* sel_state = nullptr;   // radix-select state + histogram
+    uint64_t* sel_state = nullptr;   // [SEL_STATES][SEL_STATE_WORDS] radix-select state + histogram
     float* gemm = nullptr;     // [GEMM_WS_SPLITS * N] split-k partial outputs of the dense GEMM
     size_t gemm_floats = 0;
     float* partial = nullptr;  // SDDMM partial sums [ntile][entry slots of the row view]
@@ -122,7 +122,10 @@ Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T);
 
 constexpr int GEMM_WS_SPLITS = 8;
 constexpr int SELECT_BLOCK = 2048;   // elements per block in the ordered tie pass
-constexpr int SEL_STATE_WORDS = 8 + 256;
+constexpr int SEL_DIGIT_BITS = 8;                        // radix-select digit
+constexpr int SEL_BINS = 1 << SEL_DIGIT_BITS;
+constexpr int SEL_STATE_WORDS = 8 + SEL_BINS / 2;        // one selection: 8 control words + the histogram
+constexpr int SEL_STATES = 3;                            // prune, gradient growth, random growth
 
 int64_t view_pair_capacity(int64_t cap, int64_t nchunk, int64_t R);
 int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s);

@@ -103,7 +103,7 @@ Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
     w.qlen = (int*)take((size_t)(std::max(nseg_r, nseg_c) + 1) * 4);
     w.rowcnt = (int*)take((size_t)(O + 1) * 4);
     w.blk = (uint32_t*)take((size_t)(cdiv(N, SELECT_BLOCK) + 2) * 4);
-    w.sel_state = (uint64_t*)take((size_t)SEL_STATE_WORDS * 8);
+    w.sel_state = (uint64_t*)take((size_t)SEL_STATES * SEL_STATE_WORDS * 8);
     w.gemm_floats = (size_t)GEMM_WS_SPLITS * (size_t)N;
     w.gemm = (float*)take(w.gemm_floats * 4);
     w.partial_floats = (size_t)ntile * 8 *
