@@ -136,73 +136,89 @@ __global__ void k_count_row(const uint8_t* __restrict__ mask, int O, int I, int 
     }
 }
 
-// one thread per (column i, chunk c of rows): active count of mask[c*KC .. , i]
-__global__ void k_count_col(const uint8_t* __restrict__ mask, int O, int I, int Rpad,
-                            int* __restrict__ segcnt) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    const int c = blockIdx.y;
-    if (i >= I) return;
-    const int o0 = c * KC, o1 = min(O, o0 + KC);
-    int n = 0;
-    for (int ob = o0; ob < o1; ob += 16) {
+// [KC rows x 64 columns] of the mask into LDS (rows beyond O and columns beyond I read as
+// zero); 256 threads, 32 bytes each.  Row stride 68 bytes: the 64 lanes of a wavefront read
+// one row's 64 bytes without bank conflicts.
+constexpr int MT_COLS = 64, MT_LD = 68;
+__device__ inline void load_mask_tile(const uint8_t* __restrict__ mask, int O, int I, int o0, int i0,
+                                      uint8_t* __restrict__ m, int tid) {
+    const int r = tid >> 1, half = tid & 1;
+    const int o = o0 + r, ib = i0 + 32 * half;
+    uint8_t* dst = m + r * MT_LD + 32 * half;
+    const uint8_t* src = mask + (size_t)o * I + ib;
+    if (o < O && ib + 32 <= I && ((reinterpret_cast<uintptr_t>(src) & 3) == 0)) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u)
-            if (ob + u < o1) n += mask[(size_t)(ob + u) * I + i] != 0;
+        for (int u = 0; u < 8; ++u)
+            reinterpret_cast<uint32_t*>(dst)[u] = reinterpret_cast<const uint32_t*>(src)[u];
+    } else {
+        for (int u = 0; u < 32; ++u) dst[u] = (o < O && ib + u < I) ? src[u] : (uint8_t)0;
     }
-    segcnt[(size_t)c * Rpad + i] = n;
 }
 
-// one thread per row block: order its 16 rows by total length over all chunks, longest
-// first, lower row first on ties (the empty padding blocks keep the identity).  With h rows
-// spread over whole quads (h <= #empty rows / 3) the quads cost about
+// block = (64 columns, chunk c of KC rows): active count of every column inside the chunk.
+// Thread (column j, row group rg of 32 rows) counts its rows from the LDS tile.
+__global__ __launch_bounds__(256) void k_count_col(const uint8_t* __restrict__ mask, int O, int I, int Rpad,
+                                                   int* __restrict__ segcnt) {
+    __shared__ __attribute__((aligned(16))) uint8_t m[KC * MT_LD];
+    __shared__ int part[4][MT_COLS];
+    const int tid = threadIdx.x, j = tid & 63, rg = tid >> 6;
+    const int i0 = blockIdx.x * MT_COLS, c = blockIdx.y;
+    load_mask_tile(mask, O, I, c * KC, i0, m, tid);
+    __syncthreads();
+    int n = 0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) n += m[(32 * rg + k) * MT_LD + j] != 0;
+    part[rg][j] = n;
+    __syncthreads();
+    if (rg == 0 && i0 + j < I) segcnt[(size_t)c * Rpad + i0 + j] = part[0][j] + part[1][j] + part[2][j] + part[3][j];
+}
+
+// 16 lanes per row block (lane j = row j): order its 16 rows by total length over all
+// chunks, longest first, lower row first on ties (the empty padding blocks keep the
+// identity).  With h rows spread over whole quads (h <= #empty rows / 3) the quads cost about
 //   sum_{j<h} ceil(len_j / 4)  +  sum over the quads of the other rows of their longest row,
 // h is the value that minimises it (0 for every mask without empty rows).
-__global__ void k_block_rank(const int* __restrict__ segcnt, int nchunk, int Rpad, int NBpad,
-                             int* __restrict__ rowmap, int* __restrict__ rowpos) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= NBpad) return;
-    int len[RB];
+__global__ __launch_bounds__(256) void k_block_rank(const int* __restrict__ segcnt, int nchunk, int Rpad, int NBpad,
+                                                    int* __restrict__ rowmap, int* __restrict__ rowpos) {
+    __shared__ int sorted_s[16][RB];
+    __shared__ int h_s[16];
+    const int tid = threadIdx.x, j = tid & 15, lb = tid >> 4;
+    const int b = blockIdx.x * 16 + lb;
+    const bool live = b < NBpad;
+    int len = 0;
+    if (live)
+        for (int c = 0; c < nchunk; ++c) len += segcnt[(size_t)c * Rpad + b * RB + j];
+    int rank = 0;
 #pragma unroll
-    for (int j = 0; j < RB; ++j) len[j] = 0;
-    for (int c = 0; c < nchunk; ++c) {
-        const int* p = segcnt + (size_t)c * Rpad + b * RB;
-#pragma unroll
-        for (int j = 0; j < RB; ++j) len[j] += p[j];
+    for (int u = 0; u < RB; ++u) {
+        const int lu = __shfl(len, u, 16);
+        rank += (lu > len) || (lu == len && u < j);
     }
-    int order[RB], sorted[RB];        // sorted position -> row, its length
-    int nzero = 0;
-#pragma unroll
-    for (int j = 0; j < RB; ++j) {
-        int rank = 0;
-#pragma unroll
-        for (int u = 0; u < RB; ++u) rank += (len[u] > len[j]) || (len[u] == len[j] && u < j);
-#pragma unroll
-        for (int u = 0; u < RB; ++u)
-            if (u == rank) { order[u] = j; sorted[u] = len[j]; }
-        nzero += len[j] == 0;
-    }
-    int h = 0, best = sorted[0] + sorted[4] + sorted[8] + sorted[12];
-    for (int hh = 1; hh <= 4 && 3 * hh <= nzero; ++hh) {
-        int cost = 0;
-        for (int j = 0; j < hh; ++j) cost += (sorted[j] + 3) >> 2;
-        for (int p = hh; p < RB - 3 * hh; p += 4) {
-            int v = 0;
-#pragma unroll
-            for (int u = 0; u < RB; ++u) if (u == p) v = sorted[u];
-            cost += v;
+    sorted_s[lb][rank] = len;
+    __syncthreads();
+    if (j == 0) {
+        const int* sorted = sorted_s[lb];
+        int nzero = 0;
+        for (int u = 0; u < RB; ++u) nzero += sorted[u] == 0;
+        int h = 0, best = sorted[0] + sorted[4] + sorted[8] + sorted[12];
+        for (int hh = 1; hh <= 4 && 3 * hh <= nzero; ++hh) {
+            int cost = 0;
+            for (int u = 0; u < hh; ++u) cost += (sorted[u] + 3) >> 2;
+            for (int p = hh; p < RB - 3 * hh; p += 4) cost += sorted[p];
+            if (cost < best) { best = cost; h = hh; }
         }
-        if (cost < best) { best = cost; h = hh; }
+        h_s[lb] = h;
     }
-#pragma unroll
-    for (int p = 0; p < RB; ++p) {
-        int slot, flag_row = 0;
-        if (p < h) { slot = 4 * p; flag_row = SPREAD_FLAG; }                 // spread row: lane group 0 of quad p
-        else if (p < RB - 3 * h) slot = 4 * h + (p - h);                     // ordinary rows fill the other quads
-        else { const int e = p - (RB - 3 * h); slot = 4 * (e / 3) + 1 + e % 3; }   // empty rows own the rest
-        const int flag_quad = (slot >> 2) < h ? SPREAD_FLAG : 0;
-        rowmap[b * RB + slot] = (b * RB + order[p]) | flag_quad;
-        rowpos[b * RB + order[p]] = slot | flag_row;
-    }
+    __syncthreads();
+    if (!live) return;
+    const int h = h_s[lb], p = rank;
+    int slot, flag_row = 0;
+    if (p < h) { slot = 4 * p; flag_row = SPREAD_FLAG; }                 // spread row: lane group 0 of quad p
+    else if (p < RB - 3 * h) slot = 4 * h + (p - h);                     // ordinary rows fill the other quads
+    else { const int e = p - (RB - 3 * h); slot = 4 * (e / 3) + 1 + e % 3; }   // empty rows own the rest
+    const int flag_quad = (slot >> 2) < h ? SPREAD_FLAG : 0;
+    rowmap[b * RB + slot] = (b * RB + j) | flag_quad;
+    rowpos[b * RB + j] = slot | flag_row;
 }
 
 // pairs of one quad segment: longest of its four rows (a spread row: a quarter of it),
@@ -223,17 +239,24 @@ __global__ void k_quad_len(const int* __restrict__ segcnt, const int* __restrict
     qlen[sidx] = (L + 1) >> 1;
 }
 
-// single-block exclusive scan: out[j] = sum_{j' < j} in[j'], out[n] = total
-__global__ void k_scan_excl(const int* in, int* out, int64_t n) {
+// single-block exclusive scan: out[j] = sum_{j' < j} in[j'], out[n] = total; a thread takes 8
+// consecutive elements per round (in == out is allowed)
+__global__ __launch_bounds__(1024) void k_scan_excl(const int* in, int* out, int64_t n) {
+    constexpr int PER = 8;
     __shared__ int wsum[16];
     __shared__ int carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) carry_s = 0;
     __syncthreads();
-    for (int64_t base = 0; base < n; base += blockDim.x) {
-        const int64_t j = base + tid;
-        const int v = (j < n) ? in[j] : 0;
-        int x = v;                                   // inclusive scan inside the wave
+    for (int64_t base = 0; base < n; base += (int64_t)blockDim.x * PER) {
+        const int64_t j0 = base + (int64_t)tid * PER;
+        int v[PER], tot = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            v[u] = (j0 + u < n) ? in[j0 + u] : 0;
+            tot += v[u];
+        }
+        int x = tot;                                 // inclusive scan of the threads' totals inside the wave
         for (int d = 1; d < 64; d <<= 1) {
             int y = __shfl_up(x, d, 64);
             if (lane >= d) x += y;
@@ -243,9 +266,14 @@ __global__ void k_scan_excl(const int* in, int* out, int64_t n) {
         int woff = 0;
         for (int w = 0; w < wave; ++w) woff += wsum[w];
         const int carry = carry_s;
-        if (j < n) out[j] = carry + woff + x - v;
+        int run = carry + woff + x - tot;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            if (j0 + u < n) out[j0 + u] = run;
+            run += v[u];
+        }
         __syncthreads();
-        if (tid == blockDim.x - 1) carry_s = carry + woff + x;
+        if (tid == blockDim.x - 1) carry_s = run;
         __syncthreads();
     }
     if (tid == 0) out[n] = carry_s;
@@ -307,33 +335,40 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     }
 }
 
-// one thread per (column i, chunk c of rows): row i of the col view, chunk c.  The 128
-// mask bytes of the thread's column are fetched 16 at a time (independent loads in flight).
-__global__ void k_fill_col(const uint8_t* __restrict__ mask, const float* __restrict__ W,
-                           int O, int I, int NBpad, const int* __restrict__ ptr, const int* __restrict__ rowpos,
-                           const int* __restrict__ cidx, uint2* __restrict__ ent, int* __restrict__ perm) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    const int c = blockIdx.y;
-    if (i >= I) return;
+// block = (64 columns, chunk c of KC rows): rows i0 .. i0+63 of the col view, chunk c.  The
+// mask tile sits in LDS; thread (column j, row group rg of 32 rows) counts its rows, the
+// counts of the row groups before it give the position of its first entry in the column's
+// list, then it writes its entries in row order.
+__global__ __launch_bounds__(256) void k_fill_col(const uint8_t* __restrict__ mask, const float* __restrict__ W,
+                                                  int O, int I, int NBpad, const int* __restrict__ ptr,
+                                                  const int* __restrict__ rowpos, const int* __restrict__ cidx,
+                                                  uint2* __restrict__ ent, int* __restrict__ perm) {
+    __shared__ __attribute__((aligned(16))) uint8_t m[KC * MT_LD];
+    __shared__ int part[4][MT_COLS];
+    const int tid = threadIdx.x, j = tid & 63, rg = tid >> 6;
+    const int i0 = blockIdx.x * MT_COLS, c = blockIdx.y, i = i0 + j;
+    const int o0 = c * KC;
+    load_mask_tile(mask, O, I, o0, i0, m, tid);
+    __syncthreads();
+    int n = 0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) n += m[(32 * rg + k) * MT_LD + j] != 0;
+    part[rg][j] = n;
+    __syncthreads();
+    if (i >= I || n == 0) return;
+    int jj = 0;
+    for (int r = 0; r < rg; ++r) jj += part[r][j];
     const int b = i / RB, rp = rowpos[i], rank = rp & ~SPREAD_FLAG, g = rank & 3, q = rank >> 2;
     const bool spread = (rp & SPREAD_FLAG) != 0;
     const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
-    const int o0 = c * KC, o1 = min(O, o0 + KC);
-    int j = 0;
-    for (int ob = o0; ob < o1; ob += 16) {
-        uint8_t m[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) m[u] = (ob + u < o1) ? mask[(size_t)(ob + u) * I + i] : (uint8_t)0;
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            if (m[u]) {
-                const size_t f = (size_t)(ob + u) * I + i;
-                const int64_t e = spread ? entry_slot(pair0, j & 3, j >> 2) : entry_slot(pair0, g, j);
-                ent[e] = make_uint2(lds_off((uint32_t)(ob + u - o0)), __float_as_uint(W[f]));
-                perm[e] = cidx[f];
-                ++j;
-            }
-        }
+    for (int k = 0; k < 32; ++k) {
+        const int ol = 32 * rg + k;
+        if (!m[ol * MT_LD + j]) continue;
+        const size_t f = (size_t)(o0 + ol) * I + i;
+        const int64_t e = spread ? entry_slot(pair0, jj & 3, jj >> 2) : entry_slot(pair0, g, jj);
+        ent[e] = make_uint2(lds_off((uint32_t)ol), __float_as_uint(W[f]));
+        perm[e] = cidx[f];
+        ++jj;
     }
 }
 
@@ -390,10 +425,10 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
         MST_LAUNCH_CHECK();
         if ((rc = scan_excl_i32(ws.rowcnt, L->rowptr, O, s)) != MST_OK) return rc;
     } else {
-        k_count_col<<<gcol, 64, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
+        k_count_col<<<gcol, 256, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
         MST_LAUNCH_CHECK();
     }
-    k_block_rank<<<(unsigned)cdiv(v.NBpad, 64), 64, 0, s>>>(ws.segcnt, v.nchunk, Rpad, v.NBpad, v.rowmap, v.rowpos);
+    k_block_rank<<<(unsigned)cdiv(v.NBpad, 16), 256, 0, s>>>(ws.segcnt, v.nchunk, Rpad, v.NBpad, v.rowmap, v.rowpos);
     MST_LAUNCH_CHECK();
     k_quad_len<<<(unsigned)cdiv(v.nseg, 256), 256, 0, s>>>(ws.segcnt, v.rowmap, Rpad, v.NBpad, v.nseg, ws.qlen);
     MST_LAUNCH_CHECK();
@@ -405,7 +440,7 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
                                                         v.rowpos, L->vals, L->flat, ws.cidx,
                                                         reinterpret_cast<uint2*>(v.ent), v.perm);
     } else {
-        k_fill_col<<<gcol, 64, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, v.rowpos, ws.cidx,
+        k_fill_col<<<gcol, 256, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, v.rowpos, ws.cidx,
                                         reinterpret_cast<uint2*>(v.ent), v.perm);
     }
     MST_LAUNCH_CHECK();
