@@ -233,6 +233,25 @@ def main():
         "calls": table,
     }
 
+    # MFMA utilisation of the dense gradient G = dY^T X that scores gradient growth (outside the
+    # timed region: it runs once per update inside mst_mask_update)
+    G = torch.empty(max(L.O * L.I for L in layers), dtype=torch.float32, device="cuda:0")
+    dg = {}
+    peak = MFMA_BF16_PEAK_TFLOPS if act == "bf16" else MFMA_FP32_PEAK_TFLOPS
+    for L in layers:
+        for _ in range(2):
+            mst.mst_dense_grad(L.dY, L.X, G, T, L.O, L.I, L.act, L.ws, stream)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(5):
+            mst.mst_dense_grad(L.dY, L.X, G, T, L.O, L.I, L.act, L.ws, stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / 5
+        tf = 2.0 * T * L.O * L.I / ms / 1e9
+        dg[L.name] = dict(avg_ms=round(ms, 4), tflops=round(tf, 1), mfma_frac=round(tf / peak, 4))
+    out["dense_grad_gemm"] = dict(dtype="bf16" if act == "bf16" else "f32", peak_tflops=peak, layers=dg)
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, T)
     print(json.dumps(out))

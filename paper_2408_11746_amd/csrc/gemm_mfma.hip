@@ -9,7 +9,9 @@
 // C[M x N] = sum_k A'[k][m] B'[k][n].  Each operand is given either k-major (element
 // (k, m) at src[k*ld + m]) or m-major (src[m*ld + k]); both are staged k-major in LDS.
 // Workgroup tile 128 x 128 x 16, four wavefronts of 64 x 64 (2 x 2 MFMA tiles each).
-// Optional split of the k range over blockIdx.z into separate partial outputs that a
+// Optional split of the k range over blockIdx.x (fastest index: consecutive workgroups go
+// to the 8 XCDs in turn, so an XCD's L2 mostly sees one k range of the operands instead of
+// all of them) into separate partial outputs that a
 // second kernel adds in a fixed order.
 #include "common.h"
 
@@ -112,10 +114,10 @@ __global__ __launch_bounds__(TM * 2) void k_gemm(const TA* __restrict__ A, int64
     __shared__ float Bs[BK * SB::LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TNW;
-    const int kbeg = blockIdx.z * k_per_split;
+    const int m0 = blockIdx.z * TM, n0 = blockIdx.y * TNW;
+    const int kbeg = blockIdx.x * k_per_split;
     const int kend = min(Kdim, kbeg + k_per_split);
-    float* Cz = C + (int64_t)blockIdx.z * split_stride;
+    float* Cz = C + (int64_t)blockIdx.x * split_stride;
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -166,54 +168,78 @@ __global__ __launch_bounds__(TM * 2) void k_gemm(const TA* __restrict__ A, int64
 
 // ---- bf16 x bf16 -> fp32, both operands k-major (the dense gradient G = dY^T X with
 // bfloat16 activations).  v_mfma_f32_32x32x16_bf16 wants, per lane, 8 consecutive k of one
-// row; the k-major source is transposed on its way into LDS: a thread fetches an
-// [8 k x 2 m] patch with eight 4-byte loads (a wavefront reads 256 contiguous bytes per k),
-// interleaves the halves and stores two 16-byte rows [m][8 k].
+// row, so the k-major source is transposed on its way into LDS: a thread fetches an
+// [8 k x 8 m] patch with eight 16-byte loads (threads 0..127 the A tile, 128..255 the B
+// tile; a wavefront reads four 256-byte row pieces per load), transposes it in registers
+// and stores eight 16-byte rows [m][8 k].  Workgroup tile 128 x 128 x 64; an LDS row is 64 k
+// = 128 bytes = eight 16-byte units, unit u of row m is kept at position u ^ ((m >> 1) & 7):
+// the MFMA operand reads of 16 consecutive rows then cover all banks once.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-constexpr int BKH = 32;            // k per LDS tile
-constexpr int LDH = BKH + 8;       // row stride in bf16 elements (80 bytes: conflict-free 16-byte reads)
+constexpr int BKH = 64;            // k per LDS tile
 
+__device__ inline uint32_t bf_unit(int m, int u) { return (uint32_t)(m * 128 + ((u ^ ((m >> 1) & 7)) << 4)); }
+
+// thread -> patch: 16 patches along m x 8 along k, for the A tile (tid < 128) or the B tile
 __device__ inline void fetch_patch(const uint16_t* __restrict__ src, int64_t ld, int k0, int m0, int Kdim,
-                                   int Mdim, int tid, bool pair_ok, uint32_t (&d)[8]) {
-    const int mp = tid & 63, kg = tid >> 6;
-    const int m = m0 + 2 * mp;
+                                   int Mdim, int p, bool vec_ok, uint4 (&d)[8]) {
+    const int mq = p & 15, kg = p >> 4;
+    const int m = m0 + 8 * mq;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
         const int k = k0 + 8 * kg + kk;
-        uint32_t v = 0;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (k < Kdim && m < Mdim) {
-            const uint16_t* p = src + (int64_t)k * ld + m;
-            if (pair_ok && m + 1 < Mdim) v = *reinterpret_cast<const uint32_t*>(p);
-            else v = (uint32_t)p[0] | ((m + 1 < Mdim) ? ((uint32_t)p[1] << 16) : 0u);
+            const uint16_t* q = src + (int64_t)k * ld + m;
+            if (vec_ok && m + 8 <= Mdim) {
+                v = *reinterpret_cast<const uint4*>(q);
+            } else {
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (m + j < Mdim) w[j >> 1] |= (uint32_t)q[j] << (16 * (j & 1));
+                v = make_uint4(w[0], w[1], w[2], w[3]);
+            }
         }
         d[kk] = v;
     }
 }
 
-__device__ inline void stage_patch(uint16_t* lds, int tid, const uint32_t (&d)[8]) {
-    const int mp = tid & 63, kg = tid >> 6;
-    uint4 lo, hi;     // row m: low halves, row m+1: high halves, 8 consecutive k each
-    lo.x = (d[0] & 0xFFFFu) | (d[1] << 16); hi.x = (d[0] >> 16) | (d[1] & 0xFFFF0000u);
-    lo.y = (d[2] & 0xFFFFu) | (d[3] << 16); hi.y = (d[2] >> 16) | (d[3] & 0xFFFF0000u);
-    lo.z = (d[4] & 0xFFFFu) | (d[5] << 16); hi.z = (d[4] >> 16) | (d[5] & 0xFFFF0000u);
-    lo.w = (d[6] & 0xFFFFu) | (d[7] << 16); hi.w = (d[6] >> 16) | (d[7] & 0xFFFF0000u);
-    *reinterpret_cast<uint4*>(lds + (2 * mp) * LDH + 8 * kg) = lo;
-    *reinterpret_cast<uint4*>(lds + (2 * mp + 1) * LDH + 8 * kg) = hi;
+// d[kk] holds 8 m of row k0 + kk; LDS row m gets its 8 k as one 16-byte unit
+__device__ inline uint32_t half_of(const uint4& v, int r) {      // element r (0..7) of the 8 packed in v
+    const uint32_t word = (r >> 1) == 0 ? v.x : (r >> 1) == 1 ? v.y : (r >> 1) == 2 ? v.z : v.w;
+    return (r & 1) ? (word >> 16) : (word & 0xFFFFu);
+}
+__device__ inline void stage_patch(char* lds, int p, const uint4 (&d)[8]) {
+    const int mq = p & 15, kg = p >> 4;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const uint4 out = make_uint4(half_of(d[0], r) | (half_of(d[1], r) << 16), half_of(d[2], r) | (half_of(d[3], r) << 16),
+                                     half_of(d[4], r) | (half_of(d[5], r) << 16), half_of(d[6], r) | (half_of(d[7], r) << 16));
+        *reinterpret_cast<uint4*>(lds + bf_unit(8 * mq + r, kg)) = out;
+    }
 }
 
 __global__ __launch_bounds__(256) void k_gemm_tn_bf16(const uint16_t* __restrict__ A, int64_t lda,
                                                       const uint16_t* __restrict__ B, int64_t ldb,
                                                       float* __restrict__ C, int M, int N, int Kdim,
-                                                      int k_per_split, int64_t split_stride, int pair_a,
-                                                      int pair_b) {
-    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDH];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDH];
+                                                      int k_per_split, int64_t split_stride, int vec_a,
+                                                      int vec_b) {
+    __shared__ __attribute__((aligned(16))) char As[BM * 128];
+    __shared__ __attribute__((aligned(16))) char Bs[BN * 128];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int kbeg = blockIdx.z * k_per_split;
+    const int m0 = blockIdx.z * BM, n0 = blockIdx.y * BN;
+    const int kbeg = blockIdx.x * k_per_split;
     const int kend = min(Kdim, kbeg + k_per_split);
-    float* Cz = C + (int64_t)blockIdx.z * split_stride;
+    float* Cz = C + (int64_t)blockIdx.x * split_stride;
+    // this thread's operand tile
+    const bool mine_a = tid < 128;
+    const int p = tid & 127;
+    const uint16_t* src = mine_a ? A : B;
+    const int64_t ld = mine_a ? lda : ldb;
+    const int o0 = mine_a ? m0 : n0, odim = mine_a ? M : N;
+    const bool vec = mine_a ? vec_a != 0 : vec_b != 0;
+    char* dst = mine_a ? As : Bs;
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -223,25 +249,20 @@ __global__ __launch_bounds__(256) void k_gemm_tn_bf16(const uint16_t* __restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint32_t ra[8], rb[8];
-    fetch_patch(A, lda, kbeg, m0, kend, M, tid, pair_a != 0, ra);
-    fetch_patch(B, ldb, kbeg, n0, kend, N, tid, pair_b != 0, rb);
+    uint4 rp[8];
+    fetch_patch(src, ld, kbeg, o0, kend, odim, p, vec, rp);
     const int lk = lane >> 5, lm = lane & 31;
     for (int k0 = kbeg; k0 < kend; k0 += BKH) {
         __syncthreads();
-        stage_patch(As, tid, ra);
-        stage_patch(Bs, tid, rb);
+        stage_patch(dst, p, rp);
         __syncthreads();
-        if (k0 + BKH < kend) {
-            fetch_patch(A, lda, k0 + BKH, m0, kend, M, tid, pair_a != 0, ra);
-            fetch_patch(B, ldb, k0 + BKH, n0, kend, N, tid, pair_b != 0, rb);
-        }
+        if (k0 + BKH < kend) fetch_patch(src, ld, k0 + BKH, o0, kend, odim, p, vec, rp);
 #pragma unroll
-        for (int ks = 0; ks < BKH; ks += 16) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(As + (wm + lm) * LDH + ks + 8 * lk);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(As + (wm + 32 + lm) * LDH + ks + 8 * lk);
-            const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(Bs + (wn + lm) * LDH + ks + 8 * lk);
-            const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(Bs + (wn + 32 + lm) * LDH + ks + 8 * lk);
+        for (int ks = 0; ks < BKH / 8; ks += 2) {          // 16 k per MFMA: units ks + lk
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(As + bf_unit(wm + lm, ks + lk));
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(As + bf_unit(wm + 32 + lm, ks + lk));
+            const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(Bs + bf_unit(wn + lm, ks + lk));
+            const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(Bs + bf_unit(wn + 32 + lm, ks + lk));
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
@@ -269,24 +290,31 @@ __global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, 
     C[i] = s;
 }
 
-// Number of k ranges (blockIdx.z) a GEMM of `tiles` output tiles is split into.  A CU holds
-// four workgroups; the grid should fill 256 x 4 places a whole number of times.  Cost of a
-// choice = (k steps per workgroup x step_us + wg_us) x rounds, a last partial round
-// counting 0.44 / 0.63 / 0.84 / 1 by quarters of the places it fills (fitted to timings
-// of the dense gradient at GPT-2 small / medium / large shapes), plus the pass that adds
-// the partial outputs.
-static int pick_nsplit(int64_t tiles, int Kdim, int bk, double step_us, double wg_us, int64_t max_split) {
-    const int64_t places = 1024;
+// Number of k ranges (blockIdx.x) a GEMM of `tiles` output tiles is split into.  A CU holds
+// `wg_per_cu` workgroups; the grid should fill 256 x wg_per_cu places a whole number of
+// times.  Cost of a choice = (k steps per workgroup x step_us + wg_us) x rounds, a last
+// partial round counting `last[]` by quarters of the places it fills, plus the pass that
+// adds the partial outputs.  Constants fitted to timings of the dense gradient at GPT-2
+// small / medium / large shapes (fp32 kernel: 2.7 % rms error; bf16 kernel: 9 %).
+struct SplitModel {
+    int wg_per_cu, bk;
+    double step_us, wg_us, sum_us_per_float, last[3];
+};
+static const SplitModel kSplitF32 = {4, BK, 4.63, 10.7, 5e-7, {0.44, 0.63, 0.84}};
+static const SplitModel kSplitBf16 = {3, BKH, 2.08, 3.0, 1.8e-6, {0.69, 0.76, 0.86}};
+
+static int pick_nsplit(int64_t tiles, int Kdim, const SplitModel& md, int64_t max_split) {
+    const int64_t places = 256 * md.wg_per_cu;
     int best = 1;
     double best_cost = 0.0;
     const int64_t hi = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, max_split), Kdim / 256));
     for (int ns = 1; ns <= hi; ++ns) {
         const int64_t n = tiles * ns, full = n / places, rest = n % places;
-        const double steps = (double)cdiv(cdiv(Kdim, ns), bk);
+        const double steps = (double)cdiv(cdiv(Kdim, ns), md.bk);
         const double frac = (double)rest / (double)places;
-        const double last = rest == 0 ? 0.0 : frac <= 0.25 ? 0.44 : frac <= 0.5 ? 0.63 : frac <= 0.75 ? 0.84 : 1.0;
-        const double cost = (steps * step_us + wg_us) * ((double)full + last) +
-                            (ns > 1 ? 5e-7 * (double)ns * (double)tiles * 128.0 * 128.0 : 0.0);
+        const double last = rest == 0 ? 0.0 : frac <= 0.25 ? md.last[0] : frac <= 0.5 ? md.last[1] : frac <= 0.75 ? md.last[2] : 1.0;
+        const double cost = (steps * md.step_us + md.wg_us) * ((double)full + last) +
+                            (ns > 1 ? md.sum_us_per_float * (double)ns * (double)tiles * 128.0 * 128.0 : 0.0);
         if (best_cost == 0.0 || cost < best_cost) {
             best_cost = cost;
             best = ns;
@@ -302,10 +330,10 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
     const int tm = 128;
     const int gm = (int)cdiv(M, tm), gn = (int)cdiv(N, 128);
     const int64_t mn = (int64_t)M * N;
-    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, BK, 4.63, 10.7, split_ws_floats / mn) : 1;
+    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, kSplitF32, split_ws_floats / mn) : 1;
     const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), BK) * BK);
     const int nsplit = (int)cdiv(Kdim, kps);
-    dim3 grid(gn, gm, nsplit);
+    dim3 grid(nsplit, gn, gm);
     float* dst = nsplit > 1 ? split_ws : C;
     // 16-byte loads need every row start aligned: leading dimension a multiple of 4
     // elements (the k ranges of the splits start at multiples of BK)
@@ -324,14 +352,14 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
                           int64_t split_ws_floats, hipStream_t s) {
     const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
     const int64_t mn = (int64_t)M * N;
-    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, BKH, 4.63, 10.7, split_ws_floats / mn) : 1;
+    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, kSplitBf16, split_ws_floats / mn) : 1;
     const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), BKH) * BKH);
     const int nsplit = (int)cdiv(Kdim, kps);
-    dim3 grid(gn, gm, nsplit);
+    dim3 grid(nsplit, gn, gm);
     float* dst = nsplit > 1 ? split_ws : C;
-    // 4-byte loads of element pairs need even leading dimensions (bases are 16-byte aligned)
+    // 16-byte loads of 8 elements need leading dimensions that are multiples of 8 (bases are 16-byte aligned)
     k_gemm_tn_bf16<<<grid, 256, 0, s>>>((const uint16_t*)A, M, (const uint16_t*)B, N, dst, M, N, Kdim, kps, mn,
-                                        (M % 2 == 0) ? 1 : 0, (N % 2 == 0) ? 1 : 0);
+                                        (M % 8 == 0) ? 1 : 0, (N % 8 == 0) ? 1 : 0);
     MST_LAUNCH_CHECK();
     if (nsplit > 1) {
         k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
