@@ -3,8 +3,9 @@
 // Storage (not prescribed by the paper, which only names the binary mask M of
 // Sec. 3.2): the active weights are kept once in canonical order (ascending flat
 // index o*I + i) as vals[] / flat[], plus two "views" that the product kernels walk:
-//   row view  S = W    [O x I]  -> forward and weight gradient
+//   row view  S = W    [O x I]  -> forward
 //   col view  S = W^T  [I x O]  -> input gradient
+// (the weight gradient walks whichever of the two is cheaper, see build_views).
 // A view cuts the contraction index into chunks of KC and stores, per (chunk, block of
 // 16 rows, quad), an ELL slice of four rows (see View in common.h).  perm[] maps an
 // entry slot back to its canonical position, so that values can be refreshed after an

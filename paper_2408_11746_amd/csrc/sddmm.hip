@@ -3,16 +3,18 @@
 // backward = 2 x forward).
 //
 // Same decomposition and lane mapping as the SpMM: a workgroup owns TT = 128 tokens and
-// a row block (or half of one) of the driving view per wavefront, stages chunks of one
-// dense operand in LDS and walks the ELL slices (written below for the row view: X is
-// staged, dY sits in registers; the col view swaps the two).  A lane keeps dY of its 8 tokens for the 4 rows of its lane group in
-// registers; entries reach the lanes as in the SpMM (batches of four pairs, handed round
-// the groups of four lanes through DPP operands); per step a lane reads its 8 X values of the entry's column from LDS, forms the
-// 8-term dot product and the 16 lanes of the group add their parts with four DPP row
-// shifts -- all four lane groups (four entries) at once, no LDS traffic.  Lane 15 of
-// each group stores the per-(token tile, entry slot) partial sums; a second kernel adds
-// the partials of all token tiles in a fixed order (deterministic, no floating-point
-// atomics) and writes the result at the entry's canonical position.
+// two to four quads of the driving view per wavefront, stages chunks of one dense operand
+// in LDS and walks the ELL slices (written below for the row view: X is staged, dY sits in
+// registers; the col view swaps the two).  A lane keeps dY of its 8 tokens for the row of
+// its lane group in every quad (brought in through LDS so that the global reads are
+// contiguous); entries reach the lanes as in the SpMM (batches of four pairs, handed round
+// the groups of four lanes through DPP operands).  Per step a lane reads its 8 X values
+// of the entry's column from LDS and forms the 8-term dot product; the sums over the 16
+// lanes of a group are taken for the two entries of a pair together with DPP adds -- all
+// four lane groups at once, no LDS traffic.  One lane per entry stores the per-(token
+// tile, entry slot) partial sum; a second kernel adds the partials of all token tiles in a
+// fixed order (deterministic, no floating-point atomics) and writes the result at the
+// entry's canonical position.
 #include "tile_loader.h"
 
 namespace mst {

@@ -2,17 +2,18 @@
 // Serves the forward product (S = W, A = X; App. "FLOP Calculation" Eq. (1)) and the
 // input gradient (S = W^T, A = dY; the first half of the backward pass).
 //
-// A workgroup of 16 wavefronts owns TT = 128 tokens and a slab of 256 rows (a row block of
-// 16 rows per wavefront) or 128 rows (half a block per wavefront).  It walks the
-// contraction index in chunks of KC: the chunk of A is staged (transposed) in LDS, then
-// each wavefront walks its row block's ELL slices.  A wavefront is four lane groups of 16
-// lanes; in one step each lane group multiplies ONE entry (its own row of the quad)
-// with 128 tokens, 8 per lane: the entry {offset, weight} comes from a small
-// per-wavefront LDS buffer that the wavefront refills in batches with one coalesced
-// vector load (next batch in flight while the current one is consumed), the 8 activations
-// from two 16-byte LDS reads, then 8 FMAs into the accumulators of that row, which stay
-// in registers for the whole K loop.  Nothing in the inner loop touches global memory,
-// the scalar unit or another lane.  The result tile leaves through LDS so that global
+// A workgroup of 16 wavefronts owns a tile of tokens (128 in k_spmm, 64 in k_spmm64) and a
+// slab of rows (64 rows per quad-per-wavefront: 128 .. 512).  It walks the contraction index
+// in chunks of KC: the chunk of A is staged (transposed) in LDS, then each wavefront walks
+// the ELL slices of its quads.  A wavefront is four lane groups of 16 lanes; in one step
+// each lane group multiplies ONE entry (its own row of the quad) with all tokens of the
+// tile, 8 (4) per lane.  The entries {offset, weight} come straight from global memory:
+// a lane loads 16 bytes (one pair of its lane group) of a batch of four pairs, the next
+// batch is in flight while the current one is used, and the four lanes of a group of four
+// hand their pairs round through DPP operands of the address XOR and of the FMAs.  The
+// activations come from 16-byte LDS reads; the accumulators of a row stay in registers for
+// the whole K loop.  Nothing in the inner loop touches LDS for entries, the scalar unit or
+// a lane outside the group of four.  The result tile leaves through LDS so that global
 // stores are contiguous runs of the slab's columns.
 #include "tile_loader.h"
 
