@@ -224,6 +224,18 @@ def test_bf16_activations_fp32_accumulate():
     assert rel_err(G.cpu().numpy(), opr.dense_grad(dYf, Xf)) <= TOL
 
 
+@pytest.mark.parametrize("T,I,O", [(333, 130, 203), (1000, 264, 72), (70, 8, 8)])
+def test_bf16_dense_grad_ragged_shapes(T, I, O):
+    """The bf16 MFMA gradient where rows are not multiples of eight elements (element-wise
+    edge loads), tiles are partial and the k range does not fill a step."""
+    Xf, dYf, xb, yb = synth.make_activations(12, 3, T, I, O, "bf16")
+    G = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(mst.mst_workspace_bytes(O, I, 16, T), dtype=torch.uint8, device=DEV)
+    mst.mst_dense_grad(dev(yb.view(np.int16)), dev(xb.view(np.int16)), G, T, O, I, mst.MST_BF16, ws)
+    torch.cuda.synchronize()
+    assert rel_err(G.cpu().numpy(), opr.dense_grad(dYf, Xf)) <= TOL
+
+
 def test_results_are_bit_reproducible():
     W, M, X, dY = _case(10, 384, 256, 384, 0.1)
     rig = Rig(W, M, 384)
