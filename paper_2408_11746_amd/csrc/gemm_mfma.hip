@@ -103,15 +103,15 @@ __device__ inline void stage_tile(float* lds, int tid, const float (&v)[4 * Tile
 
 // TM x 128 workgroup tile, TM / 64 x 2 wavefronts of 64 x 64 each
 template <typename TA, bool A_KMAJOR, typename TB, bool B_KMAJOR, int TM>
-__global__ __launch_bounds__(TM * 2) void k_gemm(const TA* __restrict__ A, int64_t lda,
+__global__ __launch_bounds__(TM * 2) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gemm(const TA* __restrict__ A, int64_t lda,
                                                  const TB* __restrict__ B, int64_t ldb,
                                                  float* __restrict__ C, int M, int N, int Kdim, int k_per_split,
                                                  int64_t split_stride, int vec_a, int vec_b) {
     constexpr int NT = TM * 2, TNW = 128;
     typedef TileShape<TM, NT> SA;
     typedef TileShape<TNW, NT> SB;
-    __shared__ float As[BK * SA::LD];
-    __shared__ float Bs[BK * SB::LD];
+    __shared__ float As[2][BK * SA::LD];
+    __shared__ float Bs[2][BK * SB::LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int m0 = blockIdx.z * TM, n0 = blockIdx.y * TNW;
@@ -127,30 +127,43 @@ __global__ __launch_bounds__(TM * 2) void k_gemm(const TA* __restrict__ A, int64
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // Two LDS buffers, one barrier per step: while buffer b is multiplied, the registers
+    // (tile s + 1, fetched during step s - 1) go to buffer b ^ 1 and tile s + 2 is fetched.
     float ra[4 * SA::IPT], rb[4 * SB::IPT];
     fetch_tile<TA, A_KMAJOR, TM, NT>(A, lda, kbeg, m0, kend, M, tid, vec_a != 0, ra);
     fetch_tile<TB, B_KMAJOR, TNW, NT>(B, ldb, kbeg, n0, kend, N, tid, vec_b != 0, rb);
+    stage_tile<A_KMAJOR, TM, NT>(As[0], tid, ra);
+    stage_tile<B_KMAJOR, TNW, NT>(Bs[0], tid, rb);
+    if (kbeg + BK < kend) {
+        fetch_tile<TA, A_KMAJOR, TM, NT>(A, lda, kbeg + BK, m0, kend, M, tid, vec_a != 0, ra);
+        fetch_tile<TB, B_KMAJOR, TNW, NT>(B, ldb, kbeg + BK, n0, kend, N, tid, vec_b != 0, rb);
+    }
+    __syncthreads();
     const int lk = lane >> 5, lm = lane & 31;
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
-        __syncthreads();                       // previous tile fully consumed
-        stage_tile<A_KMAJOR, TM, NT>(As, tid, ra);
-        stage_tile<B_KMAJOR, TNW, NT>(Bs, tid, rb);
-        __syncthreads();
-        if (k0 + BK < kend) {                  // next tile travels while this one is multiplied
-            fetch_tile<TA, A_KMAJOR, TM, NT>(A, lda, k0 + BK, m0, kend, M, tid, vec_a != 0, ra);
-            fetch_tile<TB, B_KMAJOR, TNW, NT>(B, ldb, k0 + BK, n0, kend, N, tid, vec_b != 0, rb);
+    int buf = 0;
+    for (int k0 = kbeg; k0 < kend; k0 += BK, buf ^= 1) {
+        const float* as = As[buf];
+        const float* bs = Bs[buf];
+        if (k0 + BK < kend) {                  // the next tile goes to the other buffer ...
+            stage_tile<A_KMAJOR, TM, NT>(As[buf ^ 1], tid, ra);
+            stage_tile<B_KMAJOR, TNW, NT>(Bs[buf ^ 1], tid, rb);
+            if (k0 + 2 * BK < kend) {          // ... and the one after it starts to travel
+                fetch_tile<TA, A_KMAJOR, TM, NT>(A, lda, k0 + 2 * BK, m0, kend, M, tid, vec_a != 0, ra);
+                fetch_tile<TB, B_KMAJOR, TNW, NT>(B, ldb, k0 + 2 * BK, n0, kend, N, tid, vec_b != 0, rb);
+            }
         }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            const float a0 = As[(kk + lk) * SA::LD + wm + lm];
-            const float a1 = As[(kk + lk) * SA::LD + wm + 32 + lm];
-            const float b0 = Bs[(kk + lk) * SB::LD + wn + lm];
-            const float b1 = Bs[(kk + lk) * SB::LD + wn + 32 + lm];
+            const float a0 = as[(kk + lk) * SA::LD + wm + lm];
+            const float a1 = as[(kk + lk) * SA::LD + wm + 32 + lm];
+            const float b0 = bs[(kk + lk) * SB::LD + wn + lm];
+            const float b1 = bs[(kk + lk) * SB::LD + wn + 32 + lm];
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
         }
+        __syncthreads();
     }
 
     // D layout of the 32x32 MFMA: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
