@@ -198,7 +198,7 @@ def main():
     # product dY^T X read at the active positions from a density of 0.045 on (T >= 2048)
     mfma_bww = drow["call"] == "bwd_weight" and act == "bf16" and density > 0.045 and T >= 2048
     if mfma_bww:
-        kernel = "k_gemm_tn_bf16+k_splitk_reduce+k_gather_flat"
+        kernel = "k_gemm_tn_bf16+k_gather_flat"
         dense_tf = 2.0 * T * dL.O * dL.I / drow["avg_ms"] / 1e9
         roof = dict(bound="mfma", achieved=round(dense_tf, 1), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=round(dense_tf / MFMA_BF16_PEAK_TFLOPS, 4))

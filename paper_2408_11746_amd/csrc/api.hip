@@ -4,10 +4,17 @@
 
 namespace mst {
 
-__global__ void k_gather_flat(const float* __restrict__ G, const int* __restrict__ flat, int64_t nnz,
-                              float* __restrict__ out) {
+// out[k] = sum over the nparts partial outputs (stride apart, added in ascending order) at
+// the k-th active position: the split sum of the dense gradient is only formed where the
+// weight gradient is wanted
+__global__ void k_gather_flat(const float* __restrict__ G, int64_t stride, int nparts, const int* __restrict__ flat,
+                              int64_t nnz, float* __restrict__ out) {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < nnz) out[k] = G[flat[k]];
+    if (k >= nnz) return;
+    const float* g = G + flat[k];
+    float sum = 0.f;
+    for (int z = 0; z < nparts; ++z) sum += g[(int64_t)z * stride];
+    out[k] = sum;
 }
 
 static int ensure_dense_copy(const mst_layer* L, hipStream_t s) {
@@ -29,10 +36,12 @@ int dense_products_bwd_input(const mst_layer* L, const void* dY, float* dX, int 
 
 int dense_products_bwd_weight(const mst_layer* L, const void* dY, const void* X, float* dW, int T,
                               mst_dtype act, const Workspace& ws, hipStream_t s) {
-    int rc = gemm_mfma(GEMM_TN, dY, act, X, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s);
+    int nparts = 1;
+    int rc = gemm_mfma(GEMM_TN, dY, act, X, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s, &nparts);
     if (rc != MST_OK) return rc;
     if (L->nnz > 0) {
-        k_gather_flat<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(ws.G, L->flat, L->nnz, dW);
+        k_gather_flat<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(nparts > 1 ? ws.gemm : ws.G, L->N, nparts, L->flat,
+                                                                  L->nnz, dW);
         MST_LAUNCH_CHECK();
     }
     return MST_OK;

@@ -336,9 +336,11 @@ static int pick_nsplit(int64_t tiles, int Kdim, const SplitModel& md, int64_t ma
     return best;
 }
 
+// `left_unsummed`: if not null the partial outputs of a split stay in split_ws and their number
+// is returned there (1: the result is in C); otherwise they are added into C.
 template <typename TA, bool AK, typename TB, bool BKM>
 static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
-                  float* split_ws, int64_t split_ws_floats, hipStream_t s) {
+                  float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
     // (a 256 x 128 tile was measured: a third less operand traffic per flop, no gain in time)
     const int tm = 128;
     const int gm = (int)cdiv(M, tm), gn = (int)cdiv(N, 128);
@@ -354,6 +356,10 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
     k_gemm<TA, AK, TB, BKM, 128><<<grid, 256, 0, s>>>((const TA*)A, lda, (const TB*)B, ldb, dst, M, N, Kdim, kps, mn,
                                                      vec_a, vec_b);
     MST_LAUNCH_CHECK();
+    if (left_unsummed) {
+        *left_unsummed = nsplit;
+        return MST_OK;
+    }
     if (nsplit > 1) {
         k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
         MST_LAUNCH_CHECK();
@@ -362,7 +368,7 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
 }
 
 static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, int Kdim, float* split_ws,
-                          int64_t split_ws_floats, hipStream_t s) {
+                          int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
     const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
     const int64_t mn = (int64_t)M * N;
     const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, kSplitBf16, split_ws_floats / mn) : 1;
@@ -374,6 +380,10 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
     k_gemm_tn_bf16<<<grid, 256, 0, s>>>((const uint16_t*)A, M, (const uint16_t*)B, N, dst, M, N, Kdim, kps, mn,
                                         (M % 8 == 0) ? 1 : 0, (N % 8 == 0) ? 1 : 0);
     MST_LAUNCH_CHECK();
+    if (left_unsummed) {
+        *left_unsummed = nsplit;
+        return MST_OK;
+    }
     if (nsplit > 1) {
         k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
         MST_LAUNCH_CHECK();
@@ -385,21 +395,21 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
 // NT: C[M x N] = A B^T, A [M x K], B [N x K] (fp32)   (Y = X Wd^T)
 // NN: C[M x N] = A B,   A [M x K], B [K x N] (fp32)   (dX = dY Wd)
 int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_dtype b_dt, float* C,
-              int M, int N, int Kdim, float* split_ws, int64_t split_ws_floats, hipStream_t s) {
+              int M, int N, int Kdim, float* split_ws, int64_t split_ws_floats, hipStream_t s, int* left_unsummed) {
     const bool ab = a_dt == MST_BF16, bb = b_dt == MST_BF16;
     switch (kind) {
         case GEMM_TN:
             if (ab != bb) return MST_ERR_ARG;
-            if (ab) return launch_tn_bf16(A, B, C, M, N, Kdim, split_ws, split_ws_floats, s);
-            return launch<float, true, float, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
+            if (ab) return launch_tn_bf16(A, B, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
+            return launch<float, true, float, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NT:
             if (bb) return MST_ERR_ARG;
-            if (ab) return launch<uint16_t, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, s);
-            return launch<float, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, s);
+            if (ab) return launch<uint16_t, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
+            return launch<float, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NN:
             if (bb) return MST_ERR_ARG;
-            if (ab) return launch<uint16_t, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
-            return launch<float, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, s);
+            if (ab) return launch<uint16_t, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
+            return launch<float, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
     }
     return MST_ERR_ARG;
 }
