@@ -193,7 +193,9 @@ def main():
     t_hbm = drow["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_alu = drow["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
     # fwd / bwd_input are one k_spmm launch; bwd_weight is k_sddmm followed by the small k_sddmm_reduce
-    kernel = {"fwd": "k_spmm", "bwd_input": "k_spmm", "bwd_weight": "k_sddmm+k_sddmm_reduce"}[drow["call"]]
+    kernel = {"fwd": "k_spmm / k_spmm64 (launch shape chosen per call)",
+              "bwd_input": "k_spmm / k_spmm64 (launch shape chosen per call)",
+              "bwd_weight": "k_sddmm+k_sddmm_reduce"}[drow["call"]]
     # with bfloat16 activations the library computes the weight gradient as the full MFMA
     # product dY^T X read at the active positions from a density of 0.045 on (T >= 2048)
     mfma_bww = drow["call"] == "bwd_weight" and act == "bf16" and density > 0.045 and T >= 2048
