@@ -69,16 +69,34 @@ __device__ inline uint32_t quad_bcast(uint32_t v) {
 
 constexpr int NW = 16;      // wavefronts per workgroup
 
+// One driving view's operands: its ELL arrays, the dense operand it stages in LDS and the one
+// its lanes keep in registers.
+template <typename TIn>
+struct SddmmSide {
+    const TIn* __restrict__ staged;      // [T x K]
+    const TIn* __restrict__ inreg;       // [T x R]
+    const int* __restrict__ ptr;
+    const uint4* __restrict__ ent;
+    const int* __restrict__ rowmap;
+    const int* __restrict__ perm;
+    int64_t slots_stride;                // partial-sum slots per token tile
+    int64_t nseg;
+    int K, R, NBpad, nchunk, nslab, vec_ok, vec_reg;
+};
+
 // QW = quads per wavefront (consecutive quads, which may cross row blocks): the slab of a
 // workgroup is 64 QW rows of the driving view
 template <typename TIn, int QW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* __restrict__ dY /* register operand [T x R] */,
-             const int* __restrict__ ptr,
-             const uint4* __restrict__ ent, const int* __restrict__ rowmap, float* __restrict__ partial, int64_t slots_stride, int T, int K,
-             int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_reg, const int* __restrict__ choice, int me) {
-    __shared__ float tile[KC * TT];
-    if (*choice != me) return;                        // the other view drives this layer's weight gradient
+__device__ __forceinline__ void sddmm_side(const SddmmSide<TIn>& a, float* __restrict__ tile, float* __restrict__ partial,
+                                           int T, int ntile) {
+    const TIn* __restrict__ X = a.staged;
+    const TIn* __restrict__ dY = a.inreg;
+    const int* __restrict__ ptr = a.ptr;
+    const uint4* __restrict__ ent = a.ent;
+    const int* __restrict__ rowmap = a.rowmap;
+    const int64_t slots_stride = a.slots_stride;
+    const int K = a.K, R = a.R, NBpad = a.NBpad, nchunk = a.nchunk, nslab = a.nslab;
+    const int vec_ok = a.vec_ok, vec_reg = a.vec_reg;
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
     const int tid = threadIdx.x;
@@ -164,17 +182,30 @@ void k_sddmm(const TIn* __restrict__ X /* staged operand [T x K] */, const TIn* 
     }
 }
 
+// Either view can drive the product; which one does is a device-side flag set when the views
+// were built.  One launch serves both: its grid covers the larger of the two, and every
+// workgroup takes the side the flag names (QW0 quads per wavefront for the row view, QW1
+// for the col view).
+template <typename TIn, int QW0, int QW1>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k_sddmm(const SddmmSide<TIn> row, const SddmmSide<TIn> col, float* __restrict__ partial, int T, int ntile,
+             const int* __restrict__ choice) {
+    __shared__ float tile[KC * TT];
+    if (*choice) sddmm_side<TIn, QW1>(col, tile, partial, T, ntile);
+    else sddmm_side<TIn, QW0>(row, tile, partial, T, ntile);
+}
+
 // dW[perm[e]] = sum over token tiles of partial[tile][e], tiles added in ascending order
-__global__ void k_sddmm_reduce(const float* __restrict__ partial, int64_t slots_stride, int ntile,
-                               const int* __restrict__ ptr, int64_t nseg, const int* __restrict__ perm,
-                               float* __restrict__ dW, const int* __restrict__ choice, int me) {
-    if (*choice != me) return;
+template <typename TIn>
+__global__ void k_sddmm_reduce(const float* __restrict__ partial, int ntile, const SddmmSide<TIn> row,
+                               const SddmmSide<TIn> col, float* __restrict__ dW, const int* __restrict__ choice) {
+    const SddmmSide<TIn>& a = *choice ? col : row;
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (int64_t)ptr[nseg] * 8) return;
-    const int p = perm[e];
+    if (e >= (int64_t)a.ptr[a.nseg] * 8) return;
+    const int p = a.perm[e];
     if (p < 0) return;
     float sum = 0.f;
-    for (int t = 0; t < ntile; ++t) sum += partial[(int64_t)t * slots_stride + e];
+    for (int t = 0; t < ntile; ++t) sum += partial[(int64_t)t * a.slots_stride + e];
     dW[p] = sum;
 }
 
@@ -209,40 +240,59 @@ static int pick_sddmm_quads(int T, int R, int K, double density) {
     return best;
 }
 
-template <typename TIn, int QW>
-static void launch_k(const View& v, const TIn* staged, const TIn* inreg, float* partial, int64_t stride, int T,
-                     const int* choice, int me, hipStream_t s) {
-    const int ntile = (int)cdiv(T, TT);
-    const int nslab = (int)cdiv((int64_t)v.NB * 4, NW * QW);
-    k_sddmm<TIn, QW><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(staged, inreg, v.ptr, v.ent, v.rowmap, partial, stride, T,
-                                                               v.K, v.R, v.NBpad, v.nchunk, nslab, ntile,
-                                                               (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0, choice, me);
+template <typename TIn, int QW0, int QW1>
+static void launch_k(const SddmmSide<TIn>& row, const SddmmSide<TIn>& col, float* partial, int T, int ntile,
+                     const int* choice, hipStream_t s) {
+    const unsigned grid = std::max(grid_for(ntile, row.nslab), grid_for(ntile, col.nslab));
+    k_sddmm<TIn, QW0, QW1><<<grid, NW * 64, 0, s>>>(row, col, partial, T, ntile, choice);
+}
+
+template <typename TIn, int QW0>
+static void launch_q(int qw1, const SddmmSide<TIn>& row, const SddmmSide<TIn>& col, float* partial, int T, int ntile,
+                     const int* choice, hipStream_t s) {
+    if (qw1 == 4) launch_k<TIn, QW0, 4>(row, col, partial, T, ntile, choice, s);
+    else if (qw1 == 3) launch_k<TIn, QW0, 3>(row, col, partial, T, ntile, choice, s);
+    else launch_k<TIn, QW0, 2>(row, col, partial, T, ntile, choice, s);
 }
 
 // The product is symmetric in its two dense operands: either view can drive it.  The row
 // view stages X and keeps dY in registers, the col view stages dY and keeps X in registers.
-// Which one is a device-side flag set when the views were built (the host does not know the
-// views' padded sizes without a synchronisation): both are launched, the workgroups of
-// the one not chosen leave at once.
+// The host does not know which one the layer uses (that would take a synchronisation after
+// the views were built), so it passes both sides to one launch of each kernel.
 template <typename TIn>
 static int launch_sddmm(const mst_layer* L, const TIn* dY, const TIn* X, float* dW, int T,
                         const Workspace& ws, hipStream_t s) {
     const int ntile = (int)cdiv(T, TT);
+    SddmmSide<TIn> side[2];
+    int qw[2];
+    int64_t upper = 0;
     for (int me = 0; me < 2; ++me) {
         const View& v = me ? L->col : L->row;
-        const TIn* staged = me ? dY : X;
-        const TIn* inreg = me ? X : dY;
-        const int qw = pick_sddmm_quads(T, v.R, v.K, (double)L->nnz / ((double)v.R * (double)v.K));
-        const int64_t stride = v.cap_pairs * 8;
-        if (qw == 4) launch_k<TIn, 4>(v, staged, inreg, ws.partial, stride, T, L->sddmm_view, me, s);
-        else if (qw == 3) launch_k<TIn, 3>(v, staged, inreg, ws.partial, stride, T, L->sddmm_view, me, s);
-        else launch_k<TIn, 2>(v, staged, inreg, ws.partial, stride, T, L->sddmm_view, me, s);
-        MST_LAUNCH_CHECK();
-        const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
-        k_sddmm_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, stride, ntile, v.ptr, v.nseg, v.perm, dW,
-                                                                  L->sddmm_view, me);
-        MST_LAUNCH_CHECK();
+        qw[me] = pick_sddmm_quads(T, v.R, v.K, (double)L->nnz / ((double)v.R * (double)v.K));
+        SddmmSide<TIn>& a = side[me];
+        a.staged = me ? dY : X;
+        a.inreg = me ? X : dY;
+        a.ptr = v.ptr;
+        a.ent = v.ent;
+        a.rowmap = v.rowmap;
+        a.perm = v.perm;
+        a.slots_stride = v.cap_pairs * 8;
+        a.nseg = v.nseg;
+        a.K = v.K;
+        a.R = v.R;
+        a.NBpad = v.NBpad;
+        a.nchunk = v.nchunk;
+        a.nslab = (int)cdiv((int64_t)v.NB * 4, NW * qw[me]);
+        a.vec_ok = (v.K % 4 == 0) ? 1 : 0;
+        a.vec_reg = (v.R % 4 == 0) ? 1 : 0;
+        upper = std::max(upper, 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4));
     }
+    if (qw[0] == 4) launch_q<TIn, 4>(qw[1], side[0], side[1], ws.partial, T, ntile, L->sddmm_view, s);
+    else if (qw[0] == 3) launch_q<TIn, 3>(qw[1], side[0], side[1], ws.partial, T, ntile, L->sddmm_view, s);
+    else launch_q<TIn, 2>(qw[1], side[0], side[1], ws.partial, T, ntile, L->sddmm_view, s);
+    MST_LAUNCH_CHECK();
+    k_sddmm_reduce<TIn><<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, ntile, side[0], side[1], dW, L->sddmm_view);
+    MST_LAUNCH_CHECK();
     return MST_OK;
 }
 
