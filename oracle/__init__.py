@@ -3,7 +3,7 @@
 TEST INFRASTRUCTURE ONLY.  This package is the plain, slow, obviously-correct
 statement of what the hot path computes, written from the paper (Sec. 3.1
 "Sparsity Variation", Sec. 3.2 / Algorithm 1 "Topology Evolution by MG",
-App. "FLOP Calculation" Eq. (1)).  Only the test-suite, the smoke check and the
+Sec. 3.3 strided attention pattern, App. "FLOP Calculation").  Only the test-suite, the smoke check and the
 benchmark's ``cpu_baseline`` leg may import it; the product (the HIP library and
 its Python binding) never does and shares no code with it.
 
@@ -25,4 +25,14 @@ Pin status (see tests/test_oracle_*.py):
   mixed_growing.update              pinned: brute force with Python's sorted() on tiny
                                     inputs, set invariants, R=0 / R=1 special cases,
                                     chi-square uniformity of the random part.
+  allocation.erdos_renyi_density    pinned: hand-computed densities of the GPT-2-small block
+                                    and of a saturating pair, budget conservation, an
+                                    independent bisection solve, special cases.
+  flops.fc_forward / transformer    pinned: the FLOPs column of the main results table
+                                    (static-sparse 80 %, Tiny, dense), multiply-add brute
+                                    counts.  The table's MST row (219.4 G) is not
+                                    reproduced by any reading tried (226.2 G here): the
+                                    schedule average is parity unpinned against it.
+  attention_mask.strided_mask       pinned: the printed Q_atten of strides 128 and 256,
+                                    the set definition, a closed-form count.
 """
