@@ -12,6 +12,8 @@
  *   mst_sparse_fc_bwd_weight  dW = (dY^T X) at active positions only
  *   mst_mask_update           Algorithm 1 "Topology Evolution by MG"
  *   mst_schedule_density      Sec. 3.1 "Sparsity Variation" + Sec. 3.2 update fraction
+ * and around them the per-layer density allocation of Sec. 3.2, the FLOP counts of
+ * App. "FLOP Calculation" and the strided attention pattern of Sec. 3.3.
  *
  * Conventions
  *   - Every pointer named *_dev is DEVICE memory, owned by the caller, 16-byte aligned;
@@ -188,6 +190,62 @@ int mst_mask_update(mst_layer_t* layer, const void* dY_dev, const void* X_dev, i
  * Either output pointer may be NULL. */
 int mst_schedule_density(const mst_schedule_cfg* cfg, int64_t step,
                          double* density_out, double* zeta_out);
+
+/* ------------------------------------------------------ per-layer densities */
+
+/* Pure host.  Sec. 3.2: the network's density d is spread over the layers by the
+ * Erdos-Renyi strategy,
+ *   d_l = min(1, eps (I_l + O_l) / (I_l O_l)),   sum_l d_l I_l O_l = d sum_l I_l O_l,
+ * a layer whose share would exceed 1 being dense and eps solved for the others.
+ * O, I, density_out: host arrays of n_layers entries (the caller's list decides which
+ * layers take part).  The densities feed the target_density argument of the update
+ * calls, whose count rule turns them into integers.
+ * MST_ERR_ARG: null pointer, n_layers < 1, a dimension < 1, d outside [0, 1]. */
+int mst_erdos_renyi_density(int n_layers, const int* O, const int* I, double global_density,
+                            double* density_out);
+
+/* ------------------------------------------------------------- FLOP counts */
+
+/* Pure host.  App. "FLOP Calculation", Eq. (1): forward FLOPs of the layers for one
+ * token, sum_l (1 - S_l)(2 I_l - 1) O_l with S_l = 1 - density[l]. */
+int mst_flops_fc_forward(int n_layers, const int* O, const int* I, const double* density,
+                         double* flops_out);
+
+typedef struct {
+    int64_t L;             /* input sequence length */
+    int64_t N_embd;        /* embedding dimensionality */
+    int64_t D_ffw;         /* feed-forward size (commonly 4 N_embd) */
+    int64_t D_vocab;       /* vocabulary size */
+    int64_t n_layers;      /* model depth */
+} mst_transformer_shape;
+
+typedef struct {
+    double kqv, scores, reduce, proj, ffw1, ffw2, lm;   /* one block's terms; lm once */
+    double forward, backward, total;                    /* whole model, one sequence */
+} mst_transformer_flops;
+
+/* Pure host.  The seven terms of the same appendix for one sequence, with sparsity
+ * S = 1 - density on every fully-connected term (the output layer included) and the
+ * attention ratio q_atten on the two attention products; the second of them is read as
+ * 2 L L N_embd (all heads together).  forward = n_layers (attention + MLP) + lm,
+ * backward = 2 forward, total = forward + backward.
+ * MST_ERR_ARG: null pointer, a size < 1, density or q_atten outside [0, 1]. */
+int mst_flops_transformer(const mst_transformer_shape* shape, double density, double q_atten,
+                          mst_transformer_flops* out);
+
+/* --------------------------------------------- strided attention pattern */
+
+/* Sec. 3.3, unfactorized strided sparse self-attention shared by all heads: output i
+ * attends to the previous `stride` positions and to every stride-th position before it,
+ *   S_i = { max(i - l + 1, 0), ..., i }  union  { j <= i : (i - j) mod l = 0 }
+ * (the text's description; the printed intersection is taken to be a misprint).
+ * Writes M_dev [L x L] bytes, row-major, M[i][j] = 1 iff j in S_i.  1 <= L <= 32768,
+ * stride >= 1.  Asynchronous on `stream`. */
+int mst_strided_attention_mask(uint8_t* M_dev, int L, int stride, mst_stream_t stream);
+
+/* Pure host.  Number of (i, j) pairs the pattern keeps; Q_atten of the appendix's
+ * pattern table is this count over L * L. */
+int mst_strided_attention_count(int L, int stride, int64_t* count_out);
 
 #ifdef __cplusplus
 }

@@ -22,6 +22,11 @@ from .binding import (  # noqa: F401
     mst_mask_update_from_scores,
     mst_dense_grad,
     mst_spmm_force_shape,
+    mst_erdos_renyi_density,
+    mst_flops_fc_forward,
+    mst_flops_transformer,
+    mst_strided_attention_mask,
+    mst_strided_attention_count,
     MST_F32,
     MST_BF16,
     MST_PATH_AUTO,

@@ -36,6 +36,19 @@ class UpdateStats(C.Structure):
         return {k: int(getattr(self, k)) for k, _ in self._fields_}
 
 
+class TransformerShape(C.Structure):
+    _fields_ = [("L", C.c_int64), ("N_embd", C.c_int64), ("D_ffw", C.c_int64), ("D_vocab", C.c_int64),
+                ("n_layers", C.c_int64)]
+
+
+class TransformerFlops(C.Structure):
+    _fields_ = [(k, C.c_double) for k in ("kqv", "scores", "reduce", "proj", "ffw1", "ffw2", "lm", "forward",
+                                          "backward", "total")]
+
+    def as_dict(self):
+        return {k: float(getattr(self, k)) for k, _ in self._fields_}
+
+
 def lib_path() -> str:
     return os.path.join(HERE, "libmst_hip.so")
 
@@ -77,6 +90,11 @@ def lib() -> C.CDLL:
         "mst_mask_update_from_scores": (i32, [vp, vp, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
         "mst_mask_update": (i32, [vp, vp, vp, i32, i32, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
         "mst_schedule_density": (i32, [C.POINTER(_ScheduleCfgC), i64, C.POINTER(dbl), C.POINTER(dbl)]),
+        "mst_erdos_renyi_density": (i32, [i32, C.POINTER(i32), C.POINTER(i32), dbl, C.POINTER(dbl)]),
+        "mst_flops_fc_forward": (i32, [i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(dbl), C.POINTER(dbl)]),
+        "mst_flops_transformer": (i32, [C.POINTER(TransformerShape), dbl, dbl, C.POINTER(TransformerFlops)]),
+        "mst_strided_attention_mask": (i32, [vp, i32, i32, vp]),
+        "mst_strided_attention_count": (i32, [i32, i32, C.POINTER(i64)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -90,7 +108,8 @@ EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_w
            "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_spmm_force_shape",
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
-           "mst_schedule_density"]
+           "mst_schedule_density", "mst_erdos_renyi_density", "mst_flops_fc_forward", "mst_flops_transformer",
+           "mst_strided_attention_mask", "mst_strided_attention_count"]
 
 
 def _check(fn: str, code: int):
@@ -249,3 +268,48 @@ def mst_mask_update(layer: Layer, dY, X, T: int, target_density: float, zeta: fl
            lib().mst_mask_update(layer.h, _ptr(dY), _ptr(X), T, act, target_density, zeta, rand_ratio, rng_seed,
                                  _ptr(ws), ws.numel(), C.byref(st), _stream(stream)))
     return st.as_dict()
+
+
+def _shape_arrays(shapes):
+    n = len(shapes)
+    O = (C.c_int * max(n, 1))(*[int(o) for o, _ in shapes])
+    I = (C.c_int * max(n, 1))(*[int(i) for _, i in shapes])
+    return n, O, I
+
+
+def mst_erdos_renyi_density(shapes, global_density: float):
+    """shapes = [(O_l, I_l)] -> per-layer densities."""
+    n, O, I = _shape_arrays(shapes)
+    out = (C.c_double * max(n, 1))()
+    _check("mst_erdos_renyi_density", lib().mst_erdos_renyi_density(n, O, I, float(global_density), out))
+    return [float(out[l]) for l in range(n)]
+
+
+def mst_flops_fc_forward(shapes, density) -> float:
+    n, O, I = _shape_arrays(shapes)
+    if len(density) != n:
+        raise ValueError("one density per layer")
+    d = (C.c_double * max(n, 1))(*[float(x) for x in density])
+    out = C.c_double(0.0)
+    _check("mst_flops_fc_forward", lib().mst_flops_fc_forward(n, O, I, d, C.byref(out)))
+    return float(out.value)
+
+
+def mst_flops_transformer(L: int, N_embd: int, D_ffw: int, D_vocab: int, n_layers: int, density: float,
+                          q_atten: float) -> dict:
+    shape = TransformerShape(int(L), int(N_embd), int(D_ffw), int(D_vocab), int(n_layers))
+    out = TransformerFlops()
+    _check("mst_flops_transformer", lib().mst_flops_transformer(C.byref(shape), float(density), float(q_atten),
+                                                                 C.byref(out)))
+    return out.as_dict()
+
+
+def mst_strided_attention_mask(M, L: int, stride: int, stream=None):
+    """M: uint8 device tensor of L * L elements."""
+    _check("mst_strided_attention_mask", lib().mst_strided_attention_mask(_ptr(M), int(L), int(stride), _stream(stream)))
+
+
+def mst_strided_attention_count(L: int, stride: int) -> int:
+    out = C.c_int64(0)
+    _check("mst_strided_attention_count", lib().mst_strided_attention_count(int(L), int(stride), C.byref(out)))
+    return int(out.value)

@@ -1,6 +1,11 @@
 // Host-only parts of the C ABI: the Sparsity Variation density schedule (Sec. 3.1),
-// the piecewise cosine update fraction (Sec. 3.2) and the count lines of Algorithm 1.
+// the piecewise cosine update fraction (Sec. 3.2), the count lines of Algorithm 1, the
+// per-layer density allocation (Sec. 3.2), the FLOP counts (App. "FLOP Calculation") and
+// the size of the strided attention pattern (Sec. 3.3).
+#include <algorithm>
 #include <cmath>
+#include <numeric>
+#include <vector>
 
 #include "../../include/mst.h"
 
@@ -78,6 +83,94 @@ int mst_update_counts(int64_t n_total, int64_t nnz, double target_density, doubl
     out->n_grow = n_grow;
     out->n_rand = (int64_t)std::floor((double)n_grow * rand_ratio);
     out->n_grad = n_grow - out->n_rand;
+    return MST_OK;
+}
+
+// Erdos-Renyi allocation.  The kept budget sum_l min(1, eps r_l) N_l, r_l = (I_l + O_l) / N_l,
+// grows with eps and the layers saturate in the order of decreasing r_l: walk that order,
+// and with the first k layers dense take eps from the rest, until the next layer fits.
+int mst_erdos_renyi_density(int n_layers, const int* O, const int* I, double global_density,
+                            double* density_out) {
+    if (n_layers < 1 || !O || !I || !density_out) return MST_ERR_ARG;
+    if (!(global_density >= 0.0 && global_density <= 1.0)) return MST_ERR_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if (O[l] < 1 || I[l] < 1) return MST_ERR_ARG;
+    std::vector<double> n(n_layers), r(n_layers);
+    double total = 0.0, edges = 0.0;
+    for (int l = 0; l < n_layers; ++l) {
+        n[l] = (double)O[l] * (double)I[l];
+        r[l] = ((double)O[l] + (double)I[l]) / n[l];
+        total += n[l];
+        edges += (double)O[l] + (double)I[l];
+    }
+    if (global_density == 1.0 || global_density == 0.0) {
+        std::fill(density_out, density_out + n_layers, global_density);
+        return MST_OK;
+    }
+    std::vector<int> order(n_layers);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return r[a] > r[b]; });
+    double budget = global_density * total;
+    int k = 0;
+    double eps = 0.0;
+    for (; k < n_layers; ++k) {
+        eps = budget / edges;
+        if (eps * r[order[k]] <= 1.0) break;     // the layer most eager to saturate fits
+        budget -= n[order[k]];
+        edges -= (double)O[order[k]] + (double)I[order[k]];
+    }
+    for (int j = 0; j < n_layers; ++j) {
+        const int l = order[j];
+        density_out[l] = (j < k) ? 1.0 : std::min(1.0, eps * r[l]);
+    }
+    return MST_OK;
+}
+
+int mst_flops_fc_forward(int n_layers, const int* O, const int* I, const double* density,
+                         double* flops_out) {
+    if (n_layers < 1 || !O || !I || !density || !flops_out) return MST_ERR_ARG;
+    double sum = 0.0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (O[l] < 1 || I[l] < 1 || !(density[l] >= 0.0 && density[l] <= 1.0)) return MST_ERR_ARG;
+        sum += density[l] * (2.0 * (double)I[l] - 1.0) * (double)O[l];
+    }
+    *flops_out = sum;
+    return MST_OK;
+}
+
+int mst_flops_transformer(const mst_transformer_shape* shape, double density, double q_atten,
+                          mst_transformer_flops* out) {
+    if (!shape || !out) return MST_ERR_ARG;
+    if (shape->L < 1 || shape->N_embd < 1 || shape->D_ffw < 1 || shape->D_vocab < 1 || shape->n_layers < 1)
+        return MST_ERR_ARG;
+    if (!(density >= 0.0 && density <= 1.0) || !(q_atten >= 0.0 && q_atten <= 1.0)) return MST_ERR_ARG;
+    const double L = (double)shape->L, E = (double)shape->N_embd, F = (double)shape->D_ffw;
+    const double V = (double)shape->D_vocab, depth = (double)shape->n_layers;
+    const double row_e = density * L * (2.0 * E - 1.0);      // (1 - S) L (2 N_embd - 1): one output of width N_embd
+    out->kqv = row_e * 3.0 * E;
+    out->proj = row_e * E;
+    out->ffw1 = row_e * F;
+    out->ffw2 = density * L * (2.0 * F - 1.0) * E;
+    out->lm = row_e * V;
+    out->scores = q_atten * 2.0 * L * L * E;
+    out->reduce = out->scores;
+    out->forward = depth * (out->kqv + out->scores + out->reduce + out->proj + out->ffw1 + out->ffw2) + out->lm;
+    out->backward = 2.0 * out->forward;
+    out->total = out->forward + out->backward;
+    return MST_OK;
+}
+
+// Row i keeps its window, min(i + 1, l) positions, and the positions i - l, i - 2l, ... >= 0
+// outside it: floor(i / l) of them.  Summed over the rows in closed form.
+int mst_strided_attention_count(int L, int stride, int64_t* count_out) {
+    if (L < 1 || stride < 1 || !count_out) return MST_ERR_ARG;
+    const int64_t n = L, l = stride;
+    const int64_t ramp = std::min(n, l);                     // rows 0 .. ramp-1 see i + 1 positions
+    int64_t window = ramp * (ramp + 1) / 2 + (n - ramp) * l;
+    const int64_t q = (n - 1) / l;                           // floor(i / l) takes 0 .. q
+    // every value v < q is taken by l rows, v = q by the last n - q l rows
+    int64_t strided = l * (q * (q - 1) / 2) + q * (n - q * l);
+    *count_out = window + strided;
     return MST_OK;
 }
 
