@@ -34,6 +34,8 @@ def parse():
     p.add_argument("--warmup", type=int, default=5)
     p.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     p.add_argument("--update-interval", type=int, default=100, help="Delta_t; 0 = never update")
+    p.add_argument("--allocation", default="uniform", choices=["uniform", "erdos_renyi"],
+                   help="C5 only: every layer at the sweep's density, or the Erdos-Renyi shares of it (Sec. 3.2)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--seed", type=int, default=2024)
     p.add_argument("--pmc-probe", action="store_true",
@@ -286,9 +288,9 @@ def sweep(args, cfg, mst, synth, torch):
     steps = max(1, args.steps // len(cfg["densities"]))
     rows, tot_time, tot_flops, seed = [], 0.0, 0.0, args.seed * 7919
 
-    def one_step(d):
+    def one_step(dl):
         nonlocal seed
-        for L in layers:
+        for L, d in zip(layers, dl):
             mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
             mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
             mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
@@ -296,15 +298,19 @@ def sweep(args, cfg, mst, synth, torch):
             mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, stream)
 
     for d in cfg["densities"]:
-        for L in layers:                       # transition to this density (untimed)
+        if args.allocation == "erdos_renyi":
+            dl = mst.mst_erdos_renyi_density([(L.O, L.I) for L in layers], d)
+        else:
+            dl = [d] * len(layers)
+        for L, dk in zip(layers, dl):          # transition to this density (untimed)
             seed += 1
-            mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, stream)
+            mst.mst_mask_update(L.layer, L.dY, L.X, T, dk, cfg["zeta"], cfg["R"], seed, L.ws, L.act, stream)
         for _ in range(min(2, args.warmup)):
-            one_step(d)
+            one_step(dl)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            one_step(d)
+            one_step(dl)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
         flops = sum(6 * L.layer.nnz * T for L in layers)
@@ -318,8 +324,8 @@ def sweep(args, cfg, mst, synth, torch):
            "ms_per_step": round(1e3 * tot_time / len(cfg["densities"]), 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": "C5: one GPT-2-large block (1280/5120; 1 of 36 identical blocks), T=%d, densities %s "
-                                  "reached by the mask update itself, products + fused Mixed-Growing update every step"
-                                  % (T, cfg["densities"])},
+                                  "(%s over the layers) reached by the mask update itself, products + fused "
+                                  "Mixed-Growing update every step" % (T, cfg["densities"], args.allocation)},
            "sweep": rows}
     print(json.dumps(out))
 

@@ -199,13 +199,17 @@ void k_sddmm(const SddmmSide<TIn> row, const SddmmSide<TIn> col, float* __restri
 template <typename TIn>
 __global__ void k_sddmm_reduce(const float* __restrict__ partial, int ntile, const SddmmSide<TIn> row,
                                const SddmmSide<TIn> col, float* __restrict__ dW, const int* __restrict__ choice) {
-    const SddmmSide<TIn>& a = *choice ? col : row;
+    const bool c = *choice != 0;                      // field by field: the arguments stay in scalar registers
+    const int* __restrict__ ptr = c ? col.ptr : row.ptr;
+    const int* __restrict__ perm = c ? col.perm : row.perm;
+    const int64_t nseg = c ? col.nseg : row.nseg;
+    const int64_t slots_stride = c ? col.slots_stride : row.slots_stride;
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (int64_t)a.ptr[a.nseg] * 8) return;
-    const int p = a.perm[e];
+    if (e >= (int64_t)ptr[nseg] * 8) return;
+    const int p = perm[e];
     if (p < 0) return;
     float sum = 0.f;
-    for (int t = 0; t < ntile; ++t) sum += partial[(int64_t)t * a.slots_stride + e];
+    for (int t = 0; t < ntile; ++t) sum += partial[(int64_t)t * slots_stride + e];
     dW[p] = sum;
 }
 
