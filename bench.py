@@ -121,34 +121,41 @@ def main():
                           "layers": {L.name: dict(I=L.I, O=L.O, nnz=L.nnz) for L in layers}}))
         return
 
-    kinds = ("fwd", "bwd_input", "bwd_weight", "mask_update")
+    kinds = ("fwd", "bwd_input", "bwd_weight", "sync_values", "mask_update")
     ev = {(L.name, k): [] for L in layers for k in kinds}
 
     def run_step(t, record):
+        # one event between consecutive calls: the end of a call is the start of the next
+        def mark():
+            e = torch.cuda.Event(enable_timing=True)
+            e.record(stream)
+            return e
+
+        last = mark() if record else None
         for L in layers:
-            for kind in ("fwd", "bwd_input", "bwd_weight"):
-                if record:
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record(stream)
+            # the three products, then the hand-over of the (optimiser-updated) active weights
+            # to the index views, which a training step pays once per layer
+            for kind in ("fwd", "bwd_input", "bwd_weight", "sync_values"):
                 if kind == "fwd":
                     mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
                 elif kind == "bwd_input":
                     mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
-                else:
+                elif kind == "bwd_weight":
                     mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+                else:
+                    L.layer.sync_values(stream)
                 if record:
-                    b.record(stream)
-                    ev[(L.name, kind)].append((a, b))
+                    nxt = mark()
+                    ev[(L.name, kind)].append((last, nxt))
+                    last = nxt
         if args.update_interval and (t + 1) % args.update_interval == 0:
             for li, L in enumerate(layers):
-                if record:
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record(stream)
                 mst.mst_mask_update(L.layer, L.dY, L.X, T, density, cfg["zeta"], cfg["R"],
                                     args.seed * 1000003 + t * 131 + li, L.ws, L.act, stream)
                 if record:
-                    b.record(stream)
-                    ev[(L.name, "mask_update")].append((a, b))
+                    nxt = mark()
+                    ev[(L.name, "mask_update")].append((last, nxt))
+                    last = nxt
 
     t = 0
     for _ in range(args.warmup):
@@ -177,7 +184,7 @@ def main():
                 continue
             ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
             row = dict(layer=L.name, call=kind, launches=len(pairs), avg_ms=round(ms, 5))
-            if kind != "mask_update":
+            if kind in ("fwd", "bwd_input", "bwd_weight"):
                 by = getattr(L, "bytes_" + kind)()
                 fl = L.flops_product()
                 row.update(eff_tflops=round(fl / ms / 1e9, 3), hbm_gbs=round(by / ms / 1e6, 1),
@@ -187,7 +194,7 @@ def main():
                 tot = ms * len(pairs)
                 if dominant is None or tot > dominant[0]:
                     dominant = (tot, row, L)
-            else:
+            elif kind == "mask_update":
                 row.update(dense_grad_gflop=round(2 * T * L.O * L.I / 1e9, 2))
             table.append(row)
 
@@ -226,7 +233,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if act == "f32" else "bf16-in/f32-acc",
         "data": "synthetic",
         "config": {"workload": "%s: %s FC set (%s), density %.2f %s mask, T=%d tokens, fwd+bwd_input+bwd_weight "
-                               "per layer, Mixed-Growing update every %d steps"
+                               "+ value hand-over to the index views per layer, Mixed-Growing update every %d steps"
                                % (args.config, "GPT-2-small block" if len(layers) > 1 else "single layer",
                                   ", ".join("%s %d->%d" % (L.name, L.I, L.O) for L in layers), density,
                                   cfg["mask"], T, args.update_interval),
@@ -294,6 +301,7 @@ def sweep(args, cfg, mst, synth, torch):
             mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
             mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
             mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+            L.layer.sync_values(stream)
             seed += 1
             mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, stream)
 

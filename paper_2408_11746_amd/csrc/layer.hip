@@ -373,9 +373,19 @@ __global__ __launch_bounds__(256) void k_fill_col(const uint8_t* __restrict__ ma
     }
 }
 
-__global__ void k_sync_view(const float* __restrict__ vals, const int* __restrict__ ptr, int64_t nseg,
-                            const int* __restrict__ perm, uint2* __restrict__ ent) {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// Both views in one launch: the first `row_blocks` blocks refresh the row view's entries,
+// the others the col view's.
+__global__ void k_sync_views(const float* __restrict__ vals, unsigned row_blocks,
+                             const int* __restrict__ ptr_r, int64_t nseg_r, const int* __restrict__ perm_r,
+                             uint2* __restrict__ ent_r,
+                             const int* __restrict__ ptr_c, int64_t nseg_c, const int* __restrict__ perm_c,
+                             uint2* __restrict__ ent_c) {
+    const bool col = blockIdx.x >= row_blocks;
+    const int* __restrict__ ptr = col ? ptr_c : ptr_r;
+    const int* __restrict__ perm = col ? perm_c : perm_r;
+    uint2* __restrict__ ent = col ? ent_c : ent_r;
+    const int64_t nseg = col ? nseg_c : nseg_r;
+    const int64_t e = (int64_t)(blockIdx.x - (col ? row_blocks : 0u)) * blockDim.x + threadIdx.x;
     if (e >= (int64_t)ptr[nseg] * 8) return;
     const int p = perm[e];
     if (p >= 0) ent[e].y = __float_as_uint(vals[p]);
@@ -609,13 +619,13 @@ int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
     hipStream_t s = (hipStream_t)stream;
     L->Wd_valid = false;
     if (L->nnz == 0) return MST_OK;
-    for (View* v : {&L->row, &L->col}) {
-        // every real entry slot lies below 4 * (nnz + #quad segments); the kernel stops at ptr[nseg] * 8
-        const int64_t upper = 4 * (L->nnz + (int64_t)v->nchunk * v->NB * 4);
-        k_sync_view<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(L->vals, v->ptr, v->nseg, v->perm,
-                                                              reinterpret_cast<uint2*>(v->ent));
-        MST_LAUNCH_CHECK();
-    }
+    // every real entry slot lies below 4 * (nnz + #quad segments); the kernel stops at ptr[nseg] * 8
+    const View &r = L->row, &c = L->col;
+    const unsigned rb = (unsigned)cdiv(4 * (L->nnz + (int64_t)r.nchunk * r.NB * 4), 256);
+    const unsigned cb = (unsigned)cdiv(4 * (L->nnz + (int64_t)c.nchunk * c.NB * 4), 256);
+    k_sync_views<<<rb + cb, 256, 0, s>>>(L->vals, rb, r.ptr, r.nseg, r.perm, reinterpret_cast<uint2*>(r.ent),
+                                         c.ptr, c.nseg, c.perm, reinterpret_cast<uint2*>(c.ent));
+    MST_LAUNCH_CHECK();
     return MST_OK;
 }
 
