@@ -38,6 +38,8 @@ def parse():
                    help="C5 only: every layer at the sweep's density, or the Erdos-Renyi shares of it (Sec. 3.2)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--seed", type=int, default=2024)
+    p.add_argument("--attention-mask", type=int, nargs=2, metavar=("L", "STRIDE"), default=None,
+                   help="time the strided attention mask of Sec. 3.3 instead of a config (its own JSON line)")
     p.add_argument("--pmc-probe", action="store_true",
                    help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration), then each product twice")
     return p.parse_args()
@@ -97,6 +99,8 @@ def main():
     import paper_2408_11746_amd as mst
     import synth
 
+    if args.attention_mask:
+        return attention_mask(args, mst, torch)
     cfg = synth.CONFIGS[args.config]
     if args.config == "C5":
         return sweep(args, cfg, mst, synth, torch)
@@ -266,6 +270,36 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, T)
     print(json.dumps(out))
+
+
+def attention_mask(args, mst, torch):
+    """The [L x L] byte mask of the strided pattern: a write-only kernel, L * L algorithmic bytes."""
+    L, stride = args.attention_mask
+    stream = torch.cuda.current_stream()
+    M = torch.empty(L * L, dtype=torch.uint8, device="cuda:0")
+    for _ in range(max(1, args.warmup)):
+        mst.mst_strided_attention_mask(M, L, stride, stream)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    a.record(stream)
+    for _ in range(args.steps):
+        mst.mst_strided_attention_mask(M, L, stride, stream)
+    b.record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps
+    ms = a.elapsed_time(b) / args.steps
+    gbs = L * L / ms / 1e6
+    kept = mst.mst_strided_attention_count(L, stride)
+    assert int(M.sum(dtype=torch.int64).item()) == kept
+    print(json.dumps({
+        "metric": "strided attention mask build, HBM GB/s written", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * wall, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "strided attention mask, L=%d, stride=%d" % (L, stride), "q_atten": kept / (L * L)},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "k_strided_mask16",
+                     "avg_launch_ms": round(ms, 5), "alg_bytes_per_launch": L * L}}))
 
 
 def sweep(args, cfg, mst, synth, torch):

@@ -117,7 +117,7 @@ Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
 // ------------------------------------------------------------------ kernels
 
 // one block per row r of the mask: active count per chunk of columns and per row
-__global__ void k_count_row(const uint8_t* __restrict__ mask, int O, int I, int nchunk, int Rpad,
+__global__ void k_count_row(const uint8_t* __restrict__ mask, int I, int nchunk, int Rpad,
                             int* __restrict__ segcnt, int* __restrict__ rowcnt) {
     extern __shared__ int cnt[];   // [nchunk]
     const int r = blockIdx.x;
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(1024) void k_scan_excl(const int* in, int* out, int
             run += v[u];
         }
         __syncthreads();
-        if (tid == blockDim.x - 1) carry_s = run;
+        if (tid == (int)blockDim.x - 1) carry_s = run;
         __syncthreads();
     }
     if (tid == 0) out[n] = carry_s;
@@ -432,7 +432,7 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     if (rc != MST_OK) return rc;
     dim3 gcol((unsigned)cdiv(I, 64), (unsigned)v.nchunk);
     if (row_view) {
-        k_count_row<<<O, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
+        k_count_row<<<O, 256, (size_t)v.nchunk * 4, s>>>(L->mask, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
         MST_LAUNCH_CHECK();
         if ((rc = scan_excl_i32(ws.rowcnt, L->rowptr, O, s)) != MST_OK) return rc;
     } else {
@@ -578,7 +578,7 @@ int mst_layer_load_dense(mst_layer_t* L, const float* W_dev, const uint8_t* M_de
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     // learn the active count first so that nothing is written when it does not fit
-    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(M_dev, L->O, L->I, L->row.nchunk, 0, nullptr, ws.rowcnt);
+    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(M_dev, L->I, L->row.nchunk, 0, nullptr, ws.rowcnt);
     MST_LAUNCH_CHECK();
     int rcs = scan_excl_i32(ws.rowcnt, L->rowptr, L->O, s);          // rebuilt below anyway
     if (rcs != MST_OK) return rcs;
