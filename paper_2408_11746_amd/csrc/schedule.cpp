@@ -121,7 +121,7 @@ int mst_erdos_renyi_density(int n_layers, const int* O, const int* I, double glo
     }
     for (int j = 0; j < n_layers; ++j) {
         const int l = order[j];
-        density_out[l] = (j < k) ? 1.0 : std::min(1.0, eps * r[l]);
+        density_out[l] = (j < k) ? 1.0 : std::min(1.0, std::max(0.0, eps * r[l]));   // rounding guard
     }
     return MST_OK;
 }
