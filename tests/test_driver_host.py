@@ -1,0 +1,61 @@
+"""Host logic of the topology driver (no GPU): which steps update and with which targets."""
+import pytest
+
+import paper_2408_11746_amd as mst
+from paper_2408_11746_amd.driver import TopologyDriver
+from oracle import allocation as oal
+from oracle import schedule as osc
+
+
+class FakeLayer:
+    def __init__(self, O, I, nnz):
+        self.O, self.I, self.nnz = O, I, nnz
+
+
+SHAPES = [(2304, 768), (768, 768), (3072, 768), (768, 3072)]
+
+
+def make(allocation="erdos_renyi", **kw):
+    layers = [FakeLayer(O, I, O * I) for O, I in SHAPES]
+    return TopologyDriver(layers, mst.ScheduleCfg(), allocation=allocation, **kw), layers
+
+
+def test_update_steps_are_the_positive_multiples_of_the_interval():
+    drv, _ = make(delta_t=100)
+    assert [t for t in range(0, 501) if drv.is_update_step(t)] == [100, 200, 300, 400, 500]
+    with pytest.raises(ValueError):
+        make(delta_t=0)
+    with pytest.raises(ValueError):
+        make(allocation="something")
+
+
+def test_targets_follow_schedule_and_allocation():
+    drv, _ = make()
+    ocfg = osc.ScheduleCfg()
+    for step in [0, 100, 1999, 2000, 4000, 9999, 10000, 60000, 110000, 112000, 118000, 119999, 120000, 139900]:
+        d, z, dl = drv.targets(step)
+        assert d == pytest.approx(osc.density(ocfg, step), abs=1e-15)
+        assert z == pytest.approx(osc.zeta(ocfg, step), abs=1e-15)
+        assert dl == pytest.approx(oal.erdos_renyi_density(SHAPES, osc.density(ocfg, step)), rel=1e-12)
+    uni, _ = make(allocation="uniform")
+    d, _, dl = uni.targets(4000)
+    assert dl == [d] * len(SHAPES)
+
+
+def test_idle_only_when_nothing_would_change():
+    drv, layers = make()
+    _, z, dl = drv.targets(130000)                 # after the restoration: dense target, zeta 0
+    assert z == 0.0 and dl == [1.0] * len(SHAPES)
+    assert drv._idle(dl, z)                        # layers are dense already
+    layers[1].nnz -= 5                             # one layer still has to grow back
+    assert not drv._idle(dl, z)
+    _, z, dl = drv.targets(50000)                  # ultra-sparse phase: zeta > 0, never idle
+    assert z > 0.0 and not drv._idle(dl, z)
+
+
+def test_layer_seeds_are_distinct_per_step_and_layer():
+    drv, _ = make(seed=7)
+    seen = {drv.layer_seed(t, k) for t in range(100, 2001, 100) for k in range(len(SHAPES))}
+    assert len(seen) == 20 * len(SHAPES)
+    big, _ = make(seed=(1 << 64) - 1)
+    assert 0 <= big.layer_seed(140000, 3) < (1 << 64)
