@@ -24,7 +24,9 @@ Pin status (see tests/test_oracle_*.py):
   mixed_growing.randk_key           pinned: the published SplitMix64 test vector.
   mixed_growing.update              pinned: brute force with Python's sorted() on tiny
                                     inputs, set invariants, R=0 / R=1 special cases,
-                                    chi-square uniformity of the random part.
+                                    chi-square uniformity of the random part; the
+                                    lambda prune criterion by brute force on dyadic
+                                    values, lambda = 0 and lambda -> large.
   allocation.erdos_renyi_density    pinned: hand-computed densities of the GPT-2-small block
                                     and of a saturating pair, budget conservation, an
                                     independent bisection solve, special cases.

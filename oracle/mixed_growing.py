@@ -23,6 +23,11 @@ Readings taken where Algorithm 1 is silent or cannot be used as printed:
            generator started at state `seed` (Steele, Lea, Flood 2014) -- and taking
            the N_rand candidates with the smallest (key, f).
   values   theta <- theta * M: pruned weights become 0; grown weights start at 0.
+  variant  the table of topology evolution schemes lists one other prune criterion,
+           min(|theta| + lambda |grad|); `prune_lambda` > 0 selects it (the gradient is the
+           same dense gradient that scores growth; lambda is the caller's, the paper gives
+           no value).  The score is formed in fp32: the product is rounded, then the sum.
+           lambda = 0 is the paper's own criterion.
 """
 from __future__ import annotations
 
@@ -69,7 +74,18 @@ def randk_key(seed: int, f) -> np.ndarray:
     return z
 
 
-def update(W, M, G, d_target: float, zeta: float, R: float, seed: int) -> Dict[str, object]:
+def prune_score_bits(w, g, prune_lambda: float) -> np.ndarray:
+    """Integer that orders like the prune score |w| + lambda |g| (fp32, two roundings)."""
+    if prune_lambda == 0.0:
+        return abs_bits(w)
+    a = np.abs(np.ascontiguousarray(w, dtype=np.float32))
+    b = np.float32(prune_lambda) * np.abs(np.ascontiguousarray(g, dtype=np.float32))
+    with np.errstate(over="ignore"):
+        return (a + b.astype(np.float32)).astype(np.float32).view(np.uint32)
+
+
+def update(W, M, G, d_target: float, zeta: float, R: float, seed: int,
+           prune_lambda: float = 0.0) -> Dict[str, object]:
     """One Mixed-Growing update of a layer.
 
     W [O, I] fp32 weights (zero at inactive positions), M [O, I] 0/1 mask, G [O, I]
@@ -84,8 +100,8 @@ def update(W, M, G, d_target: float, zeta: float, R: float, seed: int) -> Dict[s
     inactive = np.flatnonzero(~Mb)
     c = counts(n_total, active.size, d_target, zeta, R)
 
-    # prune: the n_prune active weights with the smallest (|w|, f)
-    wkey = abs_bits(W.reshape(-1)[active])
+    # prune: the n_prune active weights with the smallest (score, f), score = |w| (+ lambda |g|)
+    wkey = prune_score_bits(W.reshape(-1)[active], G.reshape(-1)[active], prune_lambda)
     order = np.lexsort((active, wkey))
     i_prune = np.sort(active[order[: c["n_prune"]]])
 

@@ -189,3 +189,53 @@ def test_random_growth_is_uniform_over_candidates():
     chi2 = float(((hits[cand] - expect) ** 2 / (expect * (1 - k / cand.size))).sum())
     dof = cand.size - 1
     assert abs(chi2 - dof) < 6 * (2 * dof) ** 0.5    # ~6 sigma band
+
+
+# ----------------------------------------------------------------- the other prune criterion
+
+def test_prune_lambda_zero_is_the_magnitude_criterion():
+    W, M, G = _layer(5, 9, 11, 0.4)
+    a = mg.update(W, M, G, 0.35, 0.3, 0.25, 77)
+    b = mg.update(W, M, G, 0.35, 0.3, 0.25, 77, prune_lambda=0.0)
+    for k in ("prune", "grad", "rand"):
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+@pytest.mark.parametrize("lam", [0.25, 1.0, 3.0])
+def test_prune_lambda_brute_force_on_dyadic_values(lam):
+    # multiples of 1/8 below 16 and a dyadic lambda: |w| + lambda |g| is exact in fp32 and in
+    # Python floats alike, so sorting Python tuples is an independent statement of the order
+    rng = np.random.default_rng(9)
+    O, I = 7, 9
+    M = (rng.random((O, I)) < 0.5).astype(np.uint8)
+    W = (rng.integers(-40, 41, (O, I)) / 8.0).astype(np.float32) * M
+    G = (rng.integers(-40, 41, (O, I)) / 8.0).astype(np.float32)
+    N = O * I
+    act = [f for f in range(N) if M.flat[f]]
+    c = mg.counts(N, len(act), 0.45, 0.4, 0.5)
+    want = sorted(sorted(act, key=lambda f: (abs(float(W.flat[f])) + lam * abs(float(G.flat[f])), f))[: c["n_prune"]])
+    got = mg.update(W, M, G, 0.45, 0.4, 0.5, 3, prune_lambda=lam)
+    assert got["prune"].tolist() == want
+    # the growth sets do not depend on the prune criterion
+    ref = mg.update(W, M, G, 0.45, 0.4, 0.5, 3)
+    np.testing.assert_array_equal(got["grad"], ref["grad"])
+    np.testing.assert_array_equal(got["rand"], ref["rand"])
+    assert got["prune"].tolist() != ref["prune"].tolist()          # the criterion matters on this input
+
+
+def test_prune_lambda_large_ranks_by_gradient_alone():
+    W, M, G = _layer(6, 10, 12, 0.5)
+    act = np.flatnonzero(M.reshape(-1))
+    got = mg.update(W, M, G, 0.5, 0.3, 0.0, 1, prune_lambda=2.0 ** 40)
+    order = sorted(act.tolist(), key=lambda f: (_abs32(G.flat[f]), f))
+    assert got["prune"].tolist() == sorted(order[: got["counts"]["n_prune"]])
+
+
+def test_prune_score_rounds_product_then_sum():
+    # 3 * (1 + 2^-23) needs 25 bits: the product rounds to 3 + 2^-21 (ties to even) before 1 is added
+    w = np.array([1.0], np.float32)
+    g = np.array([1.0 + 2.0 ** -23], np.float32)
+    bits = mg.prune_score_bits(w, g, 3.0)
+    prod = np.float32(3.0) * g[0]
+    assert bits.view(np.float32)[0] == np.float32(np.float32(1.0) + prod)
+    assert float(prod) == 3.0 + 2.0 ** -21
