@@ -115,6 +115,14 @@ int mst_layer_sync_values(mst_layer_t* layer, mst_stream_t stream);
 int mst_layer_indices(const mst_layer_t* layer, int32_t* flat_dev, mst_stream_t stream);
 
 int mst_layer_set_path(mst_layer_t* layer, mst_path path);
+
+/* Prune criterion of the following updates of this layer.  0 (the default) is the paper's:
+ * the smallest |w|.  lambda > 0 selects the other criterion of the table of topology
+ * evolution schemes in Sec. 3.2, the smallest |w| + lambda |grad|, with the same dense
+ * gradient that scores growth (the score buffer of mst_mask_update_from_scores) and the
+ * score formed in fp32 (product rounded, then the sum); ties go to the lower flat index as
+ * always.  The paper gives no value for lambda.  MST_ERR_ARG unless lambda is finite and >= 0. */
+int mst_layer_set_prune_lambda(mst_layer_t* layer, float lambda);
 int64_t mst_layer_nnz(const mst_layer_t* layer);
 
 /* Launch shape of the sparse products' SpMM kernel: tokens per workgroup (128 or 64) and

@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
         "mst_layer_sync_values": (i32, [vp, vp]),
         "mst_layer_indices": (i32, [vp, vp, vp]),
         "mst_layer_set_path": (i32, [vp, i32]),
+        "mst_layer_set_prune_lambda": (i32, [vp, C.c_float]),
         "mst_spmm_force_shape": (i32, [i32, i32]),
         "mst_layer_nnz": (i64, [vp]),
         "mst_sparse_fc_fwd": (i32, [vp, vp, vp, i32, i32, vp]),
@@ -105,7 +106,8 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_workspace_bytes",
            "mst_layer_create", "mst_layer_destroy", "mst_layer_load_dense", "mst_layer_export_dense",
-           "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_spmm_force_shape",
+           "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_layer_set_prune_lambda",
+           "mst_spmm_force_shape",
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
            "mst_schedule_density", "mst_erdos_renyi_density", "mst_flops_fc_forward", "mst_flops_transformer",
@@ -223,6 +225,9 @@ class Layer:
 
     def set_path(self, path: int):
         _check("mst_layer_set_path", lib().mst_layer_set_path(self.h, path))
+
+    def set_prune_lambda(self, lam: float):
+        _check("mst_layer_set_prune_lambda", lib().mst_layer_set_prune_lambda(self.h, float(lam)))
 
 
 # ------------------------------------------------------------------ device calls

@@ -64,6 +64,7 @@ struct mst_layer {
     int O = 0, I = 0;
     int64_t N = 0, cap = 0, nnz = 0;
     int path = MST_PATH_AUTO;
+    float prune_lambda = 0.f;  // prune score |w| + prune_lambda |grad| (0: magnitude only)
     void* buf = nullptr;
     size_t buf_bytes = 0;
     uint8_t* mask = nullptr;   // [N]

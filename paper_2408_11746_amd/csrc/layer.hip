@@ -643,6 +643,12 @@ int mst_layer_set_path(mst_layer_t* L, mst_path path) {
     return MST_OK;
 }
 
+int mst_layer_set_prune_lambda(mst_layer_t* L, float lambda) {
+    if (!L || !(lambda >= 0.f) || lambda > 3.4028234e38f) return MST_ERR_ARG;
+    L->prune_lambda = lambda;
+    return MST_OK;
+}
+
 int64_t mst_layer_nnz(const mst_layer_t* L) { return L ? L->nnz : -1; }
 
 }  // extern "C"

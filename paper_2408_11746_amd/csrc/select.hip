@@ -29,6 +29,19 @@ struct PruneKeys {
     const float* vals;
     __device__ bool get(int64_t k, key_t& key) const { key = abs_bits(vals[k]); return true; }
 };
+// |w| + lambda |grad|, both roundings explicit (no contraction into one fused operation);
+// a non-negative float orders like its bit pattern
+struct ScoredPruneKeys {
+    typedef uint32_t key_t;
+    const float* vals;
+    const int* flat;
+    const float* G;
+    float lambda;
+    __device__ bool get(int64_t k, key_t& key) const {
+        key = __float_as_uint(__fadd_rn(fabsf(vals[k]), __fmul_rn(lambda, fabsf(G[flat[k]]))));
+        return true;
+    }
+};
 struct GradKeys {
     typedef uint32_t key_t;
     const float* G;
@@ -281,7 +294,11 @@ int mask_update_device(mst_layer* L, const float* G, const mst_update_stats& st,
         (uint64_t)st.n_grad, (uint64_t)st.n_rand);
     MST_LAUNCH_CHECK();
 
-    if ((rc = select_smallest(PruneKeys{L->vals}, nnz, st.n_prune, ws.psel, 1, st0, ws, s)) != MST_OK) return rc;
+    if (L->prune_lambda == 0.f)
+        rc = select_smallest(PruneKeys{L->vals}, nnz, st.n_prune, ws.psel, 1, st0, ws, s);
+    else
+        rc = select_smallest(ScoredPruneKeys{L->vals, L->flat, G, L->prune_lambda}, nnz, st.n_prune, ws.psel, 1, st0, ws, s);
+    if (rc != MST_OK) return rc;
     if ((rc = select_smallest(GradKeys{G, L->mask}, N, st.n_grad, ws.sel, 2, st0 + SEL_STATE_WORDS, ws, s)) != MST_OK)
         return rc;
     if ((rc = select_smallest(RandKeys{L->mask, ws.sel, seed}, N, st.n_rand, ws.sel, 3, st0 + 2 * SEL_STATE_WORDS, ws,

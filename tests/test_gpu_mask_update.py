@@ -185,3 +185,42 @@ def test_schedule_sweep_chain_matches_oracle_and_switches_paths():
         assert rel_err(rig.fwd(X), opr.fc_fwd(X, Wc, Mc)) <= TOL
         assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, Wc, Mc)) <= TOL
         assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, Mc)) <= TOL
+
+
+@pytest.mark.parametrize("lam", [0.5, 0.037, 4.0])
+@pytest.mark.parametrize("quantise", [None, 4])
+def test_prune_score_with_gradient_term_is_bit_exact(lam, quantise):
+    # the other prune criterion of the scheme table: smallest |w| + lambda |grad|
+    print("case", lam, quantise, flush=True)
+    O, I, density = 300, 520, 0.08
+    W, M = synth.make_layer(26, 3, I, O, density)
+    if quantise:
+        W = (np.round(W * 50 * quantise) / (50 * quantise)).astype(np.float32) * M
+    G = _scores(26, O, I, quantise)
+    rig = Rig(W, M, 1, cap=O * I)
+    rig.layer.set_prune_lambda(lam)
+    st = mst.mst_mask_update_from_scores(rig.layer, dev(G), density, 0.3, 0.25, 99, rig.ws)
+    torch.cuda.synchronize()
+    ref = omg.update(W, M, G, density, 0.3, 0.25, 99, prune_lambda=float(np.float32(lam)))
+    plain = omg.update(W, M, G, density, 0.3, 0.25, 99)
+    assert ref["prune"].tolist() != plain["prune"].tolist()          # the criterion changes the prune set here
+    assert st["n_prune"] == ref["counts"]["n_prune"]
+    We, Me = rig.export()
+    np.testing.assert_array_equal(Me, ref["M"])
+    np.testing.assert_array_equal(We, ref["W"])
+    # back to the magnitude criterion on the same layer object
+    rig.layer.set_prune_lambda(0.0)
+    mst.mst_mask_update_from_scores(rig.layer, dev(G), density, 0.3, 0.25, 100, rig.ws)
+    torch.cuda.synchronize()
+    ref2 = omg.update(ref["W"], ref["M"], G, density, 0.3, 0.25, 100)
+    We, Me = rig.export()
+    np.testing.assert_array_equal(Me, ref2["M"])
+    np.testing.assert_array_equal(We, ref2["W"])
+
+
+def test_prune_lambda_rejects_bad_values():
+    W, M = synth.make_layer(27, 1, 64, 48, 0.1)
+    rig = Rig(W, M, 1)
+    for bad in (-1.0, float("nan"), float("inf")):
+        with pytest.raises(mst.MstError):
+            rig.layer.set_prune_lambda(bad)
