@@ -38,6 +38,9 @@ def parse():
                    help="C5 only: every layer at the sweep's density, or the Erdos-Renyi shares of it (Sec. 3.2)")
     p.add_argument("--update-streams", type=int, default=1,
                    help="C5 only: 1 = the layers' mask updates run on one stream per layer, 0 = all on the main stream")
+    p.add_argument("--fused-update", type=int, default=1,
+                   help="C5 only: 1 = weight gradient and update from one dense gradient "
+                        "(mst_sparse_fc_bwd_weight_update), 0 = separate calls")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--seed", type=int, default=2024)
     p.add_argument("--attention-mask", type=int, nargs=2, metavar=("L", "STRIDE"), default=None,
@@ -342,15 +345,23 @@ def sweep(args, cfg, mst, synth, torch):
         for L in layers:
             mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
             mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
-            mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
-            L.layer.sync_values(stream)
+            if not args.fused_update:
+                mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+                L.layer.sync_values(stream)
         fork = torch.cuda.Event()
         fork.record(stream)
         for L, d, s in zip(layers, dl, side):
             seed += 1
             if s is not stream:
                 s.wait_event(fork)
-            mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, s)
+            if args.fused_update:
+                # every step updates the topology: the dense gradient the update needs also
+                # gives the weight gradient (no separate SDDMM / dense product, and the update
+                # rebuilds the views, so no separate hand-over of the values)
+                mst.mst_sparse_fc_bwd_weight_update(L.layer, L.dY, L.X, L.dW, T, d, cfg["zeta"], cfg["R"], seed, L.ws,
+                                                    L.act, s)
+            else:
+                mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, s)
             if s is not stream:
                 done = torch.cuda.Event()
                 done.record(s)
@@ -384,9 +395,11 @@ def sweep(args, cfg, mst, synth, torch):
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": "C5: one GPT-2-large block (1280/5120; 1 of 36 identical blocks), T=%d, densities %s "
                                   "(%s over the layers) reached by the mask update itself, products + fused "
-                                  "Mixed-Growing update every step (updates of the four layers on %s)"
+                                  "Mixed-Growing update every step (updates of the four layers on %s; %s)"
                                   % (T, cfg["densities"], args.allocation,
-                                     "one stream per layer" if args.update_streams else "the main stream")},
+                                     "one stream per layer" if args.update_streams else "the main stream",
+                                     "weight gradient and update share one dense gradient" if args.fused_update
+                                     else "weight gradient and update as separate calls")},
            "sweep": rows}
     print(json.dumps(out))
 

@@ -184,6 +184,20 @@ int mst_mask_update(mst_layer_t* layer, const void* dY_dev, const void* X_dev, i
                     uint64_t rng_seed, void* ws_dev, size_t ws_bytes,
                     mst_update_stats* stats_out, mst_stream_t stream);
 
+/* The weight gradient and the update of one step from ONE dense gradient.  On a step that
+ * updates the topology the dense gradient G = dY^T X is needed anyway (Sec. 2: the
+ * infrequent full gradient calculation); this call forms it once on the matrix cores, writes
+ * dW_vals_dev = G at the positions active BEFORE the update (canonical order, the result of
+ * mst_sparse_fc_bwd_weight up to rounding order) and then performs mst_mask_update with it.
+ * When the update needs no gradient (nothing grows by gradient and the prune score has no
+ * gradient term) the weight gradient is computed as in mst_sparse_fc_bwd_weight.
+ * Workspace: mst_workspace_bytes(O, I, nnz_capacity, T). */
+int mst_sparse_fc_bwd_weight_update(mst_layer_t* layer, const void* dY_dev, const void* X_dev,
+                                    float* dW_vals_dev, int T, mst_dtype act,
+                                    double target_density, double zeta, double rand_ratio,
+                                    uint64_t rng_seed, void* ws_dev, size_t ws_bytes,
+                                    mst_update_stats* stats_out, mst_stream_t stream);
+
 /* ------------------------------------------------------------------ schedule */
 
 /* Pure host.  Density d_t = 1 - S_t of Sec. 3.1 read with stage index

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     mst_sparse_fc_bwd_weight,
     mst_mask_update,
     mst_mask_update_from_scores,
+    mst_sparse_fc_bwd_weight_update,
     mst_dense_grad,
     mst_spmm_force_shape,
     mst_erdos_renyi_density,

@@ -90,6 +90,8 @@ def lib() -> C.CDLL:
         "mst_update_counts": (i32, [i64, i64, dbl, dbl, dbl, C.POINTER(UpdateStats)]),
         "mst_mask_update_from_scores": (i32, [vp, vp, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
         "mst_mask_update": (i32, [vp, vp, vp, i32, i32, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
+        "mst_sparse_fc_bwd_weight_update": (i32, [vp, vp, vp, vp, i32, i32, dbl, dbl, dbl, u64, vp, sz,
+                                                  C.POINTER(UpdateStats), vp]),
         "mst_schedule_density": (i32, [C.POINTER(_ScheduleCfgC), i64, C.POINTER(dbl), C.POINTER(dbl)]),
         "mst_erdos_renyi_density": (i32, [i32, C.POINTER(i32), C.POINTER(i32), dbl, C.POINTER(dbl)]),
         "mst_flops_fc_forward": (i32, [i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(dbl), C.POINTER(dbl)]),
@@ -110,6 +112,7 @@ EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_w
            "mst_spmm_force_shape",
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
+           "mst_sparse_fc_bwd_weight_update",
            "mst_schedule_density", "mst_erdos_renyi_density", "mst_flops_fc_forward", "mst_flops_transformer",
            "mst_strided_attention_mask", "mst_strided_attention_count"]
 
@@ -272,6 +275,16 @@ def mst_mask_update(layer: Layer, dY, X, T: int, target_density: float, zeta: fl
     _check("mst_mask_update",
            lib().mst_mask_update(layer.h, _ptr(dY), _ptr(X), T, act, target_density, zeta, rand_ratio, rng_seed,
                                  _ptr(ws), ws.numel(), C.byref(st), _stream(stream)))
+    return st.as_dict()
+
+
+def mst_sparse_fc_bwd_weight_update(layer: Layer, dY, X, dW, T: int, target_density: float, zeta: float,
+                                    rand_ratio: float, rng_seed: int, ws, act: int = MST_F32, stream=None) -> dict:
+    st = UpdateStats()
+    _check("mst_sparse_fc_bwd_weight_update",
+           lib().mst_sparse_fc_bwd_weight_update(layer.h, _ptr(dY), _ptr(X), _ptr(dW), T, act, target_density, zeta,
+                                                 rand_ratio, rng_seed, _ptr(ws), ws.numel(), C.byref(st),
+                                                 _stream(stream)))
     return st.as_dict()
 
 

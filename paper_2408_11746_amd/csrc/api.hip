@@ -94,6 +94,12 @@ int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, i
                      ws_dev ? (int64_t)(ws_bytes / 4) : 0, (hipStream_t)stream);
 }
 
+// the dense gradient scores gradient growth and, with a prune score that has a gradient
+// term, pruning; an update that does neither does not need it
+static bool needs_gradient(const mst_layer* L, const mst_update_stats& st) {
+    return st.n_grad > 0 || (L->prune_lambda != 0.f && st.n_prune > 0);
+}
+
 static int update_common(mst_layer_t* L, const float* G, uint64_t seed, const Workspace& ws,
                          mst_update_stats* stats_out, hipStream_t s, const mst_update_stats& st) {
     if (stats_out) *stats_out = st;
@@ -126,8 +132,38 @@ int mst_mask_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, int T
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, 1);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    if (st.n_grad > 0) {      // the gradient score is only needed when something grows by gradient
+    if (needs_gradient(L, st)) {
         rc = gemm_mfma(GEMM_TN, dY_dev, act, X_dev, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s);
+        if (rc != MST_OK) return rc;
+    }
+    return update_common(L, ws.G, rng_seed, ws, stats_out, s, st);
+}
+
+int mst_sparse_fc_bwd_weight_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, float* dW_dev, int T,
+                                    mst_dtype act, double target_density, double zeta, double rand_ratio,
+                                    uint64_t rng_seed, void* ws_dev, size_t ws_bytes, mst_update_stats* stats_out,
+                                    mst_stream_t stream) {
+    if (!L || !dY_dev || !X_dev || !dW_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
+    if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dW_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    mst_update_stats st;
+    int rc = mst_update_counts(L->N, L->nnz, target_density, zeta, rand_ratio, &st);
+    if (rc != MST_OK) return rc;
+    if (st.nnz_after > L->cap) return MST_ERR_STATE;
+    const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
+    if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (needs_gradient(L, st)) {
+        // one dense gradient serves both: the weight gradient is read from it at the positions
+        // that are active now, then the update scores growth with it
+        rc = gemm_mfma(GEMM_TN, dY_dev, act, X_dev, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s);
+        if (rc != MST_OK) return rc;
+        if (L->nnz > 0) {
+            k_gather_flat<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(ws.G, L->N, 1, L->flat, L->nnz, dW_dev);
+            MST_LAUNCH_CHECK();
+        }
+    } else {
+        rc = use_dense_weight_grad(L, act, T) ? dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s)
+                                              : sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
         if (rc != MST_OK) return rc;
     }
     return update_common(L, ws.G, rng_seed, ws, stats_out, s, st);

@@ -224,3 +224,57 @@ def test_prune_lambda_rejects_bad_values():
     for bad in (-1.0, float("nan"), float("inf")):
         with pytest.raises(mst.MstError):
             rig.layer.set_prune_lambda(bad)
+
+
+@pytest.mark.parametrize("act", ["f32", "bf16"])
+@pytest.mark.parametrize("d_now,d_next,zeta,R", [(0.05, 0.05, 0.3, 0.25), (0.5, 0.3, 0.3, 0.25), (0.1, 0.1, 0.3, 1.0),
+                                                  (0.05, 0.05, 0.0, 0.25)])
+def test_weight_gradient_and_update_from_one_dense_gradient(act, d_now, d_next, zeta, R):
+    print("case", act, d_now, d_next, zeta, R, flush=True)
+    T, I, O = 512, 640, 384
+    W, M = synth.make_layer(28, 7, I, O, d_now)
+    if act == "f32":
+        X, dY = synth.make_activations(28, 7, T, I, O)
+        Xd, dYd, code = dev(X), dev(dY), mst.MST_F32
+    else:
+        X, dY, xb, yb = synth.make_activations(28, 7, T, I, O, "bf16")
+        Xd, dYd, code = dev(xb.view(np.int16)), dev(yb.view(np.int16)), mst.MST_BF16
+    rig = Rig(W, M, T, cap=O * I)
+    Gg = torch.empty((O, I), dtype=torch.float32, device=DEV)
+    mst.mst_dense_grad(dYd, Xd, Gg, T, O, I, code, rig.ws)
+    torch.cuda.synchronize()
+    G_gpu = Gg.cpu().numpy()
+    nnz0 = rig.layer.nnz
+    dW = torch.full((nnz0,), float("nan"), dtype=torch.float32, device=DEV)
+    st = mst.mst_sparse_fc_bwd_weight_update(rig.layer, dYd, Xd, dW, T, d_next, zeta, R, 777, rig.ws, code)
+    torch.cuda.synchronize()
+    # the weight gradient at the positions active before the update
+    assert rel_err(dW.cpu().numpy(), opr.fc_bwd_weight(dY, X, M)) <= TOL
+    # the update, on the GPU's own score bits
+    ref = omg.update(W, M, G_gpu, d_next, zeta, R, 777)
+    assert st["n_prune"] == ref["counts"]["n_prune"] and st["n_grad"] == ref["counts"]["n_grad"]
+    We, Me = rig.export()
+    np.testing.assert_array_equal(Me, ref["M"])
+    np.testing.assert_array_equal(We, ref["W"])
+    np.testing.assert_array_equal(rig.indices(), np.flatnonzero(ref["M"].reshape(-1)))
+
+
+def test_gradient_term_of_the_prune_score_with_random_growth_only():
+    # R = 1 (nothing grows by gradient) with lambda > 0: the fused update still has to form the gradient
+    T, I, O = 256, 320, 192
+    W, M = synth.make_layer(29, 8, I, O, 0.1)
+    X, dY = synth.make_activations(29, 8, T, I, O)
+    rig = Rig(W, M, T, cap=O * I)
+    rig.layer.set_prune_lambda(0.01)
+    Gg = torch.empty((O, I), dtype=torch.float32, device=DEV)
+    mst.mst_dense_grad(dev(dY), dev(X), Gg, T, O, I, mst.MST_F32, rig.ws)
+    torch.cuda.synchronize()
+    G_gpu = Gg.cpu().numpy()
+    Gg.zero_()                                          # nothing stale may be picked up
+    mst.mst_mask_update(rig.layer, dev(dY), dev(X), T, 0.1, 0.3, 1.0, 5, rig.ws)
+    torch.cuda.synchronize()
+    ref = omg.update(W, M, G_gpu, 0.1, 0.3, 1.0, 5, prune_lambda=float(np.float32(0.01)))
+    assert ref["counts"]["n_grad"] == 0
+    We, Me = rig.export()
+    np.testing.assert_array_equal(Me, ref["M"])
+    np.testing.assert_array_equal(We, ref["W"])
