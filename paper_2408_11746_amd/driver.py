@@ -68,3 +68,17 @@ class TopologyDriver:
             return None
         return [B.mst_mask_update(l, dY, X, T, dl, z, self.rand_ratio, self.layer_seed(step, k), ws, act, stream)
                 for k, (l, dY, X, dl) in enumerate(zip(self.layers, dYs, Xs, d_layers))]
+
+    def update_with_weight_gradient(self, step: int, dYs: Sequence, Xs: Sequence, dWs: Sequence, T: int, ws,
+                                    act: int = B.MST_F32, stream=None) -> Optional[List[dict]]:
+        """On an update step: every layer's weight gradient (into dWs, at the positions active
+        before the update) and its update from one dense gradient per layer.  None when the
+        step has no update; the caller then runs the ordinary weight gradient."""
+        if not self.is_update_step(step):
+            return None
+        _, z, d_layers = self.targets(step)
+        if self._idle(d_layers, z):
+            return None
+        return [B.mst_sparse_fc_bwd_weight_update(l, dY, X, dW, T, dl, z, self.rand_ratio, self.layer_seed(step, k), ws,
+                                                  act, stream)
+                for k, (l, dY, X, dW, dl) in enumerate(zip(self.layers, dYs, Xs, dWs, d_layers))]
