@@ -41,6 +41,9 @@ def parse():
     p.add_argument("--fused-update", type=int, default=1,
                    help="C5 only: 1 = weight gradient and update from one dense gradient "
                         "(mst_sparse_fc_bwd_weight_update), 0 = separate calls")
+    p.add_argument("--separate-bwd", action="store_true",
+                   help="time mst_sparse_fc_bwd_input and mst_sparse_fc_bwd_weight as two calls instead of "
+                        "mst_sparse_fc_bwd (both gradients from one walk)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--seed", type=int, default=2024)
     p.add_argument("--attention-mask", type=int, nargs=2, metavar=("L", "STRIDE"), default=None,
@@ -89,6 +92,11 @@ class LayerRun:
     def bytes_bwd_weight(self):
         return self.act_bytes * self.T * (self.I + self.O) + 8 * self.nnz + 4 * self.nnz
 
+    def bytes_bwd(self):
+        # both gradients in one call: dY and X read once, dX and dW written, the entries read once
+        return (self.act_bytes * self.T * (self.I + self.O) + 4 * self.T * self.I + 8 * self.nnz + 4 * self.nnz +
+                4 * (self.I + 1))
+
     def flops_product(self):
         return 2 * self.nnz * self.T
 
@@ -123,14 +131,18 @@ def main():
         for L in layers:
             for _ in range(2):
                 mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
-                mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
-                mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+                if args.separate_bwd:
+                    mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
+                    mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+                else:
+                    mst.mst_sparse_fc_bwd(L.layer, L.dY, L.X, L.dX, L.dW, T, L.ws, L.act, stream)
         torch.cuda.synchronize()
         print(json.dumps({"pmc_probe": True, "copy_bytes_each_way": 1 << 30,
                           "layers": {L.name: dict(I=L.I, O=L.O, nnz=L.nnz) for L in layers}}))
         return
 
-    kinds = ("fwd", "bwd_input", "bwd_weight", "sync_values", "mask_update")
+    products = ("fwd", "bwd_input", "bwd_weight") if args.separate_bwd else ("fwd", "bwd")
+    kinds = products + ("sync_values", "mask_update")
     ev = {(L.name, k): [] for L in layers for k in kinds}
 
     def run_step(t, record):
@@ -144,9 +156,11 @@ def main():
         for L in layers:
             # the three products, then the hand-over of the (optimiser-updated) active weights
             # to the index views, which a training step pays once per layer
-            for kind in ("fwd", "bwd_input", "bwd_weight", "sync_values"):
+            for kind in products + ("sync_values",):
                 if kind == "fwd":
                     mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
+                elif kind == "bwd":
+                    mst.mst_sparse_fc_bwd(L.layer, L.dY, L.X, L.dX, L.dW, T, L.ws, L.act, stream)
                 elif kind == "bwd_input":
                     mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
                 elif kind == "bwd_weight":
@@ -181,7 +195,8 @@ def main():
     n_updates = sum(len(ev[(L.name, "mask_update")]) for L in layers) // max(1, len(layers))
     ms_per_step = 1e3 * elapsed / args.steps
     sparse_flops_step = sum(3 * L.flops_product() for L in layers)
-    bytes_step = sum(L.bytes_fwd() + L.bytes_bwd_input() + L.bytes_bwd_weight() for L in layers)
+    bytes_step = sum(L.bytes_fwd() + (L.bytes_bwd_input() + L.bytes_bwd_weight() if args.separate_bwd else L.bytes_bwd())
+                     for L in layers)
     value = sparse_flops_step / (elapsed / args.steps) / 1e12
 
     # per-call device times from the events recorded inside the timed region
@@ -193,9 +208,9 @@ def main():
                 continue
             ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
             row = dict(layer=L.name, call=kind, launches=len(pairs), avg_ms=round(ms, 5))
-            if kind in ("fwd", "bwd_input", "bwd_weight"):
+            if kind in products:
                 by = getattr(L, "bytes_" + kind)()
-                fl = L.flops_product()
+                fl = L.flops_product() * (2 if kind == "bwd" else 1)
                 row.update(eff_tflops=round(fl / ms / 1e9, 3), hbm_gbs=round(by / ms / 1e6, 1),
                            hbm_frac=round(by / ms / 1e6 / HBM_PEAK_GBS, 4),
                            alu_frac=round(fl / ms / 1e9 / ALU_FP32_PEAK_TFLOPS, 4),
@@ -211,9 +226,16 @@ def main():
     t_hbm = drow["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_alu = drow["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
     # fwd / bwd_input are one k_spmm launch; bwd_weight is k_sddmm followed by the small k_sddmm_reduce
+    dense_bww = act == "bf16" and density > 0.045 and T >= 2048
+    if dense_bww:          # the bf16 MFMA weight gradient is faster than any sparse kernel here
+        bwd_kernels = "k_spmm64 + k_gemm_tn_bf16 + k_gather_flat (separate kernels)"
+    elif density < 0.025:  # below this density the library keeps the separate kernels with their wider slabs
+        bwd_kernels = "k_spmm64 + k_sddmm + k_sddmm_reduce (separate kernels)"
+    else:
+        bwd_kernels = "k_bwd_fused + k_bwd_fused_reduce"
     kernel = {"fwd": "k_spmm / k_spmm64 (launch shape chosen per call)",
               "bwd_input": "k_spmm / k_spmm64 (launch shape chosen per call)",
-              "bwd_weight": "k_sddmm+k_sddmm_reduce"}[drow["call"]]
+              "bwd_weight": "k_sddmm+k_sddmm_reduce", "bwd": bwd_kernels}[drow["call"]]
     # with bfloat16 activations the library computes the weight gradient as the full MFMA
     # product dY^T X read at the active positions from a density of 0.045 on (T >= 2048)
     mfma_bww = drow["call"] == "bwd_weight" and act == "bf16" and density > 0.045 and T >= 2048
@@ -241,11 +263,13 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if act == "f32" else "bf16-in/f32-acc",
         "data": "synthetic",
-        "config": {"workload": "%s: %s FC set (%s), density %.2f %s mask, T=%d tokens, fwd+bwd_input+bwd_weight "
+        "config": {"workload": "%s: %s FC set (%s), density %.2f %s mask, T=%d tokens, %s "
                                "+ value hand-over to the index views per layer, Mixed-Growing update every %d steps"
                                % (args.config, "GPT-2-small block" if len(layers) > 1 else "single layer",
                                   ", ".join("%s %d->%d" % (L.name, L.I, L.O) for L in layers), density,
-                                  cfg["mask"], T, args.update_interval),
+                                  cfg["mask"], T,
+                                  "fwd+bwd_input+bwd_weight" if args.separate_bwd
+                                  else "fwd + bwd (input and weight gradient in one call)", args.update_interval),
                    "nnz": {L.name: L.nnz for L in layers}, "mask_updates_in_timed_region": n_updates},
         "hbm_gbs_step": round(bytes_step / (elapsed / args.steps) / 1e9, 1),
         "hbm_frac_step": round(bytes_step / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),

@@ -148,6 +148,20 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* layer, const void* dY_dev, const
                              float* dW_dev, int T, mst_dtype act,
                              void* ws_dev, size_t ws_bytes, mst_stream_t stream);
 
+/* Both gradients of the backward pass in one call: dX as mst_sparse_fc_bwd_input, dW_vals as
+ * mst_sparse_fc_bwd_weight.  On the sparse path the two products share one walk of the
+ * layer's transposed view (the staged dY tile, the entries and every LDS read serve both);
+ * dX is bit-identical to mst_sparse_fc_bwd_input, dW_vals equals mst_sparse_fc_bwd_weight up
+ * to the order of the fp32 sums.  Workspace: mst_workspace_bytes(O, I, nnz_capacity, T). */
+int mst_sparse_fc_bwd(const mst_layer_t* layer, const void* dY_dev, const void* X_dev,
+                      float* dX_dev, float* dW_vals_dev, int T, mst_dtype act,
+                      void* ws_dev, size_t ws_bytes, mst_stream_t stream);
+
+/* Test hook like mst_spmm_force_shape for the shared walk of mst_sparse_fc_bwd:
+ * (8, 3) or (16, 1) wavefronts per workgroup x quads per wavefront, (0, 0) = automatic.
+ * Every shape gives the same results. */
+int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront);
+
 /* G_dev [O*I] = dY^T X at every position (the score of gradient-based growth; Sec. 2,
  * "infrequent full gradient calculation").  Runs on the matrix cores.  ws_dev may be
  * NULL; with a workspace small outputs split the token range over more workgroups. */

@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         "mst_sparse_fc_fwd": (i32, [vp, vp, vp, i32, i32, vp]),
         "mst_sparse_fc_bwd_input": (i32, [vp, vp, vp, i32, i32, vp]),
         "mst_sparse_fc_bwd_weight": (i32, [vp, vp, vp, vp, i32, i32, vp, sz, vp]),
+        "mst_sparse_fc_bwd": (i32, [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]),
+        "mst_bwd_force_shape": (i32, [i32, i32]),
         "mst_dense_grad": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]),
         "mst_update_counts": (i32, [i64, i64, dbl, dbl, dbl, C.POINTER(UpdateStats)]),
         "mst_mask_update_from_scores": (i32, [vp, vp, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
@@ -110,7 +112,7 @@ EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_w
            "mst_layer_create", "mst_layer_destroy", "mst_layer_load_dense", "mst_layer_export_dense",
            "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_layer_set_prune_lambda",
            "mst_spmm_force_shape",
-           "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight",
+           "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight", "mst_sparse_fc_bwd", "mst_bwd_force_shape",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
            "mst_sparse_fc_bwd_weight_update",
            "mst_schedule_density", "mst_erdos_renyi_density", "mst_flops_fc_forward", "mst_flops_transformer",
@@ -252,6 +254,16 @@ def mst_sparse_fc_bwd_weight(layer: Layer, dY, X, dW, T: int, ws, act: int = MST
     _check("mst_sparse_fc_bwd_weight",
            lib().mst_sparse_fc_bwd_weight(layer.h, _ptr(dY), _ptr(X), _ptr(dW), T, act, _ptr(ws), ws.numel(),
                                           _stream(stream)))
+
+
+def mst_bwd_force_shape(wavefronts_per_workgroup: int = 0, quads_per_wavefront: int = 0):
+    _check("mst_bwd_force_shape", lib().mst_bwd_force_shape(wavefronts_per_workgroup, quads_per_wavefront))
+
+
+def mst_sparse_fc_bwd(layer: Layer, dY, X, dX, dW, T: int, ws, act: int = MST_F32, stream=None):
+    _check("mst_sparse_fc_bwd",
+           lib().mst_sparse_fc_bwd(layer.h, _ptr(dY), _ptr(X), _ptr(dX), _ptr(dW), T, act, _ptr(ws), ws.numel(),
+                                   _stream(stream)))
 
 
 def mst_dense_grad(dY, X, G, T: int, O: int, I: int, act: int = MST_F32, ws=None, stream=None):

@@ -59,6 +59,10 @@ int mst_spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront) {
     return spmm_force_shape(tokens_per_workgroup, quads_per_wavefront);
 }
 
+int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront) {
+    return bwd_fused_force_shape(wavefronts_per_workgroup, quads_per_wavefront);
+}
+
 int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int T, mst_dtype act,
                       mst_stream_t stream) {
     if (!L || !X_dev || !Y_dev || T < 1 || !act_ok(act) || !aligned16(X_dev) || !aligned16(Y_dev)) return MST_ERR_ARG;
@@ -84,6 +88,26 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const voi
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_weight_grad(L, act, T)) return dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
     return sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+}
+
+int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_dev, float* dX_dev, float* dW_dev,
+                      int T, mst_dtype act, void* ws_dev, size_t ws_bytes, mst_stream_t stream) {
+    if (!L || !dY_dev || !X_dev || !dX_dev || !dW_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
+    if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dX_dev) || !aligned16(dW_dev) || !aligned16(ws_dev))
+        return MST_ERR_ARG;
+    const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
+    if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (use_dense_path(L) || use_dense_weight_grad(L, act, T) || !bwd_fused_pays(L)) {
+        // a dense contraction serves at least one of the two, or the layer is so sparse that
+        // the separate kernels with their wider slabs are faster: the separate calls
+        int rc = use_dense_path(L) ? dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s)
+                                   : spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
+        if (rc != MST_OK) return rc;
+        return use_dense_weight_grad(L, act, T) ? dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s)
+                                                : sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+    }
+    return bwd_fused(L, dY_dev, X_dev, dX_dev, dW_dev, T, act, ws, s);
 }
 
 int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, int O, int I, mst_dtype act,

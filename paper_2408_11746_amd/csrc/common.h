@@ -137,6 +137,11 @@ int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype
 int spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront);
 int sddmm(const mst_layer* L, const void* dY, const void* X, float* dW, int T, mst_dtype act,
           const Workspace& ws, hipStream_t s);
+// dX and dW from one walk of the col view; see bwd_fused.hip
+int bwd_fused(const mst_layer* L, const void* dY, const void* X, float* dX, float* dW, int T, mst_dtype act,
+              const Workspace& ws, hipStream_t s);
+bool bwd_fused_pays(const mst_layer* L);
+int bwd_fused_force_shape(int waves, int quads);
 // C[M x N] (fp32) = op(A) op(B) on the matrix cores; see gemm_mfma.hip
 enum GemmKind { GEMM_TN = 0, GEMM_NT = 1, GEMM_NN = 2 };
 int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_dtype b_dt, float* C,

@@ -16,32 +16,9 @@
 // fixed order (deterministic, no floating-point atomics) and writes the result at the
 // entry's canonical position.
 #include "tile_loader.h"
+#include "walk_ops.h"
 
 namespace mst {
-
-template <int CTRL>
-__device__ inline float dpp_add(float x) {
-    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
-}
-
-// Sums of a and b over each row of 16 lanes with six adds / selects instead of eight:
-// after the first exchange the lower eight lanes go on with a, the upper eight with b.
-// The sum of a ends up in lanes 0..7 of the row, the sum of b in lanes 8..15.
-__device__ inline float row_sum_pair(float a, float b, bool upper_half) {
-    a = dpp_add<0x128>(a);                 // row_ror:8   lane s += lane s ^ 8
-    b = dpp_add<0x128>(b);
-    float c = upper_half ? b : a;
-    c = dpp_add<0x141>(c);                 // row_half_mirror   lane s += lane 7 - s of its half
-    c = dpp_add<0xB1>(c);                  // quad_perm:[1,0,3,2]
-    c = dpp_add<0x4E>(c);                  // quad_perm:[2,3,0,1]
-    return c;
-}
-
-// value of v in lane JJ of this lane's aligned group of four lanes
-template <int JJ>
-__device__ inline uint32_t quad_bcast(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, JJ * 0x55, 0xf, 0xf, true);
-}
 
 // this lane's share (8 tokens) of the dot product of one entry
 #define MST_DOT(JJ, OFF, DY, RES)                                                    \

@@ -16,27 +16,9 @@
 // a lane outside the group of four.  The result tile leaves through LDS so that global
 // stores are contiguous runs of the slab's columns.
 #include "tile_loader.h"
+#include "walk_ops.h"
 
 namespace mst {
-
-// value of v in lane JJ of this lane's aligned group of four lanes
-template <int JJ>
-__device__ inline uint32_t quad_bcast(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, JJ * 0x55, 0xf, 0xf, true);
-}
-
-// Four FMAs whose common factor W comes from lane JJ of the group of four lanes through the
-// DPP operand of v_fmac_f32 (no separate broadcast move).  The leading s_nop covers the two
-// wait states a DPP read needs after a VALU write of its source, whatever was scheduled
-// in front of the block.
-#define MST_FMA4_BC(JJ, A0, A1, A2, A3, W, X)                                                   \
-    asm("s_nop 1\n\t"                                                                           \
-        "v_fmac_f32_dpp %0, %4, %5 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
-        "v_fmac_f32_dpp %1, %4, %6 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
-        "v_fmac_f32_dpp %2, %4, %7 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
-        "v_fmac_f32_dpp %3, %4, %8 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1"     \
-        : "+v"(A0), "+v"(A1), "+v"(A2), "+v"(A3)                                                \
-        : "v"(W), "v"(X.x), "v"(X.y), "v"(X.z), "v"(X.w))
 
 // one step: entry {OFF, W} as held by lane JJ of the group of four lanes
 #define MST_STEP(JJ, OFF, W, ACC)                                                    \
@@ -56,21 +38,6 @@ __device__ inline uint32_t quad_bcast(uint32_t v) {
     } while (0)
 
 constexpr int NW = 16;      // wavefronts per workgroup
-
-// A spread quad (one long row dealt over the four lane groups): lane group 0 takes the sum
-// of the four lane groups' accumulators, the others -- whose output positions belong to
-// empty rows -- take zero.  `spread` is the same in every lane of the wavefront.
-template <int NACC>
-__device__ inline void fold_spread(float (&acc)[NACC], int spread, int g) {
-    if (!__builtin_amdgcn_readfirstlane(spread)) return;
-#pragma unroll
-    for (int e = 0; e < NACC; ++e) {
-        float v = acc[e];
-        v += __shfl_xor(v, 16, 64);
-        v += __shfl_xor(v, 32, 64);
-        acc[e] = (g == 0) ? v : 0.f;
-    }
-}
 
 // QW = quads per wavefront: 4 (a wavefront owns a whole row block of 16 rows) or 2 (two
 // wavefronts share a block, 8 rows each) -- the latter doubles the number of wavefronts

@@ -1,0 +1,61 @@
+// Cross-lane building blocks shared by the kernels that walk the ELL slices (SpMM, SDDMM and
+// the backward kernel that does both): entry hand-over inside groups of four lanes, sums over
+// the 16 lanes of a lane group, and the fold of a spread quad.
+#pragma once
+#include "common.h"
+
+namespace mst {
+
+// value of v in lane JJ of this lane's aligned group of four lanes
+template <int JJ>
+__device__ inline uint32_t quad_bcast(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, JJ * 0x55, 0xf, 0xf, true);
+}
+
+// Four FMAs whose common factor W comes from lane JJ of the group of four lanes through the
+// DPP operand of v_fmac_f32 (no separate broadcast move).  The leading s_nop covers the two
+// wait states a DPP read needs after a VALU write of its source, whatever was scheduled
+// in front of the block.
+#define MST_FMA4_BC(JJ, A0, A1, A2, A3, W, X)                                                   \
+    asm("s_nop 1\n\t"                                                                           \
+        "v_fmac_f32_dpp %0, %4, %5 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+        "v_fmac_f32_dpp %1, %4, %6 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+        "v_fmac_f32_dpp %2, %4, %7 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+        "v_fmac_f32_dpp %3, %4, %8 quad_perm:[" #JJ "," #JJ "," #JJ "," #JJ "] row_mask:0xf bank_mask:0xf bound_ctrl:1"     \
+        : "+v"(A0), "+v"(A1), "+v"(A2), "+v"(A3)                                                \
+        : "v"(W), "v"(X.x), "v"(X.y), "v"(X.z), "v"(X.w))
+
+// A spread quad (one long row dealt over the four lane groups): lane group 0 takes the sum
+// of the four lane groups' accumulators, the others -- whose output positions belong to
+// empty rows -- take zero.  `spread` is the same in every lane of the wavefront.
+template <int NACC>
+__device__ inline void fold_spread(float (&acc)[NACC], int spread, int g) {
+    if (!__builtin_amdgcn_readfirstlane(spread)) return;
+#pragma unroll
+    for (int e = 0; e < NACC; ++e) {
+        float v = acc[e];
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+        acc[e] = (g == 0) ? v : 0.f;
+    }
+}
+
+template <int CTRL>
+__device__ inline float dpp_add(float x) {
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// Sums of a and b over each row of 16 lanes with six adds / selects instead of eight:
+// after the first exchange the lower eight lanes go on with a, the upper eight with b.
+// The sum of a ends up in lanes 0..7 of the row, the sum of b in lanes 8..15.
+__device__ inline float row_sum_pair(float a, float b, bool upper_half) {
+    a = dpp_add<0x128>(a);                 // row_ror:8   lane s += lane s ^ 8
+    b = dpp_add<0x128>(b);
+    float c = upper_half ? b : a;
+    c = dpp_add<0x141>(c);                 // row_half_mirror   lane s += lane 7 - s of its half
+    c = dpp_add<0xB1>(c);                  // quad_perm:[1,0,3,2]
+    c = dpp_add<0x4E>(c);                  // quad_perm:[2,3,0,1]
+    return c;
+}
+
+}  // namespace mst
