@@ -47,6 +47,16 @@ def test_c2_layer_products_sampled(name, I, O):
     pick = np.unique(np.concatenate([[0, flat.size - 1], rng.integers(0, flat.size, 1500)]))
     ref = np.array([opr.dense_grad_at(dY, X, int(f // I), int(f % I)) for f in flat[pick]])
     assert np.abs(dW[pick] - ref).max() / np.abs(ref).max() <= TOL
+    # the one-call backward, as the benchmark times it: the same input gradient bit for bit, the
+    # weight gradient at the sampled positions
+    dX1 = torch.full((T, I), float("nan"), dtype=torch.float32, device=DEV)
+    dW1 = torch.full((rig.layer.nnz,), float("nan"), dtype=torch.float32, device=DEV)
+    mst.mst_sparse_fc_bwd(rig.layer, dev(dY), dev(X), dX1, dW1, T, rig.ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(dX1.cpu().numpy(), dX)
+    dW1 = dW1.cpu().numpy()
+    assert np.abs(dW1[pick] - ref).max() / np.abs(ref).max() <= TOL
+    assert rel_err(dW1, dW) <= 1e-5                   # the two weight gradients differ in summation order only
     # adjoint identities tie the three full-size outputs together (fp64 reductions of fp32 outputs)
     a = float((dY.astype(np.float64) * Y).sum())
     b = float((dX.astype(np.float64) * X).sum())
