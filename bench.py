@@ -229,8 +229,6 @@ def main():
     dense_bww = act == "bf16" and density > 0.045 and T >= 2048
     if dense_bww:          # the bf16 MFMA weight gradient is faster than any sparse kernel here
         bwd_kernels = "k_spmm64 + k_gemm_tn_bf16 + k_gather_flat (separate kernels)"
-    elif density < 0.025:  # below this density the library keeps the separate kernels with their wider slabs
-        bwd_kernels = "k_spmm64 + k_sddmm + k_sddmm_reduce (separate kernels)"
     else:
         bwd_kernels = "k_bwd_fused + k_bwd_fused_reduce"
     kernel = {"fwd": "k_spmm / k_spmm64 (launch shape chosen per call)",
