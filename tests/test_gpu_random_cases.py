@@ -1,5 +1,5 @@
 """Seeded random layers (shape, density, mask kind, launch shape, path) through the C ABI
-against the oracle: the three products, a Mixed-Growing update from given scores
+against the oracle: the three products, the one-call backward, a Mixed-Growing update from given scores
 (bit-exact mask and weights) and the products again on the updated layer."""
 import numpy as np
 import pytest
@@ -12,7 +12,22 @@ from oracle import products as opr
 pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
-from gpu_util import Rig, TOL, dev, rel_err  # noqa: E402
+from gpu_util import Rig, TOL, dev, rel_err, DEV  # noqa: E402
+
+BWD_SHAPES = [(0, 0), (8, 3), (16, 1)]
+
+
+def _bwd_one_call(rig, dY, X, T, I, shape):
+    """Both gradients through mst_sparse_fc_bwd in a given launch shape."""
+    dX = torch.full((T, I), float("nan"), dtype=torch.float32, device=DEV)
+    dW = torch.full((max(rig.layer.nnz, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    try:
+        mst.mst_bwd_force_shape(*shape)
+        mst.mst_sparse_fc_bwd(rig.layer, dev(dY), dev(X), dX, dW, T, rig.ws)
+        torch.cuda.synchronize()
+    finally:
+        mst.mst_bwd_force_shape(0, 0)
+    return dX.cpu().numpy(), dW.cpu().numpy()[: rig.layer.nnz]
 
 LAUNCH_SHAPES = [(128, 2), (128, 4), (64, 2), (64, 3), (64, 4), (64, 6), (64, 8), (0, 0)]
 
@@ -53,6 +68,10 @@ def test_random_layers(stream_seed):
             mst.mst_spmm_force_shape(0, 0)
         if M.sum() > 0:
             assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, M)) <= TOL
+        dX1, dW1 = _bwd_one_call(rig, dY, X, T, I, BWD_SHAPES[case % 3])
+        assert rel_err(dX1, opr.fc_bwd_input(dY, W, M)) <= TOL
+        if M.sum() > 0:
+            assert rel_err(dW1, opr.fc_bwd_weight(dY, X, M)) <= TOL
         G = synth.normal(seed, 77, (O, I))
         mst.mst_mask_update_from_scores(rig.layer, dev(G), d2, 0.3, 0.25, seed, rig.ws)
         torch.cuda.synchronize()
@@ -64,3 +83,7 @@ def test_random_layers(stream_seed):
         assert rel_err(rig.bwd_input(dY), opr.fc_bwd_input(dY, ref["W"], ref["M"])) <= TOL
         if ref["M"].sum() > 0:
             assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, ref["M"])) <= TOL
+        dX1, dW1 = _bwd_one_call(rig, dY, X, T, I, BWD_SHAPES[(case + 1) % 3])
+        assert rel_err(dX1, opr.fc_bwd_input(dY, ref["W"], ref["M"])) <= TOL
+        if ref["M"].sum() > 0:
+            assert rel_err(dW1, opr.fc_bwd_weight(dY, X, ref["M"])) <= TOL
