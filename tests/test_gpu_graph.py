@@ -21,15 +21,18 @@ def test_products_replay_from_a_hip_graph():
     Y = torch.empty((T, O), dtype=torch.float32, device=DEV)
     dX = torch.empty((T, I), dtype=torch.float32, device=DEV)
     dW = torch.empty(rig.layer.nnz, dtype=torch.float32, device=DEV)
+    dX2, dW2 = torch.empty_like(dX), torch.empty_like(dW)
 
     def step():
         mst.mst_sparse_fc_fwd(rig.layer, Xd, Y, T)
         mst.mst_sparse_fc_bwd_input(rig.layer, dYd, dX, T)
         mst.mst_sparse_fc_bwd_weight(rig.layer, dYd, Xd, dW, T, rig.ws)
+        mst.mst_sparse_fc_bwd(rig.layer, dYd, Xd, dX2, dW2, T, rig.ws)      # both gradients in one call
+        rig.layer.sync_values()
 
     step()
     torch.cuda.synchronize()
-    ref = (Y.clone(), dX.clone(), dW.clone())
+    ref = (Y.clone(), dX.clone(), dW.clone(), dX2.clone(), dW2.clone())
 
     g = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
@@ -40,11 +43,12 @@ def test_products_replay_from_a_hip_graph():
     with torch.cuda.graph(g, stream=side):
         step()
     for rep in range(3):
-        Y.fill_(float("nan")); dX.fill_(float("nan")); dW.fill_(float("nan"))
+        for buf in (Y, dX, dW, dX2, dW2):
+            buf.fill_(float("nan"))
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        for got, want in zip((Y, dX, dW), ref):
+        for got, want in zip((Y, dX, dW, dX2, dW2), ref):
             assert torch.equal(got, want), rep     # bit-identical to the eager run
         # eager work between the replays
         Xd.mul_(1.0)
