@@ -14,6 +14,8 @@
 // order; dW: 128-token partial sums added in ascending tile order by the second kernel), so
 // the results are those of the SpMM, bit for bit, and of the SDDMM when it is driven by the
 // col view.
+#include <algorithm>
+
 #include "tile_loader.h"
 #include "walk_ops.h"
 
@@ -50,8 +52,10 @@ template <typename TIn, int NWF, int QW>
 __global__ __launch_bounds__(NWF * 64) __attribute__((amdgpu_waves_per_eu(NWF / 2, NWF / 2)))
 void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __restrict__ X /* registers [T x R] */,
                  const int* __restrict__ ptr, const uint4* __restrict__ ent, const int* __restrict__ rowmap,
-                 float* __restrict__ dX /* [T x R] */, float* __restrict__ partial, int64_t slots_stride,
-                 int T, int K, int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_reg) {
+                 float* __restrict__ dX /* [T x R], or [nsplit][T x R] partial input gradients */,
+                 float* __restrict__ partial, int64_t slots_stride,
+                 int T, int K, int R, int NBpad, int nchunk, int nslab, int ntile, int vec_ok, int vec_reg,
+                 int chunks_per_split) {
     __shared__ float tile[KC * TT];
     int tile_id, slab;
     if (!block_to_tile(nslab, ntile, tile_id, slab)) return;
@@ -114,12 +118,18 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
 
+    // blockIdx.y takes a range of chunks (short batches: more workgroups than tiles x slabs).
+    // An entry lies in one chunk, so its weight gradient is complete in one workgroup; the
+    // input gradient of a range is a partial sum, written to its own [T x R] plane.
+    const int c_begin = blockIdx.y * chunks_per_split;
+    const int c_end = min(nchunk, c_begin + chunks_per_split);
+    dX += (int64_t)blockIdx.y * T * R;
     const int pl = fq + min(lane, QW);
-    int pv = ptr[pl];
-    for (int c = 0; c < nchunk; ++c) {
+    int pv = ptr[(int64_t)c_begin * NBpad * 4 + pl];
+    for (int c = c_begin; c < c_end; ++c) {
         __syncthreads();
         load_tile<TIn, NWF * 64>(tile, dY, K, t0, c * KC, T, K, vec_ok != 0, tid);
-        const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
+        const int pv_next = (c + 1 < c_end) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
         int p = __builtin_amdgcn_readlane(pv, 0);
         uint4 nxt = ent[(int64_t)p * 4 + eoff];
         __syncthreads();
@@ -194,14 +204,24 @@ __global__ void k_bwd_fused_reduce(const float* __restrict__ partial, int64_t sl
     dW[p] = sum;
 }
 
+// dX[k] = sum of the nsplit partial planes, added in ascending order
+__global__ void k_sum_planes(const float* __restrict__ planes, int64_t n, int nsplit, float* __restrict__ out) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n) return;
+    float sum = planes[k];
+    for (int z = 1; z < nsplit; ++z) sum += planes[(int64_t)z * n + k];
+    out[k] = sum;
+}
+
 template <typename TIn, int NWF, int QW>
-static void launch_fused(const View& v, const TIn* dY, const TIn* X, float* dX, float* partial, int T, hipStream_t s) {
+static void launch_fused(const View& v, const TIn* dY, const TIn* X, float* dX, float* partial, int T, int nsplit,
+                         hipStream_t s) {
     const int ntile = (int)cdiv(T, TT);
     const int nslab = (int)cdiv((int64_t)v.NB * 4, NWF * QW);
-    k_bwd_fused<TIn, NWF, QW><<<grid_for(ntile, nslab), NWF * 64, 0, s>>>(dY, X, v.ptr, v.ent, v.rowmap, dX, partial,
-                                                                    v.cap_pairs * 8, T, v.K, v.R, v.NBpad, v.nchunk,
-                                                                    nslab, ntile, (v.K % 4 == 0) ? 1 : 0,
-                                                                    (v.R % 4 == 0) ? 1 : 0);
+    const int cps = (int)cdiv(v.nchunk, nsplit);
+    k_bwd_fused<TIn, NWF, QW><<<dim3(grid_for(ntile, nslab), (unsigned)nsplit), NWF * 64, 0, s>>>(
+        dY, X, v.ptr, v.ent, v.rowmap, dX, partial, v.cap_pairs * 8, T, v.K, v.R, v.NBpad, v.nchunk, nslab, ntile,
+        (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0, cps);
 }
 
 // Launch shapes: 8 wavefronts x 3 quads (96-row slabs, 128 registers per lane) or 16
@@ -257,25 +277,48 @@ static FusedShape pick_fused_shape(int T, int R, int K, double density) {
     return best;
 }
 
+// Short batches leave most CUs without a workgroup and every workgroup with a long chain of
+// chunks: the chunk range is then split over up to 8 workgroups (as many as keep the grid
+// within one round and the partial input gradients within `plane_floats`).  A forced launch
+// shape runs unsplit.
+static int pick_chunk_split(int T, const View& v, size_t plane_floats) {
+    if (g_forced_fused.waves != 0) return 1;
+    const int64_t nwg = cdiv(T, TT) * cdiv(v.R, 64);
+    if (nwg > 128 || v.nchunk < 4) return 1;
+    int64_t n = std::min<int64_t>({8, v.nchunk / 2, 512 / nwg, (int64_t)(plane_floats / ((size_t)T * v.R))});
+    if (n < 2) return 1;
+    const int64_t cps = cdiv(v.nchunk, n);
+    return (int)cdiv(v.nchunk, cps);                  // no empty range
+}
+
 template <typename TIn>
-static void launch_fused_any(const View& v, const TIn* dY, const TIn* X, float* dX, float* partial, int T,
-                             double density, hipStream_t s) {
+static int launch_fused_any(const View& v, const TIn* dY, const TIn* X, float* dX, const Workspace& ws, int T,
+                            double density, hipStream_t s) {
+    const int nsplit = pick_chunk_split(T, v, ws.gemm_floats);
+    if (nsplit > 1) {
+        launch_fused<TIn, 16, 1>(v, dY, X, ws.gemm, ws.partial, T, nsplit, s);
+        MST_LAUNCH_CHECK();
+        const int64_t n = (int64_t)T * v.R;
+        k_sum_planes<<<(unsigned)cdiv(n, 256), 256, 0, s>>>(ws.gemm, n, nsplit, dX);
+        MST_LAUNCH_CHECK();
+        return MST_OK;
+    }
     const FusedShape sh = pick_fused_shape(T, v.R, v.K, density);
-    if (sh.waves == 8) launch_fused<TIn, 8, 3>(v, dY, X, dX, partial, T, s);
-    else launch_fused<TIn, 16, 1>(v, dY, X, dX, partial, T, s);
+    if (sh.waves == 8) launch_fused<TIn, 8, 3>(v, dY, X, dX, ws.partial, T, 1, s);
+    else launch_fused<TIn, 16, 1>(v, dY, X, dX, ws.partial, T, 1, s);
+    MST_LAUNCH_CHECK();
+    return MST_OK;
 }
 
 int bwd_fused(const mst_layer* L, const void* dY, const void* X, float* dX, float* dW, int T, mst_dtype act,
               const Workspace& ws, hipStream_t s) {
     const View& v = L->col;
     const double density = (double)L->nnz / (double)L->N;
-    if (act == MST_F32)
-        launch_fused_any<float>(v, static_cast<const float*>(dY), static_cast<const float*>(X), dX, ws.partial, T,
-                                density, s);
-    else
-        launch_fused_any<uint16_t>(v, static_cast<const uint16_t*>(dY), static_cast<const uint16_t*>(X), dX, ws.partial,
-                                   T, density, s);
-    MST_LAUNCH_CHECK();
+    const int rc = (act == MST_F32)
+        ? launch_fused_any<float>(v, static_cast<const float*>(dY), static_cast<const float*>(X), dX, ws, T, density, s)
+        : launch_fused_any<uint16_t>(v, static_cast<const uint16_t*>(dY), static_cast<const uint16_t*>(X), dX, ws, T,
+                                     density, s);
+    if (rc != MST_OK) return rc;
     if (L->nnz > 0) {
         const int64_t upper = 4 * (L->nnz + (int64_t)v.nchunk * v.NB * 4);
         k_bwd_fused_reduce<<<(unsigned)cdiv(upper, 256), 256, 0, s>>>(ws.partial, v.cap_pairs * 8, (int)cdiv(T, TT), v.ptr,

@@ -16,7 +16,8 @@ from gpu_util import Rig, TOL, dev, rel_err, DEV  # noqa: E402
 CASES = [
     (300, 200, 333, 0.10, "uniform"),       # nothing a multiple of 4 / 64 / 128
     (129, 768, 768, 0.05, "uniform"),       # one token past a tile
-    (512, 768, 3072, 0.05, "uniform"),      # short batch: few workgroups
+    (512, 768, 3072, 0.05, "uniform"),      # short batch: the chunk range is split over workgroups
+    (200, 130, 1100, 0.10, "uniform"),      # short batch, ragged, 9 chunks split unevenly
     (640, 3072, 768, 0.10, "uniform"),      # many row slabs, 6 chunks
     (1, 5, 3, 0.6, "uniform"),              # single token, tiny
     (2100, 200, 3850, 0.05, "uniform"),     # ragged everywhere, 31 chunks
@@ -48,10 +49,15 @@ def test_both_gradients_match_oracle_in_every_launch_shape(T, I, O, density, mas
             mst.mst_bwd_force_shape(*shape)
             dX, dW = _run(rig, dev(dY), dev(X), T, I, mst.MST_F32)
             assert rel_err(dX, ref_dX) <= TOL and rel_err(dW, ref_dW) <= TOL, shape
-            np.testing.assert_array_equal(dX, sep_dX)            # the input gradient of the separate call, bit for bit
+            if shape != (0, 0):
+                # a given launch shape forms the separate call's sums, bit for bit (the automatic choice may
+                # split the chunk range of a short batch, which regroups the input gradient's sum)
+                np.testing.assert_array_equal(dX, sep_dX)
+            else:
+                assert rel_err(dX, sep_dX) <= 1e-6
             if first is None:
                 first = dW
-            np.testing.assert_array_equal(dW, first)             # every launch shape forms the same sums
+            np.testing.assert_array_equal(dW, first)             # the weight gradient is the same in every shape
     finally:
         mst.mst_bwd_force_shape(0, 0)
 
