@@ -284,7 +284,7 @@ static FusedShape pick_fused_shape(int T, int R, int K, double density) {
 static int pick_chunk_split(int T, const View& v, size_t plane_floats) {
     if (g_forced_fused.waves != 0) return 1;
     const int64_t nwg = cdiv(T, TT) * cdiv(v.R, 64);
-    if (nwg > 128 || v.nchunk < 4) return 1;
+    if (nwg > 256 || v.nchunk < 12) return 1;     // short chunk chains gain less than the extra pass costs
     int64_t n = std::min<int64_t>({8, v.nchunk / 2, 512 / nwg, (int64_t)(plane_floats / ((size_t)T * v.R))});
     if (n < 2) return 1;
     const int64_t cps = cdiv(v.nchunk, n);
