@@ -126,7 +126,7 @@ int mst_layer_set_prune_lambda(mst_layer_t* layer, float lambda);
 int64_t mst_layer_nnz(const mst_layer_t* layer);
 
 /* Launch shape of the sparse products' SpMM kernel: tokens per workgroup (128 or 64) and
- * quads of four rows per wavefront (2 or 4 with 128 tokens; 2, 3, 4, 6 or 8 with 64).  By
+ * quads of four rows per wavefront (2, 3 or 4 with 128 tokens; 2, 3, 4, 6 or 8 with 64).  By
  * default the library chooses per call from T, the layer's shape and its density; every
  * shape gives bit-identical results.  This call pins one shape for all later calls of the
  * process (tests and tuning); (0, 0) returns to the automatic choice.  Not thread-safe.
@@ -152,7 +152,9 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* layer, const void* dY_dev, const
  * mst_sparse_fc_bwd_weight.  On the sparse path the two products share one walk of the
  * layer's transposed view (the staged dY tile, the entries and every LDS read serve both);
  * dX is bit-identical to mst_sparse_fc_bwd_input, dW_vals equals mst_sparse_fc_bwd_weight up
- * to the order of the fp32 sums.  Workspace: mst_workspace_bytes(O, I, nnz_capacity, T). */
+ * to the order of the fp32 sums.  (A short batch may split the contraction over several
+ * workgroups; dX then equals mst_sparse_fc_bwd_input up to the order of its sums too.)
+ * Workspace: mst_workspace_bytes(O, I, nnz_capacity, T). */
 int mst_sparse_fc_bwd(const mst_layer_t* layer, const void* dY_dev, const void* X_dev,
                       float* dX_dev, float* dW_vals_dev, int T, mst_dtype act,
                       void* ws_dev, size_t ws_bytes, mst_stream_t stream);

@@ -39,9 +39,8 @@ namespace mst {
 
 constexpr int NW = 16;      // wavefronts per workgroup
 
-// QW = quads per wavefront: 4 (a wavefront owns a whole row block of 16 rows) or 2 (two
-// wavefronts share a block, 8 rows each) -- the latter doubles the number of wavefronts
-// when the output is too narrow to give every CU two full workgroups.
+// QW = quads per wavefront (2, 3 or 4 consecutive quads, which may cross row blocks): the
+// slab of a workgroup is 64 QW rows.
 template <typename TIn, int QW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_spmm(
     const TIn* __restrict__ A, const int* __restrict__ ptr, const uint4* __restrict__ ent,
@@ -55,9 +54,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = tile_id * TT;
-    constexpr int WPB = 4 / QW;                        // wavefronts per row block
-    const int blk = (slab * nw + wave) / WPB;         // this wavefront's row block
-    const int q0 = (wave % WPB) * QW;                 // its first quad
+    const int fq = (slab * nw + wave) * QW;           // this wavefront's first quad (4 * block + quad)
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
@@ -72,7 +69,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
         for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
 
     // lane q (0..QW) keeps the first pair of this wavefront's quad q of the current chunk
-    const int pl = blk * 4 + q0 + min(lane, QW);
+    const int pl = fq + min(lane, QW);
     int pv = ptr[pl];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
@@ -104,11 +101,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
         pv = pv_next;
     }
 
-    // rows of this lane's accumulators: rank 4 (q0 + q) + g of the block
+    // rows of this lane's accumulators: place g of quad fq + q
     int rloc[QW];
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
-        const int rm = rowmap[blk * RB + 4 * (q0 + q) + g];
+        const int rm = rowmap[(fq + q) * 4 + g];
         fold_spread(acc[q], rm & SPREAD_FLAG, g);
         rloc[q] = rm & ~SPREAD_FLAG;
     }
@@ -328,7 +325,7 @@ static SpmmShape g_forced = {0, 0};
 
 static SpmmShape pick_shape(int T, int R, int K, double density) {
     if (g_forced.tt != 0) return g_forced;
-    static const SpmmShape cand[] = {{128, 2}, {128, 4}, {64, 2}, {64, 3}, {64, 4}, {64, 6}, {64, 8}};
+    static const SpmmShape cand[] = {{128, 2}, {128, 3}, {128, 4}, {64, 2}, {64, 3}, {64, 4}, {64, 6}, {64, 8}};
     const double kWalk = 2.92e-5, kStage = 1.92e-5, kOut = 5.19e-4, kChunk = 1.87;
     const double kLoneTail = 0.60, kLoneOnly = 0.71, k64 = 0.967;
     const int64_t nchunk = cdiv(K, KC);
@@ -369,11 +366,14 @@ static int launch_spmm(const View& v, const TIn* A, float* out, int T, int64_t n
         return MST_OK;
     }
     const int ntile = (int)cdiv(T, TT);
-    const int nslab = (int)cdiv(v.NB, NW * sh.qw / 4);
+    const int nslab = (int)cdiv((int64_t)v.NB * 4, NW * sh.qw);
     const int vec_ok = (v.K % 4 == 0) ? 1 : 0;
     const int vec_store = (v.R % 4 == 0) ? 1 : 0;
     if (sh.qw == 4)
         k_spmm<TIn, 4><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, v.rowmap, out, T, v.K, v.R, v.NBpad, v.nchunk,
+                                                                 nslab, ntile, vec_ok, vec_store);
+    else if (sh.qw == 3)
+        k_spmm<TIn, 3><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, v.rowmap, out, T, v.K, v.R, v.NBpad, v.nchunk,
                                                                  nslab, ntile, vec_ok, vec_store);
     else
         k_spmm<TIn, 2><<<grid_for(ntile, nslab), NW * 64, 0, s>>>(A, v.ptr, v.ent, v.rowmap, out, T, v.K, v.R, v.NBpad, v.nchunk,
@@ -392,7 +392,7 @@ int spmm_force_shape(int tt, int qw) {
         g_forced = {0, 0};
         return MST_OK;
     }
-    const bool ok = (tt == 128 && (qw == 2 || qw == 4)) ||
+    const bool ok = (tt == 128 && (qw == 2 || qw == 3 || qw == 4)) ||
                     (tt == 64 && (qw == 2 || qw == 3 || qw == 4 || qw == 6 || qw == 8));
     if (!ok) return MST_ERR_ARG;
     g_forced = {tt, qw};

@@ -43,7 +43,7 @@ def test_products_match_oracle(T, I, O, density):
     assert rel_err(rig.bwd_weight(dY, X), opr.fc_bwd_weight(dY, X, M)) <= TOL
 
 
-SPMM_SHAPES = [(128, 2), (128, 4), (64, 2), (64, 3), (64, 4), (64, 6), (64, 8)]
+SPMM_SHAPES = [(128, 2), (128, 3), (128, 4), (64, 2), (64, 3), (64, 4), (64, 6), (64, 8)]
 
 
 @pytest.mark.parametrize("tokens,quads", SPMM_SHAPES)
@@ -69,7 +69,7 @@ def test_every_spmm_launch_shape_matches_oracle_and_each_other(tokens, quads):
 
 
 def test_spmm_force_shape_rejects_unknown_shapes():
-    for tokens, quads in [(128, 3), (64, 5), (32, 4), (0, 4), (64, 0)]:
+    for tokens, quads in [(128, 6), (64, 5), (32, 4), (0, 4), (64, 0)]:
         with pytest.raises(mst.MstError):
             mst.mst_spmm_force_shape(tokens, quads)
     mst.mst_spmm_force_shape(0, 0)

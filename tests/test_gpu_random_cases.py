@@ -29,7 +29,7 @@ def _bwd_one_call(rig, dY, X, T, I, shape):
         mst.mst_bwd_force_shape(0, 0)
     return dX.cpu().numpy(), dW.cpu().numpy()[: rig.layer.nnz]
 
-LAUNCH_SHAPES = [(128, 2), (128, 4), (64, 2), (64, 3), (64, 4), (64, 6), (64, 8), (0, 0)]
+LAUNCH_SHAPES = [(128, 2), (128, 3), (128, 4), (64, 2), (64, 3), (64, 4), (64, 6), (64, 8), (0, 0)]
 
 
 def _random_case(rng):
