@@ -3,7 +3,7 @@
  * dynamically sparse fully-connected layers of Mixed Sparsity Training.
  *
  * A layer is W [O x I] (row-major, flat index f = o*I + i) with a binary mask M of
- * the same shape (Sec. 3.2: "binary mask outlining the sparse network topology").
+ * the same shape (the mask M of Sec. 3.2).
  * Its effective weight is W (.) M (Algorithm 1, last line).  With X [T x I] the input
  * and dY [T x O] the gradient at the output:
  *
@@ -51,7 +51,7 @@ typedef enum {
     MST_ERR_ARG = -1,        /* null pointer, misaligned pointer, value out of range */
     MST_ERR_SHAPE = -2,      /* dimension not supported / inconsistent */
     MST_ERR_WORKSPACE = -3,  /* workspace or layer buffer too small */
-    MST_ERR_STATE = -4,      /* e.g. active count would exceed the layer's capacity */
+    MST_ERR_STATE = -4,      /* layer not loaded yet, or the active count would exceed its capacity */
     MST_ERR_HIP = -5         /* a HIP runtime call failed; see mst_last_hip_error() */
 } mst_status;
 
@@ -91,7 +91,10 @@ size_t mst_layer_device_bytes(int O, int I, int64_t nnz_capacity);
 size_t mst_workspace_bytes(int O, int I, int64_t nnz_capacity, int T);
 
 /* Creates the host object over the caller's buffer (kept, not copied, never freed by
- * the library).  The layer starts empty (no active weight). 1 <= O, I <= 65535. */
+ * the library; its contents are not touched).  The layer has no weights until
+ * mst_layer_load_dense has succeeded: until then every call that would read the layer's
+ * device arrays (the products, the updates, export, values, indices, sync) returns
+ * MST_ERR_STATE without launching anything.  1 <= O, I <= 65535. */
 int mst_layer_create(mst_layer_t** out, int O, int I, int64_t nnz_capacity,
                      void* buf_dev, size_t buf_bytes);
 int mst_layer_destroy(mst_layer_t* layer);   /* frees the host object only */
@@ -107,7 +110,8 @@ int mst_layer_export_dense(const mst_layer_t* layer, float* W_dev, uint8_t* M_de
                            mst_stream_t stream);
 
 /* The active weights as one fp32 vector in ascending flat-index order, for the caller's
- * optimiser to update in place.  After changing them call mst_layer_sync_values. */
+ * optimiser to update in place.  After changing them call mst_layer_sync_values.  Every
+ * mask update changes the set and therefore the meaning of position k of this vector. */
 int mst_layer_values(mst_layer_t* layer, float** vals_dev, int64_t* nnz);
 int mst_layer_sync_values(mst_layer_t* layer, mst_stream_t stream);
 
@@ -164,8 +168,8 @@ int mst_sparse_fc_bwd(const mst_layer_t* layer, const void* dY_dev, const void* 
  * Every shape gives the same results. */
 int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront);
 
-/* G_dev [O*I] = dY^T X at every position (the score of gradient-based growth; Sec. 2,
- * "infrequent full gradient calculation").  Runs on the matrix cores.  ws_dev may be
+/* G_dev [O*I] = dY^T X at every position (the score of gradient-based growth: the dense
+ * gradient that Sec. 2 notes such growth needs now and then).  Runs on the matrix cores.  ws_dev may be
  * NULL; with a workspace small outputs split the token range over more workgroups. */
 int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, int O, int I,
                    mst_dtype act, void* ws_dev, size_t ws_bytes, mst_stream_t stream);
@@ -201,12 +205,18 @@ int mst_mask_update(mst_layer_t* layer, const void* dY_dev, const void* X_dev, i
                     mst_update_stats* stats_out, mst_stream_t stream);
 
 /* The weight gradient and the update of one step from ONE dense gradient.  On a step that
- * updates the topology the dense gradient G = dY^T X is needed anyway (Sec. 2: the
- * infrequent full gradient calculation); this call forms it once on the matrix cores, writes
+ * updates the topology the dense gradient G = dY^T X is needed anyway (Sec. 2, Algorithm 1's
+ * gradient-based growth); this call forms it once on the matrix cores, writes
  * dW_vals_dev = G at the positions active BEFORE the update (canonical order, the result of
  * mst_sparse_fc_bwd_weight up to rounding order) and then performs mst_mask_update with it.
  * When the update needs no gradient (nothing grows by gradient and the prune score has no
  * gradient term) the weight gradient is computed as in mst_sparse_fc_bwd_weight.
+ * ORDER CONTRACT: on return mst_layer_values / mst_layer_indices already describe the NEW
+ * topology, while dW_vals_dev (nnz_before entries) is in the order of the OLD one.  A caller
+ * that applies this gradient, or carries per-weight optimiser state across the update, must
+ * save mst_layer_indices before the call and match flat indices afterwards (pruned positions
+ * drop out, grown ones start from zero state); a caller that simply skips the optimiser step
+ * on update steps needs nothing.
  * Workspace: mst_workspace_bytes(O, I, nnz_capacity, T). */
 int mst_sparse_fc_bwd_weight_update(mst_layer_t* layer, const void* dY_dev, const void* X_dev,
                                     float* dW_vals_dev, int T, mst_dtype act,

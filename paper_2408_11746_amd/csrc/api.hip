@@ -66,6 +66,7 @@ int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront) {
 int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int T, mst_dtype act,
                       mst_stream_t stream) {
     if (!L || !X_dev || !Y_dev || T < 1 || !act_ok(act) || !aligned16(X_dev) || !aligned16(Y_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_path(L)) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
     return spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
@@ -74,6 +75,7 @@ int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int
 int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_dev, int T, mst_dtype act,
                             mst_stream_t stream) {
     if (!L || !dY_dev || !dX_dev || T < 1 || !act_ok(act) || !aligned16(dY_dev) || !aligned16(dX_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_path(L)) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
     return spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
@@ -83,6 +85,7 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const voi
                              mst_dtype act, void* ws_dev, size_t ws_bytes, mst_stream_t stream) {
     if (!L || !dY_dev || !X_dev || !dW_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
     if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dW_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
@@ -95,6 +98,7 @@ int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_de
     if (!L || !dY_dev || !X_dev || !dX_dev || !dW_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
     if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dX_dev) || !aligned16(dW_dev) || !aligned16(ws_dev))
         return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
@@ -135,6 +139,7 @@ int mst_mask_update_from_scores(mst_layer_t* L, const float* G_dev, double targe
                                 double rand_ratio, uint64_t rng_seed, void* ws_dev, size_t ws_bytes,
                                 mst_update_stats* stats_out, mst_stream_t stream) {
     if (!L || !G_dev || !ws_dev || !aligned16(G_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     mst_update_stats st;
     int rc = mst_update_counts(L->N, L->nnz, target_density, zeta, rand_ratio, &st);
     if (rc != MST_OK) return rc;
@@ -149,6 +154,7 @@ int mst_mask_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, int T
                     size_t ws_bytes, mst_update_stats* stats_out, mst_stream_t stream) {
     if (!L || !dY_dev || !X_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
     if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     mst_update_stats st;
     int rc = mst_update_counts(L->N, L->nnz, target_density, zeta, rand_ratio, &st);
     if (rc != MST_OK) return rc;
@@ -169,6 +175,7 @@ int mst_sparse_fc_bwd_weight_update(mst_layer_t* L, const void* dY_dev, const vo
                                     mst_stream_t stream) {
     if (!L || !dY_dev || !X_dev || !dW_dev || !ws_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
     if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dW_dev) || !aligned16(ws_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     mst_update_stats st;
     int rc = mst_update_counts(L->N, L->nnz, target_density, zeta, rand_ratio, &st);
     if (rc != MST_OK) return rc;

@@ -63,6 +63,7 @@ struct View {
 struct mst_layer {
     int O = 0, I = 0;
     int64_t N = 0, cap = 0, nnz = 0;
+    bool built = false;        // the device arrays are meaningful only after mst_layer_load_dense has succeeded
     int path = MST_PATH_AUTO;
     float prune_lambda = 0.f;  // prune score |w| + prune_lambda |grad| (0: magnitude only)
     void* buf = nullptr;

@@ -2,8 +2,8 @@
 // operands, v_mfma_f32_32x32x16_bf16 when both operands are bfloat16.
 //
 // Used where a dense contraction really is the work: the dense weight gradient
-// G = dY^T X that scores gradient-based growth (Algorithm 1, ArgTopK of |grad|; Sec. 2
-// "infrequent full gradient calculation"), and the three products of a layer whose
+// G = dY^T X that scores gradient-based growth (Algorithm 1, ArgTopK of |grad|; the dense
+// gradient Sec. 2 says such growth needs), and the three products of a layer whose
 // density is high (start of warm-up / end of restoration, Sec. 3.1).
 //
 // C[M x N] = sum_k A'[k][m] B'[k][n].  Each operand is given either k-major (element

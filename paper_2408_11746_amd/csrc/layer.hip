@@ -588,12 +588,16 @@ int mst_layer_load_dense(mst_layer_t* L, const float* W_dev, const uint8_t* M_de
     if ((int64_t)total > L->cap) return MST_ERR_STATE;
     MST_HIP(hipMemcpyAsync(L->mask, M_dev, (size_t)L->N, hipMemcpyDeviceToDevice, s));
     L->nnz = total;
-    return build_views(L, W_dev, ws, s);
+    L->built = false;                                   // a failed rebuild leaves no usable layer
+    const int rc = build_views(L, W_dev, ws, s);
+    if (rc == MST_OK) L->built = true;
+    return rc;
 }
 
 int mst_layer_export_dense(const mst_layer_t* L, float* W_dev, uint8_t* M_dev, mst_stream_t stream) {
     if (!L) return MST_ERR_ARG;
     if ((W_dev && !aligned16(W_dev)) || (M_dev && !aligned16(M_dev))) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
     if (W_dev) {
         int rc = fill_u32(W_dev, 0u, L->N, s);
@@ -609,6 +613,7 @@ int mst_layer_export_dense(const mst_layer_t* L, float* W_dev, uint8_t* M_dev, m
 
 int mst_layer_values(mst_layer_t* L, float** vals_dev, int64_t* nnz) {
     if (!L) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     if (vals_dev) *vals_dev = L->vals;
     if (nnz) *nnz = L->nnz;
     return MST_OK;
@@ -616,6 +621,7 @@ int mst_layer_values(mst_layer_t* L, float** vals_dev, int64_t* nnz) {
 
 int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
     if (!L) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
     L->Wd_valid = false;
     if (L->nnz == 0) return MST_OK;
@@ -631,6 +637,7 @@ int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
 
 int mst_layer_indices(const mst_layer_t* L, int32_t* flat_dev, mst_stream_t stream) {
     if (!L || !flat_dev) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
     if (L->nnz == 0) return MST_OK;
     k_copy_i32<<<(unsigned)cdiv(L->nnz, 256), 256, 0, (hipStream_t)stream>>>(L->flat, flat_dev, L->nnz);
     MST_LAUNCH_CHECK();

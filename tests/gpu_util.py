@@ -66,3 +66,38 @@ class Rig:
         self.layer.indices(out)
         torch.cuda.synchronize()
         return out.cpu().numpy()[: self.layer.nnz]
+
+
+def sampled_check(name, got, ref_fn, shape, n=1500, seed=0, extra_cols=(), extra_rows=()):
+    """Sampled comparison of a full-size output with the oracle's one-element functions.
+
+    The scale of the error bound comes from the ORACLE's samples only, and the whole GPU
+    output must be finite and of the oracle's order of magnitude: a wild element anywhere
+    cannot widen the bound, an unsampled NaN / Inf cannot hide.  `extra_cols` / `extra_rows`
+    (e.g. the longest and the shortest rows of the mask) are sampled on top of the uniform
+    draw, 16 positions each."""
+    got = np.asarray(got)
+    assert got.shape == tuple(shape), (got.shape, shape)
+    assert np.isfinite(got).all(), name + ": non-finite output"
+    rng = np.random.default_rng(seed)
+    rows = rng.integers(0, shape[0], n)
+    cols = rng.integers(0, shape[1], n)
+    # always include the corners and the last tile / last block
+    rows[:4] = [0, shape[0] - 1, 0, shape[0] - 1]
+    cols[:4] = [0, 0, shape[1] - 1, shape[1] - 1]
+    for c in extra_cols:
+        rows = np.concatenate([rows, rng.integers(0, shape[0], 16)])
+        cols = np.concatenate([cols, np.full(16, int(c))])
+    for r in extra_rows:
+        rows = np.concatenate([rows, np.full(16, int(r))])
+        cols = np.concatenate([cols, rng.integers(0, shape[1], 16)])
+    ref = np.array([ref_fn(int(r), int(c)) for r, c in zip(rows, cols)])
+    scale = float(np.abs(ref).max())
+    assert scale > 0.0, name + ": all sampled reference values are zero"
+    err = float(np.abs(got[rows, cols] - ref).max() / scale)
+    print(name, "samples", rows.size, "max err / max ref:", err, flush=True)
+    assert err <= TOL, (name, err)
+    # nothing anywhere in the output may be far outside the sampled range (the maximum of
+    # 1500+ samples of a near-normal output is within a small factor of the true maximum)
+    assert float(np.abs(got).max()) <= 8.0 * scale, (name, float(np.abs(got).max()), scale)
+    return err

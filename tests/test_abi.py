@@ -114,3 +114,39 @@ def test_product_package_never_imports_the_oracle():
     for name in ("binding.py", "build.py", "__init__.py"):
         src = open(os.path.join(ROOT, "paper_2408_11746_amd", name)).read()
         assert "oracle" not in src
+
+
+def test_calls_on_a_layer_that_was_never_loaded_return_state_error():
+    """mst_layer_create does no device work and the caller's buffer is uninitialised: until
+    mst_layer_load_dense has succeeded, every call that would read the layer's device arrays
+    must refuse on the host (MST_ERR_STATE) before anything is launched.  No GPU is needed:
+    the pointers are never dereferenced."""
+    import ctypes as C
+    L = mst.lib()
+    O, I, cap, T = 64, 96, 512, 32
+    nbytes = mst.mst_layer_device_bytes(O, I, cap)
+    wsb = mst.mst_workspace_bytes(O, I, cap, T)
+    assert nbytes > 0 and wsb > 0
+    fake = 0x10000                      # non-null, 16-byte aligned, never touched
+    h = C.c_void_p()
+    assert L.mst_layer_create(C.byref(h), O, I, cap, fake, nbytes) == 0
+    try:
+        st = binding.UpdateStats()
+        assert L.mst_layer_nnz(h) == 0
+        assert L.mst_sparse_fc_fwd(h, fake, fake, T, 0, None) == -4
+        assert L.mst_sparse_fc_bwd_input(h, fake, fake, T, 0, None) == -4
+        assert L.mst_sparse_fc_bwd_weight(h, fake, fake, fake, T, 0, fake, wsb, None) == -4
+        assert L.mst_sparse_fc_bwd(h, fake, fake, fake, fake, T, 0, fake, wsb, None) == -4
+        assert L.mst_mask_update_from_scores(h, fake, 0.1, 0.3, 0.25, 1, fake, wsb, C.byref(st), None) == -4
+        assert L.mst_mask_update(h, fake, fake, T, 0, 0.1, 0.3, 0.25, 1, fake, wsb, C.byref(st), None) == -4
+        assert L.mst_sparse_fc_bwd_weight_update(h, fake, fake, fake, T, 0, 0.1, 0.3, 0.25, 1, fake, wsb,
+                                                 C.byref(st), None) == -4
+        assert L.mst_layer_export_dense(h, fake, fake, None) == -4
+        assert L.mst_layer_sync_values(h, None) == -4
+        assert L.mst_layer_indices(h, fake, None) == -4
+        p, n = C.c_void_p(), C.c_int64()
+        assert L.mst_layer_values(h, C.byref(p), C.byref(n)) == -4
+        # argument errors still come first
+        assert L.mst_sparse_fc_fwd(h, None, fake, T, 0, None) == -1
+    finally:
+        L.mst_layer_destroy(h)

@@ -16,18 +16,7 @@ torch = pytest.importorskip("torch")
 from gpu_util import Rig, TOL, dev, rel_err, DEV  # noqa: E402
 
 
-def _sampled_check(name, got, ref_fn, shape, n=1500, seed=0):
-    rng = np.random.default_rng(seed)
-    rows = rng.integers(0, shape[0], n)
-    cols = rng.integers(0, shape[1], n)
-    # always include the corners and the last tile / last block
-    rows[:4] = [0, shape[0] - 1, 0, shape[0] - 1]
-    cols[:4] = [0, 0, shape[1] - 1, shape[1] - 1]
-    ref = np.array([ref_fn(int(r), int(c)) for r, c in zip(rows, cols)])
-    scale = max(np.abs(ref).max(), float(np.abs(got).max()))
-    err = np.abs(got[rows, cols] - ref).max() / scale
-    print(name, "sampled max err / max ref:", err, flush=True)
-    assert err <= TOL
+from gpu_util import sampled_check as _sampled_check  # noqa: E402
 
 
 @pytest.mark.parametrize("name,I,O", [("fc1", 768, 3072), ("fc2", 3072, 768), ("qkv", 768, 2304), ("proj", 768, 768)])
