@@ -101,3 +101,75 @@ def sampled_check(name, got, ref_fn, shape, n=1500, seed=0, extra_cols=(), extra
     # 1500+ samples of a near-normal output is within a small factor of the true maximum)
     assert float(np.abs(got).max()) <= 8.0 * scale, (name, float(np.abs(got).max()), scale)
     return err
+
+
+def check_layer_products(tag, rig, W, M, X, dY, Xd, dYd, act, n=10000, with_separate=True):
+    """Every product call of one loaded layer at full size against the oracle, sampled:
+    forward, input gradient, weight gradient (separate calls and the one-call backward), at
+    `n` uniformly drawn outputs per tensor plus the longest and shortest rows and columns of
+    the mask; then the adjoint identities over the complete outputs.  X / dY are the exact
+    fp32 values the device buffers Xd / dYd hold (for bfloat16: the rounded values)."""
+    from oracle import products as opr
+    O, I = W.shape
+    T = X.shape[0]
+    rl, cl = M.sum(axis=1), M.sum(axis=0)
+    rows_of_interest = sorted({int(np.argmax(rl)), int(np.argmin(rl))})
+    cols_of_interest = sorted({int(np.argmax(cl)), int(np.argmin(cl))})
+    nnz = rig.layer.nnz
+    assert nnz == int(M.sum())
+
+    Y = torch.full((T, O), float("nan"), dtype=torch.float32, device=DEV)
+    mst.mst_sparse_fc_fwd(rig.layer, Xd, Y, T, act)
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy()
+    sampled_check(tag + " fwd", Y, lambda t, o: opr.fc_fwd_at(X, W, M, t, o), (T, O), n=n, seed=1,
+                  extra_cols=rows_of_interest)
+
+    dX1 = torch.full((T, I), float("nan"), dtype=torch.float32, device=DEV)
+    dW1 = torch.full((max(nnz, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    mst.mst_sparse_fc_bwd(rig.layer, dYd, Xd, dX1, dW1, T, rig.ws, act)
+    torch.cuda.synchronize()
+    dX1, dW1 = dX1.cpu().numpy(), dW1.cpu().numpy()[:nnz]
+    sampled_check(tag + " bwd.dX", dX1, lambda t, i: opr.fc_bwd_input_at(dY, W, M, t, i), (T, I), n=n, seed=2,
+                  extra_cols=cols_of_interest)
+
+    # weight gradient: sampled active positions incl. first / last and those of the extreme rows
+    flat = np.flatnonzero(M.reshape(-1))
+    rng = np.random.default_rng(3)
+    pick = [np.array([0, flat.size - 1]), rng.integers(0, flat.size, n)]
+    for r in rows_of_interest:
+        lo, hi = np.searchsorted(flat, [r * I, (r + 1) * I])
+        if hi > lo:
+            pick.append(rng.integers(lo, hi, 16))
+    pick = np.unique(np.concatenate(pick))
+    ref = np.array([opr.dense_grad_at(dY, X, int(f // I), int(f % I)) for f in flat[pick]])
+    scale = float(np.abs(ref).max())
+    assert np.isfinite(dW1).all() and float(np.abs(dW1).max()) <= 8.0 * scale
+    err = float(np.abs(dW1[pick] - ref).max() / scale)
+    print(tag, "bwd.dW samples", pick.size, "max err / max ref:", err, flush=True)
+    assert err <= TOL, (tag, err)
+
+    if with_separate:
+        dX = torch.full((T, I), float("nan"), dtype=torch.float32, device=DEV)
+        mst.mst_sparse_fc_bwd_input(rig.layer, dYd, dX, T, act)
+        dW = torch.full((max(nnz, 1),), float("nan"), dtype=torch.float32, device=DEV)
+        mst.mst_sparse_fc_bwd_weight(rig.layer, dYd, Xd, dW, T, rig.ws, act)
+        torch.cuda.synchronize()
+        dX, dW = dX.cpu().numpy(), dW.cpu().numpy()[:nnz]
+        assert np.isfinite(dX).all() and np.isfinite(dW).all()
+        # the separate calls compute the same sums (possibly in another order)
+        assert rel_err(dX, dX1) <= 1e-5, tag
+        assert rel_err(dW, dW1) <= 1e-5, tag
+        e2 = float(np.abs(dW[pick] - ref).max() / scale)
+        assert e2 <= TOL, (tag, e2)
+
+    # adjoint identities over the complete outputs (fp64 reductions of the fp32 results)
+    Wv = W[M != 0].astype(np.float64)
+    a = float((dY.astype(np.float64) * Y).sum())
+    b = float((dX1.astype(np.float64) * X).sum())
+    c = float((dW1.astype(np.float64) * Wv).sum())
+    tol = 1e-4 * max(abs(a), abs(b), abs(c)) + 1e-3
+    print(tag, "adjoint <dY,Y>=%.6g <dX,X>=%.6g <dW,W>=%.6g" % (a, b, c), flush=True)
+    assert abs(a - b) <= tol and abs(a - c) <= tol, (tag, a, b, c)
+    return Y, dX1, dW1
+
