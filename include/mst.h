@@ -152,6 +152,23 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* layer, const void* dY_dev, const
                              float* dW_dev, int T, mst_dtype act,
                              void* ws_dev, size_t ws_bytes, mst_stream_t stream);
 
+/* For callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): mst_sparse_fc_bwd_weight with its scratch
+ * -- the per-token-tile partial sums of the SDDMM -- in a device array that is part of the
+ * library (mst_static_scratch_bytes() = 64 MiB, held by every GPU the library runs on until
+ * the process ends).  Always runs the sparse kernels (never the dense-gradient variant), so
+ * dW_dev equals mst_sparse_fc_bwd_weight's result exactly on the sparse path and up to the
+ * order of the fp32 sums where that call would use a dense contraction.  Calls no allocating
+ * routine.  MST_ERR_WORKSPACE when ceil(T / 128) planes of partial sums (8 floats per pair of
+ * entry slots of the larger index view at the layer's CAPACITY) exceed the array: e.g. a
+ * 768 x 3072 layer of capacity 177 k fits up to T = 2944.  All calls on one GPU share the
+ * array: calls that overlap in time on one GPU (other streams, other threads) race.  The
+ * first call on a device looks the array's address up (hipGetSymbolAddress); make that call
+ * outside stream capture. */
+int mst_sparse_fc_bwd_weight_static(const mst_layer_t* layer, const void* dY_dev, const void* X_dev,
+                                    float* dW_dev, int T, mst_dtype act, mst_stream_t stream);
+size_t mst_static_scratch_bytes(void);
+
 /* Both gradients of the backward pass in one call: dX as mst_sparse_fc_bwd_input, dW_vals as
  * mst_sparse_fc_bwd_weight.  On the sparse path the two products share one walk of the
  * layer's transposed view (the staged dY tile, the entries and every LDS read serve both);

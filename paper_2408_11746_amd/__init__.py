@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     mst_sparse_fc_fwd,
     mst_sparse_fc_bwd_input,
     mst_sparse_fc_bwd_weight,
+    mst_sparse_fc_bwd_weight_static,
+    mst_static_scratch_bytes,
     mst_sparse_fc_bwd,
     mst_bwd_force_shape,
     mst_mask_update,

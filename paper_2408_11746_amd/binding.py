@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         "mst_sparse_fc_fwd": (i32, [vp, vp, vp, i32, i32, vp]),
         "mst_sparse_fc_bwd_input": (i32, [vp, vp, vp, i32, i32, vp]),
         "mst_sparse_fc_bwd_weight": (i32, [vp, vp, vp, vp, i32, i32, vp, sz, vp]),
+        "mst_sparse_fc_bwd_weight_static": (i32, [vp, vp, vp, vp, i32, i32, vp]),
+        "mst_static_scratch_bytes": (sz, []),
         "mst_sparse_fc_bwd": (i32, [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]),
         "mst_bwd_force_shape": (i32, [i32, i32]),
         "mst_dense_grad": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]),
@@ -112,7 +114,8 @@ EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_w
            "mst_layer_create", "mst_layer_destroy", "mst_layer_load_dense", "mst_layer_export_dense",
            "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_layer_set_prune_lambda",
            "mst_spmm_force_shape",
-           "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight", "mst_sparse_fc_bwd", "mst_bwd_force_shape",
+           "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight", "mst_sparse_fc_bwd_weight_static",
+           "mst_static_scratch_bytes", "mst_sparse_fc_bwd", "mst_bwd_force_shape",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
            "mst_sparse_fc_bwd_weight_update",
            "mst_schedule_density", "mst_erdos_renyi_density", "mst_flops_fc_forward", "mst_flops_transformer",
@@ -254,6 +257,15 @@ def mst_sparse_fc_bwd_weight(layer: Layer, dY, X, dW, T: int, ws, act: int = MST
     _check("mst_sparse_fc_bwd_weight",
            lib().mst_sparse_fc_bwd_weight(layer.h, _ptr(dY), _ptr(X), _ptr(dW), T, act, _ptr(ws), ws.numel(),
                                           _stream(stream)))
+
+
+def mst_sparse_fc_bwd_weight_static(layer: Layer, dY, X, dW, T: int, act: int = MST_F32, stream=None):
+    _check("mst_sparse_fc_bwd_weight_static",
+           lib().mst_sparse_fc_bwd_weight_static(layer.h, _ptr(dY), _ptr(X), _ptr(dW), T, act, _stream(stream)))
+
+
+def mst_static_scratch_bytes() -> int:
+    return int(lib().mst_static_scratch_bytes())
 
 
 def mst_bwd_force_shape(wavefronts_per_workgroup: int = 0, quads_per_wavefront: int = 0):

@@ -1,8 +1,38 @@
 // The C-ABI entry points that launch device work: argument checks on the host, then
 // dispatch to the sparse kernels or, for dense layers, to the masked dense MFMA path.
+#include <mutex>
+
 #include "common.h"
 
 namespace mst {
+
+// ---- scratch of the entry point that allocates nothing (mst_sparse_fc_bwd_weight_static):
+// the SDDMM's per-token-tile partial sums live in this file-scope device array instead of a
+// caller workspace.  Each GPU the library runs on holds its own copy at its own address until
+// the process ends; host code never uses the array's name as an address, only the pointer
+// hipGetSymbolAddress returns for the current device.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device, looked up once per device
+static int static_scratch(void** out) {
+    int dev = -1;
+    MST_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return MST_ERR_STATE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        MST_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return MST_ERR_STATE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MST_OK;
+}
 
 // out[k] = sum over the nparts partial outputs (stride apart, added in ascending order) at
 // the k-th active position: the split sum of the dense gradient is only formed where the
@@ -91,6 +121,27 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const voi
     hipStream_t s = (hipStream_t)stream;
     if (use_dense_weight_grad(L, act, T)) return dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
     return sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+}
+
+size_t mst_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int mst_sparse_fc_bwd_weight_static(const mst_layer_t* L, const void* dY_dev, const void* X_dev, float* dW_dev, int T,
+                                    mst_dtype act, mst_stream_t stream) {
+    if (!L || !dY_dev || !X_dev || !dW_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
+    if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dW_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
+    // partial sums: one plane of entry slots per tile of TT tokens; the plane's stride is that of
+    // the larger view because the view that drives the product is chosen on the device
+    const size_t slots = (size_t)std::max(L->row.cap_pairs, L->col.cap_pairs) * 8;
+    const size_t need = (size_t)cdiv(T, TT) * slots * sizeof(float);
+    if (need > STATIC_SCRATCH_BYTES) return MST_ERR_WORKSPACE;
+    void* base = nullptr;
+    const int rc = static_scratch(&base);
+    if (rc != MST_OK) return rc;
+    Workspace ws{};
+    ws.partial = static_cast<float*>(base);      // every slot the second kernel reads is written by the first
+    ws.partial_floats = STATIC_SCRATCH_BYTES / sizeof(float);
+    return sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, (hipStream_t)stream);
 }
 
 int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_dev, float* dX_dev, float* dW_dev,
