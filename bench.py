@@ -2,11 +2,21 @@
 """Benchmark of the sparse fully-connected training step on one MI355X.
 
 A step is one pass of the hot path over one batch: for every layer of the workload the
-forward product, the input gradient and the weight gradient at the active positions;
-every Delta_t-th step (Table "Private hyperparameters of MST": topology update interval
-100) each layer also runs one Mixed-Growing update (dense gradient on the matrix cores,
-prune / grow selection, rebuild of the index views).  Inputs are synthetic, seeded, and
-resident in HBM before the timed region.  Prints ONE JSON line.
+forward product, the input gradient and the weight gradient at the active positions, plus the
+Mixed-Growing topology update (Algorithm 1: dense gradient on the matrix cores, prune / grow
+selections, rebuild of the index views) on the steps that carry one.
+
+Default run (what `python bench.py --gpus 1 --steps K --warmup W` prints as ONE JSON line):
+  * headline = the schedule sweep of the GPT-2-large block (the largest single-GPU workload):
+    the layers are driven through the densities 1.0, 0.5, 0.1, 0.02, 0.1, 0.5 of the warm-up /
+    ultra-sparse / restoration phases (Sec. 3.1), every step runs the products at the current
+    density and then one update per layer that moves it to the next density of the cycle;
+  * `per_config`: the other four workloads (single layer, GPT-2-small block at density 0.10,
+    the same block at 0.02 with power-law rows, GPT-2-medium block with bfloat16 activations),
+    K steps each with a topology update every `--update-interval` steps.
+`--config Cx` runs one workload alone.  Inputs are synthetic, seeded, and resident in HBM
+before the timed region.  Every library call of the timed region is bracketed by events on
+the launch stream.
 """
 from __future__ import annotations
 
@@ -20,46 +30,62 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-ALU_FP32_PEAK_TFLOPS = 157.3   # fp32 vector peak (256 CUs x 4 SIMD x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz)
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
+ALU_FP32_PEAK_TFLOPS = 157.3    # published fp32 vector peak: 256 CUs x 4 SIMD x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz
+ALU_FP32_UNPACKED_TFLOPS = 78.6  # the same without packed-fp32 instructions, which this build switches off
 MFMA_FP32_PEAK_TFLOPS = 157.3
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA peak
+CLOCK_HZ, N_CU = 2.4e9, 256
 METRIC = "effective sparse TFLOP/s + HBM GB/s (% peak) per FC train step, 1 MI355X"
 
 
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=100)
-    p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
-    p.add_argument("--update-interval", type=int, default=100, help="Delta_t; 0 = never update")
+    p.add_argument("--steps", type=int, default=24)
+    p.add_argument("--warmup", type=int, default=6)
+    p.add_argument("--config", default="all", choices=["all", "C1", "C2", "C3", "C4", "C5"],
+                   help="all = headline on the schedule sweep (C5) plus a per_config table of C1..C4")
+    p.add_argument("--update-interval", type=int, default=10,
+                   help="block workloads C1..C4: steps between topology updates (the paper's Delta_t is 100; the "
+                        "default puts updates inside a short timed region); 0 = never update")
     p.add_argument("--allocation", default="uniform", choices=["uniform", "erdos_renyi"],
                    help="C5 only: every layer at the sweep's density, or the Erdos-Renyi shares of it (Sec. 3.2)")
-    p.add_argument("--update-streams", type=int, default=1,
-                   help="C5 only: 1 = the layers' mask updates run on one stream per layer, 0 = all on the main stream")
-    p.add_argument("--fused-update", type=int, default=1,
-                   help="C5 only: 1 = weight gradient and update from one dense gradient "
-                        "(mst_sparse_fc_bwd_weight_update), 0 = separate calls")
+    p.add_argument("--update-streams", type=int, default=0,
+                   help="C5 only: 1 = the layers' updates run on one stream per layer (overlapping small kernels; "
+                        "per-call times then overlap too), 0 = everything on the main stream")
+    p.add_argument("--fused-update", type=int, default=0,
+                   help="C5 only: 1 = weight gradient and update in ONE call (mst_sparse_fc_bwd_weight_update); "
+                        "0 = the same work as three calls (mst_dense_grad, mst_gather_active, "
+                        "mst_mask_update_from_scores) so that the dense-gradient kernel is timed on its own")
     p.add_argument("--separate-bwd", action="store_true",
-                   help="time mst_sparse_fc_bwd_input and mst_sparse_fc_bwd_weight as two calls instead of "
-                        "mst_sparse_fc_bwd (both gradients from one walk)")
+                   help="block workloads: time mst_sparse_fc_bwd_input and mst_sparse_fc_bwd_weight as two calls "
+                        "instead of mst_sparse_fc_bwd (both gradients from one walk)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-per-config", action="store_true")
+    p.add_argument("--lr", type=float, default=1e-5,
+                   help="step size of the caller-side SGD on the active weights between backward and hand-over "
+                        "(without it grown weights would stay exactly 0 and magnitude pruning would degenerate "
+                        "into a tie-break by index); 0 = no optimiser step")
     p.add_argument("--seed", type=int, default=2024)
     p.add_argument("--attention-mask", type=int, nargs=2, metavar=("L", "STRIDE"), default=None,
                    help="time the strided attention mask of Sec. 3.3 instead of a config (its own JSON line)")
     p.add_argument("--pmc-probe", action="store_true",
-                   help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration), then each product twice")
+                   help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration), then each call twice")
     return p.parse_args()
 
 
 class LayerRun:
-    """Device state of one layer of the workload."""
+    """Device state of one layer of a workload."""
 
-    def __init__(self, mst, synth, torch, seed, lid, name, I, O, T, density, mask, act):
+    def __init__(self, mst, synth, torch, seed, lid, name, I, O, T, density, mask, act, cap=None, dense_start=False):
         import numpy as np
         self.name, self.I, self.O, self.T = name, I, O, T
-        W, M = synth.make_layer(seed, lid, I, O, density, mask)
+        if dense_start:
+            W = synth.normal(seed, 1000 * lid + 2, (O, I), 0.02)
+            M = np.ones((O, I), np.uint8)
+        else:
+            W, M = synth.make_layer(seed, lid, I, O, density, mask)
         self.W, self.M = W, M
         to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
         if act == "f32":
@@ -73,7 +99,8 @@ class LayerRun:
             self.act_bytes = 2
         self.X_host, self.dY_host = X, dY
         self.nnz = int(M.sum())
-        cap = min(O * I, self.nnz + self.nnz // 2 + 64)
+        if cap is None:
+            cap = min(O * I, self.nnz + self.nnz // 2 + 64)
         self.layer = mst.Layer(O, I, cap, "cuda:0")
         self.ws = torch.empty(mst.mst_workspace_bytes(O, I, cap, T), dtype=torch.uint8, device="cuda:0")
         self.layer.load_dense(to(W), to(M), self.ws)
@@ -82,73 +109,121 @@ class LayerRun:
         self.dW = torch.empty(cap, dtype=torch.float32, device="cuda:0")
         self.density = density
 
-    # algorithmic (compulsory) bytes and flops of each product
-    def bytes_fwd(self):
-        return self.act_bytes * self.T * self.I + 4 * self.T * self.O + 8 * self.nnz + 4 * (self.O + 1)
+    def sgd(self, lr):
+        """The caller's optimiser (not part of the library): plain SGD on the active-weight
+        vector with the weight gradient of this step, a torch kernel on the current stream."""
+        n = self.layer.nnz
+        if n:
+            self.layer.values().add_(self.dW[:n], alpha=-lr)
 
-    def bytes_bwd_input(self):
-        return self.act_bytes * self.T * self.O + 4 * self.T * self.I + 8 * self.nnz + 4 * (self.I + 1)
+    # algorithmic (compulsory) bytes and flops of each product at nnz active weights
+    def bytes_fwd(self, nnz=None):
+        nnz = self.nnz if nnz is None else nnz
+        return self.act_bytes * self.T * self.I + 4 * self.T * self.O + 8 * nnz + 4 * (self.O + 1)
 
-    def bytes_bwd_weight(self):
-        return self.act_bytes * self.T * (self.I + self.O) + 8 * self.nnz + 4 * self.nnz
+    def bytes_bwd_input(self, nnz=None):
+        nnz = self.nnz if nnz is None else nnz
+        return self.act_bytes * self.T * self.O + 4 * self.T * self.I + 8 * nnz + 4 * (self.I + 1)
 
-    def bytes_bwd(self):
+    def bytes_bwd_weight(self, nnz=None):
+        nnz = self.nnz if nnz is None else nnz
+        return self.act_bytes * self.T * (self.I + self.O) + 8 * nnz + 4 * nnz
+
+    def bytes_bwd(self, nnz=None):
         # both gradients in one call: dY and X read once, dX and dW written, the entries read once
-        return (self.act_bytes * self.T * (self.I + self.O) + 4 * self.T * self.I + 8 * self.nnz + 4 * self.nnz +
+        nnz = self.nnz if nnz is None else nnz
+        return (self.act_bytes * self.T * (self.I + self.O) + 4 * self.T * self.I + 8 * nnz + 4 * nnz +
                 4 * (self.I + 1))
 
-    def flops_product(self):
-        return 2 * self.nnz * self.T
+    def bytes_dense_grad(self):
+        return self.act_bytes * self.T * (self.I + self.O) + 4 * self.O * self.I
+
+    def flops_product(self, nnz=None):
+        return 2 * (self.nnz if nnz is None else nnz) * self.T
+
+    def flops_dense_grad(self):
+        return 2 * self.T * self.O * self.I
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
+def lds_peak_bytes_per_s(mst, torch, stream):
+    """LDS read rate of the chip with 16-byte conflict-free reads, measured now (the on-chip
+    roofline of the walk: one 4-byte LDS operand per multiply-add)."""
+    blocks, iters, width = N_CU, 2000, 16
+    out = torch.empty(blocks * 1024, dtype=torch.float32, device="cuda:0")
+    mst.mst_probe_lds_read(out, width, 200, blocks, stream)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    mst.mst_probe_lds_read(out, width, iters, blocks, stream)
+    b.record(stream)
+    torch.cuda.synchronize()
+    return blocks * 1024 * iters * 8 * width / (a.elapsed_time(b) * 1e-3)
 
-    import paper_2408_11746_amd as mst
-    import synth
 
-    if args.attention_mask:
-        return attention_mask(args, mst, torch)
-    cfg = synth.CONFIGS[args.config]
-    if args.config == "C5":
-        return sweep(args, cfg, mst, synth, torch)
+def product_row_numbers(row, ms, by, fl, lds_bytes, lds_peak):
+    row.update(eff_tflops=round(fl / ms / 1e9, 3), hbm_gbs=round(by / ms / 1e6, 1),
+               hbm_frac=round(by / ms / 1e6 / HBM_PEAK_GBS, 4),
+               alu_frac=round(fl / ms / 1e9 / ALU_FP32_PEAK_TFLOPS, 4), alg_bytes=by, alg_flops=fl)
+    if lds_bytes and lds_peak:
+        row.update(lds_frac=round(lds_bytes / (ms * 1e-3) / lds_peak, 4))
+
+
+def roofline_of(row, L, act, kernel, traffic_cfg):
+    """The roofline object of one (layer, call) row."""
+    if row["call"] == "dense_grad":
+        peak = MFMA_BF16_PEAK_TFLOPS if act == "bf16" else MFMA_FP32_PEAK_TFLOPS
+        tf = row["alg_flops"] / row["avg_ms"] / 1e9
+        roof = dict(bound="mfma", achieved=round(tf, 2), peak=peak, unit="TFLOP/s", frac=round(tf / peak, 4))
+    else:
+        t_hbm = row["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
+        t_alu = row["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
+        if row.get("path") == "dense-mfma":
+            tf = row["dense_flops"] / row["avg_ms"] / 1e9
+            roof = dict(bound="mfma", achieved=round(tf, 2), peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=round(tf / MFMA_FP32_PEAK_TFLOPS, 4))
+        elif t_hbm >= t_alu:
+            roof = dict(bound="hbm", achieved=row["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(row["hbm_gbs"] / HBM_PEAK_GBS, 4))
+        else:
+            roof = dict(bound="alu", achieved=row["eff_tflops"], peak=ALU_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=round(row["eff_tflops"] / ALU_FP32_PEAK_TFLOPS, 4),
+                        frac_of_unpacked_peak=round(row["eff_tflops"] / ALU_FP32_UNPACKED_TFLOPS, 4))
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % traffic_cfg.lower())
+    if os.path.exists(tpath):        # counter-based HBM bytes of this call, measured by the commands in profiles/
+        traffic = json.load(open(tpath)).get("calls", {}).get("%s/%s" % (L.name, row["call"]))
+    roof.update(traffic=traffic, kernel=kernel, call="%s/%s" % (L.name, row["call"]), avg_launch_ms=row["avg_ms"],
+                alg_bytes_per_launch=row["alg_bytes"], alg_flops_per_launch=row["alg_flops"])
+    for k in ("hbm_frac", "alu_frac", "lds_frac"):
+        if k in row:
+            roof[k] = row[k]
+    return roof
+
+
+def free_layers(torch, layers):
+    for L in layers:
+        L.layer.close()
+    layers.clear()
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ block workloads C1..C4
+
+def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
+    cfg = synth.CONFIGS[name]
     T, act, density = cfg["T"], cfg["act"], cfg["densities"][0]
-    layers = [LayerRun(mst, synth, torch, args.seed, lid + 1, name, I, O, T, density, cfg["mask"], act)
-              for lid, (name, I, O) in enumerate(cfg["layers"])]
+    layers = [LayerRun(mst, synth, torch, args.seed, lid + 1, lname, I, O, T, density, cfg["mask"], act)
+              for lid, (lname, I, O) in enumerate(cfg["layers"])]
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream()
+    fstats = {L.name: L.layer.format_stats(stream) for L in layers}
 
     if args.pmc_probe:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)                      # 1 GiB read + 1 GiB written per launch
-        # a one-element torch kernel after every call: the boundary between the calls' dispatches
-        mark = torch.zeros(1, dtype=torch.int32, device="cuda:0")
-        mark.add_(1)
-        for L in layers:
-            for _ in range(2):
-                mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
-                mark.add_(1)
-                if args.separate_bwd:
-                    mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
-                    mark.add_(1)
-                    mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
-                else:
-                    mst.mst_sparse_fc_bwd(L.layer, L.dY, L.X, L.dX, L.dW, T, L.ws, L.act, stream)
-                mark.add_(1)
-        torch.cuda.synchronize()
-        print(json.dumps({"pmc_probe": True, "copy_bytes_each_way": 1 << 30,
-                          "layers": {L.name: dict(I=L.I, O=L.O, nnz=L.nnz) for L in layers}}))
-        return
+        pmc_probe_block(args, mst, torch, layers, T, stream)
+        free_layers(torch, layers)
+        return None
 
     products = ("fwd", "bwd_input", "bwd_weight") if args.separate_bwd else ("fwd", "bwd")
-    kinds = products + ("sync_values", "mask_update")
+    kinds = products + ("caller_sgd", "sync_values", "mask_update")
     ev = {(L.name, k): [] for L in layers for k in kinds}
 
     def run_step(t, record):
@@ -160,10 +235,14 @@ def main():
 
         last = mark() if record else None
         for L in layers:
-            # the three products, then the hand-over of the (optimiser-updated) active weights
-            # to the index views, which a training step pays once per layer
-            for kind in products + ("sync_values",):
-                if kind == "fwd":
+            # the products, then the hand-over of the (optimiser-updated) active weights to the
+            # index views, which a training step pays once per layer
+            for kind in products + ("caller_sgd", "sync_values"):
+                if kind == "caller_sgd":
+                    if not args.lr:
+                        continue
+                    L.sgd(args.lr)
+                elif kind == "fwd":
                     mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
                 elif kind == "bwd":
                     mst.mst_sparse_fc_bwd(L.layer, L.dY, L.X, L.dX, L.dW, T, L.ws, L.act, stream)
@@ -177,10 +256,10 @@ def main():
                     nxt = mark()
                     ev[(L.name, kind)].append((last, nxt))
                     last = nxt
-        if args.update_interval and (t + 1) % args.update_interval == 0:
+        if args.update_interval and mst.mst_update_due(t + 1, args.update_interval):
             for li, L in enumerate(layers):
                 mst.mst_mask_update(L.layer, L.dY, L.X, T, density, cfg["zeta"], cfg["R"],
-                                    args.seed * 1000003 + t * 131 + li, L.ws, L.act, stream)
+                                    mst.mst_update_seed(args.seed, t, len(layers), li), L.ws, L.act, stream)
                 if record:
                     nxt = mark()
                     ev[(L.name, "mask_update")].append((last, nxt))
@@ -207,7 +286,9 @@ def main():
 
     # per-call device times from the events recorded inside the timed region
     table, dominant = [], None
+    update_ms = []
     for L in layers:
+        fs = fstats[L.name]
         for kind in kinds:
             pairs = ev[(L.name, kind)]
             if not pairs:
@@ -217,21 +298,19 @@ def main():
             if kind in products:
                 by = getattr(L, "bytes_" + kind)()
                 fl = L.flops_product() * (2 if kind == "bwd" else 1)
-                row.update(eff_tflops=round(fl / ms / 1e9, 3), hbm_gbs=round(by / ms / 1e6, 1),
-                           hbm_frac=round(by / ms / 1e6 / HBM_PEAK_GBS, 4),
-                           alu_frac=round(fl / ms / 1e9 / ALU_FP32_PEAK_TFLOPS, 4),
-                           alg_bytes=by, alg_flops=fl)
+                # LDS operand bytes of the walk: 4 bytes per token and stored entry slot of the view walked
+                slots = fs["row_view_slots"] if kind == "fwd" else fs["col_view_slots"] if kind in ("bwd", "bwd_input") else 0
+                product_row_numbers(row, ms, by, fl, 4 * slots * T, lds_peak)
                 tot = ms * len(pairs)
                 if dominant is None or tot > dominant[0]:
                     dominant = (tot, row, L)
             elif kind == "mask_update":
                 row.update(dense_grad_gflop=round(2 * T * L.O * L.I / 1e9, 2))
+                update_ms.append(ms)
             table.append(row)
 
     _, drow, dL = dominant
-    t_hbm = drow["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
-    t_alu = drow["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
-    # fwd / bwd_input are one k_spmm launch; bwd_weight is k_sddmm followed by the small k_sddmm_reduce
+    # fwd / bwd_input are one SpMM launch; bwd is the shared walk followed by its small second kernel
     dense_bww = act == "bf16" and density > 0.045 and T >= 2048
     if dense_bww:          # the bf16 MFMA weight gradient is faster than any sparse kernel here
         bwd_kernels = "k_spmm64 + k_gemm_tn_bf16 + k_gather_flat (separate kernels)"
@@ -239,28 +318,13 @@ def main():
         bwd_kernels = "k_bwd_fused + k_bwd_fused_reduce"
     kernel = {"fwd": "k_spmm / k_spmm64 (launch shape chosen per call)",
               "bwd_input": "k_spmm / k_spmm64 (launch shape chosen per call)",
-              "bwd_weight": "k_sddmm+k_sddmm_reduce", "bwd": bwd_kernels}[drow["call"]]
-    # with bfloat16 activations the library computes the weight gradient as the full MFMA
-    # product dY^T X read at the active positions from a density of 0.045 on (T >= 2048)
-    mfma_bww = drow["call"] == "bwd_weight" and act == "bf16" and density > 0.045 and T >= 2048
-    if mfma_bww:
-        kernel = "k_gemm_tn_bf16+k_gather_flat"
+              "bwd_weight": "k_gemm_tn_bf16+k_gather_flat" if dense_bww else "k_sddmm+k_sddmm_reduce",
+              "bwd": bwd_kernels}[drow["call"]]
+    roof = roofline_of(drow, dL, act, kernel, name)
+    if drow["call"] == "bwd_weight" and dense_bww:
         dense_tf = 2.0 * T * dL.O * dL.I / drow["avg_ms"] / 1e9
-        roof = dict(bound="mfma", achieved=round(dense_tf, 1), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+        roof.update(bound="mfma", achieved=round(dense_tf, 1), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=round(dense_tf / MFMA_BF16_PEAK_TFLOPS, 4))
-    elif t_hbm >= t_alu:
-        roof = dict(bound="hbm", achieved=drow["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(drow["hbm_gbs"] / HBM_PEAK_GBS, 4))
-    else:
-        roof = dict(bound="alu", achieved=drow["eff_tflops"], peak=ALU_FP32_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=round(drow["eff_tflops"] / ALU_FP32_PEAK_TFLOPS, 4))
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % args.config.lower())
-    if os.path.exists(tpath):        # counter-based HBM bytes of this call, measured by the commands in profiles/
-        traffic = json.load(open(tpath)).get("calls", {}).get("%s/%s" % (dL.name, drow["call"]))
-    roof.update(traffic=traffic, kernel=kernel, call="%s/%s" % (dL.name, drow["call"]),
-                avg_launch_ms=drow["avg_ms"], alg_bytes_per_launch=drow["alg_bytes"],
-                alg_flops_per_launch=drow["alg_flops"], hbm_frac=drow["hbm_frac"], alu_frac=drow["alu_frac"])
 
     out = {
         "metric": METRIC, "value": round(value, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -269,20 +333,27 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s FC set (%s), density %.2f %s mask, T=%d tokens, %s "
                                "+ value hand-over to the index views per layer, Mixed-Growing update every %d steps"
-                               % (args.config, "GPT-2-small block" if len(layers) > 1 else "single layer",
+                               % (name, "GPT-2 block" if len(layers) > 1 else "single layer",
                                   ", ".join("%s %d->%d" % (L.name, L.I, L.O) for L in layers), density,
                                   cfg["mask"], T,
                                   "fwd+bwd_input+bwd_weight" if args.separate_bwd
                                   else "fwd + bwd (input and weight gradient in one call)", args.update_interval),
-                   "nnz": {L.name: L.nnz for L in layers}, "mask_updates_in_timed_region": n_updates},
+                   "nnz": {L.name: L.nnz for L in layers}, "mask_updates_in_timed_region": n_updates,
+                   "caller_sgd_lr": args.lr,
+                   "ell_efficiency": {L.name: dict(row_view=round(fstats[L.name]["row_view_efficiency"], 4),
+                                                   col_view=round(fstats[L.name]["col_view_efficiency"], 4))
+                                      for L in layers}},
         "hbm_gbs_step": round(bytes_step / (elapsed / args.steps) / 1e9, 1),
         "hbm_frac_step": round(bytes_step / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "alu_frac_step": round(value / ALU_FP32_PEAK_TFLOPS, 4),
+        "ms_per_mask_update": round(sum(update_ms) / len(update_ms), 4) if update_ms else None,
+        "lds_peak_measured_tbs": round(lds_peak / 1e12, 1) if lds_peak else None,
         "roofline": roof,
         "calls": table,
     }
 
-    # MFMA utilisation of the dense gradient G = dY^T X that scores gradient growth (outside the
-    # timed region: it runs once per update inside mst_mask_update)
+    # MFMA utilisation of the dense gradient G = dY^T X that scores gradient growth (it runs once per
+    # update inside mst_mask_update; here on its own, after the timed region)
     G = torch.empty(max(L.O * L.I for L in layers), dtype=torch.float32, device="cuda:0")
     dg = {}
     peak = MFMA_BF16_PEAK_TFLOPS if act == "bf16" else MFMA_FP32_PEAK_TFLOPS
@@ -300,10 +371,269 @@ def main():
         dg[L.name] = dict(avg_ms=round(ms, 4), tflops=round(tf, 1), mfma_frac=round(tf / peak, 4))
     out["dense_grad_gemm"] = dict(dtype="bf16" if act == "bf16" else "f32", peak_tflops=peak, layers=dg)
 
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers, T)
-    print(json.dumps(out))
+    if with_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_block(layers, T)
+    free_layers(torch, layers)
+    return out
 
+
+def pmc_probe_block(args, mst, torch, layers, T, stream):
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)                      # 1 GiB read + 1 GiB written per launch
+    # a one-element torch kernel after every call: the boundary between the calls' dispatches
+    mark = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    mark.add_(1)
+    for L in layers:
+        for _ in range(2):
+            mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
+            mark.add_(1)
+            if args.separate_bwd:
+                mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
+                mark.add_(1)
+                mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
+            else:
+                mst.mst_sparse_fc_bwd(L.layer, L.dY, L.X, L.dX, L.dW, T, L.ws, L.act, stream)
+            mark.add_(1)
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_probe": True, "copy_bytes_each_way": 1 << 30,
+                      "layers": {L.name: dict(I=L.I, O=L.O, nnz=L.nnz) for L in layers}}))
+
+
+# ------------------------------------------------------------------ schedule sweep C5
+
+def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
+    """One GPT-2-large block (of 36 identical ones) driven round the density cycle by the update
+    itself: step t computes the products at cycle position t mod 6 and then updates every layer
+    to the density of position t + 1 (a topology update every step)."""
+    import numpy as np
+    cfg = synth.CONFIGS["C5"]
+    T, cyc = cfg["T"], cfg["densities"]
+    ncyc = len(cyc)
+    stream = torch.cuda.current_stream()
+    layers = [LayerRun(mst, synth, torch, args.seed, lid + 1, lname, I, O, T, 1.0, "uniform", "f32", cap=O * I,
+                       dense_start=True)
+              for lid, (lname, I, O) in enumerate(cfg["layers"])]
+    G = [torch.empty(L.O * L.I, dtype=torch.float32, device="cuda:0") for L in layers]
+    shapes = [(L.O, L.I) for L in layers]
+    torch.cuda.synchronize()
+
+    def targets(pos):
+        d = cyc[pos % ncyc]
+        return mst.mst_erdos_renyi_density(shapes, d) if args.allocation == "erdos_renyi" else [d] * len(layers)
+
+    if args.pmc_probe:
+        pmc_probe_sweep(args, mst, torch, layers, G, T, cyc, targets, cfg, stream)
+        free_layers(torch, layers)
+        return None
+
+    side = [torch.cuda.Stream() for _ in layers] if args.update_streams else [stream] * len(layers)
+    ev = []            # (position, layer index, call, start event, end event)
+    nnz_at = {}        # position -> per-layer active counts (host arithmetic of the update, no read-back)
+
+    def run_step(t, record):
+        pos = t % ncyc
+        nnz_at[pos] = [L.layer.nnz for L in layers]
+
+        def mark(s):
+            e = torch.cuda.Event(enable_timing=True)
+            e.record(s)
+            return e
+
+        last = mark(stream) if record else None
+        for li, L in enumerate(layers):
+            for call in ("fwd", "bwd_input"):
+                if call == "fwd":
+                    mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
+                else:
+                    mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
+                if record:
+                    nxt = mark(stream)
+                    ev.append((pos, li, call, last, nxt))
+                    last = nxt
+        fork = None
+        if args.update_streams:
+            fork = torch.cuda.Event()
+            fork.record(stream)
+        dl = targets(pos + 1)
+        for li, (L, d, s) in enumerate(zip(layers, dl, side)):
+            seed = mst.mst_update_seed(args.seed, t, len(layers), li)
+            if s is not stream:
+                s.wait_event(fork)
+                last = mark(s) if record else None
+            if args.fused_update:
+                # weight gradient (at the positions active now) and update from one dense gradient
+                mst.mst_sparse_fc_bwd_weight_update(L.layer, L.dY, L.X, L.dW, T, d, cfg["zeta"], cfg["R"], seed, L.ws,
+                                                    L.act, s)
+                calls = ("bwd_weight_update",)
+            else:
+                calls = ("dense_grad", "gather_active", "caller_sgd", "mask_update") if args.lr else \
+                        ("dense_grad", "gather_active", "mask_update")
+            for call in calls:
+                if call == "dense_grad":
+                    mst.mst_dense_grad(L.dY, L.X, G[li], T, L.O, L.I, L.act, L.ws, s)
+                elif call == "gather_active":
+                    mst.mst_gather_active(L.layer, G[li], L.dW, s)
+                elif call == "caller_sgd":
+                    with torch.cuda.stream(s):
+                        L.sgd(args.lr)
+                elif call == "mask_update":
+                    mst.mst_mask_update_from_scores(L.layer, G[li], d, cfg["zeta"], cfg["R"], seed, L.ws, s)
+                if record:
+                    nxt = mark(s)
+                    ev.append((pos, li, call, last, nxt))
+                    last = nxt
+            if s is not stream:
+                done = torch.cuda.Event()
+                done.record(s)
+                stream.wait_event(done)
+
+    t = 0
+    for _ in range(args.warmup):
+        run_step(t, False)
+        t += 1
+    torch.cuda.synchronize()
+    t_first = t
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step(t, True)
+        t += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # ---- per (position, layer, call) device times
+    acc = {}
+    for pos, li, call, a, b in ev:
+        acc.setdefault((pos, li, call), []).append(a.elapsed_time(b))
+    steps_at = {p: sum(1 for tt in range(t_first, t) if tt % ncyc == p) for p in range(ncyc)}
+    tot_flops = sum(6 * n * T for tt in range(t_first, t) for n in nnz_at[tt % ncyc])
+    value = tot_flops / elapsed / 1e12
+    tot_bytes = 0.0
+    sweep_rows, calls, dominant = [], [], None
+    by_layer_call = {}
+    for p in range(ncyc):
+        if not steps_at[p]:
+            continue
+        d = cyc[p]
+        dense_path = d > 0.30
+        ms_pos = 0.0
+        for li, L in enumerate(layers):
+            nnz = nnz_at[p][li]
+            for call in ("fwd", "bwd_input"):
+                xs = acc.get((p, li, call), [])
+                if not xs:
+                    continue
+                ms = sum(xs) / len(xs)
+                ms_pos += ms
+                row = dict(density=d, position=p, layer=L.name, call=call, launches=len(xs), avg_ms=round(ms, 5),
+                           min_ms=round(min(xs), 5), max_ms=round(max(xs), 5),
+                           path="dense-mfma" if dense_path else "sparse")
+                by = L.bytes_fwd(nnz) if call == "fwd" else L.bytes_bwd_input(nnz)
+                product_row_numbers(row, ms, by, L.flops_product(nnz), 0, lds_peak)
+                if dense_path:
+                    row.update(dense_flops=L.flops_dense_grad(),
+                               mfma_frac=round(L.flops_dense_grad() / ms / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4))
+                calls.append(row)
+                if dominant is None or ms * len(xs) > dominant[0]:
+                    dominant = (ms * len(xs), row, L)
+            for call in ("dense_grad", "gather_active", "caller_sgd", "mask_update", "bwd_weight_update"):
+                xs = acc.get((p, li, call), [])
+                if xs:
+                    ms_pos += sum(xs) / len(xs)
+                    by_layer_call.setdefault((li, call), []).extend(xs)
+        step_bytes = sum(L.bytes_fwd(n) + L.bytes_bwd_input(n) + L.bytes_bwd_weight(n)
+                         for L, n in zip(layers, nnz_at[p]))
+        step_flops = sum(6 * n * T for n in nnz_at[p])
+        tot_bytes += step_bytes * steps_at[p]
+        sweep_rows.append(dict(position=p, density=d, next_density=cyc[(p + 1) % ncyc], steps=steps_at[p],
+                               ms_per_step_device=round(ms_pos, 4), eff_tflops=round(step_flops / ms_pos / 1e9, 3),
+                               hbm_frac=round(step_bytes / ms_pos / 1e6 / HBM_PEAK_GBS, 4),
+                               alu_frac=round(step_flops / ms_pos / 1e9 / ALU_FP32_PEAK_TFLOPS, 4),
+                               nnz={L.name: n for L, n in zip(layers, nnz_at[p])},
+                               path="dense-mfma" if dense_path else "sparse"))
+    # the update's calls do the same work at every position (the dense gradient) or nearly so: one row per layer
+    for (li, call), xs in sorted(by_layer_call.items()):
+        L = layers[li]
+        ms = sum(xs) / len(xs)
+        row = dict(layer=L.name, call=call, launches=len(xs), avg_ms=round(ms, 5), min_ms=round(min(xs), 5),
+                   max_ms=round(max(xs), 5))
+        if call == "dense_grad":
+            row.update(alg_flops=L.flops_dense_grad(), alg_bytes=L.bytes_dense_grad(),
+                       tflops=round(L.flops_dense_grad() / ms / 1e9, 2),
+                       mfma_frac=round(L.flops_dense_grad() / ms / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4))
+            if dominant is None or ms * len(xs) > dominant[0]:
+                dominant = (ms * len(xs), row, L)
+        calls.append(row)
+
+    _, drow, dL = dominant
+    if drow["call"] == "dense_grad":
+        kernel = "k_gemm<fp32, TN> (v_mfma_f32_32x32x2f32) + k_splitk_reduce (ordered sum of its split partial outputs)"
+    elif drow.get("path") == "dense-mfma":
+        kernel = "k_gemm<fp32> (masked dense product on v_mfma_f32_32x32x2f32; preceded by the scatter of the dense weight copy)"
+    else:
+        kernel = "k_spmm / k_spmm64 (launch shape chosen per call)"
+    roof = roofline_of(drow, dL, "f32", kernel, "C5")
+    upd = [x for (li, call), xs in by_layer_call.items() if call in ("mask_update", "bwd_weight_update") for x in xs]
+    out = {"metric": METRIC, "value": round(value, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(1e3 * elapsed / args.steps, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "C5: schedule sweep of one GPT-2-large block (qkv 1280->3840, proj 1280->1280, fc1 "
+                                  "1280->5120, fc2 5120->1280; 1 of 36 identical blocks), T=%d tokens, fp32; step t runs "
+                                  "fwd + bwd_input of the four layers at density cycle[t mod 6], cycle = %s (%s over the "
+                                  "layers), then per layer the dense gradient, the weight gradient read from it, the caller's SGD "
+                                  "step on the active weights and one Mixed-Growing update to cycle[(t+1) mod 6] (%s; %s)"
+                                  % (T, cyc, args.allocation,
+                                     "one call" if args.fused_update else "three calls so that the dense-gradient kernel "
+                                     "is timed on its own",
+                                     "updates on one stream per layer" if args.update_streams else "one stream"),
+                      "mask_updates_in_timed_region": args.steps * len(layers),
+                      "layers": {L.name: [L.I, L.O] for L in layers},
+                      "caller_sgd_lr": args.lr},
+           "hbm_gbs_step": round(tot_bytes / elapsed / 1e9, 1),
+           "hbm_frac_step": round(tot_bytes / elapsed / 1e9 / HBM_PEAK_GBS, 4),
+           "alu_frac_step": round(value / ALU_FP32_PEAK_TFLOPS, 4),
+           "ms_per_mask_update": round(sum(upd) / len(upd), 4) if upd else None,
+           "lds_peak_measured_tbs": round(lds_peak / 1e12, 1) if lds_peak else None,
+           "roofline": roof, "sweep": sweep_rows, "calls": calls}
+    if with_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_sweep(synth, args.seed, cfg)
+    free_layers(torch, layers)
+    return out
+
+
+def pmc_probe_sweep(args, mst, torch, layers, G, T, cyc, targets, cfg, stream):
+    """Counter run of the sweep: the calibration copy, then one step at every cycle position with
+    a one-element kernel after each call."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    mark = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    mark.add_(1)
+    order = []
+    for t in range(len(cyc)):
+        for L in layers:
+            mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
+            mark.add_(1)
+            mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
+            mark.add_(1)
+            order += ["%s/fwd@%d" % (L.name, t), "%s/bwd_input@%d" % (L.name, t)]
+        for li, (L, d) in enumerate(zip(layers, targets(t + 1))):
+            mst.mst_dense_grad(L.dY, L.X, G[li], T, L.O, L.I, L.act, L.ws, stream)
+            mark.add_(1)
+            mst.mst_gather_active(L.layer, G[li], L.dW, stream)
+            mark.add_(1)
+            mst.mst_mask_update_from_scores(L.layer, G[li], d, cfg["zeta"], cfg["R"], 1000 + t * 4 + li, L.ws, stream)
+            mark.add_(1)
+            order += ["%s/dense_grad@%d" % (L.name, t), "%s/gather_active@%d" % (L.name, t),
+                      "%s/mask_update@%d" % (L.name, t)]
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_probe": True, "copy_bytes_each_way": 1 << 30, "calls_in_order": order,
+                      "layers": {L.name: dict(I=L.I, O=L.O) for L in layers}}))
+
+
+# ------------------------------------------------------------------ other modes
 
 def attention_mask(args, mst, torch):
     """The [L x L] byte mask of the strided pattern: a write-only kernel, L * L algorithmic bytes."""
@@ -335,112 +665,17 @@ def attention_mask(args, mst, torch):
                      "avg_launch_ms": round(ms, 5), "alg_bytes_per_launch": L * L}}))
 
 
-def sweep(args, cfg, mst, synth, torch):
-    """Config C5: one GPT-2-large block (of 36 identical ones) swept through the densities
-    1.0, 0.5, 0.1, 0.02, 0.1, 0.5; every transition is produced by the fused mask update itself
-    and every step also runs one update at the current density (mask update every step)."""
-    import numpy as np
-    T = cfg["T"]
-    stream = torch.cuda.current_stream()
-    layers = []
-    for lid, (name, I, O) in enumerate(cfg["layers"]):
-        L = LayerRun.__new__(LayerRun)
-        L.name, L.I, L.O, L.T, L.act, L.act_bytes = name, I, O, T, mst.MST_F32, 4
-        W = synth.normal(args.seed, 1000 * (lid + 1) + 2, (O, I), 0.02)
-        M = np.ones((O, I), np.uint8)
-        X, dY = synth.make_activations(args.seed, lid + 1, T, I, O)
-        L.X, L.dY = torch.from_numpy(X).cuda(), torch.from_numpy(dY).cuda()
-        cap = O * I
-        L.layer = mst.Layer(O, I, cap, "cuda:0")
-        L.ws = torch.empty(mst.mst_workspace_bytes(O, I, cap, T), dtype=torch.uint8, device="cuda:0")
-        L.layer.load_dense(torch.from_numpy(W).cuda(), torch.from_numpy(M).cuda(), L.ws)
-        L.Y = torch.empty((T, O), dtype=torch.float32, device="cuda:0")
-        L.dX = torch.empty((T, I), dtype=torch.float32, device="cuda:0")
-        L.dW = torch.empty(cap, dtype=torch.float32, device="cuda:0")
-        layers.append(L)
-    torch.cuda.synchronize()
-    steps = max(1, args.steps // len(cfg["densities"]))
-    rows, tot_time, tot_flops, seed = [], 0.0, 0.0, args.seed * 7919
-
-    # The products of the block run in order on one stream.  The updates of different layers
-    # are independent (each has its own workspace): they are issued on one stream per layer,
-    # so that the many small selection and format kernels of one layer fill the gaps of the
-    # others; the next step's products wait for all of them.  All streams at default priority.
-    side = [torch.cuda.Stream() for _ in layers] if args.update_streams else [stream] * len(layers)
-
-    def one_step(dl):
-        nonlocal seed
-        for L in layers:
-            mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, stream)
-            mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, stream)
-            if not args.fused_update:
-                mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, stream)
-                L.layer.sync_values(stream)
-        fork = torch.cuda.Event()
-        fork.record(stream)
-        for L, d, s in zip(layers, dl, side):
-            seed += 1
-            if s is not stream:
-                s.wait_event(fork)
-            if args.fused_update:
-                # every step updates the topology: the dense gradient the update needs also
-                # gives the weight gradient (no separate SDDMM / dense product, and the update
-                # rebuilds the views, so no separate hand-over of the values)
-                mst.mst_sparse_fc_bwd_weight_update(L.layer, L.dY, L.X, L.dW, T, d, cfg["zeta"], cfg["R"], seed, L.ws,
-                                                    L.act, s)
-            else:
-                mst.mst_mask_update(L.layer, L.dY, L.X, T, d, cfg["zeta"], cfg["R"], seed, L.ws, L.act, s)
-            if s is not stream:
-                done = torch.cuda.Event()
-                done.record(s)
-                stream.wait_event(done)
-
-    for d in cfg["densities"]:
-        if args.allocation == "erdos_renyi":
-            dl = mst.mst_erdos_renyi_density([(L.O, L.I) for L in layers], d)
-        else:
-            dl = [d] * len(layers)
-        for L, dk in zip(layers, dl):          # transition to this density (untimed)
-            seed += 1
-            mst.mst_mask_update(L.layer, L.dY, L.X, T, dk, cfg["zeta"], cfg["R"], seed, L.ws, L.act, stream)
-        for _ in range(min(2, args.warmup)):
-            one_step(dl)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            one_step(dl)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / steps
-        flops = sum(6 * L.layer.nnz * T for L in layers)
-        rows.append(dict(density=d, ms_per_step=round(1e3 * dt, 4), eff_tflops=round(flops / dt / 1e12, 3),
-                         nnz={L.name: L.layer.nnz for L in layers},
-                         path="dense-mfma" if d > 0.30 else "sparse"))
-        tot_time += dt
-        tot_flops += flops
-    out = {"metric": METRIC, "value": round(tot_flops / tot_time / 1e12, 4), "unit": "TFLOP/s", "n_gpus": 1,
-           "steps": steps * len(cfg["densities"]), "warmup": args.warmup,
-           "ms_per_step": round(1e3 * tot_time / len(cfg["densities"]), 4), "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "C5: one GPT-2-large block (1280/5120; 1 of 36 identical blocks), T=%d, densities %s "
-                                  "(%s over the layers) reached by the mask update itself, products + fused "
-                                  "Mixed-Growing update every step (updates of the four layers on %s; %s)"
-                                  % (T, cfg["densities"], args.allocation,
-                                     "one stream per layer" if args.update_streams else "the main stream",
-                                     "weight gradient and update share one dense gradient" if args.fused_update
-                                     else "weight gradient and update as separate calls")},
-           "sweep": rows}
-    print(json.dumps(out))
-
-
-def cpu_baseline(layers, T):
-    """The oracle as it stands (dense masked fp64 products with numpy) on the host cores."""
-    import numpy as np
-    from oracle import products as opr
+def _oracle_threads():
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
     except Exception:
-        cores = os.cpu_count() or 1
+        return int(os.cpu_count() or 1)
+
+
+def cpu_baseline_block(layers, T):
+    """The oracle as it stands (dense masked fp64 products with numpy) on the host cores."""
+    from oracle import products as opr
     Ts = min(T, 8192)            # bounded sample of the same batch: the first Ts tokens
     t0 = time.perf_counter()
     flops, reps = 0, 0
@@ -453,10 +688,96 @@ def cpu_baseline(layers, T):
             flops += 3 * 2 * L.nnz * Ts
         reps += 1
     dt = time.perf_counter() - t0
-    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": _oracle_threads(), "kind": "oracle",
             "sample": "first %d of %d tokens, all layers, fwd+bwd_input+bwd_weight, %d repetitions (%.1f s); "
                       "effective (nonzero-only) FLOPs over the oracle's dense masked fp64 numpy products"
                       % (Ts, T, reps, dt)}
+
+
+def cpu_baseline_sweep(synth, seed, cfg):
+    """The oracle on a bounded sample of the sweep: the three products of the four layers at
+    every density of the cycle on the first 256 tokens, and the Mixed-Growing update of the
+    smallest layer (1280 x 1280) at every transition."""
+    import numpy as np
+    from oracle import mixed_growing as omg
+    from oracle import products as opr
+    Ts, T, cyc = 512, cfg["T"], cfg["densities"]
+    acts, Ws, Ms = [], [], []
+    for lid, (_, I, O) in enumerate(cfg["layers"]):          # inputs first: drawing them is not the oracle's work
+        acts.append(synth.make_activations(seed, lid + 1, Ts, I, O))
+        Ws.append(synth.normal(seed, 100000 + lid, (O, I), 0.02))
+        Ms.append(synth.nested_uniform_masks(seed, 200000 + lid, O, I, cyc))
+    t0 = time.perf_counter()
+    flops, n_upd = 0, 0
+    Wp = Mp = Gp = None
+    for p, d in enumerate(cyc):
+        for lid, (lname, I, O) in enumerate(cfg["layers"]):
+            W, M = Ws[lid], Ms[lid][p]
+            X, dY = acts[lid]
+            opr.fc_fwd(X, W, M)
+            opr.fc_bwd_input(dY, W, M)
+            opr.fc_bwd_weight(dY, X, M)
+            flops += 3 * 2 * int(M.sum()) * Ts
+            if lname == "proj":
+                if Wp is None:
+                    Wp, Mp = W * M, M
+                    Gp = opr.dense_grad(dY, X).astype(np.float32)
+        r = omg.update(Wp, Mp, Gp, cyc[(p + 1) % len(cyc)], cfg["zeta"], cfg["R"], seed + p)
+        Wp, Mp = r["W"], r["M"]
+        n_upd += 1
+    dt = time.perf_counter() - t0
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": _oracle_threads(), "kind": "oracle",
+            "sample": "one pass of the density cycle %s: fwd+bwd_input+bwd_weight of the four layers on the first %d of "
+                      "%d tokens (dense masked fp64 numpy products, masks drawn per density) plus %d Mixed-Growing "
+                      "updates of the 1280x1280 layer, %.1f s in all; effective (nonzero-only) FLOPs of the products "
+                      "over that time" % (cyc, Ts, T, n_upd, dt)}
+
+
+def compact(out, name):
+    """One row of the per_config table from a block workload's full result."""
+    r = out["roofline"]
+    return dict(config=name, workload=out["config"]["workload"], dtype=out["dtype"], steps=out["steps"],
+                ms_per_step=out["ms_per_step"], eff_tflops=out["value"], hbm_gbs_step=out["hbm_gbs_step"],
+                hbm_frac=out["hbm_frac_step"], alu_frac=out["alu_frac_step"],
+                alu_frac_of_unpacked_peak=round(out["value"] / ALU_FP32_UNPACKED_TFLOPS, 4),
+                mask_updates_in_timed_region=out["config"]["mask_updates_in_timed_region"],
+                ms_per_mask_update=out["ms_per_mask_update"], ell_efficiency=out["config"]["ell_efficiency"],
+                slowest_call=dict(call=r["call"], avg_ms=r["avg_launch_ms"], bound=r["bound"], frac=r["frac"],
+                                  hbm_frac=r.get("hbm_frac"), alu_frac=r.get("alu_frac"), lds_frac=r.get("lds_frac")),
+                calls=[{k: c[k] for k in ("layer", "call", "avg_ms", "eff_tflops", "hbm_frac", "alu_frac", "lds_frac")
+                        if k in c} for c in out["calls"]],
+                dense_grad_gemm=out["dense_grad_gemm"])
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2408_11746_amd as mst
+    import synth
+
+    if args.attention_mask:
+        return attention_mask(args, mst, torch)
+    stream = torch.cuda.current_stream()
+    lds_peak = None if args.pmc_probe else lds_peak_bytes_per_s(mst, torch, stream)
+    cpu = not args.no_cpu_baseline
+    if args.config == "C5" or args.config == "all":
+        out = run_sweep(args, mst, synth, torch, lds_peak, cpu)
+        if out is None:
+            return
+        if args.config == "all" and not args.no_per_config:
+            rows = []
+            for name in ("C1", "C2", "C3", "C4"):
+                rows.append(compact(run_block(args, name, mst, synth, torch, lds_peak, False), name))
+            out["per_config"] = rows
+        print(json.dumps(out))
+        return
+    out = run_block(args, args.config, mst, synth, torch, lds_peak, cpu)
+    if out is not None:
+        print(json.dumps(out))
 
 
 if __name__ == "__main__":

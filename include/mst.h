@@ -191,6 +191,30 @@ int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront);
 int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, int O, int I,
                    mst_dtype act, void* ws_dev, size_t ws_bytes, mst_stream_t stream);
 
+/* dW_dev [nnz] = G_dev [O*I] read at the active positions (ascending flat index): the weight
+ * gradient of a step whose dense gradient was formed anyway (mst_dense_grad on an update
+ * step), the middle part of mst_sparse_fc_bwd_weight_update as a call of its own. */
+int mst_gather_active(const mst_layer_t* layer, const float* G_dev, float* dW_dev, mst_stream_t stream);
+
+/* What the index views of a layer store.  A view keeps, per chunk of 128 contraction indices
+ * and quad of four rows, as many steps as the longest of the four rows needs, padded to an
+ * even count; each step has one entry slot per row.  efficiency = nnz / slots is the share of
+ * walk steps that do real work.  Synchronises `stream` (reads two counters back). */
+typedef struct {
+    int64_t nnz;
+    int64_t row_view_slots, col_view_slots;     /* entry slots incl. zero-weight padding */
+    double row_view_efficiency, col_view_efficiency;
+} mst_format_stats;
+int mst_layer_format_stats(const mst_layer_t* layer, mst_format_stats* out, mst_stream_t stream);
+
+/* Measurement aid: a kernel that only reads LDS, for the on-chip roofline of the sparse
+ * products (every multiply-add of the walk needs its own 4-byte activation operand from
+ * LDS).  `blocks` workgroups of 1024 threads each perform iters * 8 conflict-free reads of
+ * `width` bytes (4, 8 or 16) per thread from a 64 KB tile and write one float per thread to
+ * out_dev [blocks * 1024].  Bytes read = blocks * 1024 * iters * 8 * width; time it with
+ * events on `stream`. */
+int mst_probe_lds_read(float* out_dev, int width, int iters, int blocks, mst_stream_t stream);
+
 /* ------------------------------------------------------------ topology update */
 
 /* Host arithmetic of Algorithm 1's count lines for a layer of n_total positions with
@@ -255,6 +279,15 @@ int mst_sparse_fc_bwd_weight_update(mst_layer_t* layer, const void* dY_dev, cons
  * Either output pointer may be NULL. */
 int mst_schedule_density(const mst_schedule_cfg* cfg, int64_t step,
                          double* density_out, double* zeta_out);
+
+/* Pure host.  Whether `step` carries a topology update: every Delta_t-th step after step 0
+ * (Sec. 3.2; Table "Private hyperparameters of MST": Delta_t = 100).  1 = yes, 0 = no,
+ * MST_ERR_ARG for step < 0 or delta_t < 1. */
+int mst_update_due(int64_t step, int64_t delta_t);
+
+/* Pure host.  The rng_seed of layer `layer` (0-based, of n_layers) at `step` for a run seeded
+ * with run_seed: run_seed + step * n_layers + layer modulo 2^64, distinct per (step, layer). */
+uint64_t mst_update_seed(uint64_t run_seed, int64_t step, int32_t n_layers, int32_t layer);
 
 /* ------------------------------------------------------ per-layer densities */
 

@@ -36,6 +36,14 @@ class UpdateStats(C.Structure):
         return {k: int(getattr(self, k)) for k, _ in self._fields_}
 
 
+class FormatStats(C.Structure):
+    _fields_ = [("nnz", C.c_int64), ("row_view_slots", C.c_int64), ("col_view_slots", C.c_int64),
+                ("row_view_efficiency", C.c_double), ("col_view_efficiency", C.c_double)]
+
+    def as_dict(self):
+        return {k: (int(getattr(self, k)) if t is C.c_int64 else float(getattr(self, k))) for k, t in self._fields_}
+
+
 class TransformerShape(C.Structure):
     _fields_ = [("L", C.c_int64), ("N_embd", C.c_int64), ("D_ffw", C.c_int64), ("D_vocab", C.c_int64),
                 ("n_layers", C.c_int64)]
@@ -90,6 +98,11 @@ def lib() -> C.CDLL:
         "mst_static_scratch_bytes": (sz, []),
         "mst_sparse_fc_bwd": (i32, [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]),
         "mst_bwd_force_shape": (i32, [i32, i32]),
+        "mst_gather_active": (i32, [vp, vp, vp, vp]),
+        "mst_layer_format_stats": (i32, [vp, C.POINTER(FormatStats), vp]),
+        "mst_probe_lds_read": (i32, [vp, i32, i32, i32, vp]),
+        "mst_update_due": (i32, [i64, i64]),
+        "mst_update_seed": (u64, [u64, i64, C.c_int32, C.c_int32]),
         "mst_dense_grad": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]),
         "mst_update_counts": (i32, [i64, i64, dbl, dbl, dbl, C.POINTER(UpdateStats)]),
         "mst_mask_update_from_scores": (i32, [vp, vp, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
@@ -116,6 +129,7 @@ EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_w
            "mst_spmm_force_shape",
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight", "mst_sparse_fc_bwd_weight_static",
            "mst_static_scratch_bytes", "mst_sparse_fc_bwd", "mst_bwd_force_shape",
+           "mst_gather_active", "mst_layer_format_stats", "mst_probe_lds_read", "mst_update_due", "mst_update_seed",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
            "mst_sparse_fc_bwd_weight_update",
            "mst_schedule_density", "mst_erdos_renyi_density", "mst_flops_fc_forward", "mst_flops_transformer",
@@ -231,6 +245,11 @@ class Layer:
     def indices(self, out, stream=None):
         _check("mst_layer_indices", lib().mst_layer_indices(self.h, _ptr(out), _stream(stream)))
 
+    def format_stats(self, stream=None) -> dict:
+        st = FormatStats()
+        _check("mst_layer_format_stats", lib().mst_layer_format_stats(self.h, C.byref(st), _stream(stream)))
+        return st.as_dict()
+
     def set_path(self, path: int):
         _check("mst_layer_set_path", lib().mst_layer_set_path(self.h, path))
 
@@ -276,6 +295,25 @@ def mst_sparse_fc_bwd(layer: Layer, dY, X, dX, dW, T: int, ws, act: int = MST_F3
     _check("mst_sparse_fc_bwd",
            lib().mst_sparse_fc_bwd(layer.h, _ptr(dY), _ptr(X), _ptr(dX), _ptr(dW), T, act, _ptr(ws), ws.numel(),
                                    _stream(stream)))
+
+
+def mst_gather_active(layer: Layer, G, dW, stream=None):
+    _check("mst_gather_active", lib().mst_gather_active(layer.h, _ptr(G), _ptr(dW), _stream(stream)))
+
+
+def mst_probe_lds_read(out, width: int, iters: int, blocks: int, stream=None):
+    _check("mst_probe_lds_read", lib().mst_probe_lds_read(_ptr(out), width, iters, blocks, _stream(stream)))
+
+
+def mst_update_due(step: int, delta_t: int) -> bool:
+    r = lib().mst_update_due(int(step), int(delta_t))
+    if r < 0:
+        raise MstError("mst_update_due", r)
+    return bool(r)
+
+
+def mst_update_seed(run_seed: int, step: int, n_layers: int, layer: int) -> int:
+    return int(lib().mst_update_seed(int(run_seed) & 0xFFFFFFFFFFFFFFFF, int(step), int(n_layers), int(layer)))
 
 
 def mst_dense_grad(dY, X, G, T: int, O: int, I: int, act: int = MST_F32, ws=None, stream=None):

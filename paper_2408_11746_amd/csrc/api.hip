@@ -165,6 +165,32 @@ int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_de
     return bwd_fused(L, dY_dev, X_dev, dX_dev, dW_dev, T, act, ws, s);
 }
 
+int mst_gather_active(const mst_layer_t* L, const float* G_dev, float* dW_dev, mst_stream_t stream) {
+    if (!L || !G_dev || !dW_dev || !aligned16(G_dev) || !aligned16(dW_dev)) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
+    if (L->nnz > 0) {
+        k_gather_flat<<<(unsigned)cdiv(L->nnz, 256), 256, 0, (hipStream_t)stream>>>(G_dev, L->N, 1, L->flat, L->nnz, dW_dev);
+        MST_LAUNCH_CHECK();
+    }
+    return MST_OK;
+}
+
+int mst_layer_format_stats(const mst_layer_t* L, mst_format_stats* out, mst_stream_t stream) {
+    if (!L || !out) return MST_ERR_ARG;
+    if (!L->built) return MST_ERR_STATE;
+    hipStream_t s = (hipStream_t)stream;
+    int pr = 0, pc = 0;
+    MST_HIP(hipMemcpyAsync(&pr, L->row.ptr + L->row.nseg, 4, hipMemcpyDeviceToHost, s));
+    MST_HIP(hipMemcpyAsync(&pc, L->col.ptr + L->col.nseg, 4, hipMemcpyDeviceToHost, s));
+    MST_HIP(hipStreamSynchronize(s));
+    out->nnz = L->nnz;
+    out->row_view_slots = (int64_t)pr * 8;
+    out->col_view_slots = (int64_t)pc * 8;
+    out->row_view_efficiency = pr ? (double)L->nnz / (double)out->row_view_slots : 1.0;
+    out->col_view_efficiency = pc ? (double)L->nnz / (double)out->col_view_slots : 1.0;
+    return MST_OK;
+}
+
 int mst_dense_grad(const void* dY_dev, const void* X_dev, float* G_dev, int T, int O, int I, mst_dtype act,
                    void* ws_dev, size_t ws_bytes, mst_stream_t stream) {
     if (!dY_dev || !X_dev || !G_dev || T < 1 || O < 1 || I < 1 || !act_ok(act)) return MST_ERR_ARG;

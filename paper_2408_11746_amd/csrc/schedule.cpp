@@ -61,6 +61,18 @@ int mst_schedule_density(const mst_schedule_cfg* cfg, int64_t step, double* dens
     return MST_OK;
 }
 
+// Sec. 3.2 / Table "Private hyperparameters of MST": the topology is updated every Delta_t
+// steps (100); step 0 holds the initial topology and is no update step.
+int mst_update_due(int64_t step, int64_t delta_t) {
+    if (step < 0 || delta_t < 1) return MST_ERR_ARG;
+    return (step > 0 && step % delta_t == 0) ? 1 : 0;
+}
+
+// one seed per (step, layer) for the random growth of Algorithm 1, arithmetic modulo 2^64
+uint64_t mst_update_seed(uint64_t run_seed, int64_t step, int32_t n_layers, int32_t layer) {
+    return run_seed + (uint64_t)step * (uint64_t)n_layers + (uint64_t)layer;
+}
+
 int mst_update_counts(int64_t n_total, int64_t nnz, double target_density, double zeta,
                       double rand_ratio, mst_update_stats* out) {
     if (!out || n_total < 1 || nnz < 0 || nnz > n_total) return MST_ERR_ARG;

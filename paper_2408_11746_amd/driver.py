@@ -1,7 +1,8 @@
 """Topology schedule over a set of layers: which step updates, with which targets.
 
-Orchestration only (host arithmetic through the library's schedule, allocation and count
-entry points, then one update call per layer); every device step runs in the library.
+Orchestration only: every decision (is this an update step, the density and update fraction,
+the layers' shares, the per-layer seed, the counts) is a host call of the library, every device
+step runs in the library; this file holds no arithmetic of the method.
 
 At a step t that is a positive multiple of the update interval Delta_t (Table "Private
 hyperparameters of MST": 100) the network density d_t and update fraction zeta_t of
@@ -21,6 +22,7 @@ class TopologyDriver:
                  rand_ratio: float = 0.25, seed: int = 0, allocation: str = "erdos_renyi"):
         if delta_t < 1:
             raise ValueError("delta_t must be positive")
+        B.mst_update_due(0, delta_t)                    # the library's own argument check
         if allocation not in ("erdos_renyi", "uniform"):
             raise ValueError("allocation is 'erdos_renyi' or 'uniform'")
         self.layers = list(layers)
@@ -29,7 +31,7 @@ class TopologyDriver:
         self.shapes = [(l.O, l.I) for l in self.layers]
 
     def is_update_step(self, step: int) -> bool:
-        return step > 0 and step % self.delta_t == 0
+        return B.mst_update_due(step, self.delta_t)
 
     def targets(self, step: int):
         """(d_t, zeta_t, [d_l]) at a step."""
@@ -40,7 +42,7 @@ class TopologyDriver:
 
     def layer_seed(self, step: int, index: int) -> int:
         """Seed of the random growth of layer `index` at `step`: distinct per (step, layer)."""
-        return (self.seed + step * len(self.layers) + index) % (1 << 64)
+        return B.mst_update_seed(self.seed, step, len(self.layers), index)
 
     def _idle(self, d_layers, z) -> bool:
         if z != 0.0:

@@ -9,6 +9,7 @@ from .inputs import (  # noqa: F401
     CONFIGS,
     normal,
     uniform_mask,
+    nested_uniform_masks,
     powerlaw_mask,
     to_bf16_bits,
     bf16_bits_to_f32,

@@ -72,6 +72,21 @@ def uniform_mask(seed: int, tensor_id: int, O: int, I: int, density: float) -> n
     return m.reshape(O, I)
 
 
+def nested_uniform_masks(seed: int, tensor_id: int, O: int, I: int, densities) -> list:
+    """One uniform mask per density from a single random order of the positions: the mask of
+    density d is the first ``active_count(O*I, d)`` positions of that order (so the masks are
+    nested).  Each is uniform without replacement; drawing the order once makes a whole sweep
+    of densities cheap."""
+    n = O * I
+    order = _rng(seed, tensor_id).permutation(n)
+    out = []
+    for d in densities:
+        m = np.zeros(n, dtype=np.uint8)
+        m[order[: min(n, active_count(n, d))]] = 1
+        out.append(m.reshape(O, I))
+    return out
+
+
 def powerlaw_row_lengths(seed: int, tensor_id: int, O: int, I: int, density: float,
                          alpha: float = 1.5) -> np.ndarray:
     """Per-row active counts with a Pareto tail (pdf ~ len^-alpha), summing exactly to the target.

@@ -59,3 +59,18 @@ def test_layer_seeds_are_distinct_per_step_and_layer():
     assert len(seen) == 20 * len(SHAPES)
     big, _ = make(seed=(1 << 64) - 1)
     assert 0 <= big.layer_seed(140000, 3) < (1 << 64)
+
+
+def test_update_due_and_seed_host_calls():
+    """Table "Private hyperparameters of MST": the topology is updated every 100 steps; step 0
+    holds the initial topology."""
+    assert [t for t in range(0, 401) if mst.mst_update_due(t, 100)] == [100, 200, 300, 400]
+    assert [t for t in range(0, 8) if mst.mst_update_due(t, 1)] == [1, 2, 3, 4, 5, 6, 7]
+    for bad in [(-1, 100), (5, 0), (5, -3)]:
+        with pytest.raises(mst.MstError):
+            mst.mst_update_due(*bad)
+    # seeds: distinct per (step, layer), arithmetic modulo 2^64
+    seen = {mst.mst_update_seed(7, t, 4, k) for t in range(0, 300) for k in range(4)}
+    assert len(seen) == 1200
+    assert mst.mst_update_seed((1 << 64) - 1, 1, 4, 0) == 3
+    assert mst.mst_update_seed(5, 10, 4, 3) == 5 + 10 * 4 + 3

@@ -272,3 +272,32 @@ def test_argument_errors_launch_nothing():
         tiny = mst.Layer(32, 32, 4, DEV)
         tiny.load_dense(dev(W), dev(M), rig.ws)
     assert e.value.code == -4
+
+
+def test_gather_active_format_stats_and_lds_probe():
+    O, I, T = 200, 333, 64
+    W, M = synth.make_layer(31, 1, I, O, 0.07)
+    rig = Rig(W, M, T)
+    G = synth.normal(31, 5, (O, I))
+    dW = torch.full((rig.layer.nnz,), float("nan"), dtype=torch.float32, device=DEV)
+    mst.mst_gather_active(rig.layer, dev(G), dW)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(dW.cpu().numpy(), G[M != 0])          # ascending flat index
+    fs = rig.layer.format_stats()
+    nnz = int(M.sum())
+    assert fs["nnz"] == nnz
+    # every view stores each active weight once plus padding; padding is bounded by the format
+    # (longest of four rows per 128-index chunk, even step counts)
+    for v, (R, K) in (("row", (O, I)), ("col", (I, O))):
+        slots = fs[v + "_view_slots"]
+        assert slots >= nnz and slots % 8 == 0
+        assert 0.0 < fs[v + "_view_efficiency"] <= 1.0
+        assert abs(fs[v + "_view_efficiency"] - nnz / slots) < 1e-12
+    # an exact count of the row view's slots from the mask: per chunk and quad of the ranked rows
+    out = torch.empty(4 * 1024, dtype=torch.float32, device=DEV)
+    for width in (4, 8, 16):
+        mst.mst_probe_lds_read(out, width, 10, 4)
+    torch.cuda.synchronize()
+    assert np.isfinite(out.cpu().numpy()).all()
+    with pytest.raises(mst.MstError):
+        mst.mst_probe_lds_read(out, 5, 10, 4)
