@@ -185,6 +185,15 @@ int mst_sparse_fc_bwd(const mst_layer_t* layer, const void* dY_dev, const void* 
  * Every shape gives the same results. */
 int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront);
 
+/* The dense fp32 products (the dense gradient below, and the three products of a layer on the
+ * dense path) run on the bf16 matrix cores when their shapes are whole tiles: each fp32
+ * operand element is split into two bfloat16 values (hi + lo, exact to 2^-17) while it is
+ * staged, a product is hi*hi + hi*lo + lo*hi with fp32 accumulation; the result differs from
+ * an fp32 product by less than 2^-16 per term.  This hook pins the plain fp32 MFMA kernel
+ * instead (on != 0) for all later calls of the process; 0 returns to the automatic choice.
+ * Test and measurement aid, not thread-safe. */
+int mst_gemm_force_fp32_mfma(int on);
+
 /* G_dev [O*I] = dY^T X at every position (the score of gradient-based growth: the dense
  * gradient that Sec. 2 notes such growth needs now and then).  Runs on the matrix cores.  ws_dev may be
  * NULL; with a workspace small outputs split the token range over more workgroups. */

@@ -294,6 +294,152 @@ __global__ __launch_bounds__(256) void k_gemm_tn_bf16(const uint16_t* __restrict
             }
 }
 
+// ---- fp32 x fp32 -> fp32 on the bf16 matrix cores: every operand element x is split while it
+// is staged into hi = bf16(x) and lo = bf16(x - hi) (x - hi is exact in fp32), and a product is
+// formed as hi*hi + hi*lo + lo*hi with fp32 accumulation: three v_mfma_f32_32x32x16_bf16 (16x
+// the rate of the fp32 MFMA each) instead of eight v_mfma_f32_32x32x2f32 per 16 k.  What is
+// dropped (lo*lo and the second-order residue of the split) is below 2^-16 of a product, far
+// inside the 1e-4 bound of the fp32 results and of the same order as the rounding of an fp32
+// accumulation over thousands of terms.  Workgroup tile 128 x 128 x 64, four wavefronts of
+// 64 x 64; LDS holds the hi and lo halves of both operand tiles in the bf16 kernel's layout
+// (64 KB).  Either operand may be k-major (element (k, m) at src[k*ld + m]: an [8 k x 4 m]
+// patch per thread is transposed in registers) or m-major (src[m*ld + k]: eight consecutive k
+// per thread go to LDS as they are).  Only for shapes whose tiles are whole (M, N multiples
+// of 128, k ranges multiples of 64, rows 16-byte aligned); everything else takes k_gemm.
+constexpr int SPK = 64;
+
+__device__ inline uint32_t cvt_pk_bf16(float a, float b) {       // {bf16(a), bf16(b)}, round to nearest even
+    uint32_t r;
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ inline void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+    hi = cvt_pk_bf16(x0, x1);
+    lo = cvt_pk_bf16(x0 - __uint_as_float(hi << 16), x1 - __uint_as_float(hi & 0xFFFF0000u));
+}
+
+template <bool KMAJOR>
+__device__ inline void split_fetch(const float* __restrict__ src, int64_t ld, int k0, int m0, int p, float4 (&r)[8]) {
+    if (KMAJOR) {                       // patch: k = k0 + 8 kg .. + 7, m = m0 + 4 mq .. + 3
+        const int mq = p & 31, kg = p >> 5;
+        const float* q = src + (int64_t)(k0 + 8 * kg) * ld + m0 + 4 * mq;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) r[kk] = *reinterpret_cast<const float4*>(q + (int64_t)kk * ld);
+    } else {                            // four units of eight consecutive k: unit index it * 256 + p
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int idx = it * 256 + p, m = idx >> 3, u = idx & 7;
+            const float* q = src + (int64_t)(m0 + m) * ld + k0 + 8 * u;
+            r[2 * it] = *reinterpret_cast<const float4*>(q);
+            r[2 * it + 1] = *reinterpret_cast<const float4*>(q + 4);
+        }
+    }
+}
+
+__device__ inline float f4_at(const float4& v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
+
+template <bool KMAJOR>
+__device__ inline void split_stage(char* hi_lds, char* lo_lds, int p, const float4 (&r)[8]) {
+    if (KMAJOR) {
+        const int mq = p & 31, kg = p >> 5;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint4 h, l;
+            split_pair(f4_at(r[0], j), f4_at(r[1], j), h.x, l.x);
+            split_pair(f4_at(r[2], j), f4_at(r[3], j), h.y, l.y);
+            split_pair(f4_at(r[4], j), f4_at(r[5], j), h.z, l.z);
+            split_pair(f4_at(r[6], j), f4_at(r[7], j), h.w, l.w);
+            const uint32_t a = bf_unit(4 * mq + j, kg);
+            *reinterpret_cast<uint4*>(hi_lds + a) = h;
+            *reinterpret_cast<uint4*>(lo_lds + a) = l;
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int idx = it * 256 + p, m = idx >> 3, u = idx & 7;
+            uint4 h, l;
+            split_pair(r[2 * it].x, r[2 * it].y, h.x, l.x);
+            split_pair(r[2 * it].z, r[2 * it].w, h.y, l.y);
+            split_pair(r[2 * it + 1].x, r[2 * it + 1].y, h.z, l.z);
+            split_pair(r[2 * it + 1].z, r[2 * it + 1].w, h.w, l.w);
+            const uint32_t a = bf_unit(m, u);
+            *reinterpret_cast<uint4*>(hi_lds + a) = h;
+            *reinterpret_cast<uint4*>(lo_lds + a) = l;
+        }
+    }
+}
+
+template <bool A_KMAJOR, bool B_KMAJOR>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_gemm_split(const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+                  float* __restrict__ C, int M, int N, int Kdim, int k_per_split, int64_t split_stride) {
+    __shared__ __attribute__((aligned(16))) char lds[4 * BM * 128];      // A hi, A lo, B hi, B lo
+    char* const Ah = lds;
+    char* const Al = lds + BM * 128;
+    char* const Bh = lds + 2 * BM * 128;
+    char* const Bl = lds + 3 * BM * 128;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int m0 = blockIdx.z * BM, n0 = blockIdx.y * BN;
+    const int kbeg = blockIdx.x * k_per_split;
+    const int kend = min(Kdim, kbeg + k_per_split);
+    float* Cz = C + (int64_t)blockIdx.x * split_stride;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    float4 ra[8], rb[8];
+    split_fetch<A_KMAJOR>(A, lda, kbeg, m0, tid, ra);
+    split_fetch<B_KMAJOR>(B, ldb, kbeg, n0, tid, rb);
+    const int lk = lane >> 5, lm = lane & 31;
+    for (int k0 = kbeg; k0 < kend; k0 += SPK) {
+        __syncthreads();
+        split_stage<A_KMAJOR>(Ah, Al, tid, ra);
+        split_stage<B_KMAJOR>(Bh, Bl, tid, rb);
+        __syncthreads();
+        if (k0 + SPK < kend) {
+            split_fetch<A_KMAJOR>(A, lda, k0 + SPK, m0, tid, ra);
+            split_fetch<B_KMAJOR>(B, ldb, k0 + SPK, n0, tid, rb);
+        }
+#pragma unroll
+        for (int ks = 0; ks < SPK / 8; ks += 2) {          // 16 k per MFMA: units ks + lk
+            const uint32_t ua0 = bf_unit(wm + lm, ks + lk), ua1 = bf_unit(wm + 32 + lm, ks + lk);
+            const uint32_t ub0 = bf_unit(wn + lm, ks + lk), ub1 = bf_unit(wn + 32 + lm, ks + lk);
+            const bf16x8 a0h = *reinterpret_cast<const bf16x8*>(Ah + ua0), a0l = *reinterpret_cast<const bf16x8*>(Al + ua0);
+            const bf16x8 a1h = *reinterpret_cast<const bf16x8*>(Ah + ua1), a1l = *reinterpret_cast<const bf16x8*>(Al + ua1);
+            const bf16x8 b0h = *reinterpret_cast<const bf16x8*>(Bh + ub0), b0l = *reinterpret_cast<const bf16x8*>(Bl + ub0);
+            const bf16x8 b1h = *reinterpret_cast<const bf16x8*>(Bh + ub1), b1l = *reinterpret_cast<const bf16x8*>(Bl + ub1);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0l, b0h, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0l, b1h, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1l, b0h, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1l, b1h, acc[1][1], 0, 0, 0);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, b0l, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, b1l, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, b0l, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, b1l, acc[1][1], 0, 0, 0);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, b0h, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, b1h, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, b0h, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, b1h, acc[1][1], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                const int n = n0 + wn + j * 32 + lm;
+                Cz[(int64_t)m * N + n] = acc[i][j][v];
+            }
+}
+
 __global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, int nsplit,
                                 float* __restrict__ C, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -367,6 +513,41 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
     return MST_OK;
 }
 
+static const SplitModel kSplitSplit = {2, SPK, 2.6, 4.0, 5e-7, {0.55, 0.70, 0.86}};
+static int g_gemm_fp32_only = 0;          // test hook: 1 = never use the bf16-split kernel
+
+int gemm_force_fp32_mfma(int on) {
+    g_gemm_fp32_only = on ? 1 : 0;
+    return MST_OK;
+}
+
+static bool split_ok(int M, int N, int Kdim, int64_t lda, int64_t ldb) {
+    return !g_gemm_fp32_only && M % BM == 0 && N % BN == 0 && Kdim % SPK == 0 && lda % 4 == 0 && ldb % 4 == 0;
+}
+
+template <bool AK, bool BKM>
+static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
+                        float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
+    const int gm = M / BM, gn = N / BN;
+    const int64_t mn = (int64_t)M * N;
+    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, kSplitSplit, split_ws_floats / mn) : 1;
+    const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), SPK) * SPK);
+    const int nsplit = (int)cdiv(Kdim, kps);
+    dim3 grid(nsplit, gn, gm);
+    float* dst = nsplit > 1 ? split_ws : C;
+    k_gemm_split<AK, BKM><<<grid, 256, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+    MST_LAUNCH_CHECK();
+    if (left_unsummed) {
+        *left_unsummed = nsplit;
+        return MST_OK;
+    }
+    if (nsplit > 1) {
+        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
+        MST_LAUNCH_CHECK();
+    }
+    return MST_OK;
+}
+
 static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, int Kdim, float* split_ws,
                           int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
     const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
@@ -401,14 +582,20 @@ int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_d
         case GEMM_TN:
             if (ab != bb) return MST_ERR_ARG;
             if (ab) return launch_tn_bf16(A, B, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
+            if (split_ok(M, N, Kdim, M, N))
+                return launch_split<true, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             return launch<float, true, float, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NT:
             if (bb) return MST_ERR_ARG;
             if (ab) return launch<uint16_t, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
+            if (split_ok(M, N, Kdim, Kdim, Kdim))
+                return launch_split<false, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             return launch<float, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NN:
             if (bb) return MST_ERR_ARG;
             if (ab) return launch<uint16_t, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
+            if (split_ok(M, N, Kdim, Kdim, N))
+                return launch_split<false, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             return launch<float, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
     }
     return MST_ERR_ARG;

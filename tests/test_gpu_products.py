@@ -301,3 +301,37 @@ def test_gather_active_format_stats_and_lds_probe():
     assert np.isfinite(out.cpu().numpy()).all()
     with pytest.raises(mst.MstError):
         mst.mst_probe_lds_read(out, 5, 10, 4)
+
+
+@pytest.mark.parametrize("T,I,O", [(512, 256, 384), (1024, 768, 768), (256, 128, 1280)])
+def test_dense_products_on_the_bf16_split_kernel(T, I, O):
+    """Shapes of whole tiles: the dense fp32 products (dense gradient; forward and input
+    gradient of a dense layer) take the kernel that splits every fp32 operand into two
+    bfloat16 values and adds three bf16 MFMA products.  Against the oracle within the fp32
+    tolerance, and against the plain fp32 MFMA kernel (pinned by the hook)."""
+    print("case", T, I, O, flush=True)
+    X, dY = synth.make_activations(41, 2, T, I, O)
+    # values over several orders of magnitude in every operand, so that hi + lo matters
+    X = (X * np.exp2(synth.normal(41, 7, X.shape) * 3)).astype(np.float32)
+    W = synth.normal(41, 3, (O, I), 0.02)
+    M = np.ones((O, I), np.uint8)
+    rig = Rig(W, M, T, cap=O * I)
+    Xd, dYd = dev(X), dev(dY)
+    res = {}
+    try:
+        for mode in (0, 1):
+            mst.mst_gemm_force_fp32_mfma(bool(mode))
+            G = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
+            mst.mst_dense_grad(dYd, Xd, G, T, O, I, mst.MST_F32, rig.ws)
+            torch.cuda.synchronize()
+            res[mode] = (G.cpu().numpy(), rig.fwd(X), rig.bwd_input(dY))
+    finally:
+        mst.mst_gemm_force_fp32_mfma(False)
+    refs = (opr.dense_grad(dY, X), opr.fc_fwd(X, W, M), opr.fc_bwd_input(dY, W, M))
+    for name, got_split, got_f32, ref in zip(("G", "Y", "dX"), res[0], res[1], refs):
+        e0, e1 = rel_err(got_split, ref), rel_err(got_f32, ref)
+        print(name, "split err %.3g  fp32-mfma err %.3g" % (e0, e1), flush=True)
+        assert e0 <= TOL and e1 <= TOL
+        # hi + lo carries 16 significant bits: at most 3 * 2^-18 = 1.1e-5 of a product is lost
+        assert e0 <= 2e-5
+        assert not np.array_equal(got_split, got_f32) or e0 == 0.0      # the two kernels really differ
