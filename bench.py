@@ -167,19 +167,38 @@ def product_row_numbers(row, ms, by, fl, lds_bytes, lds_peak):
         row.update(lds_frac=round(lds_bytes / (ms * 1e-3) / lds_peak, 4))
 
 
+def split_gemm_applies(M, N, K):
+    """Shapes of whole tiles take the kernel that forms an fp32 product from three bf16 MFMA
+    products of the operands' bf16 halves (include/mst.h, mst_gemm_force_fp32_mfma)."""
+    return M % 128 == 0 and N % 128 == 0 and K % 64 == 0
+
+
+def dense_gemm_roofline(flops, ms, act, M, N, K):
+    """A dense contraction: the matrix cores' peak for the dtype of the MFMA instructions that
+    run.  fp32 operands on whole tiles run as 3 bf16 MFMA products per term: executed flops =
+    3 x the product's 2 M N K, against the bf16 peak."""
+    tf = flops / ms / 1e9
+    if act == "bf16":
+        return dict(bound="mfma", achieved=round(tf, 2), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(tf / MFMA_BF16_PEAK_TFLOPS, 4), mfma_dtype="bf16")
+    if split_gemm_applies(M, N, K):
+        return dict(bound="mfma", achieved=round(3 * tf, 2), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(3 * tf / MFMA_BF16_PEAK_TFLOPS, 4), mfma_dtype="bf16 (fp32 operands split hi + lo, 3 products)",
+                    fp32_equivalent_tflops=round(tf, 2), frac_of_fp32_mfma_peak=round(tf / MFMA_FP32_PEAK_TFLOPS, 4))
+    return dict(bound="mfma", achieved=round(tf, 2), peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                frac=round(tf / MFMA_FP32_PEAK_TFLOPS, 4), mfma_dtype="fp32")
+
+
 def roofline_of(row, L, act, kernel, traffic_cfg):
     """The roofline object of one (layer, call) row."""
     if row["call"] == "dense_grad":
-        peak = MFMA_BF16_PEAK_TFLOPS if act == "bf16" else MFMA_FP32_PEAK_TFLOPS
-        tf = row["alg_flops"] / row["avg_ms"] / 1e9
-        roof = dict(bound="mfma", achieved=round(tf, 2), peak=peak, unit="TFLOP/s", frac=round(tf / peak, 4))
+        roof = dense_gemm_roofline(row["alg_flops"], row["avg_ms"], act, L.O, L.I, L.T)
     else:
         t_hbm = row["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
         t_alu = row["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
         if row.get("path") == "dense-mfma":
-            tf = row["dense_flops"] / row["avg_ms"] / 1e9
-            roof = dict(bound="mfma", achieved=round(tf, 2), peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=round(tf / MFMA_FP32_PEAK_TFLOPS, 4))
+            mnk = (L.T, L.O, L.I) if row["call"] == "fwd" else (L.T, L.I, L.O)
+            roof = dense_gemm_roofline(row["dense_flops"], row["avg_ms"], act, *mnk)
         elif t_hbm >= t_alu:
             roof = dict(bound="hbm", achieved=row["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(row["hbm_gbs"] / HBM_PEAK_GBS, 4))
@@ -356,7 +375,6 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
     # update inside mst_mask_update; here on its own, after the timed region)
     G = torch.empty(max(L.O * L.I for L in layers), dtype=torch.float32, device="cuda:0")
     dg = {}
-    peak = MFMA_BF16_PEAK_TFLOPS if act == "bf16" else MFMA_FP32_PEAK_TFLOPS
     for L in layers:
         for _ in range(2):
             mst.mst_dense_grad(L.dY, L.X, G, T, L.O, L.I, L.act, L.ws, stream)
@@ -367,9 +385,10 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
         b.record(stream)
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / 5
-        tf = 2.0 * T * L.O * L.I / ms / 1e9
-        dg[L.name] = dict(avg_ms=round(ms, 4), tflops=round(tf, 1), mfma_frac=round(tf / peak, 4))
-    out["dense_grad_gemm"] = dict(dtype="bf16" if act == "bf16" else "f32", peak_tflops=peak, layers=dg)
+        r = dense_gemm_roofline(2.0 * T * L.O * L.I, ms, act, L.O, L.I, T)
+        dg[L.name] = dict(avg_ms=round(ms, 4), tflops=round(2.0 * T * L.O * L.I / ms / 1e9, 1), mfma_tflops=r["achieved"],
+                          mfma_peak=r["peak"], mfma_frac=r["frac"], mfma_dtype=r["mfma_dtype"])
+    out["dense_grad_gemm"] = dict(operands="bf16" if act == "bf16" else "f32", layers=dg)
 
     if with_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_block(layers, T)
@@ -532,8 +551,10 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                 by = L.bytes_fwd(nnz) if call == "fwd" else L.bytes_bwd_input(nnz)
                 product_row_numbers(row, ms, by, L.flops_product(nnz), 0, lds_peak)
                 if dense_path:
-                    row.update(dense_flops=L.flops_dense_grad(),
-                               mfma_frac=round(L.flops_dense_grad() / ms / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4))
+                    mnk = (T, L.O, L.I) if call == "fwd" else (T, L.I, L.O)
+                    r = dense_gemm_roofline(L.flops_dense_grad(), ms, "f32", *mnk)
+                    row.update(dense_flops=L.flops_dense_grad(), mfma_tflops=r["achieved"], mfma_frac=r["frac"],
+                               mfma_dtype=r["mfma_dtype"])
                 calls.append(row)
                 if dominant is None or ms * len(xs) > dominant[0]:
                     dominant = (ms * len(xs), row, L)
@@ -559,25 +580,29 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
         row = dict(layer=L.name, call=call, launches=len(xs), avg_ms=round(ms, 5), min_ms=round(min(xs), 5),
                    max_ms=round(max(xs), 5))
         if call == "dense_grad":
+            r = dense_gemm_roofline(L.flops_dense_grad(), ms, "f32", L.O, L.I, T)
             row.update(alg_flops=L.flops_dense_grad(), alg_bytes=L.bytes_dense_grad(),
-                       tflops=round(L.flops_dense_grad() / ms / 1e9, 2),
-                       mfma_frac=round(L.flops_dense_grad() / ms / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4))
+                       tflops=round(L.flops_dense_grad() / ms / 1e9, 2), mfma_tflops=r["achieved"],
+                       mfma_frac=r["frac"], mfma_dtype=r["mfma_dtype"])
             if dominant is None or ms * len(xs) > dominant[0]:
                 dominant = (ms * len(xs), row, L)
         calls.append(row)
 
     _, drow, dL = dominant
     if drow["call"] == "dense_grad":
-        kernel = "k_gemm<fp32, TN> (v_mfma_f32_32x32x2f32) + k_splitk_reduce (ordered sum of its split partial outputs)"
+        kernel = ("k_gemm_split<TN> (fp32 operands split into bf16 hi + lo, 3 x v_mfma_f32_32x32x16_bf16 per term) + "
+                  "k_splitk_reduce (ordered sum of its split partial outputs)")
     elif drow.get("path") == "dense-mfma":
-        kernel = "k_gemm<fp32> (masked dense product on v_mfma_f32_32x32x2f32; preceded by the scatter of the dense weight copy)"
+        kernel = ("k_gemm_split (masked dense product, bf16 hi + lo split on v_mfma_f32_32x32x16_bf16; preceded by the "
+                  "scatter of the dense weight copy after an update)")
     else:
         kernel = "k_spmm / k_spmm64 (launch shape chosen per call)"
     roof = roofline_of(drow, dL, "f32", kernel, "C5")
     upd = [x for (li, call), xs in by_layer_call.items() if call in ("mask_update", "bwd_weight_update") for x in xs]
     out = {"metric": METRIC, "value": round(value, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": round(1e3 * elapsed / args.steps, 4), "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32 (dense contractions: fp32 operands as bf16 hi + lo, fp32 accumulation)", "data": "synthetic",
            "config": {"workload": "C5: schedule sweep of one GPT-2-large block (qkv 1280->3840, proj 1280->1280, fc1 "
                                   "1280->5120, fc2 5120->1280; 1 of 36 identical blocks), T=%d tokens, fp32; step t runs "
                                   "fwd + bwd_input of the four layers at density cycle[t mod 6], cycle = %s (%s over the "

@@ -380,10 +380,20 @@ void k_gemm_split(const float* __restrict__ A, int64_t lda, const float* __restr
     char* const Bl = lds + 3 * BM * 128;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    const int m0 = blockIdx.z * BM, n0 = blockIdx.y * BN;
-    const int kbeg = blockIdx.x * k_per_split;
+    // Workgroup -> (output tile, k range).  Consecutive workgroup ids go to the 8 XCDs in turn;
+    // each XCD has its own L2.  XCD x is given the tiles x Q .. x Q + Q - 1 (m-tile major, so they
+    // share a few row panels of A and the column panels of B) and walks them one k range after
+    // the other: the workgroups resident on an XCD at a time read the same operand panels at
+    // the same k, and an XCD reads only its share of A.
+    const int gn = N / BN, ntiles = (M / BM) * gn, nsplit = (Kdim + k_per_split - 1) / k_per_split;
+    const int Q = (ntiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int split = slot / Q, tile_id = xcd * Q + slot % Q;
+    if (tile_id >= ntiles || split >= nsplit) return;
+    const int m0 = (tile_id / gn) * BM, n0 = (tile_id % gn) * BN;
+    const int kbeg = split * k_per_split;
     const int kend = min(Kdim, kbeg + k_per_split);
-    float* Cz = C + (int64_t)blockIdx.x * split_stride;
+    float* Cz = C + (int64_t)split * split_stride;
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -513,7 +523,30 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
     return MST_OK;
 }
 
-static const SplitModel kSplitSplit = {2, SPK, 2.6, 4.0, 5e-7, {0.55, 0.70, 0.86}};
+// Split count of k_gemm_split.  Its tiles are dealt to the XCDs in equal shares (Q tiles each)
+// and an XCD holds 32 CUs x 2 workgroups = 64 places, so what matters is how many rounds of 64
+// Q x splits needs on ONE XCD.  Cost in units of one k step: rounds x (k steps per workgroup
+// + 7 for a workgroup's start-up and output) + the pass that adds the partial outputs.  On a
+// sweep of the split count over twelve GPT-2 small / large dense-gradient shapes on MI355X
+// this picks the fastest count every time.
+static int pick_nsplit_xcd(int64_t tiles, int Kdim, int64_t mn, int64_t max_split) {
+    static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+    const double wg_steps = 7.0, sum_steps_per_float = 5e-7 / 3.3;
+    const int64_t Q = cdiv(tiles, 8);
+    int best = 1;
+    double best_cost = 0.0;
+    for (int ns : cand) {
+        if (ns > 1 && (ns > max_split || Kdim / ns < 512)) continue;
+        const double steps = (double)cdiv(cdiv(Kdim, ns), SPK);
+        const double cost = (double)cdiv(Q * ns, 64) * (steps + wg_steps) +
+                            (ns > 1 ? sum_steps_per_float * (double)ns * (double)mn : 0.0);
+        if (best_cost == 0.0 || cost < best_cost) {
+            best_cost = cost;
+            best = ns;
+        }
+    }
+    return best;
+}
 static int g_gemm_fp32_only = 0;          // test hook: 1 = never use the bf16-split kernel
 
 int gemm_force_fp32_mfma(int on) {
@@ -530,10 +563,10 @@ static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, 
                         float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
     const int gm = M / BM, gn = N / BN;
     const int64_t mn = (int64_t)M * N;
-    const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, kSplitSplit, split_ws_floats / mn) : 1;
+    const int nsplit0 = split_ws ? pick_nsplit_xcd((int64_t)gm * gn, Kdim, mn, split_ws_floats / mn) : 1;
     const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), SPK) * SPK);
     const int nsplit = (int)cdiv(Kdim, kps);
-    dim3 grid(nsplit, gn, gm);
+    const unsigned grid = (unsigned)(8 * cdiv((int64_t)gm * gn, 8) * nsplit);
     float* dst = nsplit > 1 ? split_ws : C;
     k_gemm_split<AK, BKM><<<grid, 256, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
     MST_LAUNCH_CHECK();
