@@ -116,11 +116,16 @@ Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
 
 // ------------------------------------------------------------------ kernels
 
-// one block per row r of the mask: active count per chunk of columns and per row
-__global__ void k_count_row(const uint8_t* __restrict__ mask, int I, int nchunk, int Rpad,
+// one block per row r of the mask: active count per chunk of columns and per row; blocks past
+// the last row (the padding rows of the view) write zero counts
+__global__ void k_count_row(const uint8_t* __restrict__ mask, int O, int I, int nchunk, int Rpad,
                             int* __restrict__ segcnt, int* __restrict__ rowcnt) {
     extern __shared__ int cnt[];   // [nchunk]
     const int r = blockIdx.x;
+    if (r >= O) {
+        for (int c = threadIdx.x; c < nchunk; c += blockDim.x) segcnt[(size_t)c * Rpad + r] = 0;
+        return;
+    }
     for (int c = threadIdx.x; c < nchunk; c += blockDim.x) cnt[c] = 0;
     __syncthreads();
     const uint8_t* m = mask + (size_t)r * I;
@@ -171,7 +176,8 @@ __global__ __launch_bounds__(256) void k_count_col(const uint8_t* __restrict__ m
     for (int k = 0; k < 32; ++k) n += m[(32 * rg + k) * MT_LD + j] != 0;
     part[rg][j] = n;
     __syncthreads();
-    if (rg == 0 && i0 + j < I) segcnt[(size_t)c * Rpad + i0 + j] = part[0][j] + part[1][j] + part[2][j] + part[3][j];
+    // (columns past the matrix read as empty: the padding rows of the view get zero counts)
+    if (rg == 0 && i0 + j < Rpad) segcnt[(size_t)c * Rpad + i0 + j] = part[0][j] + part[1][j] + part[2][j] + part[3][j];
 }
 
 // 16 lanes per row block (lane j = row j): order its 16 rows by total length over all
@@ -224,10 +230,8 @@ __global__ __launch_bounds__(256) void k_block_rank(const int* __restrict__ segc
 
 // pairs of one quad segment: longest of its four rows (a spread row: a quarter of it),
 // rounded up to even, halved
-__global__ void k_quad_len(const int* __restrict__ segcnt, const int* __restrict__ rowmap, int Rpad, int NBpad,
-                           int64_t nseg, int* __restrict__ qlen) {
-    const int64_t sidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (c*NBpad + b)*4 + q
-    if (sidx >= nseg) return;
+__device__ inline int quad_pairs(const int* __restrict__ segcnt, const int* __restrict__ rowmap, int Rpad, int NBpad,
+                                 int64_t sidx) {
     const int q = (int)(sidx & 3);
     const int64_t cb = sidx >> 2;
     const int b = (int)(cb % NBpad);
@@ -237,24 +241,23 @@ __global__ void k_quad_len(const int* __restrict__ segcnt, const int* __restrict
     int L;
     if (rm[0] & SPREAD_FLAG) L = (cnt[rm[0] & ~SPREAD_FLAG] + 3) >> 2;
     else L = max(max(cnt[rm[0]], cnt[rm[1]]), max(cnt[rm[2]], cnt[rm[3]]));
-    qlen[sidx] = (L + 1) >> 1;
+    return (L + 1) >> 1;
 }
 
-// single-block exclusive scan: out[j] = sum_{j' < j} in[j'], out[n] = total; a thread takes 8
-// consecutive elements per round (in == out is allowed)
-__global__ __launch_bounds__(1024) void k_scan_excl(const int* in, int* out, int64_t n) {
+// exclusive scan by ONE block of 1024 threads: out[j] = sum_{j' < j} f(j'), out[n] = total; a thread
+// takes 8 consecutive elements per round
+template <typename F>
+__device__ inline void block_scan_excl(F f, int* __restrict__ out, int64_t n, int* wsum, int* carry_s) {
     constexpr int PER = 8;
-    __shared__ int wsum[16];
-    __shared__ int carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) carry_s = 0;
+    if (tid == 0) *carry_s = 0;
     __syncthreads();
     for (int64_t base = 0; base < n; base += (int64_t)blockDim.x * PER) {
         const int64_t j0 = base + (int64_t)tid * PER;
         int v[PER], tot = 0;
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
-            v[u] = (j0 + u < n) ? in[j0 + u] : 0;
+            v[u] = (j0 + u < n) ? f(j0 + u) : 0;
             tot += v[u];
         }
         int x = tot;                                 // inclusive scan of the threads' totals inside the wave
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(1024) void k_scan_excl(const int* in, int* out, int
         __syncthreads();
         int woff = 0;
         for (int w = 0; w < wave; ++w) woff += wsum[w];
-        const int carry = carry_s;
+        const int carry = *carry_s;
         int run = carry + woff + x - tot;
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
@@ -274,21 +277,62 @@ __global__ __launch_bounds__(1024) void k_scan_excl(const int* in, int* out, int
             run += v[u];
         }
         __syncthreads();
-        if (tid == (int)blockDim.x - 1) carry_s = run;
+        if (tid == (int)blockDim.x - 1) *carry_s = run;
         __syncthreads();
     }
-    if (tid == 0) out[n] = carry_s;
+    if (tid == 0) out[n] = *carry_s;
 }
 
-// every pair up to the readable tail starts as padding: zero weight, offset 0, perm -1
-__global__ void k_clear_view(const int* __restrict__ ptr, int64_t nseg, uint4* __restrict__ ent,
-                             int* __restrict__ perm) {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // uint4 index
-    const int64_t n = ((int64_t)ptr[nseg] + PAIR_TAIL) * 4;
-    if (e >= n) return;
-    ent[e] = make_uint4(0u, 0u, 0u, 0u);
-    perm[2 * e] = -1;
-    perm[2 * e + 1] = -1;
+__global__ __launch_bounds__(1024) void k_scan_excl(const int* in, int* out, int64_t n) {
+    __shared__ int wsum[16];
+    __shared__ int carry_s;
+    block_scan_excl([=](int64_t j) { return in[j]; }, out, n, wsum, &carry_s);
+}
+
+// One block does what follows the ranking of a view's rows: (row view only) the canonical row
+// pointers from the per-row counts; the first pair of every quad segment (exclusive scan of
+// the segments' pair counts, formed on the fly); the view's cost for the weight gradient --
+// a workgroup of the SDDMM owns about 16 consecutive row blocks and waits at every chunk for
+// its longest wavefront, so a view costs the sum over (chunk, group of 16 blocks) of the
+// most pairs of a block -- and, when the other view's cost is known (`choice` not null), the
+// view that drives the weight gradient: the one with the clearly smaller cost, else the one
+// with more rows.
+__global__ __launch_bounds__(1024) void k_view_ptr(const int* __restrict__ rowcnt, int* __restrict__ rowptr, int nrows,
+                                                   const int* __restrict__ segcnt, const int* __restrict__ rowmap,
+                                                   int Rpad, int NBpad, int NB, int nchunk, int64_t nseg,
+                                                   int* __restrict__ ptr, unsigned long long* __restrict__ cost_mine,
+                                                   const unsigned long long* __restrict__ cost_row, int prefer_col,
+                                                   int* __restrict__ choice) {
+    __shared__ int wsum[16];
+    __shared__ int carry_s;
+    __shared__ unsigned long long cost_s;
+    if (rowcnt) block_scan_excl([=](int64_t j) { return rowcnt[j]; }, rowptr, nrows, wsum, &carry_s);
+    block_scan_excl([=](int64_t j) { return quad_pairs(segcnt, rowmap, Rpad, NBpad, j); }, ptr, nseg, wsum, &carry_s);
+    if (threadIdx.x == 0) cost_s = 0ull;
+    __syncthreads();                                  // ptr[] written by this block is visible to it
+    const int ngroup = (NB + 15) / 16;
+    unsigned long long mine = 0ull;
+    for (int idx = threadIdx.x; idx < nchunk * ngroup; idx += blockDim.x) {
+        const int c = idx / ngroup, grp = idx % ngroup;
+        int worst = 0;
+        for (int b = grp * 16; b < min(NB, grp * 16 + 16); ++b) {
+            const int64_t sidx = ((int64_t)c * NBpad + b) * 4;
+            worst = max(worst, ptr[sidx + 4] - ptr[sidx]);
+        }
+        mine += (unsigned long long)worst;
+    }
+    if (mine) atomicAdd(&cost_s, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        *cost_mine = cost_s;
+        if (choice) {
+            const unsigned long long pr = *cost_row, pc = cost_s;
+            int ch = prefer_col;
+            if (prefer_col && pr * 10 < pc * 9) ch = 0;
+            if (!prefer_col && pc * 10 < pr * 9) ch = 1;
+            *choice = ch;
+        }
+    }
 }
 
 // entry slot (as index into ent viewed as uint2[], and into perm) of step j of a row
@@ -296,25 +340,43 @@ __device__ inline int64_t entry_slot(int pair0, int g, int j) {
     return (((int64_t)pair0 + (j >> 1)) * 4 + g) * 2 + (j & 1);
 }
 
-// one wavefront per row: ordered compaction of the row into canonical arrays and the row view
+// Slots of a row's lane group (of the whole quad for a spread row) past its `run` entries, up
+// to the quad's length: zero-weight padding (offset 0, perm -1).  The three empty rows that
+// share a spread quad own no slots.  `lanes` threads of the caller share the work.
+__device__ inline void pad_row_slots(uint2* __restrict__ ent, int* __restrict__ perm, int pair0, int npairs, int g,
+                                     bool spread, int run, int lane, int lanes) {
+    const int total = spread ? 8 * npairs : 2 * npairs;
+    for (int j = run + lane; j < total; j += lanes) {
+        const int64_t e = spread ? entry_slot(pair0, j & 3, j >> 2) : entry_slot(pair0, g, j);
+        ent[e] = make_uint2(0u, 0u);
+        perm[e] = -1;
+    }
+}
+
+// one wavefront per row (incl. the padding rows of the last block, which only pad): ordered
+// compaction of the row into canonical arrays and the row view
 __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __restrict__ W,
-                           int O, int I, int nchunk, int NBpad,
+                           int O, int I, int nchunk, int NBpad, int NB,
                            const int* __restrict__ rowptr, const int* __restrict__ ptr,
-                           const int* __restrict__ rowpos,
+                           const int* __restrict__ rowpos, const int* __restrict__ rowmap,
                            float* __restrict__ vals, int* __restrict__ flat, int* __restrict__ cidx,
                            uint2* __restrict__ ent, int* __restrict__ perm) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (r >= O) return;
+    if (r >= NB * RB) return;
     const int b = r / RB, rp = rowpos[r], rank = rp & ~SPREAD_FLAG, g = rank & 3, q = rank >> 2;
     const bool spread = (rp & SPREAD_FLAG) != 0;
+    // an empty row placed in a spread quad: the quad's slots belong to the spread row
+    const bool guest = !spread && (rowmap[b * RB + 4 * q] & SPREAD_FLAG) != 0;
+    const bool real = r < O;
     const uint8_t* m = mask + (size_t)r * I;
     const float* w = W + (size_t)r * I;
-    int canon = rowptr[r];
+    int canon = real ? rowptr[r] : 0;
     for (int c = 0; c < nchunk; ++c) {
-        const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
+        const size_t seg = ((size_t)c * NBpad + b) * 4 + q;
+        const int pair0 = ptr[seg], npairs = ptr[seg + 1] - pair0;
         int run = 0;
-        const int i1 = min(I, (c + 1) * KC);
+        const int i1 = real ? min(I, (c + 1) * KC) : 0;
         for (int i0 = c * KC; i0 < i1; i0 += 64) {
             const int i = i0 + lane;
             const bool on = i < i1 && m[i] != 0;
@@ -333,6 +395,7 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
             run += __popcll(bal);
         }
         canon += run;
+        if (!guest) pad_row_slots(ent, perm, pair0, npairs, g, spread, run, lane, 64);
     }
 }
 
@@ -341,8 +404,9 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
 // counts of the row groups before it give the position of its first entry in the column's
 // list, then it writes its entries in row order.
 __global__ __launch_bounds__(256) void k_fill_col(const uint8_t* __restrict__ mask, const float* __restrict__ W,
-                                                  int O, int I, int NBpad, const int* __restrict__ ptr,
-                                                  const int* __restrict__ rowpos, const int* __restrict__ cidx,
+                                                  int O, int I, int NBpad, int NB, const int* __restrict__ ptr,
+                                                  const int* __restrict__ rowpos, const int* __restrict__ rowmap,
+                                                  const int* __restrict__ cidx,
                                                   uint2* __restrict__ ent, int* __restrict__ perm) {
     __shared__ __attribute__((aligned(16))) uint8_t m[KC * MT_LD];
     __shared__ int part[4][MT_COLS];
@@ -356,21 +420,27 @@ __global__ __launch_bounds__(256) void k_fill_col(const uint8_t* __restrict__ ma
     for (int k = 0; k < 32; ++k) n += m[(32 * rg + k) * MT_LD + j] != 0;
     part[rg][j] = n;
     __syncthreads();
-    if (i >= I || n == 0) return;
+    if (i >= NB * RB) return;                         // (columns past the matrix only pad)
     int jj = 0;
     for (int r = 0; r < rg; ++r) jj += part[r][j];
     const int b = i / RB, rp = rowpos[i], rank = rp & ~SPREAD_FLAG, g = rank & 3, q = rank >> 2;
     const bool spread = (rp & SPREAD_FLAG) != 0;
-    const int pair0 = ptr[((size_t)c * NBpad + b) * 4 + q];
-    for (int k = 0; k < 32; ++k) {
-        const int ol = 32 * rg + k;
-        if (!m[ol * MT_LD + j]) continue;
-        const size_t f = (size_t)(o0 + ol) * I + i;
-        const int64_t e = spread ? entry_slot(pair0, jj & 3, jj >> 2) : entry_slot(pair0, g, jj);
-        ent[e] = make_uint2(lds_off((uint32_t)ol), __float_as_uint(W[f]));
-        perm[e] = cidx[f];
-        ++jj;
+    const bool guest = !spread && (rowmap[b * RB + 4 * q] & SPREAD_FLAG) != 0;
+    const size_t seg = ((size_t)c * NBpad + b) * 4 + q;
+    const int pair0 = ptr[seg], npairs = ptr[seg + 1] - pair0;
+    if (n > 0) {
+        for (int k = 0; k < 32; ++k) {
+            const int ol = 32 * rg + k;
+            if (!m[ol * MT_LD + j]) continue;
+            const size_t f = (size_t)(o0 + ol) * I + i;
+            const int64_t e = spread ? entry_slot(pair0, jj & 3, jj >> 2) : entry_slot(pair0, g, jj);
+            ent[e] = make_uint2(lds_off((uint32_t)ol), __float_as_uint(W[f]));
+            perm[e] = cidx[f];
+            ++jj;
+        }
     }
+    // the thread of the last row group knows the column's whole count in this chunk: it pads
+    if (rg == 3 && !guest) pad_row_slots(ent, perm, pair0, npairs, g, spread, jj, 0, 1);
 }
 
 // Both views in one launch: the first `row_blocks` blocks refresh the row view's entries,
@@ -424,34 +494,34 @@ int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s) {
     return MST_OK;
 }
 
+// One view: count per (row, chunk) -> ranking of every block's rows -> pointers of the quad
+// segments (with the view's cost for the weight gradient and, for the second view, the choice
+// of the driving view) -> ordered compaction.  Four launches; nothing is cleared beforehand:
+// the count kernels write the padding rows' zero counts and the fill kernels their own padding.
 static int build_one_view(View& v, bool row_view, const mst_layer* L, const float* Wsrc,
-                          const Workspace& ws, hipStream_t s) {
+                          const Workspace& ws, unsigned long long* cost, hipStream_t s) {
     const int O = L->O, I = L->I;
     const int Rpad = v.NBpad * RB;
-    int rc = fill_u32(ws.segcnt, 0u, (int64_t)v.nchunk * Rpad + 1, s);      // rows >= R count as empty
-    if (rc != MST_OK) return rc;
-    dim3 gcol((unsigned)cdiv(I, 64), (unsigned)v.nchunk);
     if (row_view) {
-        k_count_row<<<O, 256, (size_t)v.nchunk * 4, s>>>(L->mask, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
-        MST_LAUNCH_CHECK();
-        if ((rc = scan_excl_i32(ws.rowcnt, L->rowptr, O, s)) != MST_OK) return rc;
+        k_count_row<<<Rpad, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
     } else {
-        k_count_col<<<gcol, 256, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
-        MST_LAUNCH_CHECK();
+        dim3 gcnt((unsigned)cdiv(Rpad, 64), (unsigned)v.nchunk);
+        k_count_col<<<gcnt, 256, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
     }
+    MST_LAUNCH_CHECK();
     k_block_rank<<<(unsigned)cdiv(v.NBpad, 16), 256, 0, s>>>(ws.segcnt, v.nchunk, Rpad, v.NBpad, v.rowmap, v.rowpos);
     MST_LAUNCH_CHECK();
-    k_quad_len<<<(unsigned)cdiv(v.nseg, 256), 256, 0, s>>>(ws.segcnt, v.rowmap, Rpad, v.NBpad, v.nseg, ws.qlen);
-    MST_LAUNCH_CHECK();
-    if ((rc = scan_excl_i32(ws.qlen, v.ptr, v.nseg, s)) != MST_OK) return rc;
-    k_clear_view<<<(unsigned)cdiv(v.cap_pairs * 4, 256), 256, 0, s>>>(v.ptr, v.nseg, v.ent, v.perm);
+    k_view_ptr<<<1, 1024, 0, s>>>(row_view ? ws.rowcnt : nullptr, L->rowptr, O, ws.segcnt, v.rowmap, Rpad, v.NBpad, v.NB,
+                                  v.nchunk, v.nseg, v.ptr, cost + (row_view ? 0 : 1), cost, L->I > L->O ? 1 : 0,
+                                  row_view ? nullptr : L->sddmm_view);
     MST_LAUNCH_CHECK();
     if (row_view) {
-        k_fill_row<<<(unsigned)cdiv(O, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.NBpad, L->rowptr, v.ptr,
-                                                        v.rowpos, L->vals, L->flat, ws.cidx,
-                                                        reinterpret_cast<uint2*>(v.ent), v.perm);
+        k_fill_row<<<(unsigned)cdiv(v.NB * RB, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.NBpad, v.NB, L->rowptr, v.ptr,
+                                                              v.rowpos, v.rowmap, L->vals, L->flat, ws.cidx,
+                                                              reinterpret_cast<uint2*>(v.ent), v.perm);
     } else {
-        k_fill_col<<<gcol, 256, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.ptr, v.rowpos, ws.cidx,
+        dim3 gcol((unsigned)cdiv(v.NB * RB, 64), (unsigned)v.nchunk);
+        k_fill_col<<<gcol, 256, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.NB, v.ptr, v.rowpos, v.rowmap, ws.cidx,
                                         reinterpret_cast<uint2*>(v.ent), v.perm);
     }
     MST_LAUNCH_CHECK();
@@ -459,49 +529,15 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
 }
 
 // Rebuilds vals / flat / rowptr and both views from the layer's mask and a dense weight
-// array.  The col view needs the canonical indices the row view pass writes to ws.cidx.
-// The weight gradient can walk either view.  A workgroup of the SDDMM owns about 16
-// consecutive row blocks and waits at every chunk for its longest wavefront, so the time of
-// a view goes with  sum over (chunk, group of 16 blocks) of the most pairs of a block  --
-// with uneven row lengths far more than its pairs / 16.  The view with the clearly smaller
-// sum drives the product, else the one with more rows.
-__global__ void k_view_cost(const int* __restrict__ ptr, int nchunk, int NBpad, int NB,
-                            unsigned long long* __restrict__ cost) {
-    const int ngroup = (NB + 15) / 16;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (int64_t)nchunk * ngroup) return;
-    const int c = (int)(idx / ngroup), grp = (int)(idx % ngroup);
-    int worst = 0;
-    for (int b = grp * 16; b < min(NB, grp * 16 + 16); ++b) {
-        const int64_t sidx = ((int64_t)c * NBpad + b) * 4;
-        worst = max(worst, ptr[sidx + 4] - ptr[sidx]);
-    }
-    if (worst) atomicAdd(cost, (unsigned long long)worst);
-}
-
-__global__ void k_choose_view(const unsigned long long* __restrict__ cost, int prefer_col, int* __restrict__ choice) {
-    const unsigned long long pr = cost[0], pc = cost[1];
-    int c = prefer_col;
-    if (prefer_col && pr * 10 < pc * 9) c = 0;
-    if (!prefer_col && pc * 10 < pr * 9) c = 1;
-    *choice = c;
-}
-
+// array (read at the active positions only).  The col view needs the canonical indices the
+// row view pass writes to ws.cidx; its pointer kernel also names the view that drives the
+// weight gradient (either can: the product is symmetric in its dense operands).
 int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s) {
-    int rc = build_one_view(L->row, true, L, Wsrc, ws, s);
-    if (rc != MST_OK) return rc;
-    rc = build_one_view(L->col, false, L, Wsrc, ws, s);
-    if (rc != MST_OK) return rc;
     unsigned long long* cost = reinterpret_cast<unsigned long long*>(ws.sel_state);
-    if ((rc = fill_u32(cost, 0u, 4, s)) != MST_OK) return rc;
-    for (int me = 0; me < 2; ++me) {
-        const View& v = me ? L->col : L->row;
-        const int64_t n = (int64_t)v.nchunk * cdiv(v.NB, 16);
-        k_view_cost<<<(unsigned)cdiv(n, 256), 256, 0, s>>>(v.ptr, v.nchunk, v.NBpad, v.NB, cost + me);
-        MST_LAUNCH_CHECK();
-    }
-    k_choose_view<<<1, 1, 0, s>>>(cost, L->I > L->O ? 1 : 0, L->sddmm_view);
-    MST_LAUNCH_CHECK();
+    int rc = build_one_view(L->row, true, L, Wsrc, ws, cost, s);
+    if (rc != MST_OK) return rc;
+    rc = build_one_view(L->col, false, L, Wsrc, ws, cost, s);
+    if (rc != MST_OK) return rc;
     L->Wd_valid = false;
     return MST_OK;
 }
@@ -578,7 +614,7 @@ int mst_layer_load_dense(mst_layer_t* L, const float* W_dev, const uint8_t* M_de
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     // learn the active count first so that nothing is written when it does not fit
-    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(M_dev, L->I, L->row.nchunk, 0, nullptr, ws.rowcnt);
+    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(M_dev, L->O, L->I, L->row.nchunk, 0, nullptr, ws.rowcnt);
     MST_LAUNCH_CHECK();
     int rcs = scan_excl_i32(ws.rowcnt, L->rowptr, L->O, s);          // rebuilt below anyway
     if (rcs != MST_OK) return rcs;
