@@ -112,7 +112,7 @@ struct Workspace {
     int* segcnt = nullptr;     // active count per (chunk, row) of the view being built
     int* qlen = nullptr;       // pairs per quad segment of the view being built
     int* rowcnt = nullptr;     // [O + 1]
-    uint32_t* blk = nullptr;   // [select_blocks(N) + 1] per-block tie counts
+    uint32_t* blk = nullptr;   // per-block tie counts: [blocks(N) + 1] of the growth selections, then [blocks(cap) + 1] of the prune selection
     uint64_t* sel_state = nullptr;   // [SEL_STATES][SEL_STATE_WORDS] radix-select state + histogram
     float* gemm = nullptr;     // [GEMM_WS_SPLITS * N] split-k partial outputs of the dense GEMM
     size_t gemm_floats = 0;
@@ -126,7 +126,7 @@ constexpr int GEMM_WS_SPLITS = 8;
 constexpr int SELECT_BLOCK = 2048;   // elements per block in the ordered tie pass
 constexpr int SEL_DIGIT_BITS = 8;                        // radix-select digit
 constexpr int SEL_BINS = 1 << SEL_DIGIT_BITS;
-constexpr int SEL_STATE_WORDS = 8 + SEL_BINS / 2;        // one selection: 8 control words + the histogram
+constexpr int SEL_STATE_WORDS = 8 + 4096 / 2;            // one selection: 8 control words + up to 4096 uint32 histogram bins
 constexpr int SEL_STATES = 3;                            // prune, gradient growth, random growth
 
 int64_t view_pair_capacity(int64_t cap, int64_t nchunk, int64_t R);

@@ -103,7 +103,7 @@ Workspace carve_workspace(void* base, int O, int I, int64_t cap, int T) {
     w.segcnt = (int*)take((size_t)(std::max(cnt_r, cnt_c) + 1) * 4);
     w.qlen = (int*)take((size_t)(std::max(nseg_r, nseg_c) + 1) * 4);
     w.rowcnt = (int*)take((size_t)(O + 1) * 4);
-    w.blk = (uint32_t*)take((size_t)(cdiv(N, SELECT_BLOCK) + 2) * 4);
+    w.blk = (uint32_t*)take((size_t)(cdiv(N, SELECT_BLOCK) + cdiv(cap > 0 ? cap : 1, SELECT_BLOCK) + 4) * 4);
     w.sel_state = (uint64_t*)take((size_t)SEL_STATES * SEL_STATE_WORDS * 8);
     w.gemm_floats = (size_t)GEMM_WS_SPLITS * (size_t)N;
     w.gemm = (float*)take(w.gemm_floats * 4);
@@ -244,70 +244,71 @@ __device__ inline int quad_pairs(const int* __restrict__ segcnt, const int* __re
     return (L + 1) >> 1;
 }
 
-// exclusive scan by ONE block of 1024 threads: out[j] = sum_{j' < j} f(j'), out[n] = total; a thread
-// takes 8 consecutive elements per round
-template <typename F>
-__device__ inline void block_scan_excl(F f, int* __restrict__ out, int64_t n, int* wsum, int* carry_s) {
-    constexpr int PER = 8;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) *carry_s = 0;
+__global__ void k_quad_len(const int* __restrict__ segcnt, const int* __restrict__ rowmap, int Rpad, int NBpad,
+                           int64_t nseg, int* __restrict__ qlen) {
+    const int64_t sidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (c*NBpad + b)*4 + q
+    if (sidx < nseg) qlen[sidx] = quad_pairs(segcnt, rowmap, Rpad, NBpad, sidx);
+}
+
+// exclusive scan by ONE block of 1024 threads: out[j] = sum_{j' < j} in[j'], out[n] = total (in == out
+// is allowed).  Each of the 16 wavefronts owns one contiguous segment and reads it with its 64
+// lanes side by side (coalesced, several rows of 64 in flight): first the segment's sum, then,
+// with the sums of the segments before it as carry, the running values (a 64-lane scan per row).
+__device__ inline void block_scan_excl(const int* in, int* out, int64_t n, int* wsum) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
+    const int64_t rows = (n + 63) / 64;                            // rows of 64 elements
+    const int64_t rpw = (rows + nwave - 1) / nwave;                // rows per wavefront
+    const int64_t r0 = (int64_t)wave * rpw, r1 = min(rows, r0 + rpw);
+    int tot = 0;
+#pragma unroll 4
+    for (int64_t r = r0; r < r1; ++r) {
+        const int64_t j = r * 64 + lane;
+        tot += (j < n) ? in[j] : 0;
+    }
+    for (int d = 32; d >= 1; d >>= 1) tot += __shfl_xor(tot, d, 64);
+    __syncthreads();                                 // wsum free again (an earlier scan of this block may still read it)
+    if (lane == 0) wsum[wave] = tot;
     __syncthreads();
-    for (int64_t base = 0; base < n; base += (int64_t)blockDim.x * PER) {
-        const int64_t j0 = base + (int64_t)tid * PER;
-        int v[PER], tot = 0;
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            v[u] = (j0 + u < n) ? f(j0 + u) : 0;
-            tot += v[u];
-        }
-        int x = tot;                                 // inclusive scan of the threads' totals inside the wave
+    int carry = 0;
+    for (int w = 0; w < wave; ++w) carry += wsum[w];
+    int v_next = (r0 < r1 && r0 * 64 + lane < n) ? in[r0 * 64 + lane] : 0;
+    for (int64_t r = r0; r < r1; ++r) {
+        const int64_t j = r * 64 + lane;
+        const int v = v_next;
+        if (r + 1 < r1) v_next = ((r + 1) * 64 + lane < n) ? in[(r + 1) * 64 + lane] : 0;   // read before the row is written: in may be out
+        int x = v;
         for (int d = 1; d < 64; d <<= 1) {
-            int y = __shfl_up(x, d, 64);
+            const int y = __shfl_up(x, d, 64);
             if (lane >= d) x += y;
         }
-        if (lane == 63) wsum[wave] = x;
-        __syncthreads();
-        int woff = 0;
-        for (int w = 0; w < wave; ++w) woff += wsum[w];
-        const int carry = *carry_s;
-        int run = carry + woff + x - tot;
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            if (j0 + u < n) out[j0 + u] = run;
-            run += v[u];
-        }
-        __syncthreads();
-        if (tid == (int)blockDim.x - 1) *carry_s = run;
-        __syncthreads();
+        if (j < n) out[j] = carry + x - v;
+        carry += __shfl(x, 63, 64);
     }
-    if (tid == 0) out[n] = *carry_s;
+    if (wave == nwave - 1 && lane == 0) out[n] = carry;            // the last segment ends at n (or is empty): the total
 }
 
 __global__ __launch_bounds__(1024) void k_scan_excl(const int* in, int* out, int64_t n) {
     __shared__ int wsum[16];
-    __shared__ int carry_s;
-    block_scan_excl([=](int64_t j) { return in[j]; }, out, n, wsum, &carry_s);
+    block_scan_excl(in, out, n, wsum);
 }
 
-// One block does what follows the ranking of a view's rows: (row view only) the canonical row
-// pointers from the per-row counts; the first pair of every quad segment (exclusive scan of
-// the segments' pair counts, formed on the fly); the view's cost for the weight gradient --
-// a workgroup of the SDDMM owns about 16 consecutive row blocks and waits at every chunk for
-// its longest wavefront, so a view costs the sum over (chunk, group of 16 blocks) of the
-// most pairs of a block -- and, when the other view's cost is known (`choice` not null), the
-// view that drives the weight gradient: the one with the clearly smaller cost, else the one
-// with more rows.
+// One block does what follows the segment lengths of a view: (row view only) the canonical row
+// pointers from the per-row counts; the first pair of every quad segment; the view's cost
+// for the weight gradient -- a workgroup of the SDDMM owns about 16 consecutive row blocks and
+// waits at every chunk for its longest wavefront, so a view costs the sum over (chunk, group
+// of 16 blocks) of the most pairs of a block -- and, when the other view's cost is known
+// (`choice` not null), the view that drives the weight gradient: the one with the clearly
+// smaller cost, else the one with more rows.
 __global__ __launch_bounds__(1024) void k_view_ptr(const int* __restrict__ rowcnt, int* __restrict__ rowptr, int nrows,
-                                                   const int* __restrict__ segcnt, const int* __restrict__ rowmap,
-                                                   int Rpad, int NBpad, int NB, int nchunk, int64_t nseg,
-                                                   int* __restrict__ ptr, unsigned long long* __restrict__ cost_mine,
+                                                   const int* __restrict__ qlen, int NBpad, int NB, int nchunk,
+                                                   int64_t nseg, int* __restrict__ ptr,
+                                                   unsigned long long* __restrict__ cost_mine,
                                                    const unsigned long long* __restrict__ cost_row, int prefer_col,
                                                    int* __restrict__ choice) {
     __shared__ int wsum[16];
-    __shared__ int carry_s;
     __shared__ unsigned long long cost_s;
-    if (rowcnt) block_scan_excl([=](int64_t j) { return rowcnt[j]; }, rowptr, nrows, wsum, &carry_s);
-    block_scan_excl([=](int64_t j) { return quad_pairs(segcnt, rowmap, Rpad, NBpad, j); }, ptr, nseg, wsum, &carry_s);
+    if (rowcnt) block_scan_excl(rowcnt, rowptr, nrows, wsum);
+    block_scan_excl(qlen, ptr, nseg, wsum);
     if (threadIdx.x == 0) cost_s = 0ull;
     __syncthreads();                                  // ptr[] written by this block is visible to it
     const int ngroup = (NB + 15) / 16;
@@ -496,7 +497,7 @@ int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s) {
 
 // One view: count per (row, chunk) -> ranking of every block's rows -> pointers of the quad
 // segments (with the view's cost for the weight gradient and, for the second view, the choice
-// of the driving view) -> ordered compaction.  Four launches; nothing is cleared beforehand:
+// of the driving view) -> ordered compaction.  Five launches; nothing is cleared beforehand:
 // the count kernels write the padding rows' zero counts and the fill kernels their own padding.
 static int build_one_view(View& v, bool row_view, const mst_layer* L, const float* Wsrc,
                           const Workspace& ws, unsigned long long* cost, hipStream_t s) {
@@ -511,8 +512,10 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     MST_LAUNCH_CHECK();
     k_block_rank<<<(unsigned)cdiv(v.NBpad, 16), 256, 0, s>>>(ws.segcnt, v.nchunk, Rpad, v.NBpad, v.rowmap, v.rowpos);
     MST_LAUNCH_CHECK();
-    k_view_ptr<<<1, 1024, 0, s>>>(row_view ? ws.rowcnt : nullptr, L->rowptr, O, ws.segcnt, v.rowmap, Rpad, v.NBpad, v.NB,
-                                  v.nchunk, v.nseg, v.ptr, cost + (row_view ? 0 : 1), cost, L->I > L->O ? 1 : 0,
+    k_quad_len<<<(unsigned)cdiv(v.nseg, 256), 256, 0, s>>>(ws.segcnt, v.rowmap, Rpad, v.NBpad, v.nseg, ws.qlen);
+    MST_LAUNCH_CHECK();
+    k_view_ptr<<<1, 1024, 0, s>>>(row_view ? ws.rowcnt : nullptr, L->rowptr, O, ws.qlen, v.NBpad, v.NB, v.nchunk, v.nseg,
+                                  v.ptr, cost + (row_view ? 0 : 1), cost, L->I > L->O ? 1 : 0,
                                   row_view ? nullptr : L->sddmm_view);
     MST_LAUNCH_CHECK();
     if (row_view) {
