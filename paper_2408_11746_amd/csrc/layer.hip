@@ -309,18 +309,34 @@ __global__ __launch_bounds__(1024) void k_view_ptr(const int* __restrict__ rowcn
     __shared__ unsigned long long cost_s;
     if (rowcnt) block_scan_excl(rowcnt, rowptr, nrows, wsum);
     block_scan_excl(qlen, ptr, nseg, wsum);
-    if (threadIdx.x == 0) cost_s = 0ull;
-    __syncthreads();                                  // ptr[] written by this block is visible to it
+    // cost: per (chunk, group of 16 blocks) the most pairs of a block, summed.  Every thread takes
+    // (chunk, block) items side by side and folds them into an LDS table of the groups.
+    constexpr int MAXG = 4096;
+    __shared__ int worst_s[MAXG];
     const int ngroup = (NB + 15) / 16;
+    const int ngrp_all = nchunk * ngroup;
+    if (threadIdx.x == 0) cost_s = 0ull;
+    for (int i = threadIdx.x; i < min(ngrp_all, MAXG); i += blockDim.x) worst_s[i] = 0;
+    __syncthreads();                                  // ptr[] written by this block is visible to it
     unsigned long long mine = 0ull;
-    for (int idx = threadIdx.x; idx < nchunk * ngroup; idx += blockDim.x) {
-        const int c = idx / ngroup, grp = idx % ngroup;
-        int worst = 0;
-        for (int b = grp * 16; b < min(NB, grp * 16 + 16); ++b) {
+    if (ngrp_all <= MAXG) {
+        for (int idx = threadIdx.x; idx < nchunk * NB; idx += blockDim.x) {
+            const int c = idx / NB, b = idx % NB;
             const int64_t sidx = ((int64_t)c * NBpad + b) * 4;
-            worst = max(worst, ptr[sidx + 4] - ptr[sidx]);
+            atomicMax(&worst_s[c * ngroup + (b >> 4)], ptr[sidx + 4] - ptr[sidx]);
         }
-        mine += (unsigned long long)worst;
+        __syncthreads();
+        for (int i = threadIdx.x; i < ngrp_all; i += blockDim.x) mine += (unsigned long long)worst_s[i];
+    } else {
+        for (int idx = threadIdx.x; idx < ngrp_all; idx += blockDim.x) {
+            const int c = idx / ngroup, grp = idx % ngroup;
+            int worst = 0;
+            for (int b = grp * 16; b < min(NB, grp * 16 + 16); ++b) {
+                const int64_t sidx = ((int64_t)c * NBpad + b) * 4;
+                worst = max(worst, ptr[sidx + 4] - ptr[sidx]);
+            }
+            mine += (unsigned long long)worst;
+        }
     }
     if (mine) atomicAdd(&cost_s, mine);
     __syncthreads();
