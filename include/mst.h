@@ -189,9 +189,10 @@ int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront);
  * dense path) run on the bf16 matrix cores when their shapes are whole tiles: each fp32
  * operand element is split into two bfloat16 values (hi + lo, exact to 2^-17) while it is
  * staged, a product is hi*hi + hi*lo + lo*hi with fp32 accumulation; the result differs from
- * an fp32 product by less than 2^-16 per term.  This hook pins the plain fp32 MFMA kernel
- * instead (on != 0) for all later calls of the process; 0 returns to the automatic choice.
- * Test and measurement aid, not thread-safe. */
+ * an fp32 product by less than 2^-16 per term.  This hook pins, for all later calls of the
+ * process: 1 = the plain fp32 MFMA kernel; 128 or 256 = the split kernel with that workgroup
+ * tile (where the shape is a multiple of it); 0 returns to the automatic choice.  Test and
+ * measurement aid, not thread-safe. */
 int mst_gemm_force_fp32_mfma(int on);
 
 /* G_dev [O*I] = dY^T X at every position (the score of gradient-based growth: the dense

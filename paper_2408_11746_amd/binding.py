@@ -292,8 +292,9 @@ def mst_bwd_force_shape(wavefronts_per_workgroup: int = 0, quads_per_wavefront: 
     _check("mst_bwd_force_shape", lib().mst_bwd_force_shape(wavefronts_per_workgroup, quads_per_wavefront))
 
 
-def mst_gemm_force_fp32_mfma(on: bool):
-    _check("mst_gemm_force_fp32_mfma", lib().mst_gemm_force_fp32_mfma(1 if on else 0))
+def mst_gemm_force_fp32_mfma(on):
+    """False / 0: automatic; True / 1: plain fp32 MFMA kernel; 128 or 256: split kernel with that tile."""
+    _check("mst_gemm_force_fp32_mfma", lib().mst_gemm_force_fp32_mfma(int(on)))
 
 
 def mst_sparse_fc_bwd(layer: Layer, dY, X, dX, dW, T: int, ws, act: int = MST_F32, stream=None):

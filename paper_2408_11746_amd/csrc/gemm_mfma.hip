@@ -13,6 +13,7 @@
 // to the 8 XCDs in turn, so an XCD's L2 mostly sees one k range of the operands instead of
 // all of them) into separate partial outputs that a
 // second kernel adds in a fixed order.
+#include <type_traits>
 #include "common.h"
 
 namespace mst {
@@ -450,6 +451,237 @@ void k_gemm_split(const float* __restrict__ A, int64_t lda, const float* __restr
             }
 }
 
+// ---- the same product with a 256 x 256 workgroup tile: half the operand bytes per flop of the
+// 128 x 128 kernel, whose speed is set by what the CUs can pull from L2, not by the matrix
+// cores.  512 threads = 8 wavefronts (4 along m x 2 along n) of 64 x 128 (2 x 4 MFMA tiles, 128
+// accumulator registers), k steps of 32 through TWO LDS stages of 64 KB (hi and lo halves of a
+// 256 x 32 tile of each operand): one barrier per step; the registers fetched during step s
+// (tile s + 2) are split and stored into the free stage at the start of step s + 1.
+// Threads 0..255 stage A, 256..511 stage B.  LDS rows are 32 k = 64 bytes = four 16-byte
+// units; row m sits at position rho(m) (the two low bit pairs of m swapped inside its group of
+// 16) and its unit u at (u ^ (rho >> 2) ^ (rho >> 4)) & 3: the MFMA operand reads of 16
+// consecutive rows, the k-major stores (rows four apart) and the m-major stores (four rows x
+// four units) each cover all banks once.
+constexpr int BM2 = 256, BN2 = 256, SPK2 = 32;
+
+__device__ inline uint32_t bf_unit32(int m, int u) {
+    const int rho = (m & ~15) | ((m & 3) << 2) | ((m >> 2) & 3);
+    return (uint32_t)(rho * 64 + (((u ^ (rho >> 2) ^ (rho >> 4)) & 3) << 4));
+}
+
+// Staging roles.  A thread stages four "pieces" per step; a piece is one 16-byte LDS unit in each
+// half (eight consecutive k of one row), made of four hi/lo pairs.
+//   operands of equal layout: threads 0..255 stage A, 256..511 stage B, p = tid & 255;
+//     k-major: registers r[kk] = four consecutive rows (m0 + 4 mq ..) at k0 + 8 kg + kk; piece j =
+//              row 4 mq + j, unit kg;
+//     m-major: r[2 it], r[2 it + 1] = eight consecutive k (unit u) of row m(it); piece it.
+//   mixed (A m-major, B k-major): every thread stages two pieces of each, h = tid >> 8:
+//     r[0..3] as the m-major case for it = 2 h, 2 h + 1; r[4 + t] = two consecutive rows
+//     (n0 + 4 mq + 2 h ..) at k = k0 + 8 kg + 2 t (.xy) and + 2 t + 1 (.zw); pieces 2, 3 = those rows.
+__device__ inline int mmajor_row(int p, int it) { return 64 * it + 16 * (p >> 6) + 4 * ((p >> 2) & 3) + ((p >> 4) & 3); }
+
+template <bool KMAJOR>
+__device__ inline void split256_fetch(const float* __restrict__ src, int64_t ld, int k0, int m0, int p, float4 (&r)[8]) {
+    if (KMAJOR) {
+        const int mq = p & 63, kg = p >> 6;
+        const float* q = src + (int64_t)(k0 + 8 * kg) * ld + m0 + 4 * mq;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) r[kk] = *reinterpret_cast<const float4*>(q + (int64_t)kk * ld);
+    } else {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const float* q = src + (int64_t)(m0 + mmajor_row(p, it)) * ld + k0 + 8 * (p & 3);
+            r[2 * it] = *reinterpret_cast<const float4*>(q);
+            r[2 * it + 1] = *reinterpret_cast<const float4*>(q + 4);
+        }
+    }
+}
+__device__ inline void split256_fetch_mixed(const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+                                            int k0, int m0, int n0, int p, int h, float4 (&r)[8]) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const float* q = A + (int64_t)(m0 + mmajor_row(p, 2 * h + t)) * lda + k0 + 8 * (p & 3);
+        r[2 * t] = *reinterpret_cast<const float4*>(q);
+        r[2 * t + 1] = *reinterpret_cast<const float4*>(q + 4);
+    }
+    const float* q = B + (int64_t)(k0 + 8 * (p >> 6)) * ldb + n0 + 4 * (p & 63) + 2 * h;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float2 e = *reinterpret_cast<const float2*>(q + (int64_t)(2 * t) * ldb);
+        const float2 o = *reinterpret_cast<const float2*>(q + (int64_t)(2 * t + 1) * ldb);
+        r[4 + t] = make_float4(e.x, e.y, o.x, o.y);
+    }
+}
+
+// hi/lo pair q (0..3) of piece `piece` (0..3).  LAYOUT 0: k-major, 1: m-major, 2: mixed.
+template <int LAYOUT>
+__device__ inline void split256_pair(const float4 (&r)[8], int piece, int q, uint32_t& hi, uint32_t& lo) {
+    if (LAYOUT == 0) {
+        split_pair(f4_at(r[2 * q], piece), f4_at(r[2 * q + 1], piece), hi, lo);
+    } else if (LAYOUT == 1 || piece < 2) {
+        const float4& v = r[2 * piece + (q >> 1)];
+        if (q & 1) split_pair(v.z, v.w, hi, lo);
+        else split_pair(v.x, v.y, hi, lo);
+    } else {
+        const float4& v = r[4 + q];
+        if (piece == 2) split_pair(v.x, v.z, hi, lo);
+        else split_pair(v.y, v.w, hi, lo);
+    }
+}
+// byte offset of that piece inside one half of its operand's tile
+template <int LAYOUT>
+__device__ inline uint32_t split256_unit(int p, int h, int piece) {
+    if (LAYOUT == 0) return bf_unit32(4 * (p & 63) + piece, p >> 6);
+    if (LAYOUT == 1) return bf_unit32(mmajor_row(p, piece), p & 3);
+    if (piece < 2) return bf_unit32(mmajor_row(p, 2 * h + piece), p & 3);
+    return bf_unit32(4 * (p & 63) + 2 * h + piece - 2, p >> 6);
+}
+
+template <bool A_KMAJOR, bool B_KMAJOR>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+                     float* __restrict__ C, int M, int N, int Kdim, int k_per_split, int64_t split_stride) {
+    constexpr int PLANE = BM2 * 64;                                       // one half (hi or lo) of one operand tile
+    __shared__ __attribute__((aligned(16))) char lds[2 * 4 * PLANE];     // [stage][A hi, A lo, B hi, B lo]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+    // workgroup -> (tile, k range): XCD x takes tiles x Q .. x Q + Q - 1, one k range after the other
+    const int gn = N / BN2, ntiles = (M / BM2) * gn, nsplit = (Kdim + k_per_split - 1) / k_per_split;
+    const int Q = (ntiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int split = slot / Q, tile_id = xcd * Q + slot % Q;
+    if (tile_id >= ntiles || split >= nsplit) return;
+    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN2;
+    const int kbeg = split * k_per_split;
+    const int kend = min(Kdim, kbeg + k_per_split);
+    float* Cz = C + (int64_t)split * split_stride;
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    static_assert(A_KMAJOR == B_KMAJOR || (!A_KMAJOR && B_KMAJOR), "layouts: TN, NT or NN");
+    constexpr int LAYOUT = A_KMAJOR == B_KMAJOR ? (A_KMAJOR ? 0 : 1) : 2;
+    const int h = tid >> 8, p = tid & 255;            // h is uniform per wavefront
+    const float* const src = h == 0 ? A : B;          // equal layouts: this thread's operand
+    const int64_t ld = h == 0 ? lda : ldb;
+    const int o0 = h == 0 ? m0 : n0;
+    auto fetch = [&](int k0, float4 (&r)[8]) __attribute__((always_inline)) {
+        if (LAYOUT == 2) split256_fetch_mixed(A, lda, B, ldb, k0, m0, n0, p, h, r);
+        else split256_fetch<A_KMAJOR>(src, ld, k0, o0, p, r);
+    };
+    const int lk = lane >> 5, lm = lane & 31;
+    uint32_t wr_unit[4];                              // this thread's four LDS units of a stage (hi half)
+#pragma unroll
+    for (int pc = 0; pc < 4; ++pc) {
+        const int plane = LAYOUT == 2 ? (pc < 2 ? 0 : 2 * PLANE) : (h == 0 ? 0 : 2 * PLANE);
+        wr_unit[pc] = plane + split256_unit<LAYOUT>(p, h, pc);
+    }
+    auto stage = [&](int buf, const float4 (&r)[8]) __attribute__((always_inline)) {
+        char* const wr = lds + buf * 4 * PLANE;
+#pragma unroll
+        for (int pc = 0; pc < 4; ++pc) {
+            uint4 hv, lv;
+            split256_pair<LAYOUT>(r, pc, 0, hv.x, lv.x);
+            split256_pair<LAYOUT>(r, pc, 1, hv.y, lv.y);
+            split256_pair<LAYOUT>(r, pc, 2, hv.z, lv.z);
+            split256_pair<LAYOUT>(r, pc, 3, hv.w, lv.w);
+            *reinterpret_cast<uint4*>(wr + wr_unit[pc]) = hv;
+            *reinterpret_cast<uint4*>(wr + PLANE + wr_unit[pc]) = lv;
+        }
+    };
+    float4 r[8];
+    // One k step on LDS stage `buf`: 48 MFMAs in four groups (ks, jp) of twelve; the three products
+    // of an accumulator are four MFMAs apart (back to back they would wait for each other).
+    // With STAGE the tile held in r is split and stored into the other LDS stage during groups
+    // 2 and 3: two pairs after every three MFMAs, fenced so that the order survives scheduling.
+    // An MFMA occupies the matrix pipe for 32 cycles and the wavefront issues the conversions
+    // meanwhile.  With FETCH the registers are refilled (tile at knext) once the last pair is split.
+    auto step = [&](int buf, auto stage_c, auto fetch_c, int knext) __attribute__((always_inline)) {
+        constexpr bool STAGE = decltype(stage_c)::value, FETCH = decltype(fetch_c)::value;
+        const char* Ah = lds + buf * 4 * PLANE;
+        const char* Al = Ah + PLANE;
+        const char* Bh = Ah + 2 * PLANE;
+        const char* Bl = Ah + 3 * PLANE;
+        char* const wr = lds + (buf ^ 1) * 4 * PLANE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {              // 16 k per MFMA: units 2 ks + lk
+            bf16x8 ah[2], al[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t ua = bf_unit32(wm + 32 * i + lm, 2 * ks + lk);
+                ah[i] = *reinterpret_cast<const bf16x8*>(Ah + ua);
+                al[i] = *reinterpret_cast<const bf16x8*>(Al + ua);
+            }
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
+                bf16x8 bh[2], bl[2];
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const uint32_t ub = bf_unit32(wn + 32 * (2 * jp + jj) + lm, 2 * ks + lk);
+                    bh[jj] = *reinterpret_cast<const bf16x8*>(Bh + ub);
+                    bl[jj] = *reinterpret_cast<const bf16x8*>(Bl + ub);
+                }
+                uint32_t hw[4], lw[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                    for (int e = 3 * c; e < 3 * c + 3; ++e) {
+                        const int t = e >> 2, jj = (e >> 1) & 1, i = e & 1;
+                        acc[i][2 * jp + jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            t == 0 ? al[i] : ah[i], t == 1 ? bl[jj] : bh[jj], acc[i][2 * jp + jj], 0, 0, 0);
+                    }
+                    if (STAGE && ks == 1) {
+                        const int piece = 2 * jp + (c >> 1), q0 = 2 * (c & 1);
+#pragma unroll
+                        for (int q = q0; q < q0 + 2; ++q) split256_pair<LAYOUT>(r, piece, q, hw[q], lw[q]);
+                        if (c & 1) {
+                            *reinterpret_cast<uint4*>(wr + wr_unit[piece]) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                            *reinterpret_cast<uint4*>(wr + PLANE + wr_unit[piece]) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+                        }
+                    }
+                    // scalar work, global loads and LDS reads may still move across
+                    __builtin_amdgcn_sched_barrier(0x124);
+                }
+            }
+        }
+        if (FETCH) fetch(knext, r);
+    };
+    using std::true_type;
+    using std::false_type;
+
+    fetch(kbeg, r);
+    stage(0, r);
+    if (kbeg + SPK2 < kend) fetch(kbeg + SPK2, r);
+    __syncthreads();
+    int buf = 0, k0 = kbeg;
+    for (; k0 + 2 * SPK2 < kend; k0 += SPK2, buf ^= 1) {
+        step(buf, true_type{}, true_type{}, k0 + 2 * SPK2);
+        __syncthreads();
+    }
+    if (k0 + SPK2 < kend) {                           // last but one step: nothing left to fetch
+        step(buf, true_type{}, false_type{}, 0);
+        __syncthreads();
+        buf ^= 1;
+    }
+    step(buf, false_type{}, false_type{}, 0);         // last step
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                const int n = n0 + wn + j * 32 + lm;
+                Cz[(int64_t)m * N + n] = acc[i][j][v];
+            }
+}
+
 __global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, int nsplit,
                                 float* __restrict__ C, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -548,9 +780,11 @@ static int pick_nsplit_xcd(int64_t tiles, int Kdim, int64_t mn, int64_t max_spli
     return best;
 }
 static int g_gemm_fp32_only = 0;          // test hook: 1 = never use the bf16-split kernel
+static int g_split_tile = 0;              // test hook: 0 = automatic, 128 / 256 = that workgroup tile when the shape allows it
 
-int gemm_force_fp32_mfma(int on) {
-    g_gemm_fp32_only = on ? 1 : 0;
+int gemm_force_fp32_mfma(int on) {       // 0 automatic, 1 fp32 MFMA kernel, 128 / 256: split kernel with that tile
+    g_gemm_fp32_only = on == 1 ? 1 : 0;
+    g_split_tile = (on == 128 || on == 256) ? on : 0;
     return MST_OK;
 }
 
@@ -558,9 +792,63 @@ static bool split_ok(int M, int N, int Kdim, int64_t lda, int64_t ldb) {
     return !g_gemm_fp32_only && M % BM == 0 && N % BN == 0 && Kdim % SPK == 0 && lda % 4 == 0 && ldb % 4 == 0;
 }
 
+static bool split256_ok(int M, int N, int Kdim) {
+    if (M % BM2 != 0 || N % BN2 != 0 || Kdim % SPK2 != 0) return false;
+    if (g_split_tile == 128) return false;
+    if (g_split_tile == 256) return true;
+    // measured: ahead of the 128-tile kernel once the grid has a few dozen tiles and the k loop is long
+    // enough to amortise the two-stage prologue
+    return (int64_t)(M / BM2) * (N / BN2) >= 32 && Kdim >= 768;
+}
+
+// split count of the 256-tile kernel: 32 places per XCD (one workgroup per CU), cost in k steps of 32
+static int pick_nsplit_xcd256(int64_t tiles, int Kdim, int64_t mn, int64_t max_split) {
+    static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+    const double wg_steps = 14.0, sum_steps_per_float = 5e-7 / 1.3;
+    const int64_t Q = cdiv(tiles, 8);
+    int best = 1;
+    double best_cost = 0.0;
+    for (int ns : cand) {
+        if (ns > 1 && (ns > max_split || Kdim / ns < 512)) continue;
+        const double steps = (double)cdiv(cdiv(Kdim, ns), SPK2);
+        const double cost = (double)cdiv(Q * ns, 32) * (steps + wg_steps) +
+                            (ns > 1 ? sum_steps_per_float * (double)ns * (double)mn : 0.0);
+        if (best_cost == 0.0 || cost < best_cost) {
+            best_cost = cost;
+            best = ns;
+        }
+    }
+    return best;
+}
+
+template <bool AK, bool BKM>
+static int launch_split256(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
+                           float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
+    const int gm = M / BM2, gn = N / BN2;
+    const int64_t mn = (int64_t)M * N;
+    const int nsplit0 = split_ws ? pick_nsplit_xcd256((int64_t)gm * gn, Kdim, mn, split_ws_floats / mn) : 1;
+    const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), SPK2) * SPK2);
+    const int nsplit = (int)cdiv(Kdim, kps);
+    const unsigned grid = (unsigned)(8 * cdiv((int64_t)gm * gn, 8) * nsplit);
+    float* dst = nsplit > 1 ? split_ws : C;
+    k_gemm_split256<AK, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+    MST_LAUNCH_CHECK();
+    if (left_unsummed) {
+        *left_unsummed = nsplit;
+        return MST_OK;
+    }
+    if (nsplit > 1) {
+        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
+        MST_LAUNCH_CHECK();
+    }
+    return MST_OK;
+}
+
 template <bool AK, bool BKM>
 static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
                         float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
+    if (split256_ok(M, N, Kdim))
+        return launch_split256<AK, BKM>(A, lda, B, ldb, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
     const int gm = M / BM, gn = N / BN;
     const int64_t mn = (int64_t)M * N;
     const int nsplit0 = split_ws ? pick_nsplit_xcd((int64_t)gm * gn, Kdim, mn, split_ws_floats / mn) : 1;

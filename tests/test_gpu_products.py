@@ -303,7 +303,7 @@ def test_gather_active_format_stats_and_lds_probe():
         mst.mst_probe_lds_read(out, 5, 10, 4)
 
 
-@pytest.mark.parametrize("T,I,O", [(512, 256, 384), (1024, 768, 768), (256, 128, 1280)])
+@pytest.mark.parametrize("T,I,O", [(512, 256, 384), (1024, 768, 768), (256, 128, 1280), (512, 256, 768), (768, 512, 256)])
 def test_dense_products_on_the_bf16_split_kernel(T, I, O):
     """Shapes of whole tiles: the dense fp32 products (dense gradient; forward and input
     gradient of a dense layer) take the kernel that splits every fp32 operand into two
@@ -319,19 +319,19 @@ def test_dense_products_on_the_bf16_split_kernel(T, I, O):
     Xd, dYd = dev(X), dev(dY)
     res = {}
     try:
-        for mode in (0, 1):
-            mst.mst_gemm_force_fp32_mfma(bool(mode))
+        for mode in (128, 256, 1):          # split kernel with either workgroup tile (where the shape allows), fp32 MFMA
+            mst.mst_gemm_force_fp32_mfma(mode)
             G = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
             mst.mst_dense_grad(dYd, Xd, G, T, O, I, mst.MST_F32, rig.ws)
             torch.cuda.synchronize()
             res[mode] = (G.cpu().numpy(), rig.fwd(X), rig.bwd_input(dY))
     finally:
-        mst.mst_gemm_force_fp32_mfma(False)
+        mst.mst_gemm_force_fp32_mfma(0)
     refs = (opr.dense_grad(dY, X), opr.fc_fwd(X, W, M), opr.fc_bwd_input(dY, W, M))
-    for name, got_split, got_f32, ref in zip(("G", "Y", "dX"), res[0], res[1], refs):
-        e0, e1 = rel_err(got_split, ref), rel_err(got_f32, ref)
-        print(name, "split err %.3g  fp32-mfma err %.3g" % (e0, e1), flush=True)
-        assert e0 <= TOL and e1 <= TOL
+    for name, got128, got256, got_f32, ref in zip(("G", "Y", "dX"), res[128], res[256], res[1], refs):
+        e0, e2, e1 = rel_err(got128, ref), rel_err(got256, ref), rel_err(got_f32, ref)
+        print(name, "split-128 err %.3g  split-256 err %.3g  fp32-mfma err %.3g" % (e0, e2, e1), flush=True)
+        assert e0 <= TOL and e1 <= TOL and e2 <= TOL
         # hi + lo carries 16 significant bits: at most 3 * 2^-18 = 1.1e-5 of a product is lost
-        assert e0 <= 2e-5
-        assert not np.array_equal(got_split, got_f32) or e0 == 0.0      # the two kernels really differ
+        assert e0 <= 2e-5 and e2 <= 2e-5
+        assert not np.array_equal(got128, got_f32) or e0 == 0.0         # the kernels really differ
