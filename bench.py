@@ -61,6 +61,9 @@ def parse():
     p.add_argument("--separate-bwd", action="store_true",
                    help="block workloads: time mst_sparse_fc_bwd_input and mst_sparse_fc_bwd_weight as two calls "
                         "instead of mst_sparse_fc_bwd (both gradients from one walk)")
+    p.add_argument("--path", default="auto", choices=["auto", "sparse", "dense"],
+                   help="pin every layer to the sparse kernels or to the masked dense MFMA contractions "
+                        "(mst_layer_set_path); auto = the library chooses per call from density, batch and dtype")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-per-config", action="store_true")
     p.add_argument("--lr", type=float, default=1e-5,
@@ -197,7 +200,7 @@ def roofline_of(row, L, act, kernel, traffic_cfg):
         t_hbm = row["alg_bytes"] / (HBM_PEAK_GBS * 1e9)
         t_alu = row["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
         if row.get("path") == "dense-mfma":
-            mnk = (L.T, L.O, L.I) if row["call"] == "fwd" else (L.T, L.I, L.O)
+            mnk = row.get("dense_mnk") or ((L.T, L.O, L.I) if row["call"] == "fwd" else (L.T, L.I, L.O))
             roof = dense_gemm_roofline(row["dense_flops"], row["avg_ms"], act, *mnk)
         elif t_hbm >= t_alu:
             roof = dict(bound="hbm", achieved=row["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
@@ -235,6 +238,20 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream()
     fstats = {L.name: L.layer.format_stats(stream) for L in layers}
+    for L in layers:
+        L.layer.set_path({"auto": mst.MST_PATH_AUTO, "sparse": mst.MST_PATH_SPARSE, "dense": mst.MST_PATH_DENSE}[args.path])
+    # which contraction serves each call (asked of the library, not re-derived here)
+    dense_prod = {L.name: L.layer.uses_dense(L.act, T) for L in layers}
+    dense_wgrad = {L.name: L.layer.uses_dense(L.act, T, True) for L in layers}
+
+    def path_of(L, kind):
+        a, b = dense_prod[L.name], dense_wgrad[L.name]
+        if kind in ("fwd", "bwd_input"):
+            return "dense-mfma" if a else "sparse"
+        if kind == "bwd_weight":
+            return "dense-mfma" if b else "sparse"
+        return "dense-mfma" if a and b else "sparse" if not (a or b) else \
+            "dX %s, dW %s" % ("dense-mfma" if a else "sparse", "dense-mfma" if b else "sparse")
 
     if args.pmc_probe:
         pmc_probe_block(args, mst, torch, layers, T, stream)
@@ -315,6 +332,7 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
             ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
             row = dict(layer=L.name, call=kind, launches=len(pairs), avg_ms=round(ms, 5))
             if kind in products:
+                row["path"] = path_of(L, kind)
                 by = getattr(L, "bytes_" + kind)()
                 fl = L.flops_product() * (2 if kind == "bwd" else 1)
                 # LDS operand bytes of the walk: 4 bytes per token and stored entry slot of the view walked
@@ -329,21 +347,23 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
             table.append(row)
 
     _, drow, dL = dominant
-    # fwd / bwd_input are one SpMM launch; bwd is the shared walk followed by its small second kernel
-    dense_bww = act == "bf16" and density > 0.045 and T >= 2048
-    if dense_bww:          # the bf16 MFMA weight gradient is faster than any sparse kernel here
-        bwd_kernels = "k_spmm64 + k_gemm_tn_bf16 + k_gather_flat (separate kernels)"
-    else:
-        bwd_kernels = "k_bwd_fused + k_bwd_fused_reduce"
-    kernel = {"fwd": "k_spmm / k_spmm64 (launch shape chosen per call)",
-              "bwd_input": "k_spmm / k_spmm64 (launch shape chosen per call)",
-              "bwd_weight": "k_gemm_tn_bf16+k_gather_flat" if dense_bww else "k_sddmm+k_sddmm_reduce",
-              "bwd": bwd_kernels}[drow["call"]]
+    # fwd / bwd_input are one SpMM launch or one masked dense product; bwd is the shared walk followed by its
+    # small second kernel unless a dense contraction serves one of the two gradients (then separate kernels)
+    dp, dw = dense_prod[dL.name], dense_wgrad[dL.name]
+    spmm_k = "k_spmm / k_spmm64 (launch shape chosen per call)"
+    gemm_k = "k_gemm_split256 / k_gemm_split (fp32 operands as bf16 hi + lo)" if act == "f32" else "k_gemm (fp32 MFMA)"
+    wgrad_dense_k = ("k_gemm_tn_bf16" if act == "bf16" else "k_gemm_split256<TN> / k_gemm_split<TN>") + " + k_gather_flat"
+    kernel = {"fwd": gemm_k if dp else spmm_k,
+              "bwd_input": gemm_k if dp else spmm_k,
+              "bwd_weight": wgrad_dense_k if dw else "k_sddmm + k_sddmm_reduce",
+              "bwd": "k_bwd_fused + k_bwd_fused_reduce" if not (dp or dw) else
+                     "%s, then %s" % (gemm_k if dp else spmm_k, wgrad_dense_k if dw else "k_sddmm + k_sddmm_reduce")}[drow["call"]]
+    if drow["path"] == "dense-mfma":
+        # every leg of the call is a dense contraction: priced against the matrix cores
+        legs = 2 if drow["call"] == "bwd" else 1
+        drow["dense_flops"] = legs * 2.0 * T * dL.O * dL.I
+        drow["dense_mnk"] = {"fwd": (T, dL.O, dL.I), "bwd_input": (T, dL.I, dL.O)}.get(drow["call"], (dL.O, dL.I, T))
     roof = roofline_of(drow, dL, act, kernel, name)
-    if drow["call"] == "bwd_weight" and dense_bww:
-        dense_tf = 2.0 * T * dL.O * dL.I / drow["avg_ms"] / 1e9
-        roof.update(bound="mfma", achieved=round(dense_tf, 1), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=round(dense_tf / MFMA_BF16_PEAK_TFLOPS, 4))
 
     out = {
         "metric": METRIC, "value": round(value, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -357,6 +377,7 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
                                   cfg["mask"], T,
                                   "fwd+bwd_input+bwd_weight" if args.separate_bwd
                                   else "fwd + bwd (input and weight gradient in one call)", args.update_interval),
+                   "path": args.path,
                    "nnz": {L.name: L.nnz for L in layers}, "mask_updates_in_timed_region": n_updates,
                    "caller_sgd_lr": args.lr,
                    "ell_efficiency": {L.name: dict(row_view=round(fstats[L.name]["row_view_efficiency"], 4),
@@ -434,6 +455,8 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
     layers = [LayerRun(mst, synth, torch, args.seed, lid + 1, lname, I, O, T, 1.0, "uniform", "f32", cap=O * I,
                        dense_start=True)
               for lid, (lname, I, O) in enumerate(cfg["layers"])]
+    for L in layers:
+        L.layer.set_path({"auto": mst.MST_PATH_AUTO, "sparse": mst.MST_PATH_SPARSE, "dense": mst.MST_PATH_DENSE}[args.path])
     G = [torch.empty(L.O * L.I, dtype=torch.float32, device="cuda:0") for L in layers]
     shapes = [(L.O, L.I) for L in layers]
     torch.cuda.synchronize()
@@ -450,10 +473,12 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
     side = [torch.cuda.Stream() for _ in layers] if args.update_streams else [stream] * len(layers)
     ev = []            # (position, layer index, call, start event, end event)
     nnz_at = {}        # position -> per-layer active counts (host arithmetic of the update, no read-back)
+    dense_at = {}      # position -> per layer: does the library route Y and dX to the masked dense contraction
 
     def run_step(t, record):
         pos = t % ncyc
         nnz_at[pos] = [L.layer.nnz for L in layers]
+        dense_at[pos] = [L.layer.uses_dense(L.act, T) for L in layers]
 
         def mark(s):
             e = torch.cuda.Event(enable_timing=True)
@@ -535,10 +560,10 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
         if not steps_at[p]:
             continue
         d = cyc[p]
-        dense_path = d > 0.30
         ms_pos = 0.0
         for li, L in enumerate(layers):
             nnz = nnz_at[p][li]
+            dense_path = dense_at[p][li]
             for call in ("fwd", "bwd_input"):
                 xs = acc.get((p, li, call), [])
                 if not xs:
@@ -572,7 +597,7 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                                hbm_frac=round(step_bytes / ms_pos / 1e6 / HBM_PEAK_GBS, 4),
                                alu_frac=round(step_flops / ms_pos / 1e9 / ALU_FP32_PEAK_TFLOPS, 4),
                                nnz={L.name: n for L, n in zip(layers, nnz_at[p])},
-                               path="dense-mfma" if dense_path else "sparse"))
+                               path="dense-mfma" if all(dense_at[p]) else "sparse" if not any(dense_at[p]) else "mixed"))
     # the update's calls do the same work at every position (the dense gradient) or nearly so: one row per layer
     for (li, call), xs in sorted(by_layer_call.items()):
         L = layers[li]
@@ -769,7 +794,8 @@ def compact(out, name):
                 ms_per_mask_update=out["ms_per_mask_update"], ell_efficiency=out["config"]["ell_efficiency"],
                 slowest_call=dict(call=r["call"], avg_ms=r["avg_launch_ms"], bound=r["bound"], frac=r["frac"],
                                   hbm_frac=r.get("hbm_frac"), alu_frac=r.get("alu_frac"), lds_frac=r.get("lds_frac")),
-                calls=[{k: c[k] for k in ("layer", "call", "avg_ms", "eff_tflops", "hbm_frac", "alu_frac", "lds_frac")
+                path=out["config"]["path"],
+                calls=[{k: c[k] for k in ("layer", "call", "path", "avg_ms", "eff_tflops", "hbm_frac", "alu_frac", "lds_frac")
                         if k in c} for c in out["calls"]],
                 dense_grad_gemm=out["dense_grad_gemm"])
 
@@ -796,7 +822,15 @@ def main():
         if args.config == "all" and not args.no_per_config:
             rows = []
             for name in ("C1", "C2", "C3", "C4"):
-                rows.append(compact(run_block(args, name, mst, synth, torch, lds_peak, False), name))
+                row = compact(run_block(args, name, mst, synth, torch, lds_peak, False), name)
+                if args.path == "auto" and any(c.get("path", "sparse") != "sparse" for c in row["calls"]):
+                    # the library sends some call of this workload to a dense contraction: the same workload with
+                    # every layer pinned to the sparse kernels, so that those stay measured
+                    pinned = argparse.Namespace(**dict(vars(args), path="sparse"))
+                    sp = compact(run_block(pinned, name, mst, synth, torch, lds_peak, False), name)
+                    row["sparse_pinned"] = {k: sp[k] for k in ("ms_per_step", "eff_tflops", "hbm_frac", "alu_frac",
+                                                               "slowest_call", "calls")}
+                rows.append(row)
             out["per_config"] = rows
         print(json.dumps(out))
         return

@@ -120,6 +120,12 @@ int mst_layer_indices(const mst_layer_t* layer, int32_t* flat_dev, mst_stream_t 
 
 int mst_layer_set_path(mst_layer_t* layer, mst_path path);
 
+/* Which path a product call with these arguments takes on the layer as it stands: 1 = masked
+ * dense MFMA contraction, 0 = sparse kernel; weight_gradient = 0 asks for Y and dX (Eq. (1) and
+ * its input gradient), 1 for the gradient of the active weights.  Host only, no device work;
+ * MST_ERR_ARG on a null layer, an unknown type or T < 1. */
+int mst_layer_uses_dense(const mst_layer_t* layer, mst_dtype act, int T, int weight_gradient);
+
 /* Prune criterion of the following updates of this layer.  0 (the default) is the paper's:
  * the smallest |w|.  lambda > 0 selects the other criterion of the table of topology
  * evolution schemes in Sec. 3.2, the smallest |w| + lambda |grad|, with the same dense

@@ -88,6 +88,7 @@ def lib() -> C.CDLL:
         "mst_layer_sync_values": (i32, [vp, vp]),
         "mst_layer_indices": (i32, [vp, vp, vp]),
         "mst_layer_set_path": (i32, [vp, i32]),
+        "mst_layer_uses_dense": (i32, [vp, i32, i32, i32]),
         "mst_layer_set_prune_lambda": (i32, [vp, C.c_float]),
         "mst_spmm_force_shape": (i32, [i32, i32]),
         "mst_layer_nnz": (i64, [vp]),
@@ -126,7 +127,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_workspace_bytes",
            "mst_layer_create", "mst_layer_destroy", "mst_layer_load_dense", "mst_layer_export_dense",
-           "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_layer_set_prune_lambda",
+           "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_layer_uses_dense", "mst_layer_set_prune_lambda",
            "mst_spmm_force_shape",
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight", "mst_sparse_fc_bwd_weight_static",
            "mst_static_scratch_bytes", "mst_sparse_fc_bwd", "mst_bwd_force_shape", "mst_gemm_force_fp32_mfma",
@@ -253,6 +254,11 @@ class Layer:
 
     def set_path(self, path: int):
         _check("mst_layer_set_path", lib().mst_layer_set_path(self.h, path))
+
+    def uses_dense(self, act: int, T: int, weight_gradient: bool = False) -> bool:
+        rc = lib().mst_layer_uses_dense(self.h, act, T, int(weight_gradient))
+        _check("mst_layer_uses_dense", min(rc, 0))
+        return rc == 1
 
     def set_prune_lambda(self, lam: float):
         _check("mst_layer_set_prune_lambda", lib().mst_layer_set_prune_lambda(self.h, float(lam)))

@@ -100,7 +100,7 @@ int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int
     if (!L || !X_dev || !Y_dev || T < 1 || !act_ok(act) || !aligned16(X_dev) || !aligned16(Y_dev)) return MST_ERR_ARG;
     if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
-    if (use_dense_path(L)) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
+    if (use_dense_path(L, act, T)) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
     return spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
 }
 
@@ -109,7 +109,7 @@ int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_
     if (!L || !dY_dev || !dX_dev || T < 1 || !act_ok(act) || !aligned16(dY_dev) || !aligned16(dX_dev)) return MST_ERR_ARG;
     if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
-    if (use_dense_path(L)) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
+    if (use_dense_path(L, act, T)) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
     return spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
 }
 
@@ -155,16 +155,21 @@ int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_de
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    if (use_dense_path(L) || use_dense_weight_grad(L, act, T) || !bwd_fused_pays(L)) {
+    if (use_dense_path(L, act, T) || use_dense_weight_grad(L, act, T) || !bwd_fused_pays(L)) {
         // a dense contraction serves at least one of the two, or the layer is so sparse that
         // the separate kernels with their wider slabs are faster: the separate calls
-        int rc = use_dense_path(L) ? dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s)
+        int rc = use_dense_path(L, act, T) ? dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s)
                                    : spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
         if (rc != MST_OK) return rc;
         return use_dense_weight_grad(L, act, T) ? dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s)
                                                 : sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
     }
     return bwd_fused(L, dY_dev, X_dev, dX_dev, dW_dev, T, act, ws, s);
+}
+
+int mst_layer_uses_dense(const mst_layer_t* L, mst_dtype act, int T, int weight_gradient) {
+    if (!L || !act_ok(act) || T < 1) return MST_ERR_ARG;
+    return (weight_gradient ? use_dense_weight_grad(L, act, T) : use_dense_path(L, act, T)) ? 1 : 0;
 }
 
 int mst_gather_active(const mst_layer_t* L, const float* G_dev, float* dW_dev, mst_stream_t stream) {

@@ -99,7 +99,7 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // true when a layer of this density should run the masked dense MFMA kernels
-bool use_dense_path(const mst_layer* L);
+bool use_dense_path(const mst_layer* L, mst_dtype act, int T);
 bool use_dense_weight_grad(const mst_layer* L, mst_dtype act, int T);
 
 // ---- workspace carving (one place so that mst_workspace_bytes and the users agree) ----

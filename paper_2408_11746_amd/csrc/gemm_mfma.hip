@@ -755,26 +755,39 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
     return MST_OK;
 }
 
-// Split count of k_gemm_split.  Its tiles are dealt to the XCDs in equal shares (Q tiles each)
-// and an XCD holds 32 CUs x 2 workgroups = 64 places, so what matters is how many rounds of 64
-// Q x splits needs on ONE XCD.  Cost in units of one k step: rounds x (k steps per workgroup
-// + 7 for a workgroup's start-up and output) + the pass that adds the partial outputs.  On a
-// sweep of the split count over twelve GPT-2 small / large dense-gradient shapes on MI355X
-// this picks the fastest count every time.
-static int pick_nsplit_xcd(int64_t tiles, int Kdim, int64_t mn, int64_t max_split) {
+// Workgroup tile and split count of the bf16-split kernels, chosen together.  Tiles are dealt to
+// the XCDs in equal shares (Q each).  An XCD has 32 CUs: 64 places for the 128-tile kernel (two
+// workgroups per CU), 32 for the 256-tile kernel, so what matters is how many rounds Q x splits
+// needs on ONE XCD.  Modelled time = rounds x (k steps per workgroup + start-up and output of a
+// workgroup, in steps) x time of a step, plus the traffic of the partial outputs.  Constants
+// from timings on MI355X: a 64-k step of two co-resident 128 x 128 tiles 3.3 us, a 32-k step of
+// a 256 x 256 tile 2.04 us (1.6x the work per CU and time), start-up + output 7 and 14 steps.
+// The model reproduces the measured times of the GPT-2 small / large products within 15 % and
+// orders the candidates as measured.
+struct SplitPlan {
+    int tile, nsplit;
+};
+static SplitPlan plan_split(int M, int N, int Kdim, int64_t max_split, bool summed, bool allow128, bool allow256) {
     static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
-    const double wg_steps = 7.0, sum_steps_per_float = 5e-7 / 3.3;
-    const int64_t Q = cdiv(tiles, 8);
-    int best = 1;
+    SplitPlan best{0, 1};
     double best_cost = 0.0;
-    for (int ns : cand) {
-        if (ns > 1 && (ns > max_split || Kdim / ns < 512)) continue;
-        const double steps = (double)cdiv(cdiv(Kdim, ns), SPK);
-        const double cost = (double)cdiv(Q * ns, 64) * (steps + wg_steps) +
-                            (ns > 1 ? sum_steps_per_float * (double)ns * (double)mn : 0.0);
-        if (best_cost == 0.0 || cost < best_cost) {
-            best_cost = cost;
-            best = ns;
+    for (int tile : {128, 256}) {
+        if (tile == 128 ? !allow128 : !allow256) continue;
+        const int kstep = tile == 128 ? SPK : 32, places = tile == 128 ? 64 : 32;
+        const double unit_us = tile == 128 ? 3.3 : 2.04, wg_steps = tile == 128 ? 7.0 : 14.0;
+        if (M % tile != 0 || N % tile != 0 || Kdim % kstep != 0) continue;
+        const int64_t Q = cdiv((int64_t)(M / tile) * (N / tile), 8);
+        for (int ns : cand) {
+            if (ns > 1 && (ns > max_split || Kdim / ns < 512)) continue;
+            const double steps = (double)cdiv(cdiv(Kdim, ns), kstep);
+            double cost = (double)cdiv(Q * ns, places) * (steps + wg_steps) * unit_us;
+            // partial outputs: written and read once each, plus the sum's write (4 B at about 4 TB/s);
+            // left unsummed they are read sparsely by the caller's gather
+            if (ns > 1) cost += 1.0e-6 * (double)M * (double)N * (summed ? ns + 1.0 : 0.25 * ns);
+            if (best.tile == 0 || cost < best_cost) {
+                best_cost = cost;
+                best = SplitPlan{tile, ns};
+            }
         }
     }
     return best;
@@ -792,71 +805,23 @@ static bool split_ok(int M, int N, int Kdim, int64_t lda, int64_t ldb) {
     return !g_gemm_fp32_only && M % BM == 0 && N % BN == 0 && Kdim % SPK == 0 && lda % 4 == 0 && ldb % 4 == 0;
 }
 
-static bool split256_ok(int M, int N, int Kdim) {
-    if (M % BM2 != 0 || N % BN2 != 0 || Kdim % SPK2 != 0) return false;
-    if (g_split_tile == 128) return false;
-    if (g_split_tile == 256) return true;
-    // measured: ahead of the 128-tile kernel once the grid has a few dozen tiles and the k loop is long
-    // enough to amortise the two-stage prologue
-    return (int64_t)(M / BM2) * (N / BN2) >= 32 && Kdim >= 768;
-}
-
-// split count of the 256-tile kernel: 32 places per XCD (one workgroup per CU), cost in k steps of 32
-static int pick_nsplit_xcd256(int64_t tiles, int Kdim, int64_t mn, int64_t max_split) {
-    static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
-    const double wg_steps = 14.0, sum_steps_per_float = 5e-7 / 1.3;
-    const int64_t Q = cdiv(tiles, 8);
-    int best = 1;
-    double best_cost = 0.0;
-    for (int ns : cand) {
-        if (ns > 1 && (ns > max_split || Kdim / ns < 512)) continue;
-        const double steps = (double)cdiv(cdiv(Kdim, ns), SPK2);
-        const double cost = (double)cdiv(Q * ns, 32) * (steps + wg_steps) +
-                            (ns > 1 ? sum_steps_per_float * (double)ns * (double)mn : 0.0);
-        if (best_cost == 0.0 || cost < best_cost) {
-            best_cost = cost;
-            best = ns;
-        }
-    }
-    return best;
-}
-
-template <bool AK, bool BKM>
-static int launch_split256(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
-                           float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
-    const int gm = M / BM2, gn = N / BN2;
-    const int64_t mn = (int64_t)M * N;
-    const int nsplit0 = split_ws ? pick_nsplit_xcd256((int64_t)gm * gn, Kdim, mn, split_ws_floats / mn) : 1;
-    const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), SPK2) * SPK2);
-    const int nsplit = (int)cdiv(Kdim, kps);
-    const unsigned grid = (unsigned)(8 * cdiv((int64_t)gm * gn, 8) * nsplit);
-    float* dst = nsplit > 1 ? split_ws : C;
-    k_gemm_split256<AK, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
-    MST_LAUNCH_CHECK();
-    if (left_unsummed) {
-        *left_unsummed = nsplit;
-        return MST_OK;
-    }
-    if (nsplit > 1) {
-        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
-        MST_LAUNCH_CHECK();
-    }
-    return MST_OK;
-}
-
 template <bool AK, bool BKM>
 static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
                         float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
-    if (split256_ok(M, N, Kdim))
-        return launch_split256<AK, BKM>(A, lda, B, ldb, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
-    const int gm = M / BM, gn = N / BN;
     const int64_t mn = (int64_t)M * N;
-    const int nsplit0 = split_ws ? pick_nsplit_xcd((int64_t)gm * gn, Kdim, mn, split_ws_floats / mn) : 1;
-    const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), SPK) * SPK);
+    const SplitPlan plan = plan_split(M, N, Kdim, split_ws ? split_ws_floats / mn : 1, left_unsummed == nullptr,
+                                      g_split_tile != 256, g_split_tile != 128);
+    const int tile = plan.tile ? plan.tile : 128;     // a pinned 256 tile that does not fit: the 128 kernel
+    const int nsplit0 = plan.tile ? plan.nsplit : 1;
+    const int kstep = tile == 128 ? SPK : SPK2;
+    const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), kstep) * kstep);
     const int nsplit = (int)cdiv(Kdim, kps);
-    const unsigned grid = (unsigned)(8 * cdiv((int64_t)gm * gn, 8) * nsplit);
+    const unsigned grid = (unsigned)(8 * cdiv((int64_t)(M / tile) * (N / tile), 8) * nsplit);
     float* dst = nsplit > 1 ? split_ws : C;
-    k_gemm_split<AK, BKM><<<grid, 256, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+    if (tile == 256)
+        k_gemm_split256<AK, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+    else
+        k_gemm_split<AK, BKM><<<grid, 256, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
     MST_LAUNCH_CHECK();
     if (left_unsummed) {
         *left_unsummed = nsplit;

@@ -27,20 +27,25 @@ int64_t view_pair_capacity(int64_t cap, int64_t nchunk, int64_t R) {
     return cdiv((cap + nqs) / 2 + 1 + PAIR_TAIL, 8) * 8;
 }
 
-bool use_dense_path(const mst_layer* L) {
+// Measured cross-overs (GPT-2 small / medium / large layer shapes).  With fp32 activations the
+// dense products run on the bf16 matrix cores (operands split hi + lo) at 250-360 TFLOP/s and
+// cost the same at every density; the sparse kernels cost about in proportion to nnz.  At
+// T >= 2048 the two meet at a density of 0.045-0.06 for Y and dX and at 0.03-0.04 for the
+// weight gradient; short batches fill the matrix cores badly and meet at about 0.15 (there the
+// one-call backward, both gradients from one walk, is also ahead of two separate products).  With
+// bfloat16 activations Y and dX of the dense path still run on the fp32 MFMA kernel (cross-over
+// 0.30), the weight gradient has both operands in bfloat16 (300-440 TFLOP/s, cross-over 0.045).
+bool use_dense_path(const mst_layer* L, mst_dtype act, int T) {
     if (L->path == MST_PATH_DENSE) return true;
     if (L->path == MST_PATH_SPARSE) return false;
-    return (double)L->nnz > 0.30 * (double)L->N;      // measured cross-over, see the benchmark table
+    const double thr = act == MST_BF16 ? 0.30 : T >= 2048 ? 0.055 : 0.15;
+    return (double)L->nnz > thr * (double)L->N;
 }
 
-// The weight gradient alone has a second cross-over: with bfloat16 activations both operands
-// of G = dY^T X are bfloat16, the MFMA kernel runs at 300-440 TFLOP/s and computing all of
-// G, then reading the active positions, beats the SDDMM (about 17 effective TFLOP/s) from a
-// density of about 0.045 on (measured at T >= 8192; short batches keep the common threshold).
 bool use_dense_weight_grad(const mst_layer* L, mst_dtype act, int T) {
     if (L->path == MST_PATH_DENSE) return true;
     if (L->path == MST_PATH_SPARSE) return false;
-    const double thr = (act == MST_BF16 && T >= 2048) ? 0.045 : 0.30;
+    const double thr = act == MST_BF16 ? (T >= 2048 ? 0.045 : 0.30) : T >= 2048 ? 0.035 : 0.15;
     return (double)L->nnz > thr * (double)L->N;
 }
 

@@ -1,8 +1,9 @@
 """Parity at the full size of the schedule-sweep workload: the GPT-2-large fully-connected set
 (1280 -> 3840 / 1280 / 5120, 5120 -> 1280) at T = 8192 tokens, fp32, at the densities the
 sweep passes through (Sec. 3.1: dense start, ultra-sparse phase, restoration).  Densities
-1.0 and 0.5 run the masked dense MFMA path, 0.1 and 0.02 the sparse kernels, in the launch
-configuration the benchmark times (automatic path and launch shape).  Outputs are compared
+1.0, 0.5 and 0.1 run the masked dense MFMA path, 0.02 the sparse kernels, in the launch
+configuration the benchmark times (automatic path and launch shape); 0.1 runs a second time
+pinned to the sparse kernels.  Outputs are compared
 with the oracle at >= 10^4 sampled positions per tensor (plus the longest / shortest rows
 and columns); the adjoint identities cover the complete outputs; masks after a fused
 Mixed-Growing update (Algorithm 1) are compared in full, bit for bit."""
@@ -33,6 +34,10 @@ def test_large_layer_products_at_every_sweep_density(name, I, O):
         W, M = synth.make_layer(2024, lid, I, O, d)
         rig = Rig(W, M, T, cap=int(M.sum()))
         check_layer_products("%s d=%.2f" % (name, d), rig, W, M, X, dY, Xd, dYd, mst.MST_F32, n=10000)
+        assert rig.layer.uses_dense(mst.MST_F32, T) == (d >= 0.1)
+        if d == 0.1:
+            rig.layer.set_path(mst.MST_PATH_SPARSE)
+            check_layer_products("%s d=%.2f sparse" % (name, d), rig, W, M, X, dY, Xd, dYd, mst.MST_F32, n=3000)
         del rig
         torch.cuda.empty_cache()
 

@@ -20,7 +20,11 @@ def _both(rig, dY, X, T, act=mst.MST_F32):
     a = torch.full((nnz,), float("nan"), dtype=torch.float32, device=DEV)
     b = torch.full((nnz,), float("nan"), dtype=torch.float32, device=DEV)
     mst.mst_sparse_fc_bwd_weight_static(rig.layer, dY, X, a, T, act)
+    # the existing entry point pinned to the kernels the static one always runs (left to itself
+    # it may form the gradient by a dense contraction: equal within tolerance, not bit for bit)
+    rig.layer.set_path(mst.MST_PATH_SPARSE)
     mst.mst_sparse_fc_bwd_weight(rig.layer, dY, X, b, T, rig.ws, act)
+    rig.layer.set_path(mst.MST_PATH_AUTO)
     torch.cuda.synchronize()
     return a.cpu().numpy(), b.cpu().numpy()
 
