@@ -338,6 +338,7 @@ __device__ inline void split_fetch(const float* __restrict__ src, int64_t ld, in
 }
 
 __device__ inline float f4_at(const float4& v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
+__device__ inline uint32_t u4_at(const uint4& v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
 
 template <bool KMAJOR>
 __device__ inline void split_stage(char* hi_lds, char* lo_lds, int p, const float4 (&r)[8]) {
@@ -480,39 +481,6 @@ __device__ inline uint32_t bf_unit32(int m, int u) {
 //     (n0 + 4 mq + 2 h ..) at k = k0 + 8 kg + 2 t (.xy) and + 2 t + 1 (.zw); pieces 2, 3 = those rows.
 __device__ inline int mmajor_row(int p, int it) { return 64 * it + 16 * (p >> 6) + 4 * ((p >> 2) & 3) + ((p >> 4) & 3); }
 
-template <bool KMAJOR>
-__device__ inline void split256_fetch(const float* __restrict__ src, int64_t ld, int k0, int m0, int p, float4 (&r)[8]) {
-    if (KMAJOR) {
-        const int mq = p & 63, kg = p >> 6;
-        const float* q = src + (int64_t)(k0 + 8 * kg) * ld + m0 + 4 * mq;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) r[kk] = *reinterpret_cast<const float4*>(q + (int64_t)kk * ld);
-    } else {
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const float* q = src + (int64_t)(m0 + mmajor_row(p, it)) * ld + k0 + 8 * (p & 3);
-            r[2 * it] = *reinterpret_cast<const float4*>(q);
-            r[2 * it + 1] = *reinterpret_cast<const float4*>(q + 4);
-        }
-    }
-}
-__device__ inline void split256_fetch_mixed(const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
-                                            int k0, int m0, int n0, int p, int h, float4 (&r)[8]) {
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const float* q = A + (int64_t)(m0 + mmajor_row(p, 2 * h + t)) * lda + k0 + 8 * (p & 3);
-        r[2 * t] = *reinterpret_cast<const float4*>(q);
-        r[2 * t + 1] = *reinterpret_cast<const float4*>(q + 4);
-    }
-    const float* q = B + (int64_t)(k0 + 8 * (p >> 6)) * ldb + n0 + 4 * (p & 63) + 2 * h;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const float2 e = *reinterpret_cast<const float2*>(q + (int64_t)(2 * t) * ldb);
-        const float2 o = *reinterpret_cast<const float2*>(q + (int64_t)(2 * t + 1) * ldb);
-        r[4 + t] = make_float4(e.x, e.y, o.x, o.y);
-    }
-}
-
 // hi/lo pair q (0..3) of piece `piece` (0..3).  LAYOUT 0: k-major, 1: m-major, 2: mixed.
 template <int LAYOUT>
 __device__ inline void split256_pair(const float4 (&r)[8], int piece, int q, uint32_t& hi, uint32_t& lo) {
@@ -566,13 +534,58 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
 
     static_assert(A_KMAJOR == B_KMAJOR || (!A_KMAJOR && B_KMAJOR), "layouts: TN, NT or NN");
     constexpr int LAYOUT = A_KMAJOR == B_KMAJOR ? (A_KMAJOR ? 0 : 1) : 2;
-    const int h = tid >> 8, p = tid & 255;            // h is uniform per wavefront
-    const float* const src = h == 0 ? A : B;          // equal layouts: this thread's operand
-    const int64_t ld = h == 0 ? lda : ldb;
-    const int o0 = h == 0 ? m0 : n0;
+    // h is uniform per wavefront: operand base and row pitch stay scalar, a load's address is a
+    // scalar base (advanced per step) plus a per-thread 32-bit byte offset fixed for the kernel
+    const int h = __builtin_amdgcn_readfirstlane(tid >> 8), p = tid & 255;
+    const int64_t pa = 4 * lda, pb = 4 * ldb;         // row pitches in bytes
+    const char* base0;                                // equal layouts: this thread's operand; mixed: A
+    const char* base1 = nullptr;                      // mixed: B
+    int64_t pitch0;
+    uint32_t voff[4];
+    if (LAYOUT == 0) {
+        pitch0 = h == 0 ? pa : pb;
+        base0 = reinterpret_cast<const char*>(h == 0 ? A + m0 : B + n0);
+        voff[0] = (uint32_t)(8 * (p >> 6) * pitch0 + 16 * (p & 63));
+    } else if (LAYOUT == 1) {
+        pitch0 = h == 0 ? pa : pb;
+        base0 = reinterpret_cast<const char*>(h == 0 ? A : B) + (int64_t)(h == 0 ? m0 : n0) * pitch0;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) voff[it] = (uint32_t)(mmajor_row(p, it) * pitch0 + 32 * (p & 3));
+    } else {
+        pitch0 = pa;
+        base0 = reinterpret_cast<const char*>(A) + (int64_t)m0 * pa;
+        base1 = reinterpret_cast<const char*>(B + n0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) voff[t] = (uint32_t)(mmajor_row(p, 2 * h + t) * pa + 32 * (p & 3));
+        voff[2] = (uint32_t)(8 * (p >> 6) * pb + 16 * (p & 63) + 8 * h);
+    }
     auto fetch = [&](int k0, float4 (&r)[8]) __attribute__((always_inline)) {
-        if (LAYOUT == 2) split256_fetch_mixed(A, lda, B, ldb, k0, m0, n0, p, h, r);
-        else split256_fetch<A_KMAJOR>(src, ld, k0, o0, p, r);
+        if (LAYOUT == 0) {
+            const char* row = base0 + (int64_t)k0 * pitch0;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) r[kk] = *reinterpret_cast<const float4*>(row + kk * pitch0 + voff[0]);
+        } else if (LAYOUT == 1) {
+            const char* col = base0 + 4 * (int64_t)k0;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                r[2 * it] = *reinterpret_cast<const float4*>(col + voff[it]);
+                r[2 * it + 1] = *reinterpret_cast<const float4*>(col + voff[it] + 16);
+            }
+        } else {
+            const char* col = base0 + 4 * (int64_t)k0;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                r[2 * t] = *reinterpret_cast<const float4*>(col + voff[t]);
+                r[2 * t + 1] = *reinterpret_cast<const float4*>(col + voff[t] + 16);
+            }
+            const char* row = base1 + (int64_t)k0 * pb;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float2 e = *reinterpret_cast<const float2*>(row + (2 * t) * pb + voff[2]);
+                const float2 o = *reinterpret_cast<const float2*>(row + (2 * t + 1) * pb + voff[2]);
+                r[4 + t] = make_float4(e.x, e.y, o.x, o.y);
+            }
+        }
     };
     const int lk = lane >> 5, lm = lane & 31;
     uint32_t wr_unit[4];                              // this thread's four LDS units of a stage (hi half)
@@ -669,6 +682,129 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
         buf ^= 1;
     }
     step(buf, false_type{}, false_type{}, 0);         // last step
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                const int n = n0 + wn + j * 32 + lm;
+                Cz[(int64_t)m * N + n] = acc[i][j][v];
+            }
+}
+
+// G = A^T B with BOTH operands bfloat16 and k-major (A [K x M], B [K x N]): the same 256 x 256
+// workgroup tile, eight wavefronts of 64 x 128 and two LDS stages as k_gemm_split256, k steps of
+// 64: the two planes of an operand hold its k halves (0..31, 32..63) instead of hi and lo, one
+// MFMA product per term.  A thread stages a patch of 8 k x 8 rows: eight 16-byte loads, an
+// 8 x 8 halfword transpose in registers (v_perm_b32), eight 16-byte LDS units (one per row).
+// Staging of the next tile is spread over the second half of a step's MFMAs, as there.
+// (Four wavefronts of 128 x 128 with the accumulators in the accumulation half of the
+// register file measured 15 % slower: one wavefront per SIMD leaves every wait exposed.)
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_gemm_tn_bf16_256(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ B, int64_t ldb,
+                        float* __restrict__ C, int M, int N, int Kdim, int k_per_split, int64_t split_stride) {
+    constexpr int PLANE = BM2 * 64, KS = 64;
+    __shared__ __attribute__((aligned(16))) char lds[2 * 4 * PLANE];     // [stage][A k<32, A k>=32, B k<32, B k>=32]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+    const int gn = N / BN2, ntiles = (M / BM2) * gn, nsplit = (Kdim + k_per_split - 1) / k_per_split;
+    const int Q = (ntiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int split = slot / Q, tile_id = xcd * Q + slot % Q;
+    if (tile_id >= ntiles || split >= nsplit) return;
+    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN2;
+    const int kbeg = split * k_per_split;
+    const int kend = min(Kdim, kbeg + k_per_split);
+    float* Cz = C + (int64_t)split * split_stride;
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // h: 0 stages A, 1 stages B; uniform per wavefront, so base and row pitch stay scalar and a
+    // load's address is scalar row + per-thread 32-bit offset
+    const int h = __builtin_amdgcn_readfirstlane(tid >> 8), p = tid & 255, mq = p & 31, kg = p >> 5;
+    const int64_t pitch = 2 * (h == 0 ? lda : ldb);
+    const char* const sbase = reinterpret_cast<const char*>(h == 0 ? A + m0 : B + n0);
+    const uint32_t voff = (uint32_t)(8 * kg * pitch + 16 * mq);
+    uint4 r[8];
+    auto fetch = [&](int k0) __attribute__((always_inline)) {
+        const char* row = sbase + (int64_t)k0 * pitch;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) r[kk] = *reinterpret_cast<const uint4*>(row + kk * pitch + voff);
+    };
+    const uint32_t wr_plane = (uint32_t)((2 * h + (kg >> 2)) * PLANE);
+    uint32_t wr_unit[8];                              // row 8 mq + j, unit kg & 3
+#pragma unroll
+    for (int j = 0; j < 8; ++j) wr_unit[j] = wr_plane + bf_unit32(8 * mq + j, kg & 3);
+    // row j of the patch: halfword j of the eight registers, k ascending
+    auto piece = [&](int j) __attribute__((always_inline)) -> uint4 {
+        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+        uint32_t o[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t w0 = u4_at(r[2 * d], j >> 1), w1 = u4_at(r[2 * d + 1], j >> 1);
+            o[d] = __builtin_amdgcn_perm(w1, w0, sel);
+        }
+        return make_uint4(o[0], o[1], o[2], o[3]);
+    };
+    const int lk = lane >> 5, lm = lane & 31;
+    // one k step (64) on LDS stage buf: four groups (k half, 16-k slice) of eight MFMAs; with STAGE
+    // groups 2 and 3 each store four rows of the next tile, one row after every two MFMAs
+    auto step = [&](int buf, auto stage_c, auto fetch_c, int knext) __attribute__((always_inline)) {
+        constexpr bool STAGE = decltype(stage_c)::value, FETCH = decltype(fetch_c)::value;
+        const char* base = lds + buf * 4 * PLANE;
+        char* const wr = lds + (buf ^ 1) * 4 * PLANE;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const char* Ap = base + (g >> 1) * PLANE;
+            const char* Bp = base + (2 + (g >> 1)) * PLANE;
+            const int ks = g & 1;
+            bf16x8 a[2], b[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(Ap + bf_unit32(wm + 32 * i + lm, 2 * ks + lk));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = *reinterpret_cast<const bf16x8*>(Bp + bf_unit32(wn + 32 * j + lm, 2 * ks + lk));
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                for (int e = 2 * c; e < 2 * c + 2; ++e)
+                    acc[e & 1][e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[e & 1], b[e >> 1], acc[e & 1][e >> 1], 0, 0, 0);
+                if (STAGE && g >= 2) {
+                    const int j = 4 * (g - 2) + c;
+                    *reinterpret_cast<uint4*>(wr + wr_unit[j]) = piece(j);
+                }
+                __builtin_amdgcn_sched_barrier(0x124);     // scalar work, global loads and LDS reads may still move
+            }
+        }
+        if (FETCH) fetch(knext);
+    };
+    using std::true_type;
+    using std::false_type;
+
+    fetch(kbeg);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(lds + wr_unit[j]) = piece(j);
+    if (kbeg + KS < kend) fetch(kbeg + KS);
+    __syncthreads();
+    int buf = 0, k0 = kbeg;
+    for (; k0 + 2 * KS < kend; k0 += KS, buf ^= 1) {
+        step(buf, true_type{}, true_type{}, k0 + 2 * KS);
+        __syncthreads();
+    }
+    if (k0 + KS < kend) {
+        step(buf, true_type{}, false_type{}, 0);
+        __syncthreads();
+        buf ^= 1;
+    }
+    step(buf, false_type{}, false_type{}, 0);
 
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -838,6 +974,39 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
                           int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
     const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
     const int64_t mn = (int64_t)M * N;
+    if (g_split_tile != 128 && M % BM2 == 0 && N % BN2 == 0 && Kdim % 64 == 0 &&
+        (g_split_tile == 256 || (int64_t)(M / BM2) * (N / BN2) >= 8)) {
+        // whole 256 x 256 tiles: the two-stage kernel; split count from the same per-XCD round model
+        // (a 64-k step takes about 1.3 us, start-up and output of a workgroup about 16 steps)
+        static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+        const int64_t Q = cdiv((int64_t)(M / BM2) * (N / BN2), 8), max_split = split_ws ? split_ws_floats / mn : 1;
+        int ns_best = 1;
+        double best_cost = 0.0;
+        for (int ns : cand) {
+            if (ns > 1 && (ns > max_split || Kdim / ns < 512)) continue;
+            double cost = (double)cdiv(Q * ns, 32) * ((double)cdiv(cdiv(Kdim, ns), 64) + 16.0) * 1.3;
+            if (ns > 1) cost += 1.0e-6 * (double)mn * (left_unsummed ? 0.25 * ns : ns + 1.0);
+            if (best_cost == 0.0 || cost < best_cost) {
+                best_cost = cost;
+                ns_best = ns;
+            }
+        }
+        const int kps = (int)(cdiv(cdiv(Kdim, ns_best), 64) * 64);
+        const int nsplit = (int)cdiv(Kdim, kps);
+        const unsigned grid = (unsigned)(8 * Q * nsplit);
+        float* dst = nsplit > 1 ? split_ws : C;
+        k_gemm_tn_bf16_256<<<grid, 512, 0, s>>>((const uint16_t*)A, M, (const uint16_t*)B, N, dst, M, N, Kdim, kps, mn);
+        MST_LAUNCH_CHECK();
+        if (left_unsummed) {
+            *left_unsummed = nsplit;
+            return MST_OK;
+        }
+        if (nsplit > 1) {
+            k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
+            MST_LAUNCH_CHECK();
+        }
+        return MST_OK;
+    }
     const int nsplit0 = split_ws ? pick_nsplit((int64_t)gm * gn, Kdim, kSplitBf16, split_ws_floats / mn) : 1;
     const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), BKH) * BKH);
     const int nsplit = (int)cdiv(Kdim, kps);

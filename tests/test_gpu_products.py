@@ -335,3 +335,32 @@ def test_dense_products_on_the_bf16_split_kernel(T, I, O):
         # hi + lo carries 16 significant bits: at most 3 * 2^-18 = 1.1e-5 of a product is lost
         assert e0 <= 2e-5 and e2 <= 2e-5
         assert not np.array_equal(got128, got_f32) or e0 == 0.0         # the kernels really differ
+
+
+@pytest.mark.parametrize("T,I,O", [(64, 256, 256), (128, 256, 512), (1088, 512, 256), (2048, 768, 768)])
+def test_bf16_dense_gradient_on_both_workgroup_tiles(T, I, O):
+    """G = dY^T X with bfloat16 operands on whole 256 x 256 tiles: the two-stage 256-tile kernel
+    (one, two, an odd and a split number of k steps) and the 128-tile kernel, each against
+    the oracle on the same bfloat16 values; the products are exact in fp32, so the two
+    kernels differ only by the order of fp32 additions."""
+    print("case", T, I, O, flush=True)
+    Xf, dYf, xb, yb = synth.make_activations(43, 5, T, I, O, "bf16")
+    Xd, dYd = dev(xb.view(np.int16)), dev(yb.view(np.int16))
+    ref = opr.dense_grad(dYf, Xf)
+    ws = torch.empty(8 * O * I * 4, dtype=torch.uint8, device=DEV)
+    got = {}
+    try:
+        for mode in (128, 256):
+            for w in (None, ws):
+                mst.mst_gemm_force_fp32_mfma(mode)
+                G = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
+                mst.mst_dense_grad(dYd, Xd, G, T, O, I, mst.MST_BF16, w)
+                torch.cuda.synchronize()
+                got[(mode, w is not None)] = G.cpu().numpy()
+    finally:
+        mst.mst_gemm_force_fp32_mfma(0)
+    for key, g in got.items():
+        e = rel_err(g, ref)
+        print(key, "err %.3g" % e, flush=True)
+        assert e <= 2e-6                      # fp32 accumulation of exact products
+    assert rel_err(got[(256, False)], got[(128, False)]) <= 2e-6
