@@ -73,6 +73,9 @@ def parse():
     p.add_argument("--seed", type=int, default=2024)
     p.add_argument("--attention-mask", type=int, nargs=2, metavar=("L", "STRIDE"), default=None,
                    help="time the strided attention mask of Sec. 3.3 instead of a config (its own JSON line)")
+    p.add_argument("--lds-probe", action="store_true",
+                   help="time the LDS read probe (4-, 8- and 16-byte conflict-free reads on every CU) instead of a "
+                        "config: the on-chip roofline of the sparse walk, as its own JSON line")
     p.add_argument("--pmc-probe", action="store_true",
                    help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration), then each call twice")
     return p.parse_args()
@@ -160,6 +163,26 @@ def lds_peak_bytes_per_s(mst, torch, stream):
     b.record(stream)
     torch.cuda.synchronize()
     return blocks * 1024 * iters * 8 * width / (a.elapsed_time(b) * 1e-3)
+
+
+def lds_probe(mst, torch, stream):
+    """The LDS read rate by read width, each width timed over three launches."""
+    blocks, iters = N_CU, 2000
+    out = torch.empty(blocks * 1024, dtype=torch.float32, device="cuda:0")
+    res = {}
+    for width in (4, 8, 16):
+        mst.mst_probe_lds_read(out, width, 200, blocks, stream)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(3):
+            mst.mst_probe_lds_read(out, width, iters, blocks, stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        rate = 3 * blocks * 1024 * iters * 8 * width / (a.elapsed_time(b) * 1e-3)
+        res["%d-byte reads" % width] = dict(tb_per_s=round(rate / 1e12, 2),
+                                            bytes_per_clk_per_cu=round(rate / N_CU / 2.4e9, 1))
+    print(json.dumps({"lds_probe": True, "workgroups": blocks, "threads_per_workgroup": 1024,
+                      "reads_per_thread": iters * 8, "clock_ghz_assumed": 2.4, "rates": res}))
 
 
 def product_row_numbers(row, ms, by, fl, lds_bytes, lds_peak):
@@ -546,6 +569,18 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # after the timed region: one more pass of the cycle to read the views' stored entry counts at every
+    # position (a read-back that must not sit between timed calls); the LDS operand bytes of a sparse walk
+    t_end = t
+    slots_at = {}
+    for _ in range(ncyc):
+        fs = [L.layer.format_stats(stream) for L in layers]
+        slots_at[t % ncyc] = [dict(fwd=f["row_view_slots"], bwd_input=f["col_view_slots"]) for f in fs]
+        run_step(t, False)
+        t += 1
+    torch.cuda.synchronize()
+    t = t_end
+
     # ---- per (position, layer, call) device times
     acc = {}
     for pos, li, call, a, b in ev:
@@ -574,7 +609,8 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                            min_ms=round(min(xs), 5), max_ms=round(max(xs), 5),
                            path="dense-mfma" if dense_path else "sparse")
                 by = L.bytes_fwd(nnz) if call == "fwd" else L.bytes_bwd_input(nnz)
-                product_row_numbers(row, ms, by, L.flops_product(nnz), 0, lds_peak)
+                lds_bytes = 0 if dense_path else 4 * slots_at[p][li][call] * T
+                product_row_numbers(row, ms, by, L.flops_product(nnz), lds_bytes, lds_peak)
                 if dense_path:
                     mnk = (T, L.O, L.I) if call == "fwd" else (T, L.I, L.O)
                     r = dense_gemm_roofline(L.flops_dense_grad(), ms, "f32", *mnk)
@@ -615,10 +651,10 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
 
     _, drow, dL = dominant
     if drow["call"] == "dense_grad":
-        kernel = ("k_gemm_split<TN> (fp32 operands split into bf16 hi + lo, 3 x v_mfma_f32_32x32x16_bf16 per term) + "
-                  "k_splitk_reduce (ordered sum of its split partial outputs)")
+        kernel = ("k_gemm_split256<TN> (256 x 256 tiles; fp32 operands split into bf16 hi + lo, 3 x "
+                  "v_mfma_f32_32x32x16_bf16 per term) + k_splitk_reduce (ordered sum of its split partial outputs)")
     elif drow.get("path") == "dense-mfma":
-        kernel = ("k_gemm_split (masked dense product, bf16 hi + lo split on v_mfma_f32_32x32x16_bf16; preceded by the "
+        kernel = ("k_gemm_split256 (masked dense product, bf16 hi + lo split on v_mfma_f32_32x32x16_bf16; preceded by the "
                   "scatter of the dense weight copy after an update)")
     else:
         kernel = "k_spmm / k_spmm64 (launch shape chosen per call)"
@@ -746,12 +782,12 @@ def cpu_baseline_block(layers, T):
 
 def cpu_baseline_sweep(synth, seed, cfg):
     """The oracle on a bounded sample of the sweep: the three products of the four layers at
-    every density of the cycle on the first 256 tokens, and the Mixed-Growing update of the
+    every density of the cycle on the first 2048 tokens, and the Mixed-Growing update of the
     smallest layer (1280 x 1280) at every transition."""
     import numpy as np
     from oracle import mixed_growing as omg
     from oracle import products as opr
-    Ts, T, cyc = 512, cfg["T"], cfg["densities"]
+    Ts, T, cyc = 2048, cfg["T"], cfg["densities"]
     acts, Ws, Ms = [], [], []
     for lid, (_, I, O) in enumerate(cfg["layers"]):          # inputs first: drawing them is not the oracle's work
         acts.append(synth.make_activations(seed, lid + 1, Ts, I, O))
@@ -813,6 +849,8 @@ def main():
     if args.attention_mask:
         return attention_mask(args, mst, torch)
     stream = torch.cuda.current_stream()
+    if args.lds_probe:
+        return lds_probe(mst, torch, stream)
     lds_peak = None if args.pmc_probe else lds_peak_bytes_per_s(mst, torch, stream)
     cpu = not args.no_cpu_baseline
     if args.config == "C5" or args.config == "all":
