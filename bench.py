@@ -782,12 +782,13 @@ def cpu_baseline_block(layers, T):
 
 def cpu_baseline_sweep(synth, seed, cfg):
     """The oracle on a bounded sample of the sweep: the three products of the four layers at
-    every density of the cycle on the first 2048 tokens, and the Mixed-Growing update of the
+    every density of the cycle on the whole batch, and the Mixed-Growing update of the
     smallest layer (1280 x 1280) at every transition."""
     import numpy as np
     from oracle import mixed_growing as omg
     from oracle import products as opr
-    Ts, T, cyc = 2048, cfg["T"], cfg["densities"]
+    T, cyc = cfg["T"], cfg["densities"]
+    Ts = T
     acts, Ws, Ms = [], [], []
     for lid, (_, I, O) in enumerate(cfg["layers"]):          # inputs first: drawing them is not the oracle's work
         acts.append(synth.make_activations(seed, lid + 1, Ts, I, O))

@@ -60,6 +60,18 @@ typedef enum {
  * from the layer's density. */
 typedef enum { MST_PATH_AUTO = 0, MST_PATH_SPARSE = 1, MST_PATH_DENSE = 2 } mst_path;
 
+/* The index views that the sparse kernels walk are built when a sparse kernel will need them.
+ * mst_layer_load_dense always builds them.  A topology update builds them unless the layer, at
+ * its new density, is served by the dense contractions (judged by the path setting and by
+ * the batch size and activation type of the layer's last product call; a layer that has seen
+ * no product call yet, or is pinned to MST_PATH_SPARSE, always gets them); such an update
+ * rebuilds only the value / index vectors and writes the layer's dense weight copy in place.
+ * While the views are unbuilt: the calls that carry a workspace (mst_sparse_fc_bwd,
+ * mst_sparse_fc_bwd_weight, mst_sparse_fc_bwd_weight_update) build them first whenever a sparse
+ * kernel is due; mst_sparse_fc_fwd and mst_sparse_fc_bwd_input, which carry none, compute the
+ * same product with the dense contraction whatever the density; mst_sparse_fc_bwd_weight_static
+ * returns MST_ERR_STATE; mst_layer_format_stats reports zero stored entries. */
+
 /* Hyper-parameters of Sec. 3.1 / 3.2 (Table "Private hyperparameters of MST"). */
 typedef struct {
     double S_M;            /* maximum sparsity, in [0, 1] (paper: 0.96) */

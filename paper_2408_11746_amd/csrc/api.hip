@@ -79,6 +79,13 @@ int dense_products_bwd_weight(const mst_layer* L, const void* dY, const void* X,
 
 static bool act_ok(mst_dtype a) { return a == MST_F32 || a == MST_BF16; }
 
+// remembered for the next update's decision whether the index views will be walked
+static void note_call(const mst_layer* L, mst_dtype act, int T) {
+    mst_layer* m = const_cast<mst_layer*>(L);
+    m->hint_T = T;
+    m->hint_act = (int)act;
+}
+
 }  // namespace mst
 
 using namespace mst;
@@ -100,7 +107,9 @@ int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int
     if (!L || !X_dev || !Y_dev || T < 1 || !act_ok(act) || !aligned16(X_dev) || !aligned16(Y_dev)) return MST_ERR_ARG;
     if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
-    if (use_dense_path(L, act, T)) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
+    note_call(L, act, T);
+    // (unbuilt views and no workspace to build them with: the dense product, same result within tolerance)
+    if (use_dense_path(L, act, T) || !L->views_valid) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
     return spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
 }
 
@@ -109,7 +118,8 @@ int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_
     if (!L || !dY_dev || !dX_dev || T < 1 || !act_ok(act) || !aligned16(dY_dev) || !aligned16(dX_dev)) return MST_ERR_ARG;
     if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
-    if (use_dense_path(L, act, T)) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
+    note_call(L, act, T);
+    if (use_dense_path(L, act, T) || !L->views_valid) return dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s);
     return spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
 }
 
@@ -121,7 +131,10 @@ int mst_sparse_fc_bwd_weight(const mst_layer_t* L, const void* dY_dev, const voi
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    note_call(L, act, T);
     if (use_dense_weight_grad(L, act, T)) return dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+    const int rc = ensure_views(L, ws, s);
+    if (rc != MST_OK) return rc;
     return sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
 }
 
@@ -131,7 +144,7 @@ int mst_sparse_fc_bwd_weight_static(const mst_layer_t* L, const void* dY_dev, co
                                     mst_dtype act, mst_stream_t stream) {
     if (!L || !dY_dev || !X_dev || !dW_dev || T < 1 || !act_ok(act)) return MST_ERR_ARG;
     if (!aligned16(dY_dev) || !aligned16(X_dev) || !aligned16(dW_dev)) return MST_ERR_ARG;
-    if (!L->built) return MST_ERR_STATE;
+    if (!L->built || !L->views_valid) return MST_ERR_STATE;      // (it has no workspace to build unbuilt views with)
     // partial sums: one plane of entry slots per tile of TT tokens; the plane's stride is that of
     // the larger view because the view that drives the product is chosen on the device
     const size_t slots = (size_t)std::max(L->row.cap_pairs, L->col.cap_pairs) * 8;
@@ -155,6 +168,11 @@ int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_de
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    note_call(L, act, T);
+    if (!(use_dense_path(L, act, T) && use_dense_weight_grad(L, act, T))) {
+        const int rcv = ensure_views(L, ws, s);                   // a sparse kernel serves at least one of the two
+        if (rcv != MST_OK) return rcv;
+    }
     if (use_dense_path(L, act, T) || use_dense_weight_grad(L, act, T) || !bwd_fused_pays(L)) {
         // a dense contraction serves at least one of the two, or the layer is so sparse that
         // the separate kernels with their wider slabs are faster: the separate calls
@@ -169,7 +187,8 @@ int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_de
 
 int mst_layer_uses_dense(const mst_layer_t* L, mst_dtype act, int T, int weight_gradient) {
     if (!L || !act_ok(act) || T < 1) return MST_ERR_ARG;
-    return (weight_gradient ? use_dense_weight_grad(L, act, T) : use_dense_path(L, act, T)) ? 1 : 0;
+    // Y and dX have no workspace to build unbuilt views with: they then run dense whatever the density
+    return (weight_gradient ? use_dense_weight_grad(L, act, T) : (use_dense_path(L, act, T) || !L->views_valid)) ? 1 : 0;
 }
 
 int mst_gather_active(const mst_layer_t* L, const float* G_dev, float* dW_dev, mst_stream_t stream) {
@@ -186,6 +205,12 @@ int mst_layer_format_stats(const mst_layer_t* L, mst_format_stats* out, mst_stre
     if (!L || !out) return MST_ERR_ARG;
     if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
+    if (!L->views_valid) {                            // unbuilt (layer on the dense contractions): nothing stored
+        out->nnz = L->nnz;
+        out->row_view_slots = out->col_view_slots = 0;
+        out->row_view_efficiency = out->col_view_efficiency = 0.0;
+        return MST_OK;
+    }
     int pr = 0, pc = 0;
     MST_HIP(hipMemcpyAsync(&pr, L->row.ptr + L->row.nseg, 4, hipMemcpyDeviceToHost, s));
     MST_HIP(hipMemcpyAsync(&pc, L->col.ptr + L->col.nseg, 4, hipMemcpyDeviceToHost, s));
@@ -246,6 +271,7 @@ int mst_mask_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, int T
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, 1);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    note_call(L, act, T);
     if (needs_gradient(L, st)) {
         rc = gemm_mfma(GEMM_TN, dY_dev, act, X_dev, act, ws.G, L->O, L->I, T, ws.gemm, (int64_t)ws.gemm_floats, s);
         if (rc != MST_OK) return rc;
@@ -267,6 +293,7 @@ int mst_sparse_fc_bwd_weight_update(mst_layer_t* L, const void* dY_dev, const vo
     const Workspace ws = carve_workspace(ws_dev, L->O, L->I, L->cap, T);
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    note_call(L, act, T);
     if (needs_gradient(L, st)) {
         // one dense gradient serves both: the weight gradient is read from it at the positions
         // that are active now, then the update scores growth with it
@@ -277,8 +304,12 @@ int mst_sparse_fc_bwd_weight_update(mst_layer_t* L, const void* dY_dev, const vo
             MST_LAUNCH_CHECK();
         }
     } else {
-        rc = use_dense_weight_grad(L, act, T) ? dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s)
-                                              : sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+        if (use_dense_weight_grad(L, act, T)) {
+            rc = dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+        } else {
+            rc = ensure_views(L, ws, s);
+            if (rc == MST_OK) rc = sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
+        }
         if (rc != MST_OK) return rc;
     }
     return update_common(L, ws.G, rng_seed, ws, stats_out, s, st);

@@ -73,7 +73,14 @@ struct mst_layer {
     int* flat = nullptr;       // [cap] canonical flat indices
     int* rowptr = nullptr;     // [O + 1] canonical CSR row pointers
     float* Wd = nullptr;       // [N] dense W . M, maintained only while the dense path is in use
-    bool Wd_valid = false;
+    bool Wd_valid = false;     // Wd equals W . M
+    bool Wd_zeros = false;     // Wd is zero at every inactive position (survives a change of the values)
+    // The index views are built lazily: an update of a layer that the dense contractions serve
+    // (path choice at the batch size and type of the last product call) leaves them unbuilt; a
+    // call that needs them and has a workspace builds them, one without runs the dense product.
+    bool views_valid = false;
+    int hint_T = 0;            // batch size and activation type of the last product call (0: none yet)
+    int hint_act = 0;
     mst::View row;             // S = W   [O x I], used by fwd (and bwd_weight)
     mst::View col;             // S = W^T [I x O], used by bwd_input
     int* sddmm_view = nullptr; // device flag: view that drives bwd_weight (0 row, 1 col), set when the views are built
@@ -133,7 +140,10 @@ int64_t view_pair_capacity(int64_t cap, int64_t nchunk, int64_t R);
 int fill_u32(void* dst, uint32_t value, int64_t n_words, hipStream_t s);
 
 // ---- internal entry points implemented across the .hip files ----
-int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s);
+int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s, bool keep_dense_copy = false);
+int build_canonical(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s);
+int ensure_views(const mst_layer* L, const Workspace& ws, hipStream_t s);
+bool views_wanted(const mst_layer* L);
 int spmm(const View& v, const void* A, float* out, int T, int64_t nnz, mst_dtype act, hipStream_t s);
 int spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront);
 int sddmm(const mst_layer* L, const void* dY, const void* X, float* dW, int T, mst_dtype act,

@@ -421,6 +421,28 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     }
 }
 
+// vals / flat only (ascending flat index): one wavefront per row, as k_fill_row without the view
+__global__ void k_fill_canonical(const uint8_t* __restrict__ mask, const float* __restrict__ W, int O, int I,
+                                 const int* __restrict__ rowptr, float* __restrict__ vals, int* __restrict__ flat) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (r >= O) return;
+    const uint8_t* m = mask + (size_t)r * I;
+    const float* w = W + (size_t)r * I;
+    int canon = rowptr[r];
+    for (int i0 = 0; i0 < I; i0 += 64) {
+        const int i = i0 + lane;
+        const bool on = i < I && m[i] != 0;
+        const unsigned long long bal = __ballot(on);
+        if (on) {
+            const int k = canon + __popcll(bal & ((1ull << lane) - 1ull));
+            vals[k] = w[i];
+            flat[k] = r * I + i;
+        }
+        canon += __popcll(bal);
+    }
+}
+
 // block = (64 columns, chunk c of KC rows): rows i0 .. i0+63 of the col view, chunk c.  The
 // mask tile sits in LDS; thread (column j, row group rg of 32 rows) counts its rows, the
 // counts of the row groups before it give the position of its first entry in the column's
@@ -556,25 +578,61 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
 // array (read at the active positions only).  The col view needs the canonical indices the
 // row view pass writes to ws.cidx; its pointer kernel also names the view that drives the
 // weight gradient (either can: the product is symmetric in its dense operands).
-int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s) {
+int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s, bool keep_dense_copy) {
     unsigned long long* cost = reinterpret_cast<unsigned long long*>(ws.sel_state);
+    L->views_valid = false;
     int rc = build_one_view(L->row, true, L, Wsrc, ws, cost, s);
     if (rc != MST_OK) return rc;
     rc = build_one_view(L->col, false, L, Wsrc, ws, cost, s);
     if (rc != MST_OK) return rc;
-    L->Wd_valid = false;
+    L->views_valid = true;
+    if (!keep_dense_copy) L->Wd_valid = L->Wd_zeros = false;
+    return MST_OK;
+}
+
+// vals / flat / rowptr alone (three launches): what a layer served by the dense contractions needs
+int build_canonical(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s) {
+    L->views_valid = false;
+    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(L->mask, L->O, L->I, L->row.nchunk, 0, nullptr, ws.rowcnt);
+    MST_LAUNCH_CHECK();
+    const int rc = scan_excl_i32(ws.rowcnt, L->rowptr, L->O, s);
+    if (rc != MST_OK) return rc;
+    k_fill_canonical<<<(unsigned)cdiv(L->O, 4), 256, 0, s>>>(L->mask, Wsrc, L->O, L->I, L->rowptr, L->vals, L->flat);
+    MST_LAUNCH_CHECK();
     return MST_OK;
 }
 
 int refresh_dense_copy(mst_layer* L, hipStream_t s) {
-    int rc = fill_u32(L->Wd, 0u, L->N, s);
-    if (rc != MST_OK) return rc;
+    if (!L->Wd_zeros) {                              // the active set is unchanged since the last fill: only values move
+        const int rc = fill_u32(L->Wd, 0u, L->N, s);
+        if (rc != MST_OK) return rc;
+    }
     if (L->nnz > 0) {
         k_scatter_dense<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(L->vals, L->flat, L->nnz, L->Wd);
         MST_LAUNCH_CHECK();
     }
-    L->Wd_valid = true;
+    L->Wd_valid = L->Wd_zeros = true;
     return MST_OK;
+}
+
+// The views of a layer whose last update left them unbuilt, from the mask and the dense copy.
+int ensure_views(const mst_layer* Lc, const Workspace& ws, hipStream_t s) {
+    if (Lc->views_valid) return MST_OK;
+    mst_layer* L = const_cast<mst_layer*>(Lc);       // a cache of (mask, vals), not layer state
+    if (!L->Wd_valid) {
+        const int rc = refresh_dense_copy(L, s);
+        if (rc != MST_OK) return rc;
+    }
+    return build_views(L, L->Wd, ws, s, true);
+}
+
+// After an update: will a sparse kernel walk the views?  Judged at the batch size and type of
+// the last product call; a layer that has seen none yet, or is pinned to the sparse kernels, says yes.
+bool views_wanted(const mst_layer* L) {
+    if (L->path == MST_PATH_SPARSE) return true;
+    if (L->path == MST_PATH_DENSE) return false;
+    if (L->hint_T <= 0) return true;
+    return !(use_dense_path(L, (mst_dtype)L->hint_act, L->hint_T) && use_dense_weight_grad(L, (mst_dtype)L->hint_act, L->hint_T));
 }
 
 }  // namespace mst
@@ -684,7 +742,7 @@ int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
     if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
     L->Wd_valid = false;
-    if (L->nnz == 0) return MST_OK;
+    if (L->nnz == 0 || !L->views_valid) return MST_OK;     // unbuilt views take the values when they are built
     // every real entry slot lies below 4 * (nnz + #quad segments); the kernel stops at ptr[nseg] * 8
     const View &r = L->row, &c = L->col;
     const unsigned rb = (unsigned)cdiv(4 * (L->nnz + (int64_t)r.nchunk * r.NB * 4), 256);

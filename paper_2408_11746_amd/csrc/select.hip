@@ -559,14 +559,19 @@ __global__ void k_update_init(uint64_t* __restrict__ state, uint64_t k0, uint64_
 }
 
 // kept weights go to the dense scratch, pruned positions leave the mask (psel null: nothing is pruned)
+// (zero_pruned: Wd is the layer's dense copy, whose inactive positions must read 0)
 __global__ void k_apply_prune(const float* __restrict__ vals, const int* __restrict__ flat,
                               const uint8_t* __restrict__ psel, int64_t nnz, float* __restrict__ Wd,
-                              uint8_t* __restrict__ mask) {
+                              uint8_t* __restrict__ mask, int zero_pruned) {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= nnz) return;
     const int f = flat[k];
-    if (psel && psel[k]) mask[f] = 0;
-    else Wd[f] = vals[k];
+    if (psel && psel[k]) {
+        mask[f] = 0;
+        if (zero_pruned) Wd[f] = 0.f;
+    } else {
+        Wd[f] = vals[k];
+    }
 }
 
 static unsigned digit_blocks(int64_t n) { return (unsigned)std::min<int64_t>(cdiv(n, SEL_NT * 4), 256); }
@@ -576,7 +581,8 @@ static unsigned rand_blocks(int64_t n) { return (unsigned)std::min<int64_t>(cdiv
 // update, side by side: 4 digit launches, one tie-count launch, one flag launch
 template <typename PK>
 static int select_prune_and_grad(PK pk, int64_t nnz, int64_t n_prune, GradKeys gk, int64_t N, int64_t n_grad,
-                                 uint64_t* st_prune, uint64_t* st_grad, const Workspace& ws, uint8_t* mask, hipStream_t s) {
+                                 uint64_t* st_prune, uint64_t* st_grad, const Workspace& ws, uint8_t* mask, float* Wnew,
+                                 hipStream_t s) {
     const bool do_p = n_prune > 0 && nnz > 0, do_g = n_grad > 0;
     if (!do_p && !do_g) return MST_OK;
     const int nb0 = do_p ? (int)digit_blocks(nnz) : 0, nb1 = do_g ? (int)digit_blocks(N) : 0;
@@ -592,7 +598,7 @@ static int select_prune_and_grad(PK pk, int64_t nnz, int64_t n_prune, GradKeys g
     k_select_ties2<PK, GradKeys><<<(unsigned)(fb0 + fb1), 256, 0, s>>>(pk, nnz, st_prune, blk_p, fb0, gk, N, st_grad, blk_g);
     MST_LAUNCH_CHECK();
     const FlagSink sink_p{ws.psel, 1, 1, nullptr, nullptr};
-    const FlagSink sink_g{ws.sel, 2, 1, mask, ws.Wd};
+    const FlagSink sink_g{ws.sel, 2, 1, mask, Wnew};
     k_select_flag2<PK, GradKeys><<<(unsigned)(fb0 + fb1), 256, 0, s>>>(pk, nnz, st_prune, blk_p, sink_p, fb0, gk, N, st_grad, blk_g,
                                                                      sink_g);
     MST_LAUNCH_CHECK();
@@ -603,6 +609,16 @@ int mask_update_device(mst_layer* L, const float* G, const mst_update_stats& st,
                        const Workspace& ws, hipStream_t s) {
     const int64_t N = L->N, nnz = L->nnz;
     int rc;
+    // Where the new dense weights are formed.  A layer that stays on the dense contractions after
+    // this update gets them straight into its dense copy (zero at every inactive position: kept
+    // weights are rewritten, pruned and grown positions written 0) and only vals / flat / rowptr
+    // are rebuilt; otherwise they go to the workspace and both index views are rebuilt from them.
+    const int64_t nnz_before = L->nnz;
+    L->nnz = st.nnz_after;
+    const bool with_views = views_wanted(L);
+    L->nnz = nnz_before;
+    float* const Wnew = with_views ? ws.Wd : L->Wd;
+    if (!with_views && !L->Wd_zeros && (rc = fill_u32(L->Wd, 0u, N, s)) != MST_OK) return rc;
     uint64_t* st0 = ws.sel_state;
     k_update_init<<<(unsigned)cdiv((int64_t)SEL_STATES * SEL_STATE_WORDS, 256), 256, 0, s>>>(
         st0, (uint64_t)st.n_prune, (uint64_t)st.n_grad, (uint64_t)st.n_rand);
@@ -614,10 +630,10 @@ int mask_update_device(mst_layer* L, const float* G, const mst_update_stats& st,
     const GradKeys gk{G, L->mask};
     uint64_t* st_grad = st0 + SEL_STATE_WORDS;
     if (L->prune_lambda == 0.f)
-        rc = select_prune_and_grad(PruneKeys{L->vals}, nnz, st.n_prune, gk, N, st.n_grad, st0, st_grad, ws, L->mask, s);
+        rc = select_prune_and_grad(PruneKeys{L->vals}, nnz, st.n_prune, gk, N, st.n_grad, st0, st_grad, ws, L->mask, Wnew, s);
     else
         rc = select_prune_and_grad(ScoredPruneKeys{L->vals, L->flat, G, L->prune_lambda}, nnz, st.n_prune, gk, N, st.n_grad,
-                                   st0, st_grad, ws, L->mask, s);
+                                   st0, st_grad, ws, L->mask, Wnew, s);
     if (rc != MST_OK) return rc;
 
     if (st.n_rand > 0) {
@@ -631,18 +647,21 @@ int mask_update_device(mst_layer* L, const float* G, const mst_update_stats& st,
         MST_LAUNCH_CHECK();
         k_rand_finish<<<1, SEL_NT, 0, s>>>(st_rand, list);
         MST_LAUNCH_CHECK();
-        const FlagSink sink_r{ws.sel, 3, 0, L->mask, ws.Wd};
+        const FlagSink sink_r{ws.sel, 3, 0, L->mask, Wnew};
         k_select_flag<RandKeys><<<(unsigned)cdiv(N, SELECT_BLOCK), 256, 0, s>>>(rk, N, st_rand, reinterpret_cast<int*>(ws.blk), sink_r);
         MST_LAUNCH_CHECK();
     }
 
     if (nnz > 0) {
         const bool pruned = st.n_prune > 0;
-        k_apply_prune<<<(unsigned)cdiv(nnz, 256), 256, 0, s>>>(L->vals, L->flat, pruned ? ws.psel : nullptr, nnz, ws.Wd, L->mask);
+        k_apply_prune<<<(unsigned)cdiv(nnz, 256), 256, 0, s>>>(L->vals, L->flat, pruned ? ws.psel : nullptr, nnz, Wnew, L->mask,
+                                                               with_views ? 0 : 1);
         MST_LAUNCH_CHECK();
     }
     L->nnz = st.nnz_after;
-    return build_views(L, ws.Wd, ws, s);
+    if (with_views) return build_views(L, ws.Wd, ws, s);
+    L->Wd_valid = L->Wd_zeros = true;
+    return build_canonical(L, L->Wd, ws, s);
 }
 
 }  // namespace mst
