@@ -98,6 +98,8 @@ int mst_spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront) {
 
 int mst_gemm_force_fp32_mfma(int on) { return gemm_force_fp32_mfma(on); }
 
+int mst_gemm_last_tile(void) { return gemm_last_tile(); }
+
 int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront) {
     return bwd_fused_force_shape(wavefronts_per_workgroup, quads_per_wavefront);
 }

@@ -158,6 +158,7 @@ enum GemmKind { GEMM_TN = 0, GEMM_NT = 1, GEMM_NN = 2 };
 int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_dtype b_dt, float* C,
               int M, int N, int Kdim, float* split_ws, int64_t split_ws_floats, hipStream_t s, int* left_unsummed = nullptr);
 int gemm_force_fp32_mfma(int on);
+int gemm_last_tile();
 int mask_update_device(mst_layer* L, const float* G, const mst_update_stats& st, uint64_t seed,
                        const Workspace& ws, hipStream_t s);
 int dense_products_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s);

@@ -695,6 +695,191 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
             }
 }
 
+// The same split product on a 256 x 160 workgroup tile, for outputs 1280 wide (five 256-tiles
+// across leave 160 tiles for 256 CUs at T = 8192; eight 160-tiles across give 256).  A m-major
+// (NT and NN products).  Eight wavefronts stacked along m, each 32 rows x 160 columns (5 MFMA
+// tiles, 80 accumulator registers); per 16-k slice a wavefront reads 2 A and 10 B fragments for 15
+// MFMAs, issued product-major so that the three products of an accumulator are five apart.
+// Staging roles (p = tid & 255, h = tid >> 8, uniform per wavefront):
+//   m-major B (NT): threads 0..255 stage A as in k_gemm_split256; of threads 256..511 the first
+//     160 stage B, unit p & 3 of rows 16 (p >> 4) + 4 ((p >> 2) & 3) + it, it = 0..3; the other 96
+//     repeat the first 96 (same loads, same LDS values), so the loop has no predicate.
+//   k-major B (NN): every thread stages two m-major pieces of A (it = 2 h, 2 h + 1) and two columns
+//     of B: the patch 8 k x 2 columns (k group (tid / 80) & 3, columns 2 (tid % 80) ..) of the
+//     first 320 threads, repeated by the rest; registers as the mixed form of k_gemm_split256.
+// The next tile is split and stored during the second 16-k slice, one pair after every MFMA.
+// (Measured and dropped for a k-major B: four-byte loads that give both roles one register
+// form, and a mask-select between the two forms: both leave the loads too little time.)
+constexpr int BN3 = 160;
+template <bool B_KMAJOR>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+                       float* __restrict__ C, int M, int N, int Kdim, int k_per_split, int64_t split_stride) {
+    constexpr int PLANE = BM2 * 64;
+    constexpr int LAYOUT = B_KMAJOR ? 2 : 1;
+    __shared__ __attribute__((aligned(16))) char lds[2 * 4 * PLANE];     // [stage][A hi, A lo, B hi, B lo]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave * 32;
+    const int gn = N / BN3, ntiles = (M / BM2) * gn, nsplit = (Kdim + k_per_split - 1) / k_per_split;
+    const int Q = (ntiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int split = slot / Q, tile_id = xcd * Q + slot % Q;
+    if (tile_id >= ntiles || split >= nsplit) return;
+    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN3;
+    const int kbeg = split * k_per_split;
+    const int kend = min(Kdim, kbeg + k_per_split);
+    float* Cz = C + (int64_t)split * split_stride;
+
+    floatx16 acc[5];
+#pragma unroll
+    for (int j = 0; j < 5; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+    const int h = __builtin_amdgcn_readfirstlane(tid >> 8), p = tid & 255;
+    const int64_t pa = 4 * lda, pb = 4 * ldb;
+    const char* base0;                                // NT: this thread's operand; NN: A
+    const char* base1 = nullptr;                      // NN: B
+    uint32_t voff[4], wr_unit[4];
+    if (LAYOUT == 1) {
+        if (h == 0) {
+            base0 = reinterpret_cast<const char*>(A) + (int64_t)m0 * pa;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                voff[it] = (uint32_t)(mmajor_row(p, it) * pa + 32 * (p & 3));
+                wr_unit[it] = bf_unit32(mmajor_row(p, it), p & 3);
+            }
+        } else {
+            const int q = p < BN3 ? p : p - BN3;
+            base0 = reinterpret_cast<const char*>(B) + (int64_t)n0 * pb;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int row = 16 * (q >> 4) + 4 * ((q >> 2) & 3) + it;
+                voff[it] = (uint32_t)(row * pb + 32 * (q & 3));
+                wr_unit[it] = 2 * PLANE + bf_unit32(row, q & 3);
+            }
+        }
+    } else {
+        base0 = reinterpret_cast<const char*>(A) + (int64_t)m0 * pa;
+        base1 = reinterpret_cast<const char*>(B + n0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            voff[t] = (uint32_t)(mmajor_row(p, 2 * h + t) * pa + 32 * (p & 3));
+            wr_unit[t] = bf_unit32(mmajor_row(p, 2 * h + t), p & 3);
+        }
+        const int q = tid < 320 ? tid : tid - 320, nq = q % 80, kg = q / 80;
+        voff[2] = (uint32_t)(8 * kg * pb + 8 * nq);
+        voff[3] = 0;
+        wr_unit[2] = 2 * PLANE + bf_unit32(2 * nq, kg);
+        wr_unit[3] = 2 * PLANE + bf_unit32(2 * nq + 1, kg);
+    }
+    float4 r[8];
+    auto fetch = [&](int k0) __attribute__((always_inline)) {
+        const char* col = base0 + 4 * (int64_t)k0;
+        if (LAYOUT == 1) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                r[2 * it] = *reinterpret_cast<const float4*>(col + voff[it]);
+                r[2 * it + 1] = *reinterpret_cast<const float4*>(col + voff[it] + 16);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                r[2 * t] = *reinterpret_cast<const float4*>(col + voff[t]);
+                r[2 * t + 1] = *reinterpret_cast<const float4*>(col + voff[t] + 16);
+            }
+            const char* row = base1 + (int64_t)k0 * pb;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float2 e = *reinterpret_cast<const float2*>(row + (2 * t) * pb + voff[2]);
+                const float2 o = *reinterpret_cast<const float2*>(row + (2 * t + 1) * pb + voff[2]);
+                r[4 + t] = make_float4(e.x, e.y, o.x, o.y);
+            }
+        }
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        char* const wr = lds + buf * 4 * PLANE;
+#pragma unroll
+        for (int pc = 0; pc < 4; ++pc) {
+            uint4 hv, lv;
+            split256_pair<LAYOUT>(r, pc, 0, hv.x, lv.x);
+            split256_pair<LAYOUT>(r, pc, 1, hv.y, lv.y);
+            split256_pair<LAYOUT>(r, pc, 2, hv.z, lv.z);
+            split256_pair<LAYOUT>(r, pc, 3, hv.w, lv.w);
+            *reinterpret_cast<uint4*>(wr + wr_unit[pc]) = hv;
+            *reinterpret_cast<uint4*>(wr + PLANE + wr_unit[pc]) = lv;
+        }
+    };
+    const int lk = lane >> 5, lm = lane & 31;
+    auto step = [&](int buf, auto stage_c, auto fetch_c, int knext) __attribute__((always_inline)) {
+        constexpr bool STAGE = decltype(stage_c)::value, FETCH = decltype(fetch_c)::value;
+        const char* Ah = lds + buf * 4 * PLANE;
+        const char* Al = Ah + PLANE;
+        const char* Bh = Ah + 2 * PLANE;
+        const char* Bl = Ah + 3 * PLANE;
+        char* const wr = lds + (buf ^ 1) * 4 * PLANE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const uint32_t ua = bf_unit32(wm + lm, 2 * ks + lk);
+            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Ah + ua);
+            const bf16x8 al = *reinterpret_cast<const bf16x8*>(Al + ua);
+            bf16x8 bh[5], bl[5];
+#pragma unroll
+            for (int j = 0; j < 5; ++j) {
+                const uint32_t ub = bf_unit32(32 * j + lm, 2 * ks + lk);
+                bh[j] = *reinterpret_cast<const bf16x8*>(Bh + ub);
+                bl[j] = *reinterpret_cast<const bf16x8*>(Bl + ub);
+            }
+            uint32_t hw[4], lw[4];
+#pragma unroll
+            for (int e = 0; e < 15; ++e) {                          // e = 5 t + j; products t: lo.hi, hi.lo, hi.hi
+                const int t = e / 5, j = e % 5;
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t == 0 ? al : ah, t == 1 ? bl[j] : bh[j], acc[j], 0, 0, 0);
+                if (STAGE && ks == 1) {
+                    // pair e (and the sixteenth with the last MFMA); a piece's two units leave after its fourth pair
+#pragma unroll
+                    for (int pr = e; pr < (e == 14 ? 16 : e + 1); ++pr) {
+                        split256_pair<LAYOUT>(r, pr >> 2, pr & 3, hw[pr & 3], lw[pr & 3]);
+                        if ((pr & 3) == 3) {
+                            *reinterpret_cast<uint4*>(wr + wr_unit[pr >> 2]) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                            *reinterpret_cast<uint4*>(wr + PLANE + wr_unit[pr >> 2]) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0x124);
+            }
+        }
+        if (FETCH) fetch(knext);
+    };
+    using std::true_type;
+    using std::false_type;
+
+    fetch(kbeg);
+    stage(0);
+    if (kbeg + SPK2 < kend) fetch(kbeg + SPK2);
+    __syncthreads();
+    int buf = 0, k0 = kbeg;
+    for (; k0 + 2 * SPK2 < kend; k0 += SPK2, buf ^= 1) {
+        step(buf, true_type{}, true_type{}, k0 + 2 * SPK2);
+        __syncthreads();
+    }
+    if (k0 + SPK2 < kend) {
+        step(buf, true_type{}, false_type{}, 0);
+        __syncthreads();
+        buf ^= 1;
+    }
+    step(buf, false_type{}, false_type{}, 0);
+
+#pragma unroll
+    for (int j = 0; j < 5; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = m0 + wm + 8 * (v >> 2) + 4 * lk + (v & 3);
+            const int n = n0 + j * 32 + lm;
+            Cz[(int64_t)m * N + n] = acc[j][v];
+        }
+}
+
 // G = A^T B with BOTH operands bfloat16 and k-major (A [K x M], B [K x N]): the same 256 x 256
 // workgroup tile, eight wavefronts of 64 x 128 and two LDS stages as k_gemm_split256, k steps of
 // 64: the two planes of an operand hold its k halves (0..31, 32..63) instead of hi and lo, one
@@ -897,22 +1082,26 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
 // needs on ONE XCD.  Modelled time = rounds x (k steps per workgroup + start-up and output of a
 // workgroup, in steps) x time of a step, plus the traffic of the partial outputs.  Constants
 // from timings on MI355X: a 64-k step of two co-resident 128 x 128 tiles 3.3 us, a 32-k step of
-// a 256 x 256 tile 2.04 us (1.6x the work per CU and time), start-up + output 7 and 14 steps.
+// a 256 x 256 tile 2.0 us (1.6x the work per CU and time), of a 256 x 160 tile 1.8 us (less work
+// per staged byte: it pays only where it fills CUs that the 256 tile leaves idle), start-up +
+// output 7, 13 and 7 steps.
 // The model reproduces the measured times of the GPT-2 small / large products within 15 % and
 // orders the candidates as measured.
 struct SplitPlan {
     int tile, nsplit;
 };
-static SplitPlan plan_split(int M, int N, int Kdim, int64_t max_split, bool summed, bool allow128, bool allow256) {
+static SplitPlan plan_split(int M, int N, int Kdim, int64_t max_split, bool summed, bool allow128, bool allow256,
+                            bool allow160) {
     static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
     SplitPlan best{0, 1};
     double best_cost = 0.0;
-    for (int tile : {128, 256}) {
-        if (tile == 128 ? !allow128 : !allow256) continue;
+    for (int tile : {128, 256, 160}) {                // 160: 256 rows x 160 columns (A m-major only)
+        if (tile == 128 ? !allow128 : tile == 256 ? !allow256 : !allow160) continue;
+        const int tm = tile == 128 ? 128 : 256, tn = tile;
         const int kstep = tile == 128 ? SPK : 32, places = tile == 128 ? 64 : 32;
-        const double unit_us = tile == 128 ? 3.3 : 2.04, wg_steps = tile == 128 ? 7.0 : 14.0;
-        if (M % tile != 0 || N % tile != 0 || Kdim % kstep != 0) continue;
-        const int64_t Q = cdiv((int64_t)(M / tile) * (N / tile), 8);
+        const double unit_us = tile == 128 ? 3.3 : tile == 256 ? 2.0 : 1.8, wg_steps = tile == 128 ? 7.0 : tile == 256 ? 13.0 : 7.0;
+        if (M % tm != 0 || N % tn != 0 || Kdim % kstep != 0) continue;
+        const int64_t Q = cdiv((int64_t)(M / tm) * (N / tn), 8);
         for (int ns : cand) {
             if (ns > 1 && (ns > max_split || Kdim / ns < 512)) continue;
             const double steps = (double)cdiv(cdiv(Kdim, ns), kstep);
@@ -929,32 +1118,44 @@ static SplitPlan plan_split(int M, int N, int Kdim, int64_t max_split, bool summ
     return best;
 }
 static int g_gemm_fp32_only = 0;          // test hook: 1 = never use the bf16-split kernel
-static int g_split_tile = 0;              // test hook: 0 = automatic, 128 / 256 = that workgroup tile when the shape allows it
+static int g_last_tile = 0;               // workgroup tile of the last split-kernel launch (128 / 256 / 160), 0: another kernel
+static int g_split_tile = 0;              // test hook: 0 = automatic, 128 / 256 / 160 = that workgroup tile when the shape allows it
 
-int gemm_force_fp32_mfma(int on) {       // 0 automatic, 1 fp32 MFMA kernel, 128 / 256: split kernel with that tile
+int gemm_last_tile() { return g_last_tile; }
+
+int gemm_force_fp32_mfma(int on) {       // 0 automatic, 1 fp32 MFMA kernel, 128 / 256 / 160: split kernel with that tile
     g_gemm_fp32_only = on == 1 ? 1 : 0;
-    g_split_tile = (on == 128 || on == 256) ? on : 0;
+    g_split_tile = (on == 128 || on == 256 || on == 160) ? on : 0;
     return MST_OK;
 }
 
-static bool split_ok(int M, int N, int Kdim, int64_t lda, int64_t ldb) {
-    return !g_gemm_fp32_only && M % BM == 0 && N % BN == 0 && Kdim % SPK == 0 && lda % 4 == 0 && ldb % 4 == 0;
+// whole tiles of one of the split kernels: 128 x 128 (256 x 256 is a subset) or, for an m-major A, 256 x 160
+static bool split_ok(int M, int N, int Kdim, int64_t lda, int64_t ldb, bool a_kmajor) {
+    if (g_gemm_fp32_only || Kdim % SPK != 0 || lda % 4 != 0 || ldb % 4 != 0) return false;
+    return (M % BM == 0 && N % BN == 0) || (!a_kmajor && M % BM2 == 0 && N % BN3 == 0);
 }
 
 template <bool AK, bool BKM>
 static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
                         float* split_ws, int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
     const int64_t mn = (int64_t)M * N;
-    const SplitPlan plan = plan_split(M, N, Kdim, split_ws ? split_ws_floats / mn : 1, left_unsummed == nullptr,
-                                      g_split_tile != 256, g_split_tile != 128);
-    const int tile = plan.tile ? plan.tile : 128;     // a pinned 256 tile that does not fit: the 128 kernel
-    const int nsplit0 = plan.tile ? plan.nsplit : 1;
+    const int pin = g_split_tile;
+    SplitPlan plan = plan_split(M, N, Kdim, split_ws ? split_ws_floats / mn : 1, left_unsummed == nullptr,
+                                pin == 0 || pin == 128, pin == 0 || pin == 256, !AK && (pin == 0 || pin == 160));
+    if (plan.tile == 0)                               // the pinned tile does not fit this shape: any that does
+        plan = plan_split(M, N, Kdim, split_ws ? split_ws_floats / mn : 1, left_unsummed == nullptr, true, true, !AK);
+    const int tile = plan.tile, nsplit0 = plan.nsplit;
+    g_last_tile = tile;
     const int kstep = tile == 128 ? SPK : SPK2;
     const int kps = (int)(cdiv(cdiv(Kdim, nsplit0), kstep) * kstep);
     const int nsplit = (int)cdiv(Kdim, kps);
-    const unsigned grid = (unsigned)(8 * cdiv((int64_t)(M / tile) * (N / tile), 8) * nsplit);
+    const int tm = tile == 128 ? 128 : 256;
+    const unsigned grid = (unsigned)(8 * cdiv((int64_t)(M / tm) * (N / tile), 8) * nsplit);
     float* dst = nsplit > 1 ? split_ws : C;
-    if (tile == 256)
+    if (tile == 160) {
+        if constexpr (!AK)
+            k_gemm_split_n160<BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+    } else if (tile == 256)
         k_gemm_split256<AK, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
     else
         k_gemm_split<AK, BKM><<<grid, 256, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
@@ -1033,23 +1234,24 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
 int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_dtype b_dt, float* C,
               int M, int N, int Kdim, float* split_ws, int64_t split_ws_floats, hipStream_t s, int* left_unsummed) {
     const bool ab = a_dt == MST_BF16, bb = b_dt == MST_BF16;
+    g_last_tile = 0;
     switch (kind) {
         case GEMM_TN:
             if (ab != bb) return MST_ERR_ARG;
             if (ab) return launch_tn_bf16(A, B, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
-            if (split_ok(M, N, Kdim, M, N))
+            if (split_ok(M, N, Kdim, M, N, true))
                 return launch_split<true, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             return launch<float, true, float, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NT:
             if (bb) return MST_ERR_ARG;
             if (ab) return launch<uint16_t, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
-            if (split_ok(M, N, Kdim, Kdim, Kdim))
+            if (split_ok(M, N, Kdim, Kdim, Kdim, false))
                 return launch_split<false, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             return launch<float, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NN:
             if (bb) return MST_ERR_ARG;
             if (ab) return launch<uint16_t, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
-            if (split_ok(M, N, Kdim, Kdim, N))
+            if (split_ok(M, N, Kdim, Kdim, N, false))
                 return launch_split<false, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             return launch<float, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
     }

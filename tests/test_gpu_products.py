@@ -337,6 +337,40 @@ def test_dense_products_on_the_bf16_split_kernel(T, I, O):
         assert not np.array_equal(got128, got_f32) or e0 == 0.0         # the kernels really differ
 
 
+@pytest.mark.parametrize("T,I,O", [(256, 320, 128), (512, 320, 640), (768, 128, 160), (1024, 640, 320)])
+def test_dense_products_on_the_256_by_160_tile(T, I, O):
+    """Forward (output O wide) and input gradient (output I wide) of a dense layer pinned to the
+    256 x 160 workgroup tile of the split kernel where the output width is a multiple of 160
+    (the other product falls back to the 128 tile), against the oracle."""
+    print("case", T, I, O, flush=True)
+    X, dY = synth.make_activations(45, 2, T, I, O)
+    X = (X * np.exp2(synth.normal(45, 7, X.shape) * 3)).astype(np.float32)
+    W = synth.normal(45, 3, (O, I), 0.02)
+    M = np.ones((O, I), np.uint8)
+    rig = Rig(W, M, T, cap=O * I)
+    rig.layer.set_path(mst.MST_PATH_DENSE)
+    tiles = {}
+    try:
+        mst.mst_gemm_force_fp32_mfma(160)
+        Y = rig.fwd(X)
+        tiles["Y"] = mst.mst_gemm_last_tile()
+        dX = rig.bwd_input(dY)
+        tiles["dX"] = mst.mst_gemm_last_tile()
+        mst.mst_gemm_force_fp32_mfma(128)
+        Y128, dX128 = rig.fwd(X), rig.bwd_input(dY)
+    finally:
+        mst.mst_gemm_force_fp32_mfma(0)
+    for name, got, got128, ref, width, depth in (("Y", Y, Y128, opr.fc_fwd(X, W, M), O, I),
+                                                 ("dX", dX, dX128, opr.fc_bwd_input(dY, W, M), I, O)):
+        e = rel_err(got, ref)
+        print(name, "width", width, "tile", tiles[name], "err %.3g" % e, flush=True)
+        assert e <= 2e-5
+        if width % 160 == 0 and depth % 64 == 0:
+            assert tiles[name] == 160                    # the pinned tile really ran
+            if width % 128 == 0:
+                np.testing.assert_array_equal(got, got128)   # every tile adds a result's terms in the same order
+
+
 @pytest.mark.parametrize("T,I,O", [(64, 256, 256), (128, 256, 512), (1088, 512, 256), (2048, 768, 768)])
 def test_bf16_dense_gradient_on_both_workgroup_tiles(T, I, O):
     """G = dY^T X with bfloat16 operands on whole 256 x 256 tiles: the two-stage 256-tile kernel
