@@ -797,7 +797,8 @@ def cpu_baseline_sweep(synth, seed, cfg):
     t0 = time.perf_counter()
     flops, n_upd = 0, 0
     Wp = Mp = Gp = None
-    for p, d in enumerate(cyc):
+    for p, d in enumerate(cyc + cyc):                       # two passes of the cycle: 10-15 s of host work
+        p %= len(cyc)
         for lid, (lname, I, O) in enumerate(cfg["layers"]):
             W, M = Ws[lid], Ms[lid][p]
             X, dY = acts[lid]
@@ -814,7 +815,7 @@ def cpu_baseline_sweep(synth, seed, cfg):
         n_upd += 1
     dt = time.perf_counter() - t0
     return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": _oracle_threads(), "kind": "oracle",
-            "sample": "one pass of the density cycle %s: fwd+bwd_input+bwd_weight of the four layers on the first %d of "
+            "sample": "two passes of the density cycle %s: fwd+bwd_input+bwd_weight of the four layers on the first %d of "
                       "%d tokens (dense masked fp64 numpy products, masks drawn per density) plus %d Mixed-Growing "
                       "updates of the 1280x1280 layer, %.1f s in all; effective (nonzero-only) FLOPs of the products "
                       "over that time" % (cyc, Ts, T, n_upd, dt)}
