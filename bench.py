@@ -199,14 +199,16 @@ def split_gemm_applies(M, N, K):
     return M % 128 == 0 and N % 128 == 0 and K % 64 == 0
 
 
-def dense_gemm_roofline(flops, ms, act, M, N, K):
+def dense_gemm_roofline(flops, ms, act, M, N, K, bf16_products=1.0):
     """A dense contraction: the matrix cores' peak for the dtype of the MFMA instructions that
     run.  fp32 operands on whole tiles run as 3 bf16 MFMA products per term: executed flops =
-    3 x the product's 2 M N K, against the bf16 peak."""
+    3 x the product's 2 M N K, against the bf16 peak.  With bfloat16 activations the weight
+    gradient is one product per term, Y and dX (fp32 weights split hi + lo) two."""
     tf = flops / ms / 1e9
     if act == "bf16":
-        return dict(bound="mfma", achieved=round(tf, 2), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=round(tf / MFMA_BF16_PEAK_TFLOPS, 4), mfma_dtype="bf16")
+        return dict(bound="mfma", achieved=round(bf16_products * tf, 2), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(bf16_products * tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                    mfma_dtype="bf16 (%.3g MFMA products per term)" % bf16_products)
     if split_gemm_applies(M, N, K):
         return dict(bound="mfma", achieved=round(3 * tf, 2), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=round(3 * tf / MFMA_BF16_PEAK_TFLOPS, 4), mfma_dtype="bf16 (fp32 operands split hi + lo, 3 products)",
@@ -224,7 +226,8 @@ def roofline_of(row, L, act, kernel, traffic_cfg):
         t_alu = row["alg_flops"] / (ALU_FP32_PEAK_TFLOPS * 1e12)
         if row.get("path") == "dense-mfma":
             mnk = row.get("dense_mnk") or ((L.T, L.O, L.I) if row["call"] == "fwd" else (L.T, L.I, L.O))
-            roof = dense_gemm_roofline(row["dense_flops"], row["avg_ms"], act, *mnk)
+            roof = dense_gemm_roofline(row["dense_flops"], row["avg_ms"], act, *mnk,
+                                       bf16_products=row.get("bf16_products", 1.0))
         elif t_hbm >= t_alu:
             roof = dict(bound="hbm", achieved=row["hbm_gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(row["hbm_gbs"] / HBM_PEAK_GBS, 4))
@@ -360,7 +363,7 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
                 fl = L.flops_product() * (2 if kind == "bwd" else 1)
                 # LDS operand bytes of the walk: 4 bytes per token and stored entry slot of the view walked
                 slots = fs["row_view_slots"] if kind == "fwd" else fs["col_view_slots"] if kind in ("bwd", "bwd_input") else 0
-                product_row_numbers(row, ms, by, fl, 4 * slots * T, lds_peak)
+                product_row_numbers(row, ms, by, fl, 4 * slots * T if row["path"] == "sparse" else 0, lds_peak)
                 tot = ms * len(pairs)
                 if dominant is None or tot > dominant[0]:
                     dominant = (tot, row, L)
@@ -374,7 +377,8 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
     # small second kernel unless a dense contraction serves one of the two gradients (then separate kernels)
     dp, dw = dense_prod[dL.name], dense_wgrad[dL.name]
     spmm_k = "k_spmm / k_spmm64 (launch shape chosen per call)"
-    gemm_k = "k_gemm_split256 / k_gemm_split (fp32 operands as bf16 hi + lo)" if act == "f32" else "k_gemm (fp32 MFMA)"
+    gemm_k = "k_gemm_split256 / k_gemm_split_n160 / k_gemm_split (fp32 operands as bf16 hi + lo)" if act == "f32" else \
+        "k_gemm_a16_256 (bfloat16 activations x fp32 weights as bf16 hi + lo, 2 products per term)"
     wgrad_dense_k = ("k_gemm_tn_bf16" if act == "bf16" else "k_gemm_split256<TN> / k_gemm_split<TN>") + " + k_gather_flat"
     kernel = {"fwd": gemm_k if dp else spmm_k,
               "bwd_input": gemm_k if dp else spmm_k,
@@ -386,6 +390,8 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
         legs = 2 if drow["call"] == "bwd" else 1
         drow["dense_flops"] = legs * 2.0 * T * dL.O * dL.I
         drow["dense_mnk"] = {"fwd": (T, dL.O, dL.I), "bwd_input": (T, dL.I, dL.O)}.get(drow["call"], (dL.O, dL.I, T))
+        # bfloat16 activations: Y, dX = 2 MFMA products per term, weight gradient 1, the one-call backward both
+        drow["bf16_products"] = {"fwd": 2.0, "bwd_input": 2.0, "bwd_weight": 1.0, "bwd": 1.5}[drow["call"]]
     roof = roofline_of(drow, dL, act, kernel, name)
 
     out = {

@@ -695,6 +695,182 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
             }
 }
 
+// Y = X Wd^T and dX = dY Wd with BFLOAT16 activations (A m-major, bfloat16) and the fp32 dense
+// weight copy (B m-major for NT, k-major for NN): A is exact in bfloat16, so a term is
+// a b_hi + a b_lo, two MFMAs, and A's tile is copied to LDS as it is (one 16-byte unit = eight k of
+// one row).  Tile, wavefront layout, LDS stages and swizzle of k_gemm_split256; every thread
+// stages two units of A (rows mmajor_row(p, 2 h + t), unit p & 3) and two pieces of B (m-major:
+// the same rows and unit; k-major: the patch 8 k x 2 columns of the mixed form there).  A step
+// is 32 MFMAs; the eight hi/lo pairs of the next B tile follow every second MFMA of its second half.
+template <bool B_KMAJOR>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_gemm_a16_256(const uint16_t* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
+                    float* __restrict__ C, int M, int N, int Kdim) {
+    constexpr int PLANE = BM2 * 64;
+    __shared__ __attribute__((aligned(16))) char lds[2 * 4 * PLANE];     // [stage][A, (unused), B hi, B lo]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+    const int gn = N / BN2, ntiles = (M / BM2) * gn;
+    const int Q = (ntiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tile_id = xcd * Q + slot;
+    if (slot >= Q || tile_id >= ntiles) return;
+    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN2;
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int h = __builtin_amdgcn_readfirstlane(tid >> 8), p = tid & 255;
+    const int64_t pa = 2 * lda, pb = 4 * ldb;
+    const char* const base_a = reinterpret_cast<const char*>(A) + (int64_t)m0 * pa;
+    const char* const base_b = B_KMAJOR ? reinterpret_cast<const char*>(B + n0)
+                                        : reinterpret_cast<const char*>(B) + (int64_t)n0 * pb;
+    uint32_t voff_a[2], voff_b[2], wr_a[2], wr_b[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int row = mmajor_row(p, 2 * h + t);
+        voff_a[t] = (uint32_t)(row * pa + 16 * (p & 3));
+        wr_a[t] = bf_unit32(row, p & 3);
+        if (!B_KMAJOR) {
+            voff_b[t] = (uint32_t)(row * pb + 32 * (p & 3));
+            wr_b[t] = 2 * PLANE + bf_unit32(row, p & 3);
+        } else {
+            wr_b[t] = 2 * PLANE + bf_unit32(4 * (p & 63) + 2 * h + t, p >> 6);
+        }
+    }
+    if (B_KMAJOR) {
+        voff_b[0] = (uint32_t)(8 * (p >> 6) * pb + 16 * (p & 63) + 8 * h);
+        voff_b[1] = 0;
+    }
+    uint4 ra[2];
+    float4 rb[4];
+    auto fetch = [&](int k0) __attribute__((always_inline)) {
+        const char* ca = base_a + 2 * (int64_t)k0;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) ra[t] = *reinterpret_cast<const uint4*>(ca + voff_a[t]);
+        if (!B_KMAJOR) {
+            const char* cb = base_b + 4 * (int64_t)k0;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                rb[2 * t] = *reinterpret_cast<const float4*>(cb + voff_b[t]);
+                rb[2 * t + 1] = *reinterpret_cast<const float4*>(cb + voff_b[t] + 16);
+            }
+        } else {
+            const char* row = base_b + (int64_t)k0 * pb;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float2 e = *reinterpret_cast<const float2*>(row + (2 * t) * pb + voff_b[0]);
+                const float2 o = *reinterpret_cast<const float2*>(row + (2 * t + 1) * pb + voff_b[0]);
+                rb[t] = make_float4(e.x, e.y, o.x, o.y);
+            }
+        }
+    };
+    // pair q (0..3) of B piece pc (0..1)
+    auto pair_b = [&](int pc, int q, uint32_t& hi, uint32_t& lo) __attribute__((always_inline)) {
+        if (!B_KMAJOR) {
+            const float4& v = rb[2 * pc + (q >> 1)];
+            if (q & 1) split_pair(v.z, v.w, hi, lo);
+            else split_pair(v.x, v.y, hi, lo);
+        } else {
+            const float4& v = rb[q];
+            if (pc == 0) split_pair(v.x, v.z, hi, lo);
+            else split_pair(v.y, v.w, hi, lo);
+        }
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        char* const wr = lds + buf * 4 * PLANE;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            *reinterpret_cast<uint4*>(wr + wr_a[t]) = ra[t];
+            uint4 hv, lv;
+            pair_b(t, 0, hv.x, lv.x);
+            pair_b(t, 1, hv.y, lv.y);
+            pair_b(t, 2, hv.z, lv.z);
+            pair_b(t, 3, hv.w, lv.w);
+            *reinterpret_cast<uint4*>(wr + wr_b[t]) = hv;
+            *reinterpret_cast<uint4*>(wr + PLANE + wr_b[t]) = lv;
+        }
+    };
+    const int lk = lane >> 5, lm = lane & 31;
+    auto step = [&](int buf, auto stage_c, auto fetch_c, int knext) __attribute__((always_inline)) {
+        constexpr bool STAGE = decltype(stage_c)::value, FETCH = decltype(fetch_c)::value;
+        const char* Ap = lds + buf * 4 * PLANE;
+        const char* Bh = Ap + 2 * PLANE;
+        const char* Bl = Ap + 3 * PLANE;
+        char* const wr = lds + (buf ^ 1) * 4 * PLANE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 a[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(Ap + bf_unit32(wm + 32 * i + lm, 2 * ks + lk));
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
+                bf16x8 bh[2], bl[2];
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const uint32_t ub = bf_unit32(wn + 32 * (2 * jp + jj) + lm, 2 * ks + lk);
+                    bh[jj] = *reinterpret_cast<const bf16x8*>(Bh + ub);
+                    bl[jj] = *reinterpret_cast<const bf16x8*>(Bl + ub);
+                }
+                uint32_t hw[4], lw[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                    for (int e = 2 * c; e < 2 * c + 2; ++e) {           // e = 4 t + 2 jj + i: a b_lo first, then a b_hi
+                        const int t = e >> 2, jj = (e >> 1) & 1, i = e & 1;
+                        acc[i][2 * jp + jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], t == 0 ? bl[jj] : bh[jj],
+                                                                                      acc[i][2 * jp + jj], 0, 0, 0);
+                    }
+                    if (STAGE && ks == 1) {
+                        pair_b(jp, c, hw[c], lw[c]);                    // piece jp: its four pairs over this group's chunks
+                        if (c == 3) {
+                            *reinterpret_cast<uint4*>(wr + wr_a[jp]) = ra[jp];
+                            *reinterpret_cast<uint4*>(wr + wr_b[jp]) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                            *reinterpret_cast<uint4*>(wr + PLANE + wr_b[jp]) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0x124);
+                }
+            }
+        }
+        if (FETCH) fetch(knext);
+    };
+    using std::true_type;
+    using std::false_type;
+
+    fetch(0);
+    stage(0);
+    if (SPK2 < Kdim) fetch(SPK2);
+    __syncthreads();
+    int buf = 0, k0 = 0;
+    for (; k0 + 2 * SPK2 < Kdim; k0 += SPK2, buf ^= 1) {
+        step(buf, true_type{}, true_type{}, k0 + 2 * SPK2);
+        __syncthreads();
+    }
+    if (k0 + SPK2 < Kdim) {
+        step(buf, true_type{}, false_type{}, 0);
+        __syncthreads();
+        buf ^= 1;
+    }
+    step(buf, false_type{}, false_type{}, 0);
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                const int n = n0 + wn + j * 32 + lm;
+                C[(int64_t)m * N + n] = acc[i][j][v];
+            }
+}
+
 // The same split product on a 256 x 160 workgroup tile, for outputs 1280 wide (five 256-tiles
 // across leave 160 tiles for 256 CUs at T = 8192; eight 160-tiles across give 256).  A m-major
 // (NT and NN products).  Eight wavefronts stacked along m, each 32 rows x 160 columns (5 MFMA
@@ -1171,6 +1347,21 @@ static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, 
     return MST_OK;
 }
 
+// bfloat16 activations x fp32 dense weights on whole 256 x 256 tiles (16-byte loads of eight bfloat16: K % 32)
+static bool a16_ok(int M, int N, int Kdim) {
+    return !g_gemm_fp32_only && g_split_tile != 128 && M % BM2 == 0 && N % BN2 == 0 && Kdim % SPK2 == 0;
+}
+template <bool BKM>
+static int launch_a16(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int M, int N, int Kdim,
+                      int* left_unsummed, hipStream_t s) {
+    const unsigned grid = (unsigned)(8 * cdiv((int64_t)(M / BM2) * (N / BN2), 8));
+    k_gemm_a16_256<BKM><<<grid, 512, 0, s>>>((const uint16_t*)A, lda, (const float*)B, ldb, C, M, N, Kdim);
+    MST_LAUNCH_CHECK();
+    g_last_tile = 256;
+    if (left_unsummed) *left_unsummed = 1;
+    return MST_OK;
+}
+
 static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, int Kdim, float* split_ws,
                           int64_t split_ws_floats, int* left_unsummed, hipStream_t s) {
     const int gm = (int)cdiv(M, BM), gn = (int)cdiv(N, BN);
@@ -1244,12 +1435,14 @@ int gemm_mfma(GemmKind kind, const void* A, mst_dtype a_dt, const void* B, mst_d
             return launch<float, true, float, true>(A, M, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NT:
             if (bb) return MST_ERR_ARG;
+            if (ab && a16_ok(M, N, Kdim)) return launch_a16<false>(A, Kdim, B, Kdim, C, M, N, Kdim, left_unsummed, s);
             if (ab) return launch<uint16_t, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             if (split_ok(M, N, Kdim, Kdim, Kdim, false))
                 return launch_split<false, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             return launch<float, false, float, false>(A, Kdim, B, Kdim, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
         case GEMM_NN:
             if (bb) return MST_ERR_ARG;
+            if (ab && a16_ok(M, N, Kdim)) return launch_a16<true>(A, Kdim, B, N, C, M, N, Kdim, left_unsummed, s);
             if (ab) return launch<uint16_t, false, float, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);
             if (split_ok(M, N, Kdim, Kdim, N, false))
                 return launch_split<false, true>(A, Kdim, B, N, C, M, N, Kdim, split_ws, split_ws_floats, left_unsummed, s);

@@ -32,13 +32,21 @@ int64_t view_pair_capacity(int64_t cap, int64_t nchunk, int64_t R) {
 // cost the same at every density; the sparse kernels cost about in proportion to nnz.  At
 // T >= 2048 the two meet at a density of 0.045-0.06 for Y and dX and at 0.03-0.04 for the
 // weight gradient; short batches fill the matrix cores badly and meet at about 0.15 (there the
-// one-call backward, both gradients from one walk, is also ahead of two separate products).  With
-// bfloat16 activations Y and dX of the dense path still run on the fp32 MFMA kernel (cross-over
-// 0.30), the weight gradient has both operands in bfloat16 (300-440 TFLOP/s, cross-over 0.045).
+// one-call backward, both gradients from one walk, is also ahead of two separate products).
+// With bfloat16 activations on whole 256 x 256 tiles Y and dX take two bf16 products per term
+// (490 TFLOP/s at the GPT-2-medium shapes) and meet the sparse kernels at 0.042-0.05; other
+// shapes run on the fp32 MFMA kernel (cross-over 0.30).  The bfloat16 weight gradient has both
+// operands in bfloat16 (cross-over 0.045).
 bool use_dense_path(const mst_layer* L, mst_dtype act, int T) {
     if (L->path == MST_PATH_DENSE) return true;
     if (L->path == MST_PATH_SPARSE) return false;
-    const double thr = act == MST_BF16 ? 0.30 : T >= 2048 ? 0.055 : 0.15;
+    double thr;
+    if (act == MST_BF16) {
+        const bool tiles = T % 256 == 0 && L->O % 256 == 0 && L->I % 256 == 0;
+        thr = tiles && T >= 2048 ? 0.045 : 0.30;
+    } else {
+        thr = T >= 2048 ? 0.055 : 0.15;
+    }
     return (double)L->nnz > thr * (double)L->N;
 }
 

@@ -4,8 +4,9 @@
   1.5: a few completely full rows, most rows nearly empty), T = 16384, fp32: all four
   layers, every product call incl. the one-call backward and the weight gradient.
 * GPT-2-medium block at density 0.05 with bfloat16 activations and fp32 accumulation,
-  T = 16384: the layers the other full-size file does not cover, and a fused Mixed-Growing
-  update (Algorithm 1) whose dense gradient runs on the bf16 matrix cores.
+  T = 16384: the layers the other full-size file does not cover, on the automatic path
+  (dense bf16 MFMA contractions at this density) and pinned to the sparse kernels, and a
+  fused Mixed-Growing update (Algorithm 1) whose dense gradient runs on the bf16 matrix cores.
 
 Sampled outputs (>= 10^4 per tensor plus the longest / shortest rows and columns) against
 the oracle, adjoint identities over the complete outputs, masks in full."""
@@ -48,15 +49,19 @@ def test_medium_bf16_layer_every_product(name, I, O):
     Xf, dYf, xb, yb = synth.make_activations(2024, lid, T, I, O, "bf16")
     Xd, dYd = dev(xb.view(np.int16)), dev(yb.view(np.int16))
     rig = Rig(W, M, T, cap=int(M.sum()) * 3 // 2)
-    # automatic choice: input gradient by the sparse kernel, weight gradient as the bf16 MFMA
-    # product read at the active positions
+    # automatic choice at this density: Y and dX as two-product bf16 MFMA contractions (bfloat16
+    # activations x fp32 weights split hi + lo), weight gradient as the bf16 MFMA product read
+    # at the active positions
     _, dX_auto, dW_auto = check_layer_products("bf16 auto " + name, rig, W, M, Xf, dYf, Xd, dYd, mst.MST_BF16,
                                                n=10000)
     # pinned to the sparse kernels: both gradients from one walk of the transposed view
     rig.layer.set_path(mst.MST_PATH_SPARSE)
     _, dX_sp, dW_sp = check_layer_products("bf16 sparse " + name, rig, W, M, Xf, dYf, Xd, dYd, mst.MST_BF16,
                                            n=3000)
-    np.testing.assert_array_equal(dX_sp, dX_auto)             # the same sums in the same order
+    assert rig.layer.nnz > 0 and not rig.layer.uses_dense(mst.MST_BF16, T)
+    rig.layer.set_path(mst.MST_PATH_AUTO)
+    assert rig.layer.uses_dense(mst.MST_BF16, T) and rig.layer.uses_dense(mst.MST_BF16, T, True)
+    assert np.abs(dX_sp - dX_auto).max() <= 2e-5 * np.abs(dX_auto).max()   # split weights: 2^-17 per term
     assert np.abs(dW_sp - dW_auto).max() <= 1e-5 * np.abs(dW_auto).max()
 
 

@@ -398,3 +398,42 @@ def test_bf16_dense_gradient_on_both_workgroup_tiles(T, I, O):
         print(key, "err %.3g" % e, flush=True)
         assert e <= 2e-6                      # fp32 accumulation of exact products
     assert rel_err(got[(256, False)], got[(128, False)]) <= 2e-6
+
+
+@pytest.mark.parametrize("T,I,O", [(256, 256, 512), (512, 768, 256), (768, 32, 256), (1024, 288, 768)])
+def test_dense_products_with_bf16_activations_on_the_256_tile(T, I, O):
+    """Y and dX of a dense-path layer with bfloat16 activations on whole 256 x 256 tiles: the
+    activations go to the matrix cores as they are, the fp32 weights as bf16 hi + lo (two
+    products per term).  Against the oracle on the same bfloat16 values, and against the fp32
+    MFMA kernel that serves ragged shapes (pinned by the hook)."""
+    print("case", T, I, O, flush=True)
+    W = synth.normal(47, 3, (O, I), 0.02)
+    W = (W * np.exp2(synth.normal(47, 8, W.shape) * 3)).astype(np.float32)     # weights over several orders of magnitude
+    M = synth.make_layer(47, 1, I, O, 0.5)[1]
+    Xf, dYf, xb, yb = synth.make_activations(47, 1, T, I, O, "bf16")
+    rig = Rig(W * M, M, T, cap=O * I)
+    rig.layer.set_path(mst.MST_PATH_DENSE)
+
+    def run():
+        Y = torch.full((T, O), float("nan"), dtype=torch.float32, device=DEV)
+        dX = torch.full((T, I), float("nan"), dtype=torch.float32, device=DEV)
+        mst.mst_sparse_fc_fwd(rig.layer, dev(xb.view(np.int16)), Y, T, mst.MST_BF16)
+        ty = mst.mst_gemm_last_tile()
+        mst.mst_sparse_fc_bwd_input(rig.layer, dev(yb.view(np.int16)), dX, T, mst.MST_BF16)
+        tx = mst.mst_gemm_last_tile()
+        torch.cuda.synchronize()
+        return Y.cpu().numpy(), dX.cpu().numpy(), ty, tx
+
+    try:
+        Y, dX, ty, tx = run()
+        mst.mst_gemm_force_fp32_mfma(1)
+        Y32, dX32, _, _ = run()
+    finally:
+        mst.mst_gemm_force_fp32_mfma(0)
+    # Y is O wide with depth I, dX is I wide with depth O: whole tiles and a depth that is a multiple of 32
+    assert ty == (256 if O % 256 == 0 and I % 32 == 0 else 0)
+    assert tx == (256 if I % 256 == 0 and O % 32 == 0 else 0)
+    for name, got, got32, ref in (("Y", Y, Y32, opr.fc_fwd(Xf, W, M)), ("dX", dX, dX32, opr.fc_bwd_input(dYf, W, M))):
+        e, e32 = rel_err(got, ref), rel_err(got32, ref)
+        print(name, "err %.3g  fp32-mfma err %.3g" % (e, e32), flush=True)
+        assert e <= 2e-5 and e32 <= TOL
