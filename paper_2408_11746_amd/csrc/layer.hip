@@ -749,7 +749,15 @@ int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
     if (!L) return MST_ERR_ARG;
     if (!L->built) return MST_ERR_STATE;
     hipStream_t s = (hipStream_t)stream;
-    L->Wd_valid = false;
+    // A dense copy that is in use (zero at every inactive position) takes the new values now rather
+    // than at the next product, so that products recorded into a graph never see stale weights.
+    if (L->Wd_zeros && L->nnz > 0) {
+        k_scatter_dense<<<(unsigned)cdiv(L->nnz, 256), 256, 0, s>>>(L->vals, L->flat, L->nnz, L->Wd);
+        MST_LAUNCH_CHECK();
+        L->Wd_valid = true;
+    } else {
+        L->Wd_valid = false;
+    }
     if (L->nnz == 0 || !L->views_valid) return MST_OK;     // unbuilt views take the values when they are built
     // every real entry slot lies below 4 * (nnz + #quad segments); the kernel stops at ptr[nseg] * 8
     const View &r = L->row, &c = L->col;

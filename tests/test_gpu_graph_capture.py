@@ -71,3 +71,14 @@ def test_forward_and_backward_replay_from_a_graph(density, path):
         errs = [rel_err(g, r) for g, r in zip(got, refs)]
         print("density", density, "replay", rep, "errors", errs, flush=True)
         assert max(errs) <= TOL
+
+    # the caller's optimiser changes the values and hands them over OUTSIDE the graph: the hand-over
+    # itself refreshes whatever the recorded products read (index views, dense weight copy)
+    graph.replay()
+    torch.cuda.synchronize()
+    Y1 = Y.cpu().numpy().copy()
+    L.values().mul_(2.0)
+    L.sync_values()
+    graph.replay()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(Y.cpu().numpy(), 2.0 * Y1)          # doubling is exact in fp32
