@@ -360,8 +360,9 @@ __global__ __launch_bounds__(256) void k_select_flag(KS ks, int64_t n, const uin
 // distinct indices.  One pass builds the histogram of the top 10 bits (no hot bins, so one
 // LDS copy per block) and picks the bin of the k-th key; one pass appends the candidates of
 // that bin -- about n / 1024 of them -- to a list; one block finishes the search on the list
-// (seven more 8-bit digits, then the index cut among equal keys) and leaves the threshold in
-// the state for the flag pass (mode 2).  Four launches whatever the keys are.
+// (seven more 8-bit digits, then the index cut among equal keys).  Selected positions are marked
+// where they are decided: candidates below the picked bin by the list pass, those inside it by
+// the finishing block.  Three launches whatever the keys are.
 constexpr int RAND_TOP_BITS = 10, RAND_BINS = 1 << RAND_TOP_BITS, RAND_SHIFT = 64 - RAND_TOP_BITS;
 
 struct RandItem {
@@ -434,15 +435,16 @@ __global__ __launch_bounds__(SEL_NT) void k_rand_hist(RandKeys ks, int64_t n, ui
     if (tid == 0) { state[3] = 0; state[4] = 0; }
 }
 
-// block of 1024 threads, 16 indices each: the hits (about 16 per block) are gathered in LDS and
-// appended to the list with ONE add to its length (an add per hit would queue up at the counter)
+// block of 1024 threads, 16 indices each.  Candidates in a bin below the picked one are selected on
+// the spot; those of the picked bin (about 16 per block) are gathered in LDS and appended to the
+// list with ONE add to its length (an add per hit would queue up at the counter)
 constexpr int COMPACT_PER_BLOCK = SEL_NT * 16, COMPACT_STAGE = 512;
 __global__ __launch_bounds__(SEL_NT) void k_rand_compact(RandKeys ks, int64_t n, uint64_t* __restrict__ state,
-                                                         RandItem* __restrict__ list) {
+                                                         RandItem* __restrict__ list, FlagSink sink) {
     __shared__ RandItem stage[COMPACT_STAGE];
     __shared__ unsigned int nstage;
     __shared__ unsigned long long base_s;
-    if (state[2] != 0) return;
+    const bool whole_bin = state[2] != 0;            // every candidate of the picked bin is wanted: no list
     const int tid = threadIdx.x;
     if (tid == 0) nstage = 0;
     __syncthreads();
@@ -458,7 +460,13 @@ __global__ __launch_bounds__(SEL_NT) void k_rand_compact(RandKeys ks, int64_t n,
         keys_of_group(ks, i4, n, key, ok);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (!ok[u] || (key[u] >> RAND_SHIFT) != top) continue;
+            if (!ok[u]) continue;
+            const uint64_t bin = key[u] >> RAND_SHIFT;
+            if (bin < top || (whole_bin && bin == top)) {     // decided here: selected (each thread owns its indices)
+                sink.put(i4 + u, true);
+                continue;
+            }
+            if (bin != top) continue;
             const unsigned int at = atomicAdd(&nstage, 1u);
             if (at < COMPACT_STAGE) stage[at] = RandItem{key[u], i4 + u};
             else list[atomicAdd(len, 1ull)] = RandItem{key[u], i4 + u};      // (a block with more hits than the stage holds)
@@ -474,7 +482,8 @@ __global__ __launch_bounds__(SEL_NT) void k_rand_compact(RandKeys ks, int64_t n,
 // one block: the state[1]-th smallest (key, index) of the list decides the threshold.  Lists of up to
 // RAND_LDS_KEYS items (the usual case by far) are searched in LDS.
 constexpr int RAND_LDS_KEYS = 7168;
-__global__ __launch_bounds__(SEL_NT) void k_rand_finish(uint64_t* __restrict__ state, const RandItem* __restrict__ list) {
+__global__ __launch_bounds__(SEL_NT) void k_rand_finish(uint64_t* __restrict__ state, const RandItem* __restrict__ list,
+                                                        FlagSink sink) {
     __shared__ uint64_t keys[RAND_LDS_KEYS];
     __shared__ uint32_t h[SEL_BINS];
     __shared__ uint32_t wtot[4];
@@ -527,12 +536,16 @@ __global__ __launch_bounds__(SEL_NT) void k_rand_finish(uint64_t* __restrict__ s
         }
         __syncthreads();
     }
-    if (done_s) {
+    if (done_s) {                                     // every listed key <= prefix_s is taken
+        const uint64_t top_key = prefix_s;
+        for (int64_t i = tid; i < c; i += SEL_NT)
+            if (list[i].key <= top_key) sink.put(list[i].f, true);
         if (tid == 0) { state[0] = prefix_s; state[1] = need_s; state[2] = 1; }
         return;
     }
     // equal keys (cannot happen with distinct indices, kept for exactness): the need_s lowest indices.
     // The cut is the need_s-th smallest index among the items whose key is the threshold.
+    __shared__ long long cut_s;
     if (tid == 0) {
         const uint64_t tau = prefix_s, need = need_s;
         long long lo = -1;
@@ -546,6 +559,14 @@ __global__ __launch_bounds__(SEL_NT) void k_rand_finish(uint64_t* __restrict__ s
         state[1] = need;
         state[2] = 2;
         state[6] = (uint64_t)lo;
+        cut_s = lo;
+    }
+    __syncthreads();
+    const uint64_t tau = prefix_s;
+    const long long cut = cut_s;
+    for (int64_t i = tid; i < c; i += SEL_NT) {
+        const RandItem it = list[i];
+        if (it.key < tau || (it.key == tau && (long long)it.f <= cut)) sink.put(it.f, true);
     }
 }
 
@@ -643,12 +664,12 @@ int mask_update_device(mst_layer* L, const float* G, const mst_update_stats& st,
         RandItem* list = reinterpret_cast<RandItem*>(ws.gemm);          // 2 N items fit: more than any candidate count
         k_rand_hist<<<rand_blocks(N), SEL_NT, 0, s>>>(rk, N, st_rand);
         MST_LAUNCH_CHECK();
-        k_rand_compact<<<(unsigned)cdiv(N, COMPACT_PER_BLOCK), SEL_NT, 0, s>>>(rk, N, st_rand, list);
-        MST_LAUNCH_CHECK();
-        k_rand_finish<<<1, SEL_NT, 0, s>>>(st_rand, list);
-        MST_LAUNCH_CHECK();
+        // selected positions become active (weight 0) where they are decided: below the picked bin in the
+        // compaction pass, inside it by the finishing block; no separate flag pass
         const FlagSink sink_r{ws.sel, 3, 0, L->mask, Wnew};
-        k_select_flag<RandKeys><<<(unsigned)cdiv(N, SELECT_BLOCK), 256, 0, s>>>(rk, N, st_rand, reinterpret_cast<int*>(ws.blk), sink_r);
+        k_rand_compact<<<(unsigned)cdiv(N, COMPACT_PER_BLOCK), SEL_NT, 0, s>>>(rk, N, st_rand, list, sink_r);
+        MST_LAUNCH_CHECK();
+        k_rand_finish<<<1, SEL_NT, 0, s>>>(st_rand, list, sink_r);
         MST_LAUNCH_CHECK();
     }
 
