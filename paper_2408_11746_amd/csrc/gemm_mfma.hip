@@ -508,29 +508,52 @@ __device__ inline uint32_t split256_unit(int p, int h, int piece) {
 template <bool A_KMAJOR, bool B_KMAJOR>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
-                     float* __restrict__ C, int M, int N, int Kdim, int k_per_split, int64_t split_stride) {
+                     float* __restrict__ C, int M, int N, int Kdim, int k_per_split, int64_t split_stride, int sched) {
     constexpr int PLANE = BM2 * 64;                                       // one half (hi or lo) of one operand tile
     __shared__ __attribute__((aligned(16))) char lds[2 * 4 * PLANE];     // [stage][A hi, A lo, B hi, B lo]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
-    // workgroup -> (tile, k range): XCD x takes tiles x Q .. x Q + Q - 1, one k range after the other
-    const int gn = N / BN2, ntiles = (M / BM2) * gn, nsplit = (Kdim + k_per_split - 1) / k_per_split;
-    const int Q = (ntiles + 7) >> 3;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int split = slot / Q, tile_id = xcd * Q + slot % Q;
-    if (tile_id >= ntiles || split >= nsplit) return;
-    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN2;
-    const int kbeg = split * k_per_split;
-    const int kend = min(Kdim, kbeg + k_per_split);
-    float* Cz = C + (int64_t)split * split_stride;
+    const int gn = N / BN2, ntiles = (M / BM2) * gn;
+    // This workgroup's one or two segments (tile, k range, partial-output plane).
+    int nseg = 1, seg_tile[2], seg_kb[2], seg_ke[2], seg_plane[2];
+    if (sched == 0) {
+        // XCD x takes tiles x Q .. x Q + Q - 1, one k range after the other
+        const int nsplit = (Kdim + k_per_split - 1) / k_per_split;
+        const int Q = (ntiles + 7) >> 3;
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int split = slot / Q, tile_id = xcd * Q + slot % Q;
+        if (tile_id >= ntiles || split >= nsplit) return;
+        seg_tile[0] = tile_id;
+        seg_kb[0] = split * k_per_split;
+        seg_ke[0] = min(Kdim, seg_kb[0] + k_per_split);
+        seg_plane[0] = split;
+    } else {
+        // Five workgroups per two tiles (about 100 tiles on 256 CUs: two k ranges per tile fill 78 % of
+        // the CUs, three need a second round).  Workgroups 0, 1 take x = k_per_split of tile A each, 3, 4 of
+        // tile B; workgroup 2 takes what is left of A and the same amount at the start of B (x is chosen
+        // so that its two start-ups and outputs even out).  Every tile ends with three partial planes in
+        // ascending k order, as with three plain k ranges.
+        // (an XCD takes 32 consecutive work items, so the workgroups of neighbouring tiles share its L2)
+        const int item = (blockIdx.x & 7) * 32 + (blockIdx.x >> 3);
+        const int g = item / 5, r = item % 5, x = k_per_split, hk = Kdim - 2 * x;
+        if ((blockIdx.x >> 3) >= 32 || 2 * g + 1 >= ntiles) return;
+        const int tA = 2 * g, tB = 2 * g + 1;
+        seg_tile[0] = r < 3 ? tA : tB;
+        seg_plane[0] = r < 3 ? r : r - 2;
+        seg_kb[0] = r == 0 ? 0 : r == 1 ? x : r == 2 ? 2 * x : r == 3 ? hk : hk + x;
+        seg_ke[0] = r == 0 ? x : r == 1 ? 2 * x : r == 2 ? Kdim : r == 3 ? hk + x : Kdim;
+        if (r == 2) {
+            nseg = 2;
+            seg_tile[1] = tB;
+            seg_plane[1] = 0;
+            seg_kb[1] = 0;
+            seg_ke[1] = hk;
+        }
+    }
+    int m0 = 0, n0 = 0, kbeg = 0, kend = 0;
+    float* Cz = C;
 
     floatx16 acc[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     static_assert(A_KMAJOR == B_KMAJOR || (!A_KMAJOR && B_KMAJOR), "layouts: TN, NT or NN");
     constexpr int LAYOUT = A_KMAJOR == B_KMAJOR ? (A_KMAJOR ? 0 : 1) : 2;
@@ -538,27 +561,30 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
     // scalar base (advanced per step) plus a per-thread 32-bit byte offset fixed for the kernel
     const int h = __builtin_amdgcn_readfirstlane(tid >> 8), p = tid & 255;
     const int64_t pa = 4 * lda, pb = 4 * ldb;         // row pitches in bytes
-    const char* base0;                                // equal layouts: this thread's operand; mixed: A
+    const char* base0 = nullptr;                      // equal layouts: this thread's operand; mixed: A
     const char* base1 = nullptr;                      // mixed: B
-    int64_t pitch0;
+    const int64_t pitch0 = LAYOUT == 2 ? pa : (h == 0 ? pa : pb);
     uint32_t voff[4];
     if (LAYOUT == 0) {
-        pitch0 = h == 0 ? pa : pb;
-        base0 = reinterpret_cast<const char*>(h == 0 ? A + m0 : B + n0);
         voff[0] = (uint32_t)(8 * (p >> 6) * pitch0 + 16 * (p & 63));
     } else if (LAYOUT == 1) {
-        pitch0 = h == 0 ? pa : pb;
-        base0 = reinterpret_cast<const char*>(h == 0 ? A : B) + (int64_t)(h == 0 ? m0 : n0) * pitch0;
 #pragma unroll
         for (int it = 0; it < 4; ++it) voff[it] = (uint32_t)(mmajor_row(p, it) * pitch0 + 32 * (p & 3));
     } else {
-        pitch0 = pa;
-        base0 = reinterpret_cast<const char*>(A) + (int64_t)m0 * pa;
-        base1 = reinterpret_cast<const char*>(B + n0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) voff[t] = (uint32_t)(mmajor_row(p, 2 * h + t) * pa + 32 * (p & 3));
         voff[2] = (uint32_t)(8 * (p >> 6) * pb + 16 * (p & 63) + 8 * h);
     }
+    auto set_tile = [&]() {                           // operand bases of the tile at (m0, n0)
+        if (LAYOUT == 0) {
+            base0 = reinterpret_cast<const char*>(h == 0 ? A + m0 : B + n0);
+        } else if (LAYOUT == 1) {
+            base0 = reinterpret_cast<const char*>(h == 0 ? A : B) + (int64_t)(h == 0 ? m0 : n0) * pitch0;
+        } else {
+            base0 = reinterpret_cast<const char*>(A) + (int64_t)m0 * pa;
+            base1 = reinterpret_cast<const char*>(B + n0);
+        }
+    };
     auto fetch = [&](int k0, float4 (&r)[8]) __attribute__((always_inline)) {
         if (LAYOUT == 0) {
             const char* row = base0 + (int64_t)k0 * pitch0;
@@ -667,32 +693,49 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
     using std::true_type;
     using std::false_type;
 
-    fetch(kbeg, r);
-    stage(0, r);
-    if (kbeg + SPK2 < kend) fetch(kbeg + SPK2, r);
-    __syncthreads();
-    int buf = 0, k0 = kbeg;
-    for (; k0 + 2 * SPK2 < kend; k0 += SPK2, buf ^= 1) {
-        step(buf, true_type{}, true_type{}, k0 + 2 * SPK2);
+    for (int sg = 0; sg < nseg; ++sg) {
+        const int tile_id = seg_tile[sg];
+        m0 = (tile_id / gn) * BM2;
+        n0 = (tile_id % gn) * BN2;
+        kbeg = seg_kb[sg];
+        kend = seg_ke[sg];
+        Cz = C + (int64_t)seg_plane[sg] * split_stride;
+        set_tile();
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+        fetch(kbeg, r);
+        stage(0, r);
+        if (kbeg + SPK2 < kend) fetch(kbeg + SPK2, r);
         __syncthreads();
-    }
-    if (k0 + SPK2 < kend) {                           // last but one step: nothing left to fetch
-        step(buf, true_type{}, false_type{}, 0);
-        __syncthreads();
-        buf ^= 1;
-    }
-    step(buf, false_type{}, false_type{}, 0);         // last step
+        int buf = 0, k0 = kbeg;
+        for (; k0 + 2 * SPK2 < kend; k0 += SPK2, buf ^= 1) {
+            step(buf, true_type{}, true_type{}, k0 + 2 * SPK2);
+            __syncthreads();
+        }
+        if (k0 + SPK2 < kend) {                       // last but one step: nothing left to fetch
+            step(buf, true_type{}, false_type{}, 0);
+            __syncthreads();
+            buf ^= 1;
+        }
+        step(buf, false_type{}, false_type{}, 0);     // last step
 
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-                const int n = n0 + wn + j * 32 + lm;
-                Cz[(int64_t)m * N + n] = acc[i][j][v];
-            }
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                    const int n = n0 + wn + j * 32 + lm;
+                    Cz[(int64_t)m * N + n] = acc[i][j][v];
+                }
+        if (sg + 1 < nseg) __syncthreads();           // the next segment reuses the LDS stages
+    }
 }
 
 // Y = X Wd^T and dX = dY Wd with BFLOAT16 activations (A m-major, bfloat16) and the fp32 dense
@@ -1295,11 +1338,16 @@ static SplitPlan plan_split(int M, int N, int Kdim, int64_t max_split, bool summ
 }
 static int g_gemm_fp32_only = 0;          // test hook: 1 = never use the bf16-split kernel
 static int g_last_tile = 0;               // workgroup tile of the last split-kernel launch (128 / 256 / 160), 0: another kernel
+static int g_sched52 = 1;                 // test hook: 0 = never the five-for-two schedule
 static int g_split_tile = 0;              // test hook: 0 = automatic, 128 / 256 / 160 = that workgroup tile when the shape allows it
 
 int gemm_last_tile() { return g_last_tile; }
 
 int gemm_force_fp32_mfma(int on) {       // 0 automatic, 1 fp32 MFMA kernel, 128 / 256 / 160: split kernel with that tile
+    if (on == 52 || on == -52) {                    // (the other settings stay as they are)
+        g_sched52 = on > 0;
+        return MST_OK;
+    }
     g_gemm_fp32_only = on == 1 ? 1 : 0;
     g_split_tile = (on == 128 || on == 256 || on == 160) ? on : 0;
     return MST_OK;
@@ -1328,11 +1376,28 @@ static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, 
     const int tm = tile == 128 ? 128 : 256;
     const unsigned grid = (unsigned)(8 * cdiv((int64_t)(M / tm) * (N / tile), 8) * nsplit);
     float* dst = nsplit > 1 ? split_ws : C;
+    // About 100 tiles of 256 x 256 with two k ranges each leave a fifth of the CUs idle: five
+    // workgroups per two tiles instead (k_gemm_split256, sched = 1), three partial planes per tile.
+    const int64_t tiles256 = (int64_t)(M / BM2) * (N / BN2);
+    const int S = Kdim / SPK2, x_steps = (int)cdiv(2 * S + 13, 5);
+    if (tile == 256 && nsplit == 2 && g_sched52 && split_ws && split_ws_floats / mn >= 3 && tiles256 % 2 == 0 &&
+        tiles256 * 5 / 2 <= 256 && tiles256 * 2 <= 218 && S - 2 * x_steps >= 8) {
+        k_gemm_split256<AK, BKM><<<256u, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, split_ws,
+                                                                              M, N, Kdim, x_steps * SPK2, mn, 1);
+        MST_LAUNCH_CHECK();
+        if (left_unsummed) {
+            *left_unsummed = 3;
+            return MST_OK;
+        }
+        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, 3, C, mn);
+        MST_LAUNCH_CHECK();
+        return MST_OK;
+    }
     if (tile == 160) {
         if constexpr (!AK)
             k_gemm_split_n160<BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
     } else if (tile == 256)
-        k_gemm_split256<AK, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+        k_gemm_split256<AK, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn, 0);
     else
         k_gemm_split<AK, BKM><<<grid, 256, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
     MST_LAUNCH_CHECK();

@@ -53,6 +53,19 @@ def test_large_dense_gradient_with_the_split_grid(name, I, O):
     mst.mst_dense_grad(dev(dY), dev(X), G, T, O, I, mst.MST_F32, ws)
     torch.cuda.synchronize()
     sampled_check("G " + name, G.cpu().numpy(), lambda o, i: opr.dense_grad_at(dY, X, o, i), (O, I), n=10000, seed=4)
+    # the 100-tile shapes (fc1, fc2) run five workgroups per two tiles; with that schedule switched off
+    # (plain k ranges) the result is the same up to summation order
+    try:
+        mst.mst_gemm_force_fp32_mfma(-52)
+        G3 = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
+        mst.mst_dense_grad(dev(dY), dev(X), G3, T, O, I, mst.MST_F32, ws)
+        torch.cuda.synchronize()
+    finally:
+        mst.mst_gemm_force_fp32_mfma(52)
+    a3 = G3.cpu().numpy()
+    assert np.abs(G.cpu().numpy() - a3).max() <= 1e-5 * np.abs(a3).max()
+    if O * I == 5120 * 1280:
+        assert not np.array_equal(G.cpu().numpy(), a3)             # the two schedules really differ
     # without a workspace (one pass over all tokens) the result is the same up to summation order
     G2 = torch.full((O, I), float("nan"), dtype=torch.float32, device=DEV)
     mst.mst_dense_grad(dev(dY), dev(X), G2, T, O, I, mst.MST_F32, None)
