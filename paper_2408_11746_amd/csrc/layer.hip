@@ -45,7 +45,10 @@ bool use_dense_path(const mst_layer* L, mst_dtype act, int T) {
         const bool tiles = T % 256 == 0 && L->O % 256 == 0 && L->I % 256 == 0;
         thr = tiles && T >= 2048 ? 0.045 : 0.30;
     } else {
-        thr = T >= 2048 ? 0.055 : 0.15;
+        // the split kernels need whole 128-tiles (and a depth that is a multiple of 64); other shapes
+        // run on the fp32 MFMA kernel, a third as fast
+        const bool tiles = T % 128 == 0 && L->O % 128 == 0 && L->I % 128 == 0;
+        thr = !tiles ? 0.30 : T >= 2048 ? 0.055 : 0.15;
     }
     return (double)L->nnz > thr * (double)L->N;
 }
@@ -53,7 +56,8 @@ bool use_dense_path(const mst_layer* L, mst_dtype act, int T) {
 bool use_dense_weight_grad(const mst_layer* L, mst_dtype act, int T) {
     if (L->path == MST_PATH_DENSE) return true;
     if (L->path == MST_PATH_SPARSE) return false;
-    const double thr = act == MST_BF16 ? (T >= 2048 ? 0.045 : 0.30) : T >= 2048 ? 0.035 : 0.15;
+    const bool tiles = act == MST_BF16 || (T % 64 == 0 && L->O % 128 == 0 && L->I % 128 == 0);   // (the bf16 kernels take any shape)
+    const double thr = act == MST_BF16 ? (T >= 2048 ? 0.045 : 0.30) : !tiles ? 0.30 : T >= 2048 ? 0.035 : 0.15;
     return (double)L->nnz > thr * (double)L->N;
 }
 

@@ -51,7 +51,7 @@ def _update(rig, W, M, Gd, Gh, d, seed):
 
 
 def test_views_follow_the_path_across_updates():
-    I, O, T = 320, 576, 2048                       # ragged against every tile size; T at the long-batch thresholds
+    I, O, T = 384, 640, 2048                       # whole 128-tiles (the fast dense kernels), not whole 256-tiles; long batch
     W, M = synth.make_layer(77, 1, I, O, 0.5)
     X, dY = synth.make_activations(77, 1, T, I, O)
     Xd, dYd = dev(X), dev(dY)
