@@ -122,7 +122,10 @@ int mst_layer_export_dense(const mst_layer_t* layer, float* W_dev, uint8_t* M_de
                            mst_stream_t stream);
 
 /* The active weights as one fp32 vector in ascending flat-index order, for the caller's
- * optimiser to update in place.  After changing them call mst_layer_sync_values.  Every
+ * optimiser to update in place.  After changing them call mst_layer_sync_values: it copies
+ * the values into whatever the products read (the entries of built index views, a dense
+ * weight copy that is in use) with one or two kernels on `stream`, nothing else; products
+ * recorded into a HIP graph therefore see the new values on their next replay.  Every
  * mask update changes the set and therefore the meaning of position k of this vector. */
 int mst_layer_values(mst_layer_t* layer, float** vals_dev, int64_t* nnz);
 int mst_layer_sync_values(mst_layer_t* layer, mst_stream_t stream);
