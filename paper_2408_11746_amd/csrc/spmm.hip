@@ -316,8 +316,12 @@ static void launch64(const View& v, const TIn* A, float* out, int T, hipStream_t
 // candidate is the cost of one workgroup -- walk (proportional to its entries x tokens),
 // activation staging (tokens x K) and output (tokens x rows) -- times the number of
 // rounds its grid needs on 256 CUs x 2 workgroups; a last round that leaves every CU at
-// most one workgroup costs less than a full one.  The constants were fitted to timings
-// of GPT-2 small/medium/large layer shapes at densities 0.02 .. 0.10 on MI355X.
+// most one workgroup costs less than a full one.  A wavefront also pays a fixed amount per
+// quad segment it walks (pointer and first entry batch, padding to an even step count), which
+// at densities of a few percent decides for few quads per wavefront.  The constants were fitted
+// to timings of 138 cases (GPT-2 small / medium / large layer shapes, T = 512 .. 16384, densities
+// 0.01 .. 0.10: the range the sparse kernels serve) on MI355X: the chosen shape is 1.9 % slower
+// than the best one on average, 19 % at worst.
 struct SpmmShape {
     int tt, qw;
 };
@@ -326,8 +330,8 @@ static SpmmShape g_forced = {0, 0};
 static SpmmShape pick_shape(int T, int R, int K, double density) {
     if (g_forced.tt != 0) return g_forced;
     static const SpmmShape cand[] = {{128, 2}, {128, 3}, {128, 4}, {64, 2}, {64, 3}, {64, 4}, {64, 6}, {64, 8}};
-    const double kWalk = 2.92e-5, kStage = 1.92e-5, kOut = 5.19e-4, kChunk = 1.87;
-    const double kLoneTail = 0.60, kLoneOnly = 0.71, k64 = 0.967;
+    const double kWalk = 2.2e-5, kStage = 0.0, kOut = 2.69e-4, kChunk = 1.31;
+    const double kLoneTail = 0.68, kLoneOnly = 0.71, k64 = 0.893, kSeg128 = 0.49, kSeg64 = 0.35;
     const int64_t nchunk = cdiv(K, KC);
     SpmmShape best = cand[0];
     double best_cost = 0.0;
@@ -336,7 +340,8 @@ static SpmmShape pick_shape(int T, int R, int K, double density) {
         const int64_t nslab = cdiv(R, rows), ntile = cdiv(T, c.tt), nwg = ntile * nslab;
         const double rows_eff = (double)R / (double)nslab;
         const double wg = c.tt * (rows_eff * density * K * kWalk * (c.tt == 64 ? k64 : 1.0) +
-                                  (double)nchunk * KC * kStage + rows * kOut) + kChunk * (double)nchunk;
+                                  (double)nchunk * KC * kStage + rows * kOut) + kChunk * (double)nchunk +
+                          (double)c.qw * (double)nchunk * (c.tt == 128 ? kSeg128 : kSeg64);
         const int64_t full = nwg / 512, rest = nwg % 512;
         double rounds;
         if (full == 0) rounds = rest <= 256 ? kLoneOnly : 1.0;
