@@ -820,7 +820,29 @@ def cpu_baseline_sweep(synth, seed, cfg):
         Wp, Mp = r["W"], r["M"]
         n_upd += 1
     dt = time.perf_counter() - t0
+    # the same products on ONE thread, on a smaller token sample (one pass of the cycle)
+    single = None
+    try:
+        from threadpoolctl import threadpool_limits
+        T1 = 256
+        with threadpool_limits(limits=1):
+            t1 = time.perf_counter()
+            f1 = 0
+            for p in range(len(cyc)):
+                for lid in range(len(cfg["layers"])):
+                    W, M = Ws[lid], Ms[lid][p]
+                    X, dY = acts[lid][0][:T1], acts[lid][1][:T1]
+                    opr.fc_fwd(X, W, M)
+                    opr.fc_bwd_input(dY, W, M)
+                    opr.fc_bwd_weight(dY, X, M)
+                    f1 += 3 * 2 * int(M.sum()) * T1
+            d1 = time.perf_counter() - t1
+        single = {"value": round(f1 / d1 / 1e12, 5), "unit": "TFLOP/s", "cores": 1,
+                  "sample": "one pass of the cycle, products only, first %d tokens, %.1f s" % (T1, d1)}
+    except ImportError:
+        pass
     return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": _oracle_threads(), "kind": "oracle",
+            "single_thread": single,
             "sample": "two passes of the density cycle %s: fwd+bwd_input+bwd_weight of the four layers on the first %d of "
                       "%d tokens (dense masked fp64 numpy products, masks drawn per density) plus %d Mixed-Growing "
                       "updates of the 1280x1280 layer, %.1f s in all; effective (nonzero-only) FLOPs of the products "
