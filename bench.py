@@ -241,6 +241,12 @@ def roofline_of(row, L, act, kernel, traffic_cfg):
         traffic = json.load(open(tpath)).get("calls", {}).get("%s/%s" % (L.name, row["call"]))
     roof.update(traffic=traffic, kernel=kernel, call="%s/%s" % (L.name, row["call"]), avg_launch_ms=row["avg_ms"],
                 alg_bytes_per_launch=row["alg_bytes"], alg_flops_per_launch=row["alg_flops"])
+    if traffic and row["call"] == "dense_grad":
+        # FETCH_SIZE counts what the eight L2s fetch from the fabric (Infinity Cache hits included): every XCD
+        # reads all of X and its share of dY, and the partial outputs of the k ranges are written and read back
+        roof["traffic_note"] = ("bytes per call from profiles/hbm_traffic_%s.json: L2 fills and write-backs of all 8 XCDs "
+                                "(operands re-read per XCD, k-range partial outputs), not unique HBM bytes"
+                                % traffic_cfg.lower())
     for k in ("hbm_frac", "alu_frac", "lds_frac"):
         if k in row:
             roof[k] = row[k]
