@@ -529,25 +529,28 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
         seg_plane[0] = split;
     } else {
         // Five workgroups per two tiles (about 100 tiles on 256 CUs: two k ranges per tile fill 78 % of
-        // the CUs, three need a second round).  Workgroups 0, 1 take x = k_per_split of tile A each, 3, 4 of
-        // tile B; workgroup 2 takes what is left of A and the same amount at the start of B (x is chosen
-        // so that its two start-ups and outputs even out).  Every tile ends with three partial planes in
-        // ascending k order, as with three plain k ranges.
-        // (an XCD takes 32 consecutive work items, so the workgroups of neighbouring tiles share its L2)
+        // the CUs, three need a second round).  Both tiles are cut into the same three k ranges [0, x),
+        // [x, 2 x), [2 x, K) with x = k_per_split a little more than a third (so that the shorter last range
+        // makes up for a second start-up and output): workgroups 0, 1 take the first two ranges of tile A,
+        // 3, 4 those of tile B, workgroup 2 the last range of A and then of B.  Every tile ends with three
+        // partial planes in ascending k order, as with three plain k ranges, and neighbouring workgroups walk
+        // the same k range at the same time (they share operand tiles in L2).
+        // (an XCD takes 32 consecutive work items)
         const int item = (blockIdx.x & 7) * 32 + (blockIdx.x >> 3);
-        const int g = item / 5, r = item % 5, x = k_per_split, hk = Kdim - 2 * x;
+        const int g = item / 5, r = item % 5, x = k_per_split;
         if ((blockIdx.x >> 3) >= 32 || 2 * g + 1 >= ntiles) return;
         const int tA = 2 * g, tB = 2 * g + 1;
+        const int range = r < 2 ? r : r == 2 ? 2 : r - 3;        // 0, 1, 2 (both tiles), 0, 1
         seg_tile[0] = r < 3 ? tA : tB;
-        seg_plane[0] = r < 3 ? r : r - 2;
-        seg_kb[0] = r == 0 ? 0 : r == 1 ? x : r == 2 ? 2 * x : r == 3 ? hk : hk + x;
-        seg_ke[0] = r == 0 ? x : r == 1 ? 2 * x : r == 2 ? Kdim : r == 3 ? hk + x : Kdim;
+        seg_plane[0] = range;
+        seg_kb[0] = range * x;
+        seg_ke[0] = range == 2 ? Kdim : (range + 1) * x;
         if (r == 2) {
             nseg = 2;
             seg_tile[1] = tB;
-            seg_plane[1] = 0;
-            seg_kb[1] = 0;
-            seg_ke[1] = hk;
+            seg_plane[1] = 2;
+            seg_kb[1] = 2 * x;
+            seg_ke[1] = Kdim;
         }
     }
     int m0 = 0, n0 = 0, kbeg = 0, kend = 0;
