@@ -465,6 +465,17 @@ void k_gemm_split(const float* __restrict__ A, int64_t lda, const float* __restr
 // four units) each cover all banks once.
 constexpr int BM2 = 256, BN2 = 256, SPK2 = 32;
 
+// Tile number -> tile coordinates for the 256-row kernels.  Tiles are numbered in bands of four tile
+// rows, column by column inside a band: the 32 tiles an XCD works on at a time then span about
+// 4 rows x 8 columns instead of 2 x 20, so its L2 is filled with 12 operand panels instead of 22.
+constexpr int TILE_BAND = 4;
+__device__ inline void tile_coords(int tile_id, int gm, int gn, int& mi, int& ni) {
+    const int band = tile_id / (TILE_BAND * gn), rem = tile_id - band * TILE_BAND * gn;
+    const int hgt = min(TILE_BAND, gm - band * TILE_BAND);
+    ni = rem / hgt;
+    mi = band * TILE_BAND + rem - ni * hgt;
+}
+
 __device__ inline uint32_t bf_unit32(int m, int u) {
     const int rho = (m & ~15) | ((m & 3) << 2) | ((m >> 2) & 3);
     return (uint32_t)(rho * 64 + (((u ^ (rho >> 2) ^ (rho >> 4)) & 3) << 4));
@@ -698,8 +709,10 @@ void k_gemm_split256(const float* __restrict__ A, int64_t lda, const float* __re
 
     for (int sg = 0; sg < nseg; ++sg) {
         const int tile_id = seg_tile[sg];
-        m0 = (tile_id / gn) * BM2;
-        n0 = (tile_id % gn) * BN2;
+        int mi, ni;
+        tile_coords(tile_id, M / BM2, gn, mi, ni);
+        m0 = mi * BM2;
+        n0 = ni * BN2;
         kbeg = seg_kb[sg];
         kend = seg_ke[sg];
         Cz = C + (int64_t)seg_plane[sg] * split_stride;
@@ -761,7 +774,9 @@ void k_gemm_a16_256(const uint16_t* __restrict__ A, int64_t lda, const float* __
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int tile_id = xcd * Q + slot;
     if (slot >= Q || tile_id >= ntiles) return;
-    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN2;
+    int mi, ni;
+    tile_coords(tile_id, M / BM2, gn, mi, ni);
+    const int m0 = mi * BM2, n0 = ni * BN2;
 
     floatx16 acc[2][4];
 #pragma unroll
@@ -947,7 +962,9 @@ void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int split = slot / Q, tile_id = xcd * Q + slot % Q;
     if (tile_id >= ntiles || split >= nsplit) return;
-    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN3;
+    int mi, ni;
+    tile_coords(tile_id, M / BM2, gn, mi, ni);
+    const int m0 = mi * BM2, n0 = ni * BN3;
     const int kbeg = split * k_per_split;
     const int kend = min(Kdim, kbeg + k_per_split);
     float* Cz = C + (int64_t)split * split_stride;
@@ -1122,7 +1139,9 @@ void k_gemm_tn_bf16_256(const uint16_t* __restrict__ A, int64_t lda, const uint1
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int split = slot / Q, tile_id = xcd * Q + slot % Q;
     if (tile_id >= ntiles || split >= nsplit) return;
-    const int m0 = (tile_id / gn) * BM2, n0 = (tile_id % gn) * BN2;
+    int mi, ni;
+    tile_coords(tile_id, M / BM2, gn, mi, ni);
+    const int m0 = mi * BM2, n0 = ni * BN2;
     const int kbeg = split * k_per_split;
     const int kend = min(Kdim, kbeg + k_per_split);
     float* Cz = C + (int64_t)split * split_stride;
