@@ -433,26 +433,92 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     }
 }
 
-// vals / flat only (ascending flat index): one wavefront per row, as k_fill_row without the view
-__global__ void k_fill_canonical(const uint8_t* __restrict__ mask, const float* __restrict__ W, int O, int I,
-                                 const int* __restrict__ rowptr, float* __restrict__ vals, int* __restrict__ flat) {
+// ---- vals / flat / rowptr alone.  Canonical order is ascending flat index, so the arrays are
+// the ordered compaction of the mask as ONE sequence of N positions: a wavefront owns a segment of
+// CSEG consecutive positions whatever the layer's shape is (one wavefront per row leaves a
+// layer of few long rows with a handful of workgroups).
+constexpr int CSEG = 2048;
+
+__device__ inline int nonzero_bytes(uint32_t x) {
+    const uint32_t t = (((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u;
+    return __popc(t);
+}
+
+// active positions of every segment
+__global__ __launch_bounds__(256) void k_count_seg(const uint8_t* __restrict__ mask, int64_t N, int nseg,
+                                                   int* __restrict__ segcnt) {
     const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (r >= O) return;
-    const uint8_t* m = mask + (size_t)r * I;
-    const float* w = W + (size_t)r * I;
-    int canon = rowptr[r];
-    for (int i0 = 0; i0 < I; i0 += 64) {
-        const int i = i0 + lane;
-        const bool on = i < I && m[i] != 0;
-        const unsigned long long bal = __ballot(on);
-        if (on) {
-            const int k = canon + __popcll(bal & ((1ull << lane) - 1ull));
-            vals[k] = w[i];
-            flat[k] = r * I + i;
+    const int sg = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (sg >= nseg) return;
+    const int64_t base = (int64_t)sg * CSEG;
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < CSEG; j += 1024) {           // 16 bytes per lane and round
+        const int64_t p = base + j + 16 * lane;
+        if (p + 16 <= N) {
+            const uint4 m = *reinterpret_cast<const uint4*>(mask + p);
+            c += nonzero_bytes(m.x) + nonzero_bytes(m.y) + nonzero_bytes(m.z) + nonzero_bytes(m.w);
+        } else {
+            for (int u = 0; u < 16; ++u) c += (p + u < N && mask[p + u] != 0) ? 1 : 0;
         }
-        canon += __popcll(bal);
     }
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
+    if (lane == 0) segcnt[sg] = c;
+}
+
+// segptr[sg] = active positions before segment sg.  A lane takes four consecutive positions of a
+// window of 256; the row pointers are written by the wavefront whose segment holds the row's
+// first position (rowptr[O] by the last one).
+__global__ __launch_bounds__(256) void k_fill_canonical(const uint8_t* __restrict__ mask, const float* __restrict__ W, int O, int I,
+                                                        int64_t N, int nseg, const int* __restrict__ segptr,
+                                                        int* __restrict__ rowptr, float* __restrict__ vals,
+                                                        int* __restrict__ flat) {
+    const int lane = threadIdx.x & 63;
+    const int sg = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (sg >= nseg) return;
+    const int64_t base = (int64_t)sg * CSEG, end = min(N, base + (int64_t)CSEG);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int canon = segptr[sg];
+    int64_t row = (base + I - 1) / I;                 // first row that starts at or after base
+    for (int64_t w0 = base; w0 < end; w0 += 256) {
+        const int64_t p = w0 + 4 * lane;
+        bool on[4] = {false, false, false, false};
+        float w[4] = {0.f, 0.f, 0.f, 0.f};
+        if (p + 4 <= end) {
+            const uint32_t m4 = *reinterpret_cast<const uint32_t*>(mask + p);
+            if (m4) {
+                const float4 w4 = *reinterpret_cast<const float4*>(W + p);
+                w[0] = w4.x; w[1] = w4.y; w[2] = w4.z; w[3] = w4.w;
+            }
+            on[0] = (m4 & 0xFFu) != 0; on[1] = (m4 & 0xFF00u) != 0; on[2] = (m4 & 0xFF0000u) != 0; on[3] = (m4 & 0xFF000000u) != 0;
+        } else {
+            for (int u = 0; u < 4; ++u)
+                if (p + u < end && mask[p + u] != 0) { on[u] = true; w[u] = W[p + u]; }
+        }
+        unsigned long long bal[4];
+        int before = 0, total = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            bal[u] = __ballot(on[u]);
+            before += __popcll(bal[u] & below);
+            total += __popcll(bal[u]);
+        }
+        int k = canon + before;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (on[u]) { vals[k] = w[u]; flat[k] = (int)(p + u); ++k; }
+        const int64_t wend = min(end, w0 + 256);
+        for (int64_t q = row * I; q < wend; q += I, ++row) {   // rows that start inside the window
+            const int l = (int)(q - w0) >> 2, u0 = (int)(q - w0) & 3;
+            const unsigned long long lt = (1ull << l) - 1ull;
+            int cnt = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cnt += __popcll(bal[u] & lt) + ((u < u0) ? (int)((bal[u] >> l) & 1ull) : 0);
+            if (lane == 0) rowptr[row] = canon + cnt;
+        }
+        canon += total;
+    }
+    if (sg == nseg - 1 && lane == 0) rowptr[O] = canon;
 }
 
 // block = (64 columns, chunk c of KC rows): rows i0 .. i0+63 of the col view, chunk c.  The
@@ -605,11 +671,13 @@ int build_views(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_
 // vals / flat / rowptr alone (three launches): what a layer served by the dense contractions needs
 int build_canonical(mst_layer* L, const float* Wsrc, const Workspace& ws, hipStream_t s) {
     L->views_valid = false;
-    k_count_row<<<L->O, 256, (size_t)L->row.nchunk * 4, s>>>(L->mask, L->O, L->I, L->row.nchunk, 0, nullptr, ws.rowcnt);
+    const int nseg = (int)cdiv(L->N, CSEG);
+    k_count_seg<<<(unsigned)cdiv(nseg, 4), 256, 0, s>>>(L->mask, L->N, nseg, ws.segcnt);
     MST_LAUNCH_CHECK();
-    const int rc = scan_excl_i32(ws.rowcnt, L->rowptr, L->O, s);
+    const int rc = scan_excl_i32(ws.segcnt, ws.segcnt, nseg, s);
     if (rc != MST_OK) return rc;
-    k_fill_canonical<<<(unsigned)cdiv(L->O, 4), 256, 0, s>>>(L->mask, Wsrc, L->O, L->I, L->rowptr, L->vals, L->flat);
+    k_fill_canonical<<<(unsigned)cdiv(nseg, 4), 256, 0, s>>>(L->mask, Wsrc, L->O, L->I, L->N, nseg, ws.segcnt, L->rowptr, L->vals,
+                                                          L->flat);
     MST_LAUNCH_CHECK();
     return MST_OK;
 }

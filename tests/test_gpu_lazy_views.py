@@ -130,3 +130,22 @@ def test_first_update_before_any_product_call_builds_the_views():
     W, M = _update(rig, W, M, dev(Gh), Gh, 0.4, 11)
     assert rig.layer.format_stats()["row_view_slots"] >= rig.layer.nnz
     assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL
+
+
+@pytest.mark.parametrize("O,I", [(7, 5), (37, 131), (3, 3000), (2500, 3), (9, 4099), (1, 1)])
+def test_canonical_arrays_after_a_dense_path_update_of_a_ragged_layer(O, I):
+    """vals / flat of a layer whose views stay unbuilt are the ordered compaction of the mask taken as
+    one sequence of O*I positions: shapes whose rows do not align with anything."""
+    T = 64
+    W, M = synth.make_layer(300 + O, 1, I, O, 0.7)
+    X, dY = synth.make_activations(300 + O, 1, T, I, O)
+    rig = Rig(W, M, T, cap=O * I)
+    L = rig.layer
+    assert rel_err(rig.fwd(X), opr.fc_fwd(X, W, M)) <= TOL            # the call tells the layer its batch
+    Gh = opr.dense_grad(dY, X).astype(np.float32)
+    W, M = _update(rig, W, M, dev(Gh), Gh, 0.5, 17)
+    nnz = int(M.sum())
+    if nnz > 0.3 * O * I and O * I > 1:                                # (an update that changes nothing rebuilds nothing)
+        assert L.format_stats()["row_view_slots"] == 0                 # canonical arrays only
+    np.testing.assert_array_equal(L.values().cpu().numpy()[:nnz], W.reshape(-1)[np.flatnonzero(M.reshape(-1))])
+    _check_products("ragged %dx%d" % (O, I), rig, W, M, X, dY, dev(X), dev(dY), T)
