@@ -382,7 +382,7 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
     # fwd / bwd_input are one SpMM launch or one masked dense product; bwd is the shared walk followed by its
     # small second kernel unless a dense contraction serves one of the two gradients (then separate kernels)
     dp, dw = dense_prod[dL.name], dense_wgrad[dL.name]
-    spmm_k = "k_spmm / k_spmm64 (launch shape chosen per call)"
+    spmm_k = "k_spmm / k_spmm64 (launch shape chosen per call) + k_heavy_fwd after the forward (heavy rows as a dense product; returns at once without any)"
     gemm_k = "k_gemm_split256 / k_gemm_split_n160 / k_gemm_split (fp32 operands as bf16 hi + lo)" if act == "f32" else \
         "k_gemm_a16_256 (bfloat16 activations x fp32 weights as bf16 hi + lo, 2 products per term)"
     wgrad_dense_k = ("k_gemm_tn_bf16" if act == "bf16" else "k_gemm_split256<TN> / k_gemm_split<TN>") + " + k_gather_flat"

@@ -158,6 +158,21 @@ int64_t mst_layer_nnz(const mst_layer_t* layer);
  * MST_ERR_ARG for a combination that does not exist. */
 int mst_spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront);
 
+/* Heavy rows.  When the index views of a layer are built, rows of W . M that hold at least a
+ * quarter of a row's positions AND at least four times the mean row (and at least 32 entries) --
+ * the first 64 such rows in row order -- are kept out of the row view and stored as a small
+ * dense matrix instead; mst_sparse_fc_fwd computes their outputs Y[:, row] with a dense
+ * contraction on the matrix cores (fp32 operands split into bfloat16 hi + lo as described at
+ * mst_gemm_force_fp32_mfma: within 2^-16 per term of the fp32 product) after the sparse kernel
+ * has written the others.  Masks with power-law row lengths have such rows (a few dozen rows
+ * holding most of the nonzeros); uniformly random masks have none, and nothing changes for
+ * them.  The backward products and every index order are unaffected.  By default (1) the rule
+ * applies to layers of at least 2^20 positions (smaller ones do not earn the extra pass back);
+ * mst_heavy_rows(0) switches it off and mst_heavy_rows(2) on for every layer, for the views
+ * built from then on in this process.  Test and measurement aid, not thread-safe; MST_ERR_ARG
+ * for another value. */
+int mst_heavy_rows(int on);
+
 /* ------------------------------------------------------------- the products */
 
 /* Y_dev [T*O] = X_dev [T*I] (W.M)^T.  T >= 1. */

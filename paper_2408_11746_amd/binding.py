@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
         "mst_bwd_force_shape": (i32, [i32, i32]),
         "mst_gemm_force_fp32_mfma": (i32, [i32]),
         "mst_gemm_last_tile": (i32, []),
+        "mst_heavy_rows": (i32, [i32]),
         "mst_gather_active": (i32, [vp, vp, vp, vp]),
         "mst_layer_format_stats": (i32, [vp, C.POINTER(FormatStats), vp]),
         "mst_probe_lds_read": (i32, [vp, i32, i32, i32, vp]),
@@ -131,7 +132,7 @@ EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_w
            "mst_layer_values", "mst_layer_sync_values", "mst_layer_indices", "mst_layer_set_path", "mst_layer_uses_dense", "mst_layer_set_prune_lambda",
            "mst_spmm_force_shape",
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight", "mst_sparse_fc_bwd_weight_static",
-           "mst_static_scratch_bytes", "mst_sparse_fc_bwd", "mst_bwd_force_shape", "mst_gemm_force_fp32_mfma", "mst_gemm_last_tile",
+           "mst_static_scratch_bytes", "mst_sparse_fc_bwd", "mst_bwd_force_shape", "mst_gemm_force_fp32_mfma", "mst_gemm_last_tile", "mst_heavy_rows",
            "mst_gather_active", "mst_layer_format_stats", "mst_probe_lds_read", "mst_update_due", "mst_update_seed",
            "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
            "mst_sparse_fc_bwd_weight_update",
@@ -301,6 +302,10 @@ def mst_bwd_force_shape(wavefronts_per_workgroup: int = 0, quads_per_wavefront: 
 
 def mst_gemm_last_tile() -> int:
     return lib().mst_gemm_last_tile()
+
+
+def mst_heavy_rows(on: int = 1):
+    _check("mst_heavy_rows", lib().mst_heavy_rows(on))
 
 
 def mst_gemm_force_fp32_mfma(on):

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmst_hip.so")
-SOURCES = ["schedule.cpp", "layer.hip", "spmm.hip", "sddmm.hip", "bwd_fused.hip", "gemm_mfma.hip", "select.hip", "attention_mask.hip", "probe.hip", "api.hip"]
+SOURCES = ["schedule.cpp", "layer.hip", "spmm.hip", "sddmm.hip", "bwd_fused.hip", "gemm_mfma.hip", "select.hip", "heavy.hip", "attention_mask.hip", "probe.hip", "api.hip"]
 # packed-fp32 VALU forms are switched off for every HIP translation unit
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -100,6 +100,8 @@ int mst_gemm_force_fp32_mfma(int on) { return gemm_force_fp32_mfma(on); }
 
 int mst_gemm_last_tile(void) { return gemm_last_tile(); }
 
+int mst_heavy_rows(int on) { return heavy_rows_enable(on); }
+
 int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront) {
     return bwd_fused_force_shape(wavefronts_per_workgroup, quads_per_wavefront);
 }
@@ -112,7 +114,9 @@ int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int
     note_call(L, act, T);
     // (unbuilt views and no workspace to build them with: the dense product, same result within tolerance)
     if (use_dense_path(L, act, T) || !L->views_valid) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
-    return spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
+    const int rc = spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
+    if (rc != MST_OK) return rc;
+    return heavy_fwd(L, X_dev, Y_dev, T, act, s);        // the rows the view leaves out (returns at once without any)
 }
 
 int mst_sparse_fc_bwd_input(const mst_layer_t* L, const void* dY_dev, float* dX_dev, int T, mst_dtype act,

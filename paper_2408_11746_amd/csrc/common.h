@@ -17,6 +17,7 @@ constexpr int TT = 128;          // tokens per LDS tile
 constexpr int RB = 16;           // rows per row block: 4 lane groups x 4 quads
 constexpr int MAX_WG_BLOCKS = 32;
 constexpr int SPREAD_FLAG = 1 << 30;   // in rowmap / rowpos: the quad holds ONE row spread over its four lane groups   // most row blocks one workgroup may own
+constexpr int HEAVY_MAX = 64;   // rows a layer may keep out of its row view as a small dense matrix (heavy.hip)
 constexpr int PAIR_TAIL = 16;    // readable step pairs past the last one (a whole entry batch may be fetched there)
 
 // LDS tile layout: row k (one contraction index) holds TT tokens = 512 bytes as 32
@@ -58,6 +59,20 @@ struct View {
     int* rowpos = nullptr; // [NBpad * 16] row -> rank inside its block
 };
 
+// Hd row j = row heavy[1 + j] of W . M, from the canonical arrays, by one block (heavy rows, heavy.hip).
+// Every thread of the block must call it; j at or past the count does nothing.
+__device__ inline void heavy_fill_row(int j, const int* __restrict__ heavy, const int* __restrict__ rowptr,
+                                      const int* __restrict__ flat, const float* __restrict__ vals, int I,
+                                      float* __restrict__ Hd) {
+    if (j >= min(heavy[0], HEAVY_MAX)) return;
+    const int h = heavy[1 + j];
+    float* row = Hd + (int64_t)j * I;
+    for (int i = threadIdx.x; i < I; i += blockDim.x) row[i] = 0.f;
+    __syncthreads();
+    const int k1 = rowptr[h + 1];
+    for (int k = rowptr[h] + threadIdx.x; k < k1; k += blockDim.x) row[flat[k] - h * I] = vals[k];
+}
+
 }  // namespace mst
 
 struct mst_layer {
@@ -84,6 +99,10 @@ struct mst_layer {
     mst::View row;             // S = W   [O x I], used by fwd (and bwd_weight)
     mst::View col;             // S = W^T [I x O], used by bwd_input
     int* sddmm_view = nullptr; // device flag: view that drives bwd_weight (0 row, 1 col), set when the views are built
+    // Heavy rows (see heavy.hip): device list [0] = count, [1 + j] = row; Hd [HEAVY_MAX x I] their dense weights.
+    // Both follow the views: written when they are built, Hd again whenever the values change.
+    int* heavy = nullptr;
+    float* Hd = nullptr;
 };
 
 namespace mst {
@@ -166,5 +185,10 @@ int dense_products_bwd_input(const mst_layer* L, const void* dY, float* dX, int 
 int dense_products_bwd_weight(const mst_layer* L, const void* dY, const void* X, float* dW, int T,
                               mst_dtype act, const Workspace& ws, hipStream_t s);
 int refresh_dense_copy(mst_layer* L, hipStream_t s);
+// heavy rows of the forward product; see heavy.hip
+int heavy_rows_enable(int on);
+int heavy_mark(const mst_layer* L, const Workspace& ws, int Rpad, hipStream_t s);
+int heavy_fill(const mst_layer* L, hipStream_t s);
+int heavy_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s);
 
 }  // namespace mst

@@ -15,10 +15,9 @@
 // second kernel adds in a fixed order.
 #include <type_traits>
 #include "common.h"
+#include "split_bf16.h"
 
 namespace mst {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 128, BN = 128;      // bf16 kernel tile
 constexpr int BK = 16;                 // k per LDS tile of the fp32 kernel
@@ -188,10 +187,8 @@ __global__ __launch_bounds__(TM * 2) __attribute__((amdgpu_waves_per_eu(4, 4))) 
 // and stores eight 16-byte rows [m][8 k].  Workgroup tile 128 x 128 x 64; an LDS row is 64 k
 // = 128 bytes = eight 16-byte units, unit u of row m is kept at position u ^ ((m >> 1) & 7):
 // the MFMA operand reads of 16 consecutive rows then cover all banks once.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BKH = 64;            // k per LDS tile
 
-__device__ inline uint32_t bf_unit(int m, int u) { return (uint32_t)(m * 128 + ((u ^ ((m >> 1) & 7)) << 4)); }
 
 // thread -> patch: 16 patches along m x 8 along k, for the A tile (tid < 128) or the B tile
 __device__ inline void fetch_patch(const uint16_t* __restrict__ src, int64_t ld, int k0, int m0, int Kdim,
@@ -309,15 +306,6 @@ __global__ __launch_bounds__(256) void k_gemm_tn_bf16(const uint16_t* __restrict
 // of 128, k ranges multiples of 64, rows 16-byte aligned); everything else takes k_gemm.
 constexpr int SPK = 64;
 
-__device__ inline uint32_t cvt_pk_bf16(float a, float b) {       // {bf16(a), bf16(b)}, round to nearest even
-    uint32_t r;
-    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-__device__ inline void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
-    hi = cvt_pk_bf16(x0, x1);
-    lo = cvt_pk_bf16(x0 - __uint_as_float(hi << 16), x1 - __uint_as_float(hi & 0xFFFF0000u));
-}
 
 template <bool KMAJOR>
 __device__ inline void split_fetch(const float* __restrict__ src, int64_t ld, int k0, int m0, int p, float4 (&r)[8]) {

@@ -63,7 +63,7 @@ bool use_dense_weight_grad(const mst_layer* L, mst_dtype act, int T) {
 
 struct LayerCarve {
     size_t mask, vals, flat, rowptr, Wd;
-    size_t rptr, rent, rperm, rmap, rpos, cptr, cent, cperm, cmap, cpos, choice;
+    size_t rptr, rent, rperm, rmap, rpos, cptr, cent, cperm, cmap, cpos, choice, heavy, Hd;
     size_t total;
 };
 
@@ -90,6 +90,8 @@ static LayerCarve carve_layer(int O, int I, int64_t cap) {
     c.cmap = take((size_t)nbpad(I) * RB * 4);
     c.cpos = take((size_t)nbpad(I) * RB * 4);
     c.choice = take(16);
+    c.heavy = take((size_t)(HEAVY_MAX + 1) * 4);
+    c.Hd = take((size_t)HEAVY_MAX * I * 4);
     c.total = off;
     return c;
 }
@@ -321,7 +323,7 @@ __global__ __launch_bounds__(1024) void k_view_ptr(const int* __restrict__ rowcn
                                                    int64_t nseg, int* __restrict__ ptr,
                                                    unsigned long long* __restrict__ cost_mine,
                                                    const unsigned long long* __restrict__ cost_row, int prefer_col,
-                                                   int* __restrict__ choice) {
+                                                   int* __restrict__ choice, const int* __restrict__ heavy) {
     __shared__ int wsum[16];
     __shared__ unsigned long long cost_s;
     if (rowcnt) block_scan_excl(rowcnt, rowptr, nrows, wsum);
@@ -358,7 +360,8 @@ __global__ __launch_bounds__(1024) void k_view_ptr(const int* __restrict__ rowcn
     if (mine) atomicAdd(&cost_s, mine);
     __syncthreads();
     if (threadIdx.x == 0) {
-        *cost_mine = cost_s;
+        // a row view that leaves heavy rows out cannot drive the weight gradient
+        *cost_mine = (heavy && heavy[0] > 0) ? (1ull << 50) : cost_s;
         if (choice) {
             const unsigned long long pr = *cost_row, pc = cost_s;
             int ch = prefer_col;
@@ -394,10 +397,12 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
                            const int* __restrict__ rowptr, const int* __restrict__ ptr,
                            const int* __restrict__ rowpos, const int* __restrict__ rowmap,
                            float* __restrict__ vals, int* __restrict__ flat, int* __restrict__ cidx,
-                           uint2* __restrict__ ent, int* __restrict__ perm) {
+                           uint2* __restrict__ ent, int* __restrict__ perm, const int* __restrict__ heavy) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (r >= NB * RB) return;
+    // a heavy row (HEAVY_MAX = 64 list entries, one per lane) fills the canonical arrays only
+    const bool hv = __ballot(lane < heavy[0] && heavy[1 + lane] == r) != 0ull;
     const int b = r / RB, rp = rowpos[r], rank = rp & ~SPREAD_FLAG, g = rank & 3, q = rank >> 2;
     const bool spread = (rp & SPREAD_FLAG) != 0;
     // an empty row placed in a spread quad: the quad's slots belong to the spread row
@@ -422,14 +427,16 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
                 vals[k] = v;
                 flat[k] = r * I + i;
                 cidx[(size_t)r * I + i] = k;
-                const int64_t e = spread ? entry_slot(pair0, j & 3, j >> 2) : entry_slot(pair0, g, j);
-                ent[e] = make_uint2(lds_off((uint32_t)(i - c * KC)), __float_as_uint(v));
-                perm[e] = k;
+                if (!hv) {
+                    const int64_t e = spread ? entry_slot(pair0, j & 3, j >> 2) : entry_slot(pair0, g, j);
+                    ent[e] = make_uint2(lds_off((uint32_t)(i - c * KC)), __float_as_uint(v));
+                    perm[e] = k;
+                }
             }
             run += __popcll(bal);
         }
         canon += run;
-        if (!guest) pad_row_slots(ent, perm, pair0, npairs, g, spread, run, lane, 64);
+        if (!guest) pad_row_slots(ent, perm, pair0, npairs, g, spread, hv ? 0 : run, lane, 64);
     }
 }
 
@@ -566,12 +573,17 @@ __global__ __launch_bounds__(256) void k_fill_col(const uint8_t* __restrict__ ma
 }
 
 // Both views in one launch: the first `row_blocks` blocks refresh the row view's entries,
-// the others the col view's.
-__global__ void k_sync_views(const float* __restrict__ vals, unsigned row_blocks,
+// the next `col_blocks` the col view's, the last HEAVY_MAX the dense matrix of the heavy rows.
+__global__ void k_sync_views(const float* __restrict__ vals, unsigned row_blocks, unsigned col_blocks,
                              const int* __restrict__ ptr_r, int64_t nseg_r, const int* __restrict__ perm_r,
                              uint2* __restrict__ ent_r,
                              const int* __restrict__ ptr_c, int64_t nseg_c, const int* __restrict__ perm_c,
-                             uint2* __restrict__ ent_c) {
+                             uint2* __restrict__ ent_c, const int* __restrict__ heavy, const int* __restrict__ rowptr,
+                             const int* __restrict__ flat, int I, float* __restrict__ Hd) {
+    if (blockIdx.x >= row_blocks + col_blocks) {
+        heavy_fill_row((int)(blockIdx.x - row_blocks - col_blocks), heavy, rowptr, flat, vals, I, Hd);
+        return;
+    }
     const bool col = blockIdx.x >= row_blocks;
     const int* __restrict__ ptr = col ? ptr_c : ptr_r;
     const int* __restrict__ perm = col ? perm_c : perm_r;
@@ -626,6 +638,9 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     const int Rpad = v.NBpad * RB;
     if (row_view) {
         k_count_row<<<Rpad, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
+        MST_LAUNCH_CHECK();
+        const int rc = heavy_mark(L, ws, Rpad, s);      // heavy rows leave the view
+        if (rc != MST_OK) return rc;
     } else {
         dim3 gcnt((unsigned)cdiv(Rpad, 64), (unsigned)v.nchunk);
         k_count_col<<<gcnt, 256, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
@@ -637,12 +652,15 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     MST_LAUNCH_CHECK();
     k_view_ptr<<<1, 1024, 0, s>>>(row_view ? ws.rowcnt : nullptr, L->rowptr, O, ws.qlen, v.NBpad, v.NB, v.nchunk, v.nseg,
                                   v.ptr, cost + (row_view ? 0 : 1), cost, L->I > L->O ? 1 : 0,
-                                  row_view ? nullptr : L->sddmm_view);
+                                  row_view ? nullptr : L->sddmm_view, row_view ? L->heavy : nullptr);
     MST_LAUNCH_CHECK();
     if (row_view) {
         k_fill_row<<<(unsigned)cdiv(v.NB * RB, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.NBpad, v.NB, L->rowptr, v.ptr,
                                                               v.rowpos, v.rowmap, L->vals, L->flat, ws.cidx,
-                                                              reinterpret_cast<uint2*>(v.ent), v.perm);
+                                                              reinterpret_cast<uint2*>(v.ent), v.perm, L->heavy);
+        MST_LAUNCH_CHECK();
+        const int rc = heavy_fill(L, s);
+        if (rc != MST_OK) return rc;
     } else {
         dim3 gcol((unsigned)cdiv(v.NB * RB, 64), (unsigned)v.nchunk);
         k_fill_col<<<gcol, 256, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.NB, v.ptr, v.rowpos, v.rowmap, ws.cidx,
@@ -750,6 +768,8 @@ int mst_layer_create(mst_layer_t** out, int O, int I, int64_t nnz_capacity, void
     L->rowptr = (int*)(b + c.rowptr);
     L->Wd = (float*)(b + c.Wd);
     L->sddmm_view = (int*)(b + c.choice);
+    L->heavy = (int*)(b + c.heavy);
+    L->Hd = (float*)(b + c.Hd);
     auto init_view = [&](View& v, int R, int K, size_t optr, size_t oent, size_t operm, size_t omap, size_t opos) {
         v.R = R; v.K = K; v.nchunk = (int)nchunks(K); v.NB = (int)nblocks(R); v.NBpad = (int)nbpad(R);
         v.nseg = (int64_t)v.nchunk * v.NBpad * 4;
@@ -835,8 +855,9 @@ int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
     const View &r = L->row, &c = L->col;
     const unsigned rb = (unsigned)cdiv(4 * (L->nnz + (int64_t)r.nchunk * r.NB * 4), 256);
     const unsigned cb = (unsigned)cdiv(4 * (L->nnz + (int64_t)c.nchunk * c.NB * 4), 256);
-    k_sync_views<<<rb + cb, 256, 0, s>>>(L->vals, rb, r.ptr, r.nseg, r.perm, reinterpret_cast<uint2*>(r.ent),
-                                         c.ptr, c.nseg, c.perm, reinterpret_cast<uint2*>(c.ent));
+    k_sync_views<<<rb + cb + HEAVY_MAX, 256, 0, s>>>(L->vals, rb, cb, r.ptr, r.nseg, r.perm, reinterpret_cast<uint2*>(r.ent),
+                                                     c.ptr, c.nseg, c.perm, reinterpret_cast<uint2*>(c.ent), L->heavy,
+                                                     L->rowptr, L->flat, L->I, L->Hd);
     MST_LAUNCH_CHECK();
     return MST_OK;
 }

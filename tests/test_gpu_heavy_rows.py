@@ -1,0 +1,160 @@
+"""Heavy rows: rows of W . M that a power-law mask fills (nearly) completely are kept out of the
+row view and multiplied as a small dense matrix on the matrix cores.
+
+Whatever the split, every product is the one of App. "FLOP Calculation" Eq. (1) and its
+gradients: each call is compared with the oracle on the complete outputs, with the rule on and
+off, on shapes whose sizes align with nothing, with more qualifying rows than the dense matrix
+holds, with bfloat16 activations, and across a change of the values and a Mixed-Growing update
+(Algorithm 1), whose masks and weights stay bit-exact."""
+import numpy as np
+import pytest
+
+import paper_2408_11746_amd as mst
+import synth
+from oracle import mixed_growing as omg
+from oracle import products as opr
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from gpu_util import Rig, TOL, DEV, dev, rel_err  # noqa: E402
+
+HEAVY_MAX = 64
+
+
+def heavy_rule(M):
+    """Rows the library's rule takes: length >= max(I / 4, 4 * ceil(nnz / O), 32), the first 64 in row order."""
+    O, I = M.shape
+    lens = M.sum(axis=1).astype(np.int64)
+    nnz = int(lens.sum())
+    thr = max(I // 4, 4 * -(-nnz // O), 32)
+    return np.flatnonzero(lens >= thr)
+
+
+@pytest.fixture(autouse=True)
+def _rule_for_every_layer():
+    mst.mst_heavy_rows(2)          # (the default leaves layers as small as these alone)
+    yield
+    mst.mst_heavy_rows(1)
+
+
+def _all_products(tag, rig, W, M, X, dY, act=mst.MST_F32, Xd=None, dYd=None):
+    T = X.shape[0]
+    Xd = dev(X) if Xd is None else Xd
+    dYd = dev(dY) if dYd is None else dYd
+    nnz = rig.layer.nnz
+    Y = torch.full((T, rig.O), float("nan"), dtype=torch.float32, device=DEV)
+    dX = torch.full((T, rig.I), float("nan"), dtype=torch.float32, device=DEV)
+    dW = torch.full((max(nnz, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    dX2 = torch.full((T, rig.I), float("nan"), dtype=torch.float32, device=DEV)
+    dW2 = torch.full((max(nnz, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    mst.mst_sparse_fc_fwd(rig.layer, Xd, Y, T, act)
+    mst.mst_sparse_fc_bwd_input(rig.layer, dYd, dX, T, act)
+    mst.mst_sparse_fc_bwd_weight(rig.layer, dYd, Xd, dW, T, rig.ws, act)
+    mst.mst_sparse_fc_bwd(rig.layer, dYd, Xd, dX2, dW2, T, rig.ws, act)
+    torch.cuda.synchronize()
+    ref_dw = opr.fc_bwd_weight(dY, X, M)
+    e = (rel_err(Y.cpu().numpy(), opr.fc_fwd(X, W, M)), rel_err(dX.cpu().numpy(), opr.fc_bwd_input(dY, W, M)),
+         rel_err(dW.cpu().numpy()[:nnz], ref_dw), rel_err(dX2.cpu().numpy(), opr.fc_bwd_input(dY, W, M)),
+         rel_err(dW2.cpu().numpy()[:nnz], ref_dw))
+    print(tag, "errors fwd / dX / dW / bwd.dX / bwd.dW:", e, flush=True)
+    assert max(e) <= TOL, (tag, e)
+    return Y.cpu().numpy()
+
+
+@pytest.mark.parametrize("O,I,T,d", [(300, 200, 150, 0.06), (512, 256, 256, 0.04), (96, 1000, 77, 0.08), (130, 257, 65, 0.08),
+                                      (1024, 768, 320, 0.02)])
+def test_products_of_a_power_law_layer_with_heavy_rows(O, I, T, d):
+    W, M = synth.make_layer(500 + O, 1, I, O, d, "powerlaw")
+    X, dY = synth.make_activations(500 + O, 1, T, I, O)
+    hv = heavy_rule(M)
+    assert 0 < hv.size, "the case must have heavy rows"
+    mst.mst_heavy_rows(2)
+    rig = Rig(W, M, T)
+    rig.layer.set_path(mst.MST_PATH_SPARSE)
+    slots_on = rig.layer.format_stats()["row_view_slots"]
+    Y_on = _all_products("rule on  %dx%d" % (O, I), rig, W, M, X, dY)
+    mst.mst_heavy_rows(0)
+    rig0 = Rig(W, M, T)
+    rig0.layer.set_path(mst.MST_PATH_SPARSE)
+    slots_off = rig0.layer.format_stats()["row_view_slots"]
+    Y_off = _all_products("rule off %dx%d" % (O, I), rig0, W, M, X, dY)
+    assert slots_off >= int(M.sum()) and slots_on < slots_off       # the view lost the heavy rows' entries
+    # the columns of the other rows come from the same sparse kernel either way (a row may change its
+    # place in its block, and with it the order of its additions: equal to fp32 rounding, not bit for bit)
+    others = np.setdiff1d(np.arange(O), hv[:HEAVY_MAX])
+    assert rel_err(Y_on[:, others], Y_off[:, others]) <= 2e-6
+
+
+def test_more_qualifying_rows_than_the_dense_matrix_holds():
+    """100 rows of 40 entries among 900 rows of one entry (I = 128: a quarter row is 32): the first 64
+    qualifying rows go to the dense matrix, the other 36 stay in the row view."""
+    O, I, T = 1000, 128, 200
+    rng = np.random.default_rng(5)
+    M = np.zeros((O, I), np.uint8)
+    big = np.sort(rng.choice(O, 100, replace=False))
+    for r in range(O):
+        M[r, rng.choice(I, 40 if r in set(big.tolist()) else 1, replace=False)] = 1
+    W = (rng.standard_normal((O, I)) * 0.05).astype(np.float32) * M
+    X, dY = synth.make_activations(77, 2, T, I, O)
+    hv = heavy_rule(M)
+    assert hv.size == 100
+    rig = Rig(W, M, T)
+    rig.layer.set_path(mst.MST_PATH_SPARSE)
+    fs = rig.layer.format_stats()
+    assert fs["nnz"] == int(M.sum())
+    _all_products("100 qualifying rows", rig, W, M, X, dY)
+
+
+def test_bf16_activations_with_heavy_rows():
+    O, I, T = 384, 520, 190
+    W, M = synth.make_layer(41, 1, I, O, 0.05, "powerlaw")
+    assert heavy_rule(M).size > 0
+    Xf, dYf, xb, yb = synth.make_activations(41, 1, T, I, O, "bf16")
+    rig = Rig(W, M, T)
+    rig.layer.set_path(mst.MST_PATH_SPARSE)
+    _all_products("bf16", rig, W, M, Xf, dYf, mst.MST_BF16, dev(xb.view(np.int16)), dev(yb.view(np.int16)))
+
+
+def test_values_and_topology_changes_reach_the_dense_matrix():
+    O, I, T = 400, 320, 128
+    W, M = synth.make_layer(61, 1, I, O, 0.05, "powerlaw")
+    assert heavy_rule(M).size > 0
+    X, dY = synth.make_activations(61, 1, T, I, O)
+    rig = Rig(W, M, T, cap=O * I)
+    L = rig.layer
+    L.set_path(mst.MST_PATH_SPARSE)
+    _all_products("loaded", rig, W, M, X, dY)
+    # the caller's optimiser changes the values
+    L.values().mul_(-0.75)
+    L.sync_values()
+    W = (W * np.float32(-0.75)).astype(np.float32)
+    _all_products("after a value change", rig, W, M, X, dY)
+    # Algorithm 1 moves the topology (heavy rows lose and gain entries, other rows may become heavy)
+    Gh = opr.dense_grad(dY, X).astype(np.float32)
+    for step, d in enumerate((0.04, 0.08, 0.03)):
+        st = mst.mst_mask_update_from_scores(L, dev(Gh), d, 0.3, 0.25, 900 + step, rig.ws)
+        torch.cuda.synchronize()
+        ref = omg.update(W, M, Gh, d, 0.3, 0.25, 900 + step)
+        We, Me = rig.export()
+        np.testing.assert_array_equal(Me, ref["M"])
+        np.testing.assert_array_equal(We, ref["W"])
+        W, M = ref["W"], ref["M"]
+        assert st["nnz_after"] == int(M.sum())
+        _all_products("after update to %.2f (%d heavy rows)" % (d, heavy_rule(M).size), rig, W, M, X, dY)
+
+
+def test_the_default_takes_layers_of_a_million_positions_only():
+    X, dY = synth.make_activations(7, 1, 96, 1024, 1024)
+    slots = {}
+    for (O, I) in ((1024, 1024), (1024, 768)):
+        W, M = synth.make_layer(70 + I, 1, I, O, 0.02, "powerlaw")
+        assert heavy_rule(M).size > 0
+        for mode in (1, 0):
+            mst.mst_heavy_rows(mode)
+            rig = Rig(W, M, 96)
+            rig.layer.set_path(mst.MST_PATH_SPARSE)
+            slots[(I, mode)] = rig.layer.format_stats()["row_view_slots"]
+            if mode == 1:
+                assert rel_err(rig.fwd(X[:, :I]), opr.fc_fwd(X[:, :I], W, M)) <= TOL
+    assert slots[(1024, 1)] < slots[(1024, 0)] and slots[(768, 1)] == slots[(768, 0)]
