@@ -167,10 +167,11 @@ int mst_spmm_force_shape(int tokens_per_workgroup, int quads_per_wavefront);
  * has written the others.  Masks with power-law row lengths have such rows (a few dozen rows
  * holding most of the nonzeros); uniformly random masks have none, and nothing changes for
  * them.  The backward products and every index order are unaffected.  By default (1) the rule
- * applies to layers of at least 2^20 positions (smaller ones do not earn the extra pass back);
- * mst_heavy_rows(0) switches it off and mst_heavy_rows(2) on for every layer, for the views
- * built from then on in this process.  Test and measurement aid, not thread-safe; MST_ERR_ARG
- * for another value. */
+ * applies to a layer of at least 2^20 positions whose mask, as mst_layer_load_dense received it,
+ * has such rows, and then for the layer's lifetime (smaller layers do not earn the extra pass
+ * back; the others are spared its launch); mst_heavy_rows(0) switches it off and
+ * mst_heavy_rows(2) on for every layer, for the layers loaded from then on in this process.
+ * Test and measurement aid, not thread-safe; MST_ERR_ARG for another value. */
 int mst_heavy_rows(int on);
 
 /* ------------------------------------------------------------- the products */

@@ -115,7 +115,7 @@ int mst_sparse_fc_fwd(const mst_layer_t* L, const void* X_dev, float* Y_dev, int
     // (unbuilt views and no workspace to build them with: the dense product, same result within tolerance)
     if (use_dense_path(L, act, T) || !L->views_valid) return dense_products_fwd(L, X_dev, Y_dev, T, act, s);
     const int rc = spmm(L->row, X_dev, Y_dev, T, L->nnz, act, s);
-    if (rc != MST_OK) return rc;
+    if (rc != MST_OK || !L->heavy_on) return rc;
     return heavy_fwd(L, X_dev, Y_dev, T, act, s);        // the rows the view leaves out (returns at once without any)
 }
 

@@ -103,6 +103,7 @@ struct mst_layer {
     // Both follow the views: written when they are built, Hd again whenever the values change.
     int* heavy = nullptr;
     float* Hd = nullptr;
+    bool heavy_on = false;     // the rule applies to this layer (decided when it is loaded)
 };
 
 namespace mst {
@@ -187,6 +188,7 @@ int dense_products_bwd_weight(const mst_layer* L, const void* dY, const void* X,
 int refresh_dense_copy(mst_layer* L, hipStream_t s);
 // heavy rows of the forward product; see heavy.hip
 int heavy_rows_enable(int on);
+int heavy_rows_mode();
 int heavy_mark(const mst_layer* L, const Workspace& ws, int Rpad, hipStream_t s);
 int heavy_fill(const mst_layer* L, hipStream_t s);
 int heavy_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s);

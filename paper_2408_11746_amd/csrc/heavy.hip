@@ -196,7 +196,8 @@ __global__ __launch_bounds__(1024) void k_mark_heavy(const int* __restrict__ row
     if (tid >= n && tid < HEAVY_MAX) heavy[1 + tid] = 0;
 }
 
-static int g_heavy_rows = 1;     // 0 off, 1 layers of at least 2^20 positions, 2 every layer
+static int g_heavy_rows = 1;     // 0 off, 1 large layers whose loaded mask has heavy rows, 2 every layer
+int heavy_rows_mode() { return g_heavy_rows; }
 
 int heavy_rows_enable(int on) {
     if (on < 0 || on > 2) return MST_ERR_ARG;
@@ -205,13 +206,10 @@ int heavy_rows_enable(int on) {
 }
 
 // Row length from which a row counts as heavy: a quarter of the row and four times the mean row
-// (no row of a uniformly random mask comes near it), never below 32.  INT_MAX when switched off,
-// and for small layers: the dense pass costs a launch, a read of X and T scattered stores per heavy
-// row, which a layer of less than 2^20 positions does not earn back (measured: 768 x 768 at
-// T = 16384 loses 10 us, 768 x 2304 gains 19 us).
+// (no row of a uniformly random mask comes near it), never below 32.  INT_MAX for a layer the rule
+// does not apply to (mst_layer::heavy_on, decided by mst_layer_load_dense).
 int heavy_threshold(const mst_layer* L) {
-    if (!g_heavy_rows || !L->Hd || L->O < 1) return 0x7FFFFFFF;
-    if (g_heavy_rows == 1 && L->N < ((int64_t)1 << 20)) return 0x7FFFFFFF;
+    if (!L->heavy_on || !L->Hd || L->O < 1) return 0x7FFFFFFF;
     const int64_t mean4 = 4 * cdiv(L->nnz, L->O);
     return (int)std::min<int64_t>(0x7FFFFFFF, std::max<int64_t>(std::max<int64_t>(L->I / 4, mean4), 32));
 }

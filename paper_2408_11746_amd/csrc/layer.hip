@@ -402,7 +402,7 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (r >= NB * RB) return;
     // a heavy row (HEAVY_MAX = 64 list entries, one per lane) fills the canonical arrays only
-    const bool hv = __ballot(lane < heavy[0] && heavy[1 + lane] == r) != 0ull;
+    const bool hv = heavy != nullptr && __ballot(lane < heavy[0] && heavy[1 + lane] == r) != 0ull;
     const int b = r / RB, rp = rowpos[r], rank = rp & ~SPREAD_FLAG, g = rank & 3, q = rank >> 2;
     const bool spread = (rp & SPREAD_FLAG) != 0;
     // an empty row placed in a spread quad: the quad's slots belong to the spread row
@@ -638,9 +638,11 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     const int Rpad = v.NBpad * RB;
     if (row_view) {
         k_count_row<<<Rpad, 256, (size_t)v.nchunk * 4, s>>>(L->mask, O, I, v.nchunk, Rpad, ws.segcnt, ws.rowcnt);
-        MST_LAUNCH_CHECK();
-        const int rc = heavy_mark(L, ws, Rpad, s);      // heavy rows leave the view
-        if (rc != MST_OK) return rc;
+        if (L->heavy_on) {
+            MST_LAUNCH_CHECK();
+            const int rc = heavy_mark(L, ws, Rpad, s);  // heavy rows leave the view
+            if (rc != MST_OK) return rc;
+        }
     } else {
         dim3 gcnt((unsigned)cdiv(Rpad, 64), (unsigned)v.nchunk);
         k_count_col<<<gcnt, 256, 0, s>>>(L->mask, O, I, Rpad, ws.segcnt);
@@ -652,15 +654,18 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     MST_LAUNCH_CHECK();
     k_view_ptr<<<1, 1024, 0, s>>>(row_view ? ws.rowcnt : nullptr, L->rowptr, O, ws.qlen, v.NBpad, v.NB, v.nchunk, v.nseg,
                                   v.ptr, cost + (row_view ? 0 : 1), cost, L->I > L->O ? 1 : 0,
-                                  row_view ? nullptr : L->sddmm_view, row_view ? L->heavy : nullptr);
+                                  row_view ? nullptr : L->sddmm_view, row_view && L->heavy_on ? L->heavy : nullptr);
     MST_LAUNCH_CHECK();
     if (row_view) {
         k_fill_row<<<(unsigned)cdiv(v.NB * RB, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.NBpad, v.NB, L->rowptr, v.ptr,
                                                               v.rowpos, v.rowmap, L->vals, L->flat, ws.cidx,
-                                                              reinterpret_cast<uint2*>(v.ent), v.perm, L->heavy);
-        MST_LAUNCH_CHECK();
-        const int rc = heavy_fill(L, s);
-        if (rc != MST_OK) return rc;
+                                                              reinterpret_cast<uint2*>(v.ent), v.perm,
+                                                              L->heavy_on ? L->heavy : nullptr);
+        if (L->heavy_on) {
+            MST_LAUNCH_CHECK();
+            const int rc = heavy_fill(L, s);
+            if (rc != MST_OK) return rc;
+        }
     } else {
         dim3 gcol((unsigned)cdiv(v.NB * RB, 64), (unsigned)v.nchunk);
         k_fill_col<<<gcol, 256, 0, s>>>(L->mask, Wsrc, O, I, v.NBpad, v.NB, v.ptr, v.rowpos, v.rowmap, ws.cidx,
@@ -807,9 +812,24 @@ int mst_layer_load_dense(mst_layer_t* L, const float* W_dev, const uint8_t* M_de
     MST_HIP(hipMemcpyAsync(L->mask, M_dev, (size_t)L->N, hipMemcpyDeviceToDevice, s));
     L->nnz = total;
     L->built = false;                                   // a failed rebuild leaves no usable layer
+    // Heavy rows (heavy.hip).  The dense pass costs a launch after every sparse forward, a read of
+    // X and T scattered stores per heavy row: a layer of less than 2^20 positions does not earn
+    // that back (measured: 768 x 768 at T = 16384 loses 10 us, 768 x 2304 gains 19 us), and a layer
+    // whose loaded mask has no heavy row (every uniformly random mask) should not pay the launch.
+    // So the rule is tried on this first build of a large layer and kept for the layer's lifetime
+    // only if it found rows; the forced mode of the hook keeps it for every layer.
+    const int mode = heavy_rows_mode();
+    L->heavy_on = mode == 2 || (mode == 1 && L->N >= ((int64_t)1 << 20));
     const int rc = build_views(L, W_dev, ws, s);
-    if (rc == MST_OK) L->built = true;
-    return rc;
+    if (rc != MST_OK) return rc;
+    if (L->heavy_on && mode == 1) {
+        int found = 0;
+        MST_HIP(hipMemcpyAsync(&found, L->heavy, 4, hipMemcpyDeviceToHost, s));
+        MST_HIP(hipStreamSynchronize(s));
+        L->heavy_on = found > 0;
+    }
+    L->built = true;
+    return MST_OK;
 }
 
 int mst_layer_export_dense(const mst_layer_t* L, float* W_dev, uint8_t* M_dev, mst_stream_t stream) {
@@ -855,7 +875,7 @@ int mst_layer_sync_values(mst_layer_t* L, mst_stream_t stream) {
     const View &r = L->row, &c = L->col;
     const unsigned rb = (unsigned)cdiv(4 * (L->nnz + (int64_t)r.nchunk * r.NB * 4), 256);
     const unsigned cb = (unsigned)cdiv(4 * (L->nnz + (int64_t)c.nchunk * c.NB * 4), 256);
-    k_sync_views<<<rb + cb + HEAVY_MAX, 256, 0, s>>>(L->vals, rb, cb, r.ptr, r.nseg, r.perm, reinterpret_cast<uint2*>(r.ent),
+    k_sync_views<<<rb + cb + (L->heavy_on ? HEAVY_MAX : 0), 256, 0, s>>>(L->vals, rb, cb, r.ptr, r.nseg, r.perm, reinterpret_cast<uint2*>(r.ent),
                                                      c.ptr, c.nseg, c.perm, reinterpret_cast<uint2*>(c.ent), L->heavy,
                                                      L->rowptr, L->flat, L->I, L->Hd);
     MST_LAUNCH_CHECK();
