@@ -416,7 +416,9 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
                    "nnz": {L.name: L.nnz for L in layers}, "mask_updates_in_timed_region": n_updates,
                    "caller_sgd_lr": args.lr,
                    "ell_efficiency": {L.name: dict(row_view=round(fstats[L.name]["row_view_efficiency"], 4),
-                                                   col_view=round(fstats[L.name]["col_view_efficiency"], 4))
+                                                   col_view=round(fstats[L.name]["col_view_efficiency"], 4),
+                                                   heavy_rows=fstats[L.name]["heavy_rows"],
+                                                   heavy_entries=fstats[L.name]["heavy_entries"])
                                       for L in layers}},
         "hbm_gbs_step": round(bytes_step / (elapsed / args.steps) / 1e9, 1),
         "hbm_frac_step": round(bytes_step / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),

@@ -254,11 +254,13 @@ int mst_gather_active(const mst_layer_t* layer, const float* G_dev, float* dW_de
 /* What the index views of a layer store.  A view keeps, per chunk of 128 contraction indices
  * and quad of four rows, as many steps as the longest of the four rows needs, padded to an
  * even count; each step has one entry slot per row.  efficiency = nnz / slots is the share of
- * walk steps that do real work.  Synchronises `stream` (reads two counters back). */
+ * walk steps that do real work (for the row view: of the entries it holds, nnz minus those of
+ * the heavy rows, see mst_heavy_rows).  Synchronises `stream` (reads a few counters back). */
 typedef struct {
     int64_t nnz;
     int64_t row_view_slots, col_view_slots;     /* entry slots incl. zero-weight padding */
     double row_view_efficiency, col_view_efficiency;
+    int64_t heavy_rows, heavy_entries;          /* rows kept as a dense matrix and their entries (0 if the rule is off) */
 } mst_format_stats;
 int mst_layer_format_stats(const mst_layer_t* layer, mst_format_stats* out, mst_stream_t stream);
 

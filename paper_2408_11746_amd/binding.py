@@ -38,7 +38,8 @@ class UpdateStats(C.Structure):
 
 class FormatStats(C.Structure):
     _fields_ = [("nnz", C.c_int64), ("row_view_slots", C.c_int64), ("col_view_slots", C.c_int64),
-                ("row_view_efficiency", C.c_double), ("col_view_efficiency", C.c_double)]
+                ("row_view_efficiency", C.c_double), ("col_view_efficiency", C.c_double),
+                ("heavy_rows", C.c_int64), ("heavy_entries", C.c_int64)]
 
     def as_dict(self):
         return {k: (int(getattr(self, k)) if t is C.c_int64 else float(getattr(self, k))) for k, t in self._fields_}

@@ -215,16 +215,23 @@ int mst_layer_format_stats(const mst_layer_t* L, mst_format_stats* out, mst_stre
         out->nnz = L->nnz;
         out->row_view_slots = out->col_view_slots = 0;
         out->row_view_efficiency = out->col_view_efficiency = 0.0;
+        out->heavy_rows = out->heavy_entries = 0;
         return MST_OK;
     }
-    int pr = 0, pc = 0;
+    int pr = 0, pc = 0, hv[2] = {0, 0};
     MST_HIP(hipMemcpyAsync(&pr, L->row.ptr + L->row.nseg, 4, hipMemcpyDeviceToHost, s));
     MST_HIP(hipMemcpyAsync(&pc, L->col.ptr + L->col.nseg, 4, hipMemcpyDeviceToHost, s));
+    if (L->heavy_on) {
+        MST_HIP(hipMemcpyAsync(&hv[0], L->heavy, 4, hipMemcpyDeviceToHost, s));
+        MST_HIP(hipMemcpyAsync(&hv[1], L->heavy + HEAVY_MAX + 1, 4, hipMemcpyDeviceToHost, s));
+    }
     MST_HIP(hipStreamSynchronize(s));
     out->nnz = L->nnz;
+    out->heavy_rows = hv[0];
+    out->heavy_entries = hv[1];
     out->row_view_slots = (int64_t)pr * 8;
     out->col_view_slots = (int64_t)pc * 8;
-    out->row_view_efficiency = pr ? (double)L->nnz / (double)out->row_view_slots : 1.0;
+    out->row_view_efficiency = pr ? (double)(L->nnz - hv[1]) / (double)out->row_view_slots : 1.0;
     out->col_view_efficiency = pc ? (double)L->nnz / (double)out->col_view_slots : 1.0;
     return MST_OK;
 }

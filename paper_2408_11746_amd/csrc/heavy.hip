@@ -165,12 +165,16 @@ __global__ __launch_bounds__(256) void k_heavy_fill(const int* __restrict__ heav
 }
 
 // The rows that leave the row view: rowcnt[r] >= thr, the first HEAVY_MAX of them in row order.
-// heavy[0] = their count, heavy[1 + j] = the j-th such row (0 past the count); their per-chunk
-// counts are cleared, so that the view's ranking and pointers see empty rows.  One block.
+// heavy[0] = their count, heavy[1 + j] = the j-th such row (0 past the count), heavy[1 + HEAVY_MAX] =
+// their entries in total; their per-chunk counts are cleared, so that the view's ranking and
+// pointers see empty rows.  One block.
 __global__ __launch_bounds__(1024) void k_mark_heavy(const int* __restrict__ rowcnt, int O, int thr, int* __restrict__ segcnt,
                                                      int nchunk, int Rpad, int* __restrict__ heavy) {
     __shared__ int wsum[16];
+    __shared__ int entries_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) entries_s = 0;
+    __syncthreads();
     int base = 0;
     for (int r0 = 0; r0 < O && base < HEAVY_MAX; r0 += 1024) {
         const int r = r0 + tid;
@@ -186,13 +190,14 @@ __global__ __launch_bounds__(1024) void k_mark_heavy(const int* __restrict__ row
         const int pos = base + before + __popcll(bal & ((1ull << lane) - 1ull));
         if (is && pos < HEAVY_MAX) {
             heavy[1 + pos] = r;
+            atomicAdd(&entries_s, rowcnt[r]);
             for (int c = 0; c < nchunk; ++c) segcnt[(size_t)c * Rpad + r] = 0;
         }
         base += total;
         __syncthreads();
     }
     const int n = min(base, HEAVY_MAX);
-    if (tid == 0) heavy[0] = n;
+    if (tid == 0) { heavy[0] = n; heavy[1 + HEAVY_MAX] = entries_s; }
     if (tid >= n && tid < HEAVY_MAX) heavy[1 + tid] = 0;
 }
 

@@ -90,7 +90,7 @@ static LayerCarve carve_layer(int O, int I, int64_t cap) {
     c.cmap = take((size_t)nbpad(I) * RB * 4);
     c.cpos = take((size_t)nbpad(I) * RB * 4);
     c.choice = take(16);
-    c.heavy = take((size_t)(HEAVY_MAX + 1) * 4);
+    c.heavy = take((size_t)(HEAVY_MAX + 2) * 4);
     c.Hd = take((size_t)HEAVY_MAX * I * 4);
     c.total = off;
     return c;

@@ -72,12 +72,16 @@ def test_products_of_a_power_law_layer_with_heavy_rows(O, I, T, d):
     mst.mst_heavy_rows(2)
     rig = Rig(W, M, T)
     rig.layer.set_path(mst.MST_PATH_SPARSE)
-    slots_on = rig.layer.format_stats()["row_view_slots"]
+    fs = rig.layer.format_stats()
+    slots_on = fs["row_view_slots"]
+    assert fs["heavy_rows"] == min(hv.size, HEAVY_MAX) and fs["heavy_entries"] == int(M[hv[:HEAVY_MAX]].sum())
+    assert 0.0 < fs["row_view_efficiency"] <= 1.0
     Y_on = _all_products("rule on  %dx%d" % (O, I), rig, W, M, X, dY)
     mst.mst_heavy_rows(0)
     rig0 = Rig(W, M, T)
     rig0.layer.set_path(mst.MST_PATH_SPARSE)
     slots_off = rig0.layer.format_stats()["row_view_slots"]
+    assert rig0.layer.format_stats()["heavy_rows"] == 0
     Y_off = _all_products("rule off %dx%d" % (O, I), rig0, W, M, X, dY)
     assert slots_off >= int(M.sum()) and slots_on < slots_off       # the view lost the heavy rows' entries
     # the columns of the other rows come from the same sparse kernel either way (a row may change its
@@ -102,7 +106,7 @@ def test_more_qualifying_rows_than_the_dense_matrix_holds():
     rig = Rig(W, M, T)
     rig.layer.set_path(mst.MST_PATH_SPARSE)
     fs = rig.layer.format_stats()
-    assert fs["nnz"] == int(M.sum())
+    assert fs["nnz"] == int(M.sum()) and fs["heavy_rows"] == HEAVY_MAX and fs["heavy_entries"] == 40 * HEAVY_MAX
     _all_products("100 qualifying rows", rig, W, M, X, dY)
 
 
