@@ -10,9 +10,12 @@
 // v_mfma_f32_32x32x16_bf16 per 16 k (two when X is bfloat16), fp32 accumulation, the same
 // arithmetic as the dense GEMM kernels.  The sparse kernel writes zeros to those columns of Y
 // first (the rows look empty to it); this kernel, launched after it on the same stream,
-// overwrites them.  The count and the list live in device memory (the host never reads them
-// back): the kernel is launched after every sparse forward and returns at once when the
-// layer has no heavy row.
+// overwrites them.  The count and the list live in device memory (an update never reads them
+// back): for a layer the rule applies to, the kernel is launched after every sparse forward and
+// returns at once when the layer has no heavy row at the moment.
+#include <algorithm>
+#include <type_traits>
+
 #include "common.h"
 #include "split_bf16.h"
 
