@@ -77,6 +77,12 @@ def test_products_of_a_power_law_layer_with_heavy_rows(O, I, T, d):
     assert fs["heavy_rows"] == min(hv.size, HEAVY_MAX) and fs["heavy_entries"] == int(M[hv[:HEAVY_MAX]].sum())
     assert 0.0 < fs["row_view_efficiency"] <= 1.0
     Y_on = _all_products("rule on  %dx%d" % (O, I), rig, W, M, X, dY)
+    # the entry point without a workspace walks whichever view the layer names: never the incomplete row view
+    Ts = min(T, 128)
+    dWs = torch.full((rig.layer.nnz,), float("nan"), dtype=torch.float32, device=DEV)
+    mst.mst_sparse_fc_bwd_weight_static(rig.layer, dev(dY[:Ts]), dev(X[:Ts]), dWs, Ts)
+    torch.cuda.synchronize()
+    assert rel_err(dWs.cpu().numpy(), opr.fc_bwd_weight(dY[:Ts], X[:Ts], M)) <= TOL
     mst.mst_heavy_rows(0)
     rig0 = Rig(W, M, T)
     rig0.layer.set_path(mst.MST_PATH_SPARSE)
