@@ -211,7 +211,9 @@ size_t mst_static_scratch_bytes(void);
  * layer's transposed view (the staged dY tile, the entries and every LDS read serve both);
  * dX is bit-identical to mst_sparse_fc_bwd_input, dW_vals equals mst_sparse_fc_bwd_weight up
  * to the order of the fp32 sums.  (A short batch may split the contraction over several
- * workgroups; dX then equals mst_sparse_fc_bwd_input up to the order of its sums too.)
+ * workgroups; dX then equals mst_sparse_fc_bwd_input up to the order of its sums too.  The same
+ * holds on the dense path: with the workspace at hand the dense product for dX may cut its
+ * contraction range into two or three where the output has too few tiles to fill the chip.)
  * Workspace: mst_workspace_bytes(O, I, nnz_capacity, T). */
 int mst_sparse_fc_bwd(const mst_layer_t* layer, const void* dY_dev, const void* X_dev,
                       float* dX_dev, float* dW_vals_dev, int T, mst_dtype act,

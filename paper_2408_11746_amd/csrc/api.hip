@@ -52,16 +52,20 @@ static int ensure_dense_copy(const mst_layer* L, hipStream_t s) {
     return refresh_dense_copy(const_cast<mst_layer*>(L), s);   // cache of vals[], not layer state
 }
 
-int dense_products_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s) {
+// (split_ws: room for partial outputs of a split of the contraction range, used where the output
+// has too few tiles to fill the chip; null: one workgroup per tile whatever their number)
+int dense_products_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s,
+                       float* split_ws, int64_t split_ws_floats) {
     int rc = ensure_dense_copy(L, s);
     if (rc != MST_OK) return rc;
-    return gemm_mfma(GEMM_NT, X, act, L->Wd, MST_F32, Y, T, L->O, L->I, nullptr, 0, s);
+    return gemm_mfma(GEMM_NT, X, act, L->Wd, MST_F32, Y, T, L->O, L->I, split_ws, split_ws_floats, s);
 }
 
-int dense_products_bwd_input(const mst_layer* L, const void* dY, float* dX, int T, mst_dtype act, hipStream_t s) {
+int dense_products_bwd_input(const mst_layer* L, const void* dY, float* dX, int T, mst_dtype act, hipStream_t s,
+                             float* split_ws, int64_t split_ws_floats) {
     int rc = ensure_dense_copy(L, s);
     if (rc != MST_OK) return rc;
-    return gemm_mfma(GEMM_NN, dY, act, L->Wd, MST_F32, dX, T, L->I, L->O, nullptr, 0, s);
+    return gemm_mfma(GEMM_NN, dY, act, L->Wd, MST_F32, dX, T, L->I, L->O, split_ws, split_ws_floats, s);
 }
 
 int dense_products_bwd_weight(const mst_layer* L, const void* dY, const void* X, float* dW, int T,
@@ -182,8 +186,10 @@ int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_de
     if (use_dense_path(L, act, T) || use_dense_weight_grad(L, act, T) || !bwd_fused_pays(L)) {
         // a dense contraction serves at least one of the two, or the layer is so sparse that
         // the separate kernels with their wider slabs are faster: the separate calls
-        int rc = use_dense_path(L, act, T) ? dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s)
-                                   : spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
+        // (the split area of the workspace serves dX first, then the weight gradient: same stream)
+        int rc = use_dense_path(L, act, T)
+                     ? dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s, ws.gemm, (int64_t)ws.gemm_floats)
+                     : spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
         if (rc != MST_OK) return rc;
         return use_dense_weight_grad(L, act, T) ? dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s)
                                                 : sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);

@@ -181,8 +181,10 @@ int gemm_force_fp32_mfma(int on);
 int gemm_last_tile();
 int mask_update_device(mst_layer* L, const float* G, const mst_update_stats& st, uint64_t seed,
                        const Workspace& ws, hipStream_t s);
-int dense_products_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s);
-int dense_products_bwd_input(const mst_layer* L, const void* dY, float* dX, int T, mst_dtype act, hipStream_t s);
+int dense_products_fwd(const mst_layer* L, const void* X, float* Y, int T, mst_dtype act, hipStream_t s,
+                       float* split_ws = nullptr, int64_t split_ws_floats = 0);
+int dense_products_bwd_input(const mst_layer* L, const void* dY, float* dX, int T, mst_dtype act, hipStream_t s,
+                             float* split_ws = nullptr, int64_t split_ws_floats = 0);
 int dense_products_bwd_weight(const mst_layer* L, const void* dY, const void* X, float* dW, int T,
                               mst_dtype act, const Workspace& ws, hipStream_t s);
 int refresh_dense_copy(mst_layer* L, hipStream_t s);

@@ -36,13 +36,18 @@ def test_c2_layer_products_sampled(name, I, O):
     pick = np.unique(np.concatenate([[0, flat.size - 1], rng.integers(0, flat.size, 1500)]))
     ref = np.array([opr.dense_grad_at(dY, X, int(f // I), int(f % I)) for f in flat[pick]])
     assert np.abs(dW[pick] - ref).max() / np.abs(ref).max() <= TOL
-    # the one-call backward, as the benchmark times it: the same input gradient bit for bit, the
+    # the one-call backward, as the benchmark times it: the same input gradient (bit for bit from the
+    # sparse kernels; on the dense path the call may cut the contraction range with its workspace,
+    # another order of additions), the
     # weight gradient at the sampled positions
     dX1 = torch.full((T, I), float("nan"), dtype=torch.float32, device=DEV)
     dW1 = torch.full((rig.layer.nnz,), float("nan"), dtype=torch.float32, device=DEV)
     mst.mst_sparse_fc_bwd(rig.layer, dev(dY), dev(X), dX1, dW1, T, rig.ws)
     torch.cuda.synchronize()
-    np.testing.assert_array_equal(dX1.cpu().numpy(), dX)
+    if rig.layer.uses_dense(mst.MST_F32, T):
+        assert np.abs(dX1.cpu().numpy() - dX).max() <= 2e-6 * np.abs(dX).max()
+    else:
+        np.testing.assert_array_equal(dX1.cpu().numpy(), dX)
     dW1 = dW1.cpu().numpy()
     assert np.abs(dW1[pick] - ref).max() / np.abs(ref).max() <= TOL
     assert rel_err(dW1, dW) <= 1e-5                   # the two weight gradients differ in summation order only
