@@ -666,7 +666,7 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
     _, drow, dL = dominant
     if drow["call"] == "dense_grad":
         kernel = ("k_gemm_split256<TN> (256 x 256 tiles; fp32 operands split into bf16 hi + lo, 3 x "
-                  "v_mfma_f32_32x32x16_bf16 per term) + k_splitk_reduce (ordered sum of its split partial outputs)")
+                  "v_mfma_f32_32x32x16_bf16 per term) + k_splitk_reduce4 (ordered sum of its split partial outputs)")
     elif drow.get("path") == "dense-mfma":
         kernel = ("k_gemm_split256 (masked dense product, bf16 hi + lo split on v_mfma_f32_32x32x16_bf16; preceded by the "
                   "scatter of the dense weight copy after an update)")

@@ -199,9 +199,7 @@ __global__ void k_bwd_fused_reduce(const float* __restrict__ partial, int64_t sl
     if (e >= (int64_t)ptr[nseg] * 8) return;
     const int p = perm[e];
     if (p < 0) return;
-    float sum = 0.f;
-    for (int t = 0; t < ntile; ++t) sum += partial[(int64_t)t * slots_stride + e];
-    dW[p] = sum;
+    dW[p] = ordered_plane_sum(partial + e, slots_stride, ntile);
 }
 
 // dX[k] = sum of the nsplit partial planes, added in ascending order

@@ -1232,6 +1232,7 @@ void k_gemm_tn_bf16_256(const uint16_t* __restrict__ A, int64_t lda, const uint1
             }
 }
 
+// C[i] = part[i] + part[stride + i] + ... (nsplit planes, added in ascending order)
 __global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, int nsplit,
                                 float* __restrict__ C, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1239,6 +1240,37 @@ __global__ void k_splitk_reduce(const float* __restrict__ part, int64_t stride, 
     float s = 0.f;
     for (int z = 0; z < nsplit; ++z) s += part[(int64_t)z * stride + i];
     C[i] = s;
+}
+// the same with four consecutive outputs per thread (n and stride multiples of 4, 16-byte aligned
+// bases): 16-byte loads, a quarter of the threads
+__global__ void k_splitk_reduce4(const float* __restrict__ part, int64_t stride, int nsplit,
+                                 float* __restrict__ C, int64_t n4) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    const float4* p = reinterpret_cast<const float4*>(part) + i;
+    const int64_t s4 = stride >> 2;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    int z = 0;
+    for (; z + 4 <= nsplit; z += 4) {
+        const float4 a = p[(int64_t)z * s4], b = p[(int64_t)(z + 1) * s4], c = p[(int64_t)(z + 2) * s4], d = p[(int64_t)(z + 3) * s4];
+        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+        s.x += b.x; s.y += b.y; s.z += b.z; s.w += b.w;
+        s.x += c.x; s.y += c.y; s.z += c.z; s.w += c.w;
+        s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
+    }
+    for (; z < nsplit; ++z) {
+        const float4 a = p[(int64_t)z * s4];
+        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+    reinterpret_cast<float4*>(C)[i] = s;
+}
+static int sum_split_planes(const float* part, int64_t stride, int nsplit, float* C, int64_t n, hipStream_t s) {
+    if (n % 4 == 0 && stride % 4 == 0 && aligned16(part) && aligned16(C))
+        k_splitk_reduce4<<<(unsigned)cdiv(n / 4, 256), 256, 0, s>>>(part, stride, nsplit, C, n / 4);
+    else
+        k_splitk_reduce<<<(unsigned)cdiv(n, 256), 256, 0, s>>>(part, stride, nsplit, C, n);
+    MST_LAUNCH_CHECK();
+    return MST_OK;
 }
 
 // Number of k ranges (blockIdx.x) a GEMM of `tiles` output tiles is split into.  A CU holds
@@ -1299,8 +1331,8 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
         return MST_OK;
     }
     if (nsplit > 1) {
-        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
-        MST_LAUNCH_CHECK();
+        const int rcs = sum_split_planes(split_ws, mn, nsplit, C, mn, s);
+        if (rcs != MST_OK) return rcs;
     }
     return MST_OK;
 }
@@ -1399,8 +1431,8 @@ static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, 
             *left_unsummed = 3;
             return MST_OK;
         }
-        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, 3, C, mn);
-        MST_LAUNCH_CHECK();
+        const int rcs = sum_split_planes(split_ws, mn, 3, C, mn, s);
+        if (rcs != MST_OK) return rcs;
         return MST_OK;
     }
     if (tile == 160) {
@@ -1416,8 +1448,8 @@ static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, 
         return MST_OK;
     }
     if (nsplit > 1) {
-        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
-        MST_LAUNCH_CHECK();
+        const int rcs = sum_split_planes(split_ws, mn, nsplit, C, mn, s);
+        if (rcs != MST_OK) return rcs;
     }
     return MST_OK;
 }
@@ -1469,8 +1501,8 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
             return MST_OK;
         }
         if (nsplit > 1) {
-            k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
-            MST_LAUNCH_CHECK();
+            const int rcs = sum_split_planes(split_ws, mn, nsplit, C, mn, s);
+            if (rcs != MST_OK) return rcs;
         }
         return MST_OK;
     }
@@ -1488,8 +1520,8 @@ static int launch_tn_bf16(const void* A, const void* B, float* C, int M, int N, 
         return MST_OK;
     }
     if (nsplit > 1) {
-        k_splitk_reduce<<<(unsigned)cdiv(mn, 256), 256, 0, s>>>(split_ws, mn, nsplit, C, mn);
-        MST_LAUNCH_CHECK();
+        const int rcs = sum_split_planes(split_ws, mn, nsplit, C, mn, s);
+        if (rcs != MST_OK) return rcs;
     }
     return MST_OK;
 }

@@ -185,9 +185,7 @@ __global__ void k_sddmm_reduce(const float* __restrict__ partial, int ntile, con
     if (e >= (int64_t)ptr[nseg] * 8) return;
     const int p = perm[e];
     if (p < 0) return;
-    float sum = 0.f;
-    for (int t = 0; t < ntile; ++t) sum += partial[(int64_t)t * slots_stride + e];
-    dW[p] = sum;
+    dW[p] = ordered_plane_sum(partial + e, slots_stride, ntile);
 }
 
 // Quads per wavefront (2, 3 or 4: slabs of 128, 192 or 256 rows), by the cost model of the

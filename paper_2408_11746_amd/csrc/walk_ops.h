@@ -40,6 +40,22 @@ __device__ inline void fold_spread(float (&acc)[NACC], int spread, int g) {
     }
 }
 
+// p[0] + p[stride] + ... + p[(ntile - 1) stride], added in that order (the order is part of the
+// result); sixteen loads are in flight before the first add, a one-by-one loop waits for each.
+__device__ inline float ordered_plane_sum(const float* __restrict__ p, int64_t stride, int ntile) {
+    float sum = 0.f;
+    int t = 0;
+    for (; t + 16 <= ntile; t += 16) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)(t + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum += v[u];
+    }
+    for (; t < ntile; ++t) sum += p[(int64_t)t * stride];
+    return sum;
+}
+
 template <int CTRL>
 __device__ inline float dpp_add(float x) {
     return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
