@@ -390,16 +390,22 @@ __device__ inline void pad_row_slots(uint2* __restrict__ ent, int* __restrict__ 
     }
 }
 
-// one wavefront per row (incl. the padding rows of the last block, which only pad): ordered
-// compaction of the row into canonical arrays and the row view
+// one wavefront per (row, part of its chunks) (incl. the padding rows of the last block, which
+// only pad): ordered compaction of the row into canonical arrays and the row view.  A layer of
+// few long rows gives every row `nparts` wavefronts of `cpp` chunks each (one per row would leave
+// the 1280 rows of a 5120-wide layer on 320 workgroups); a part finds its first canonical index
+// from the per-chunk counts of the chunks before it.  With heavy rows (whose counts were cleared)
+// the launch uses one part.
 __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __restrict__ W,
                            int O, int I, int nchunk, int NBpad, int NB,
                            const int* __restrict__ rowptr, const int* __restrict__ ptr,
                            const int* __restrict__ rowpos, const int* __restrict__ rowmap,
                            float* __restrict__ vals, int* __restrict__ flat, int* __restrict__ cidx,
-                           uint2* __restrict__ ent, int* __restrict__ perm, const int* __restrict__ heavy) {
+                           uint2* __restrict__ ent, int* __restrict__ perm, const int* __restrict__ heavy,
+                           int nparts, int cpp, const int* __restrict__ segcnt, int Rpad) {
     const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int unit = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int r = unit / nparts, c0 = (unit % nparts) * cpp, c1 = min(nchunk, c0 + cpp);
     if (r >= NB * RB) return;
     // a heavy row (HEAVY_MAX = 64 list entries, one per lane) fills the canonical arrays only
     const bool hv = heavy != nullptr && __ballot(lane < heavy[0] && heavy[1 + lane] == r) != 0ull;
@@ -411,7 +417,13 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     const uint8_t* m = mask + (size_t)r * I;
     const float* w = W + (size_t)r * I;
     int canon = real ? rowptr[r] : 0;
-    for (int c = 0; c < nchunk; ++c) {
+    if (real && c0 > 0) {                             // entries of this row in the chunks before c0
+        int before = 0;
+        for (int c = lane; c < c0; c += 64) before += segcnt[(size_t)c * Rpad + r];
+        for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, 64);
+        canon += before;
+    }
+    for (int c = c0; c < c1; ++c) {
         const size_t seg = ((size_t)c * NBpad + b) * 4 + q;
         const int pair0 = ptr[seg], npairs = ptr[seg + 1] - pair0;
         int run = 0;
@@ -657,10 +669,12 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
                                   row_view ? nullptr : L->sddmm_view, row_view && L->heavy_on ? L->heavy : nullptr);
     MST_LAUNCH_CHECK();
     if (row_view) {
-        k_fill_row<<<(unsigned)cdiv(v.NB * RB, 4), 256, 0, s>>>(L->mask, Wsrc, O, I, v.nchunk, v.NBpad, v.NB, L->rowptr, v.ptr,
-                                                              v.rowpos, v.rowmap, L->vals, L->flat, ws.cidx,
-                                                              reinterpret_cast<uint2*>(v.ent), v.perm,
-                                                              L->heavy_on ? L->heavy : nullptr);
+        const int nrows = v.NB * RB;
+        const int nparts = L->heavy_on ? 1 : std::max(1, std::min(v.nchunk, 8192 / nrows));
+        const int cpp = (int)cdiv(v.nchunk, nparts);
+        k_fill_row<<<(unsigned)cdiv((int64_t)nrows * nparts, 4), 256, 0, s>>>(
+            L->mask, Wsrc, O, I, v.nchunk, v.NBpad, v.NB, L->rowptr, v.ptr, v.rowpos, v.rowmap, L->vals, L->flat, ws.cidx,
+            reinterpret_cast<uint2*>(v.ent), v.perm, L->heavy_on ? L->heavy : nullptr, nparts, cpp, ws.segcnt, Rpad);
         if (L->heavy_on) {
             MST_LAUNCH_CHECK();
             const int rc = heavy_fill(L, s);
