@@ -51,9 +51,11 @@ def parse():
                         "default puts updates inside a short timed region); 0 = never update")
     p.add_argument("--allocation", default="uniform", choices=["uniform", "erdos_renyi"],
                    help="C5 only: every layer at the sweep's density, or the Erdos-Renyi shares of it (Sec. 3.2)")
-    p.add_argument("--update-streams", type=int, default=0,
-                   help="C5 only: 1 = the layers' updates run on one stream per layer (overlapping small kernels; "
-                        "per-call times then overlap too), 0 = everything on the main stream")
+    p.add_argument("--update-streams", type=int, default=3, choices=[0, 1, 2, 3],
+                   help="C5 only: 0 = everything on the main stream; 3 (default) = after the four dense gradients the "
+                        "layers' gathers and SGD steps run on one stream per layer and the four updates in ONE "
+                        "mst_mask_update_from_scores_multi call on those streams (chains of small dependent kernels "
+                        "side by side; their per-call times overlap); 1, 2 = the same streams with per-layer calls")
     p.add_argument("--fused-update", type=int, default=0,
                    help="C5 only: 1 = weight gradient and update in ONE call (mst_sparse_fc_bwd_weight_update); "
                         "0 = the same work as three calls (mst_dense_grad, mst_gather_active, "
@@ -508,7 +510,12 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
         free_layers(torch, layers)
         return None
 
-    side = [torch.cuda.Stream() for _ in layers] if args.update_streams else [stream] * len(layers)
+    # (the box gives a process four hardware queues: three side streams and the main one for the last layer)
+    side = ([torch.cuda.Stream() for _ in layers[:-1]] + [stream]) if args.update_streams == 3 else \
+        [torch.cuda.Stream() for _ in layers] if args.update_streams else [stream] * len(layers)
+    upd_start = {}
+    step_ev = {}       # position -> (first, last) events of its steps on the main stream
+    phase_ev = []      # (fork, join) of the layers' update chains when they run side by side
     ev = []            # (position, layer index, call, start event, end event)
     nnz_at = {}        # position -> per-layer active counts (host arithmetic of the update, no read-back)
     dense_at = {}      # position -> per layer: does the library route Y and dX to the masked dense contraction
@@ -524,6 +531,7 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
             return e
 
         last = mark(stream) if record else None
+        step_begin = last
         for li, L in enumerate(layers):
             for call in ("fwd", "bwd_input"):
                 if call == "fwd":
@@ -535,15 +543,27 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                     ev.append((pos, li, call, last, nxt))
                     last = nxt
         fork = None
+        grads_first = args.update_streams >= 2 and not args.fused_update
+        multi = args.update_streams == 3 and not args.fused_update
+        if grads_first:
+            # the four dense gradients (each fills the chip) one after the other on the main stream; only
+            # then the layers' chains of small kernels (gather, SGD, update), side by side on their streams
+            for li, L in enumerate(layers):
+                mst.mst_dense_grad(L.dY, L.X, G[li], T, L.O, L.I, L.act, L.ws, stream)
+                if record:
+                    nxt = mark(stream)
+                    ev.append((pos, li, "dense_grad", last, nxt))
+                    last = nxt
         if args.update_streams:
-            fork = torch.cuda.Event()
+            fork = torch.cuda.Event(enable_timing=True)
             fork.record(stream)
         dl = targets(pos + 1)
         for li, (L, d, s) in enumerate(zip(layers, dl, side)):
             seed = mst.mst_update_seed(args.seed, t, len(layers), li)
             if s is not stream:
                 s.wait_event(fork)
-                last = mark(s) if record else None
+            if args.update_streams:
+                last = mark(s) if record else None       # every layer's chain is timed on its own stream
             if args.fused_update:
                 # weight gradient (at the positions active now) and update from one dense gradient
                 mst.mst_sparse_fc_bwd_weight_update(L.layer, L.dY, L.X, L.dW, T, d, cfg["zeta"], cfg["R"], seed, L.ws,
@@ -553,6 +573,8 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                 calls = ("dense_grad", "gather_active", "caller_sgd", "mask_update") if args.lr else \
                         ("dense_grad", "gather_active", "mask_update")
             for call in calls:
+                if call == "dense_grad" and grads_first:
+                    continue
                 if call == "dense_grad":
                     mst.mst_dense_grad(L.dY, L.X, G[li], T, L.O, L.I, L.act, L.ws, s)
                 elif call == "gather_active":
@@ -561,15 +583,36 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                     with torch.cuda.stream(s):
                         L.sgd(args.lr)
                 elif call == "mask_update":
+                    if multi:
+                        if record:
+                            upd_start[li] = last
+                        continue
                     mst.mst_mask_update_from_scores(L.layer, G[li], d, cfg["zeta"], cfg["R"], seed, L.ws, s)
                 if record:
                     nxt = mark(s)
                     ev.append((pos, li, call, last, nxt))
                     last = nxt
-            if s is not stream:
+            if s is not stream and not multi:
                 done = torch.cuda.Event()
                 done.record(s)
                 stream.wait_event(done)
+        if multi:
+            # the four updates in ONE native call, each on its layer's stream
+            mst.mst_mask_update_from_scores_multi([L.layer for L in layers], G, dl, cfg["zeta"], cfg["R"],
+                                                  [mst.mst_update_seed(args.seed, t, len(layers), li) for li in range(len(layers))],
+                                                  [L.ws for L in layers], side)
+            for li, s in enumerate(side):
+                if record:
+                    ev.append((pos, li, "mask_update", upd_start[li], mark(s)))
+                if s is not stream:
+                    done = torch.cuda.Event()
+                    done.record(s)
+                    stream.wait_event(done)
+        if record:
+            step_end = mark(stream)                                          # (after the side streams have joined)
+            step_ev.setdefault(pos, []).append((step_begin, step_end))
+            if grads_first:
+                phase_ev.append((fork, step_end))
 
     clock_ramp(mst, torch, stream)
     t = 0
@@ -640,6 +683,8 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                 if xs:
                     ms_pos += sum(xs) / len(xs)
                     by_layer_call.setdefault((li, call), []).extend(xs)
+        # the step's own span on the main stream (with side streams the calls' times overlap and their sum overstates)
+        ms_pos = sum(a.elapsed_time(b) for a, b in step_ev[p]) / len(step_ev[p])
         step_bytes = sum(L.bytes_fwd(n) + L.bytes_bwd_input(n) + L.bytes_bwd_weight(n)
                          for L, n in zip(layers, nnz_at[p]))
         step_flops = sum(6 * n * T for n in nnz_at[p])
@@ -688,7 +733,14 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
                                   % (T, cyc, args.allocation,
                                      "one call" if args.fused_update else "three calls so that the dense-gradient kernel "
                                      "is timed on its own",
-                                     "updates on one stream per layer" if args.update_streams else "one stream"),
+                                     {0: "one stream",
+                                      1: "every layer's dense gradient, gather, SGD and update on a stream of its own",
+                                      2: "the dense gradients on the main stream, then the layers' chains (gather, SGD, "
+                                         "update) on one stream per layer",
+                                      3: "the dense gradients on the main stream, then gather and SGD per layer on its "
+                                         "stream and the four updates in one mst_mask_update_from_scores_multi call, side "
+                                         "by side on four streams (the mask_update rows are times on a layer's stream and "
+                                         "overlap; update_phase_ms is the span of all of it)"}[args.update_streams]),
                       "mask_updates_in_timed_region": args.steps * len(layers),
                       "layers": {L.name: [L.I, L.O] for L in layers},
                       "caller_sgd_lr": args.lr},
@@ -696,6 +748,7 @@ def run_sweep(args, mst, synth, torch, lds_peak, with_cpu_baseline):
            "hbm_frac_step": round(tot_bytes / elapsed / 1e9 / HBM_PEAK_GBS, 4),
            "alu_frac_step": round(value / ALU_FP32_PEAK_TFLOPS, 4),
            "ms_per_mask_update": round(sum(upd) / len(upd), 4) if upd else None,
+           "update_phase_ms": round(sum(a.elapsed_time(b) for a, b in phase_ev) / len(phase_ev), 4) if phase_ev else None,
            "lds_peak_measured_tbs": round(lds_peak / 1e12, 1) if lds_peak else None,
            "roofline": roof, "sweep": sweep_rows, "calls": calls}
     if with_cpu_baseline:

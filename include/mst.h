@@ -298,6 +298,21 @@ int mst_mask_update_from_scores(mst_layer_t* layer, const float* G_dev,
                                 uint64_t rng_seed, void* ws_dev, size_t ws_bytes,
                                 mst_update_stats* stats_out, mst_stream_t stream);
 
+/* mst_mask_update_from_scores for n_layers layers in one call: layer j with score buffer
+ * G_dev[j], density target_density[j], seed rng_seed[j], workspace ws_dev[j] (ws_bytes[j]) on
+ * stream streams[j]; zeta and rand_ratio are shared.  An update is a chain of about fifteen small
+ * kernels that depend on one another; the chains of different layers are independent, so on
+ * different streams they run side by side, and issued from one native call the host keeps up
+ * with them (issued call by call from an interpreter the host is the bound).  The layers, their
+ * workspaces and score buffers must be distinct; streams may repeat (those layers then follow
+ * one another).  Every argument of every layer is checked before any device work; a failure of a
+ * later step (MST_ERR_HIP) leaves the earlier layers updated.  stats_out (host, [n_layers]) may be
+ * NULL.  Results per layer are those of the single-layer call, bit for bit. */
+int mst_mask_update_from_scores_multi(int n_layers, mst_layer_t* const* layers, const float* const* G_dev,
+                                      const double* target_density, double zeta, double rand_ratio,
+                                      const uint64_t* rng_seed, void* const* ws_dev, const size_t* ws_bytes,
+                                      mst_update_stats* stats_out, const mst_stream_t* streams);
+
 /* The same with the score computed inside: G = dY^T X on the matrix cores. */
 int mst_mask_update(mst_layer_t* layer, const void* dY_dev, const void* X_dev, int T,
                     mst_dtype act, double target_density, double zeta, double rand_ratio,

@@ -111,6 +111,7 @@ def lib() -> C.CDLL:
         "mst_dense_grad": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]),
         "mst_update_counts": (i32, [i64, i64, dbl, dbl, dbl, C.POINTER(UpdateStats)]),
         "mst_mask_update_from_scores": (i32, [vp, vp, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
+        "mst_mask_update_from_scores_multi": (i32, [i32, vp, vp, vp, dbl, dbl, vp, vp, vp, vp, vp]),
         "mst_mask_update": (i32, [vp, vp, vp, i32, i32, dbl, dbl, dbl, u64, vp, sz, C.POINTER(UpdateStats), vp]),
         "mst_sparse_fc_bwd_weight_update": (i32, [vp, vp, vp, vp, i32, i32, dbl, dbl, dbl, u64, vp, sz,
                                                   C.POINTER(UpdateStats), vp]),
@@ -135,7 +136,7 @@ EXPORTS = ["mst_version", "mst_last_hip_error", "mst_layer_device_bytes", "mst_w
            "mst_layer_nnz", "mst_sparse_fc_fwd", "mst_sparse_fc_bwd_input", "mst_sparse_fc_bwd_weight", "mst_sparse_fc_bwd_weight_static",
            "mst_static_scratch_bytes", "mst_sparse_fc_bwd", "mst_bwd_force_shape", "mst_gemm_force_fp32_mfma", "mst_gemm_last_tile", "mst_heavy_rows",
            "mst_gather_active", "mst_layer_format_stats", "mst_probe_lds_read", "mst_update_due", "mst_update_seed",
-           "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update",
+           "mst_dense_grad", "mst_update_counts", "mst_mask_update_from_scores", "mst_mask_update_from_scores_multi", "mst_mask_update",
            "mst_sparse_fc_bwd_weight_update",
            "mst_schedule_density", "mst_erdos_renyi_density", "mst_flops_fc_forward", "mst_flops_transformer",
            "mst_strided_attention_mask", "mst_strided_attention_count"]
@@ -352,6 +353,23 @@ def mst_mask_update_from_scores(layer: Layer, G, target_density: float, zeta: fl
            lib().mst_mask_update_from_scores(layer.h, _ptr(G), target_density, zeta, rand_ratio, rng_seed,
                                              _ptr(ws), ws.numel(), C.byref(st), _stream(stream)))
     return st.as_dict()
+
+
+def mst_mask_update_from_scores_multi(layers, G, target_density, zeta: float, rand_ratio: float, rng_seed, ws,
+                                      streams) -> list:
+    """One native call for several layers, layer j on streams[j] (arrays marshalled here, nothing else)."""
+    n = len(layers)
+    hs = (C.c_void_p * n)(*[L.h.value for L in layers])
+    gs = (C.c_void_p * n)(*[_ptr(g) for g in G])
+    ds = (C.c_double * n)(*[float(d) for d in target_density])
+    seeds = (C.c_uint64 * n)(*[int(x) for x in rng_seed])
+    wss = (C.c_void_p * n)(*[_ptr(w) for w in ws])
+    wbs = (C.c_size_t * n)(*[w.numel() for w in ws])
+    sts = (UpdateStats * n)()
+    ss = (C.c_void_p * n)(*[_stream(x) for x in streams])
+    _check("mst_mask_update_from_scores_multi",
+           lib().mst_mask_update_from_scores_multi(n, hs, gs, ds, zeta, rand_ratio, seeds, wss, wbs, sts, ss))
+    return [st.as_dict() for st in sts]
 
 
 def mst_mask_update(layer: Layer, dY, X, T: int, target_density: float, zeta: float, rand_ratio: float,

@@ -277,6 +277,33 @@ int mst_mask_update_from_scores(mst_layer_t* L, const float* G_dev, double targe
     return update_common(L, G_dev, rng_seed, ws, stats_out, (hipStream_t)stream, st);
 }
 
+int mst_mask_update_from_scores_multi(int n_layers, mst_layer_t* const* layers, const float* const* G_dev,
+                                      const double* target_density, double zeta, double rand_ratio,
+                                      const uint64_t* rng_seed, void* const* ws_dev, const size_t* ws_bytes,
+                                      mst_update_stats* stats_out, const mst_stream_t* streams) {
+    if (n_layers < 0 || (n_layers > 0 && (!layers || !G_dev || !target_density || !rng_seed || !ws_dev || !ws_bytes || !streams)))
+        return MST_ERR_ARG;
+    // everything that can be refused is refused before the first launch
+    for (int j = 0; j < n_layers; ++j) {
+        mst_layer_t* L = layers[j];
+        if (!L || !G_dev[j] || !ws_dev[j] || !aligned16(G_dev[j]) || !aligned16(ws_dev[j])) return MST_ERR_ARG;
+        for (int u = 0; u < j; ++u)
+            if (layers[u] == L || ws_dev[u] == ws_dev[j] || G_dev[u] == G_dev[j]) return MST_ERR_ARG;
+        if (!L->built) return MST_ERR_STATE;
+        mst_update_stats st;
+        const int rc = mst_update_counts(L->N, L->nnz, target_density[j], zeta, rand_ratio, &st);
+        if (rc != MST_OK) return rc;
+        if (st.nnz_after > L->cap) return MST_ERR_STATE;
+        if (ws_bytes[j] < carve_workspace(nullptr, L->O, L->I, L->cap, 1).total) return MST_ERR_WORKSPACE;
+    }
+    for (int j = 0; j < n_layers; ++j) {
+        const int rc = mst_mask_update_from_scores(layers[j], G_dev[j], target_density[j], zeta, rand_ratio, rng_seed[j],
+                                                   ws_dev[j], ws_bytes[j], stats_out ? stats_out + j : nullptr, streams[j]);
+        if (rc != MST_OK) return rc;
+    }
+    return MST_OK;
+}
+
 int mst_mask_update(mst_layer_t* L, const void* dY_dev, const void* X_dev, int T, mst_dtype act,
                     double target_density, double zeta, double rand_ratio, uint64_t rng_seed, void* ws_dev,
                     size_t ws_bytes, mst_update_stats* stats_out, mst_stream_t stream) {

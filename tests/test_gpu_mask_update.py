@@ -278,3 +278,47 @@ def test_gradient_term_of_the_prune_score_with_random_growth_only():
     We, Me = rig.export()
     np.testing.assert_array_equal(Me, ref["M"])
     np.testing.assert_array_equal(We, ref["W"])
+
+
+def test_several_layers_in_one_call_on_their_own_streams():
+    """mst_mask_update_from_scores_multi: the layers' update chains run side by side on different streams;
+    every layer ends as the single-layer call (and the oracle's Algorithm 1) leaves it, bit for bit."""
+    shapes = [(333, 200, 0.10, 0.05), (768, 512, 0.05, 0.12), (130, 4100, 0.30, 0.02), (64, 64, 0.5, 0.5)]
+    rigs, Ws, Ms, Gs, Gd, seeds = [], [], [], [], [], []
+    for j, (O, I, d0, _) in enumerate(shapes):
+        W, M = synth.make_layer(600 + j, 1, I, O, d0)
+        Ws.append(W); Ms.append(M)
+        Gs.append(_scores(600 + j, O, I, 4 if j == 1 else None))
+        Gd.append(dev(Gs[-1]))
+        rigs.append(Rig(W, M, 1, cap=O * I))
+        seeds.append(2 ** 63 + 17 * j)
+    streams = [torch.cuda.Stream() for _ in shapes[:-1]] + [torch.cuda.current_stream()]
+    targets = [s[3] for s in shapes]
+    for rnd in range(2):                                     # twice: the second call starts from the first one's topology
+        sts = mst.mst_mask_update_from_scores_multi([r.layer for r in rigs], Gd, targets, 0.3, 0.25, seeds,
+                                                    [r.ws for r in rigs], streams)
+        torch.cuda.synchronize()
+        for j, rig in enumerate(rigs):
+            ref = omg.update(Ws[j], Ms[j], Gs[j], targets[j], 0.3, 0.25, seeds[j])
+            c = ref["counts"]
+            assert (sts[j]["n_prune"], sts[j]["n_grad"], sts[j]["n_rand"], sts[j]["nnz_after"]) == \
+                (c["n_prune"], c["n_grad"], c["n_rand"], c["nnz_target"])
+            We, Me = rig.export()
+            np.testing.assert_array_equal(Me, ref["M"])
+            np.testing.assert_array_equal(We, ref["W"])
+            np.testing.assert_array_equal(rig.indices(), np.flatnonzero(ref["M"].reshape(-1)))
+            Ws[j], Ms[j] = ref["W"], ref["M"]
+        targets = [0.08, 0.05, 0.02, 0.9]
+    # nothing runs when any layer's arguments are refused: a layer twice, a density out of range
+    before = [r.export() for r in rigs]
+    with pytest.raises(mst.MstError):
+        mst.mst_mask_update_from_scores_multi([rigs[0].layer, rigs[0].layer], Gd[:2], [0.1, 0.1], 0.3, 0.25, seeds[:2],
+                                              [rigs[0].ws, rigs[1].ws], streams[:2])
+    with pytest.raises(mst.MstError):
+        mst.mst_mask_update_from_scores_multi([r.layer for r in rigs], Gd, [0.1, 0.1, 1.5, 0.1], 0.3, 0.25, seeds,
+                                              [r.ws for r in rigs], streams)
+    torch.cuda.synchronize()
+    for r, (W0, M0) in zip(rigs, before):
+        We, Me = r.export()
+        np.testing.assert_array_equal(Me, M0)
+        np.testing.assert_array_equal(We, W0)
