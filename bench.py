@@ -793,14 +793,14 @@ def clock_ramp(mst, torch, stream, ms=40.0):
     host); a short workload timed right after one reads 5-40 % slow.  Before the W warm-up steps of a
     timed region this runs a dense contraction on scratch buffers for `ms` milliseconds.  It touches no
     layer state, so the W warm-up steps and the K timed steps are the same steps with or without it."""
-    n = 2048
+    n = 4096
     a = torch.randn(n, n, device="cuda:0")
     b = torch.randn(n, n, device="cuda:0")
     c = torch.empty(n, n, device="cuda:0")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     while 1e3 * (time.perf_counter() - t0) < ms:
-        for _ in range(8):
+        for _ in range(4):
             mst.mst_dense_grad(a, b, c, n, n, n, mst.MST_F32, None, stream)
         torch.cuda.synchronize()
 
