@@ -18,13 +18,21 @@ torch = pytest.importorskip("torch")
 from gpu_util import Rig, TOL, DEV, dev, rel_err  # noqa: E402
 
 
-@pytest.mark.parametrize("density,path", [(0.03, mst.MST_PATH_AUTO), (0.5, mst.MST_PATH_AUTO), (0.2, mst.MST_PATH_SPARSE)])
-def test_forward_and_backward_replay_from_a_graph(density, path):
+@pytest.mark.parametrize("density,path,mask", [(0.03, mst.MST_PATH_AUTO, "uniform"), (0.5, mst.MST_PATH_AUTO, "uniform"),
+                                               (0.2, mst.MST_PATH_SPARSE, "uniform"),
+                                               (0.05, mst.MST_PATH_SPARSE, "powerlaw")])
+def test_forward_and_backward_replay_from_a_graph(density, path, mask):
     I, O, T = 384, 640, 2048
-    W, M = synth.make_layer(91, 1, I, O, density)
-    rig = Rig(W, M, T, cap=int(M.sum()) * 2)
+    W, M = synth.make_layer(91, 1, I, O, density, mask)
+    if mask == "powerlaw":                          # the forward is then two launches: sparse kernel + heavy rows' dense pass
+        mst.mst_heavy_rows(2)
+    try:
+        rig = Rig(W, M, T, cap=int(M.sum()) * 2)
+    finally:
+        mst.mst_heavy_rows(1)
     L = rig.layer
     L.set_path(path)
+    assert (L.format_stats()["heavy_rows"] > 0) == (mask == "powerlaw")
     nnz = L.nnz
     X = torch.empty((T, I), dtype=torch.float32, device=DEV)
     dY = torch.empty((T, O), dtype=torch.float32, device=DEV)
