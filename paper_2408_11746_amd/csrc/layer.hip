@@ -394,8 +394,8 @@ __device__ inline void pad_row_slots(uint2* __restrict__ ent, int* __restrict__ 
 // only pad): ordered compaction of the row into canonical arrays and the row view.  A layer of
 // few long rows gives every row `nparts` wavefronts of `cpp` chunks each (one per row would leave
 // the 1280 rows of a 5120-wide layer on 320 workgroups); a part finds its first canonical index
-// from the per-chunk counts of the chunks before it.  With heavy rows (whose counts were cleared)
-// the launch uses one part.
+// from the per-chunk counts of the chunks before it (a heavy row, whose counts were cleared, from
+// the mask itself).
 __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __restrict__ W,
                            int O, int I, int nchunk, int NBpad, int NB,
                            const int* __restrict__ rowptr, const int* __restrict__ ptr,
@@ -419,7 +419,11 @@ __global__ void k_fill_row(const uint8_t* __restrict__ mask, const float* __rest
     int canon = real ? rowptr[r] : 0;
     if (real && c0 > 0) {                             // entries of this row in the chunks before c0
         int before = 0;
-        for (int c = lane; c < c0; c += 64) before += segcnt[(size_t)c * Rpad + r];
+        if (hv) {                                     // (a heavy row's per-chunk counts were cleared: count the mask)
+            for (int i = lane; i < c0 * KC; i += 64) before += m[i] != 0;
+        } else {
+            for (int c = lane; c < c0; c += 64) before += segcnt[(size_t)c * Rpad + r];
+        }
         for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, 64);
         canon += before;
     }
@@ -670,7 +674,7 @@ static int build_one_view(View& v, bool row_view, const mst_layer* L, const floa
     MST_LAUNCH_CHECK();
     if (row_view) {
         const int nrows = v.NB * RB;
-        const int nparts = L->heavy_on ? 1 : std::max(1, std::min(v.nchunk, 8192 / nrows));
+        const int nparts = std::max(1, std::min(v.nchunk, 8192 / nrows));
         const int cpp = (int)cdiv(v.nchunk, nparts);
         k_fill_row<<<(unsigned)cdiv((int64_t)nrows * nparts, 4), 256, 0, s>>>(
             L->mask, Wsrc, O, I, v.nchunk, v.NBpad, v.NB, L->rowptr, v.ptr, v.rowpos, v.rowmap, L->vals, L->flat, ws.cidx,
