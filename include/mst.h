@@ -229,16 +229,16 @@ int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront);
  * operand element is split into two bfloat16 values (hi + lo, exact to 2^-17) while it is
  * staged, a product is hi*hi + hi*lo + lo*hi with fp32 accumulation; the result differs from
  * an fp32 product by less than 2^-16 per term.  This hook pins, for all later calls of the
- * process: 1 = the plain fp32 MFMA kernel; 128, 256 or 160 = the split kernel with the
- * workgroup tile 128 x 128, 256 x 256 or 256 x 160 (where the shape is a multiple of it;
- * 256 x 160 serves Y and dX only); 0 returns to the automatic choice.  All tiles add a
+ * process: 1 = the plain fp32 MFMA kernel; 128, 256, 160 or 192 = the split kernel with the
+ * workgroup tile 128 x 128, 256 x 256, 256 x 160 or 256 x 192 (where the shape is a multiple of
+ * it; the last two serve Y and dX only); 0 returns to the automatic choice.  All tiles add a
  * result's terms in the same order and give identical bits.  -52 / 52 switch off / on the
  * schedule that gives two 256 x 256 tiles five workgroups (used where plain k ranges would
  * leave a fifth of the CUs idle; other cut points of the k range, so another order of
  * additions); these two leave the other settings as they are.  Test and measurement aid,
  * not thread-safe. */
 int mst_gemm_force_fp32_mfma(int on);
-/* Workgroup tile (128, 256 or 160 as above) of the last dense product that ran on a split
+/* Workgroup tile (128, 256, 160 or 192 as above) of the last dense product that ran on a split
  * kernel in this process, 0 if it ran on another kernel.  Test aid, not thread-safe. */
 int mst_gemm_last_tile(void);
 

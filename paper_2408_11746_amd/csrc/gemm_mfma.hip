@@ -920,23 +920,25 @@ void k_gemm_a16_256(const uint16_t* __restrict__ A, int64_t lda, const float* __
             }
 }
 
-// The same split product on a 256 x 160 workgroup tile, for outputs 1280 wide (five 256-tiles
-// across leave 160 tiles for 256 CUs at T = 8192; eight 160-tiles across give 256).  A m-major
-// (NT and NN products).  Eight wavefronts stacked along m, each 32 rows x 160 columns (5 MFMA
-// tiles, 80 accumulator registers); per 16-k slice a wavefront reads 2 A and 10 B fragments for 15
-// MFMAs, issued product-major so that the three products of an accumulator are five apart.
+// The same split product on a 256 x 160 or 256 x 192 workgroup tile: for outputs 1280 wide (five
+// 256-tiles across leave 160 tiles for 256 CUs at T = 8192; eight 160-tiles across give 256) and
+// for outputs 2304 or 3072 wide (288 / 384 tiles of 256 x 256 need two rounds of which the second is
+// an eighth / half full; 384 / 512 tiles of 256 x 192 fill one and a half / two).  A m-major
+// (NT and NN products).  Eight wavefronts stacked along m, each 32 rows x 160 (192) columns (5 (6) MFMA
+// tiles, 80 (96) accumulator registers); per 16-k slice a wavefront reads 2 A and 10 (12) B fragments for
+// 15 (18) MFMAs, issued product-major so that the three products of an accumulator are five (six) apart.
 // Staging roles (p = tid & 255, h = tid >> 8, uniform per wavefront):
 //   m-major B (NT): threads 0..255 stage A as in k_gemm_split256; of threads 256..511 the first
-//     160 stage B, unit p & 3 of rows 16 (p >> 4) + 4 ((p >> 2) & 3) + it, it = 0..3; the other 96
-//     repeat the first 96 (same loads, same LDS values), so the loop has no predicate.
+//     160 (192) stage B, unit p & 3 of rows 16 (p >> 4) + 4 ((p >> 2) & 3) + it, it = 0..3; the other
+//     96 (64) repeat the first ones (same loads, same LDS values), so the loop has no predicate.
 //   k-major B (NN): every thread stages two m-major pieces of A (it = 2 h, 2 h + 1) and two columns
-//     of B: the patch 8 k x 2 columns (k group (tid / 80) & 3, columns 2 (tid % 80) ..) of the
-//     first 320 threads, repeated by the rest; registers as the mixed form of k_gemm_split256.
+//     of B: the patch 8 k x 2 columns (k group tid / 80 (96), columns 2 (tid % 80 (96)) ..) of the
+//     first 320 (384) threads, repeated by the rest; registers as the mixed form of k_gemm_split256.
 // The next tile is split and stored during the second 16-k slice, one pair after every MFMA.
 // (Measured and dropped for a k-major B: four-byte loads that give both roles one register
 // form, and a mask-select between the two forms: both leave the loads too little time.)
-constexpr int BN3 = 160;
-template <bool B_KMAJOR>
+constexpr int BN3 = 160;          // (the narrower of the two widths; whole-tile test of the dispatch)
+template <int BNW, bool B_KMAJOR>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb,
                        float* __restrict__ C, int M, int N, int Kdim, int k_per_split, int64_t split_stride) {
@@ -945,21 +947,23 @@ void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __
     __shared__ __attribute__((aligned(16))) char lds[2 * 4 * PLANE];     // [stage][A hi, A lo, B hi, B lo]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave * 32;
-    const int gn = N / BN3, ntiles = (M / BM2) * gn, nsplit = (Kdim + k_per_split - 1) / k_per_split;
+    constexpr int NJ = BNW / 32;
+    static_assert(BNW == 160 || BNW == 192, "five or six MFMA tiles across");
+    const int gn = N / BNW, ntiles = (M / BM2) * gn, nsplit = (Kdim + k_per_split - 1) / k_per_split;
     const int Q = (ntiles + 7) >> 3;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int split = slot / Q, tile_id = xcd * Q + slot % Q;
     if (tile_id >= ntiles || split >= nsplit) return;
     int mi, ni;
     tile_coords(tile_id, M / BM2, gn, mi, ni);
-    const int m0 = mi * BM2, n0 = ni * BN3;
+    const int m0 = mi * BM2, n0 = ni * BNW;
     const int kbeg = split * k_per_split;
     const int kend = min(Kdim, kbeg + k_per_split);
     float* Cz = C + (int64_t)split * split_stride;
 
-    floatx16 acc[5];
+    floatx16 acc[NJ];
 #pragma unroll
-    for (int j = 0; j < 5; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
@@ -977,7 +981,7 @@ void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __
                 wr_unit[it] = bf_unit32(mmajor_row(p, it), p & 3);
             }
         } else {
-            const int q = p < BN3 ? p : p - BN3;
+            const int q = p < BNW ? p : p - BNW;
             base0 = reinterpret_cast<const char*>(B) + (int64_t)n0 * pb;
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
@@ -994,7 +998,7 @@ void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __
             voff[t] = (uint32_t)(mmajor_row(p, 2 * h + t) * pa + 32 * (p & 3));
             wr_unit[t] = bf_unit32(mmajor_row(p, 2 * h + t), p & 3);
         }
-        const int q = tid < 320 ? tid : tid - 320, nq = q % 80, kg = q / 80;
+        const int q = tid < 2 * BNW ? tid : tid - 2 * BNW, nq = q % (BNW / 2), kg = q / (BNW / 2);
         voff[2] = (uint32_t)(8 * kg * pb + 8 * nq);
         voff[3] = 0;
         wr_unit[2] = 2 * PLANE + bf_unit32(2 * nq, kg);
@@ -1050,22 +1054,23 @@ void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __
             const uint32_t ua = bf_unit32(wm + lm, 2 * ks + lk);
             const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Ah + ua);
             const bf16x8 al = *reinterpret_cast<const bf16x8*>(Al + ua);
-            bf16x8 bh[5], bl[5];
+            bf16x8 bh[NJ], bl[NJ];
 #pragma unroll
-            for (int j = 0; j < 5; ++j) {
+            for (int j = 0; j < NJ; ++j) {
                 const uint32_t ub = bf_unit32(32 * j + lm, 2 * ks + lk);
                 bh[j] = *reinterpret_cast<const bf16x8*>(Bh + ub);
                 bl[j] = *reinterpret_cast<const bf16x8*>(Bl + ub);
             }
             uint32_t hw[4], lw[4];
 #pragma unroll
-            for (int e = 0; e < 15; ++e) {                          // e = 5 t + j; products t: lo.hi, hi.lo, hi.hi
-                const int t = e / 5, j = e % 5;
+            for (int e = 0; e < 3 * NJ; ++e) {                      // e = NJ t + j; products t: lo.hi, hi.lo, hi.hi
+                const int t = e / NJ, j = e % NJ;
                 acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t == 0 ? al : ah, t == 1 ? bl[j] : bh[j], acc[j], 0, 0, 0);
                 if (STAGE && ks == 1) {
-                    // pair e (and the sixteenth with the last MFMA); a piece's two units leave after its fourth pair
+                    // pair e after MFMA e (with 15 MFMAs the sixteenth pair goes with the last, with 18 the last two
+                    // carry none); a piece's two units leave after its fourth pair
 #pragma unroll
-                    for (int pr = e; pr < (e == 14 ? 16 : e + 1); ++pr) {
+                    for (int pr = e; pr < ((3 * NJ < 16 && e == 3 * NJ - 1) ? 16 : (e < 16 ? e + 1 : e)); ++pr) {
                         split256_pair<LAYOUT>(r, pr >> 2, pr & 3, hw[pr & 3], lw[pr & 3]);
                         if ((pr & 3) == 3) {
                             *reinterpret_cast<uint4*>(wr + wr_unit[pr >> 2]) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
@@ -1098,7 +1103,7 @@ void k_gemm_split_n160(const float* __restrict__ A, int64_t lda, const float* __
     step(buf, false_type{}, false_type{}, 0);
 
 #pragma unroll
-    for (int j = 0; j < 5; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int m = m0 + wm + 8 * (v >> 2) + 4 * lk + (v & 3);
@@ -1343,24 +1348,24 @@ static int launch(const void* A, int64_t lda, const void* B, int64_t ldb, float*
 // needs on ONE XCD.  Modelled time = rounds x (k steps per workgroup + start-up and output of a
 // workgroup, in steps) x time of a step, plus the traffic of the partial outputs.  Constants
 // from timings on MI355X: a 64-k step of two co-resident 128 x 128 tiles 3.3 us, a 32-k step of
-// a 256 x 256 tile 2.0 us (1.6x the work per CU and time), of a 256 x 160 tile 1.8 us (less work
-// per staged byte: it pays only where it fills CUs that the 256 tile leaves idle), start-up +
-// output 7, 13 and 7 steps.
+// a 256 x 256 tile 2.0 us (1.6x the work per CU and time), of a 256 x 160 tile 1.8 us and of a
+// 256 x 192 tile 2.1 us (less work per staged byte: they pay only where they fill CUs that the 256
+// tile leaves idle), start-up + output 7, 13, 7 and 7 steps.
 // The model reproduces the measured times of the GPT-2 small / large products within 15 % and
 // orders the candidates as measured.
 struct SplitPlan {
     int tile, nsplit;
 };
 static SplitPlan plan_split(int M, int N, int Kdim, int64_t max_split, bool summed, bool allow128, bool allow256,
-                            bool allow160) {
+                            bool allow160, bool allow192) {
     static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
     SplitPlan best{0, 1};
     double best_cost = 0.0;
-    for (int tile : {128, 256, 160}) {                // 160: 256 rows x 160 columns (A m-major only)
-        if (tile == 128 ? !allow128 : tile == 256 ? !allow256 : !allow160) continue;
+    for (int tile : {128, 256, 160, 192}) {           // 160, 192: 256 rows x 160 / 192 columns (A m-major only)
+        if (tile == 128 ? !allow128 : tile == 256 ? !allow256 : tile == 160 ? !allow160 : !allow192) continue;
         const int tm = tile == 128 ? 128 : 256, tn = tile;
         const int kstep = tile == 128 ? SPK : 32, places = tile == 128 ? 64 : 32;
-        const double unit_us = tile == 128 ? 3.3 : tile == 256 ? 2.0 : 1.8, wg_steps = tile == 128 ? 7.0 : tile == 256 ? 13.0 : 7.0;
+        const double unit_us = tile == 128 ? 3.3 : tile == 256 ? 2.0 : tile == 160 ? 1.8 : 2.1, wg_steps = tile == 128 ? 7.0 : tile == 256 ? 13.0 : 7.0;
         if (M % tm != 0 || N % tn != 0 || Kdim % kstep != 0) continue;
         const int64_t Q = cdiv((int64_t)(M / tm) * (N / tn), 8);
         for (int ns : cand) {
@@ -1381,7 +1386,7 @@ static SplitPlan plan_split(int M, int N, int Kdim, int64_t max_split, bool summ
 static int g_gemm_fp32_only = 0;          // test hook: 1 = never use the bf16-split kernel
 static int g_last_tile = 0;               // workgroup tile of the last split-kernel launch (128 / 256 / 160), 0: another kernel
 static int g_sched52 = 1;                 // test hook: 0 = never the five-for-two schedule
-static int g_split_tile = 0;              // test hook: 0 = automatic, 128 / 256 / 160 = that workgroup tile when the shape allows it
+static int g_split_tile = 0;              // test hook: 0 = automatic, 128 / 256 / 160 / 192 = that workgroup tile when the shape allows it
 
 int gemm_last_tile() { return g_last_tile; }
 
@@ -1391,14 +1396,14 @@ int gemm_force_fp32_mfma(int on) {       // 0 automatic, 1 fp32 MFMA kernel, 128
         return MST_OK;
     }
     g_gemm_fp32_only = on == 1 ? 1 : 0;
-    g_split_tile = (on == 128 || on == 256 || on == 160) ? on : 0;
+    g_split_tile = (on == 128 || on == 256 || on == 160 || on == 192) ? on : 0;
     return MST_OK;
 }
 
 // whole tiles of one of the split kernels: 128 x 128 (256 x 256 is a subset) or, for an m-major A, 256 x 160
 static bool split_ok(int M, int N, int Kdim, int64_t lda, int64_t ldb, bool a_kmajor) {
     if (g_gemm_fp32_only || Kdim % SPK != 0 || lda % 4 != 0 || ldb % 4 != 0) return false;
-    return (M % BM == 0 && N % BN == 0) || (!a_kmajor && M % BM2 == 0 && N % BN3 == 0);
+    return (M % BM == 0 && N % BN == 0) || (!a_kmajor && M % BM2 == 0 && (N % BN3 == 0 || N % 192 == 0));
 }
 
 template <bool AK, bool BKM>
@@ -1407,9 +1412,10 @@ static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, 
     const int64_t mn = (int64_t)M * N;
     const int pin = g_split_tile;
     SplitPlan plan = plan_split(M, N, Kdim, split_ws ? split_ws_floats / mn : 1, left_unsummed == nullptr,
-                                pin == 0 || pin == 128, pin == 0 || pin == 256, !AK && (pin == 0 || pin == 160));
+                                pin == 0 || pin == 128, pin == 0 || pin == 256, !AK && (pin == 0 || pin == 160),
+                                !AK && (pin == 0 || pin == 192));
     if (plan.tile == 0)                               // the pinned tile does not fit this shape: any that does
-        plan = plan_split(M, N, Kdim, split_ws ? split_ws_floats / mn : 1, left_unsummed == nullptr, true, true, !AK);
+        plan = plan_split(M, N, Kdim, split_ws ? split_ws_floats / mn : 1, left_unsummed == nullptr, true, true, !AK, !AK);
     const int tile = plan.tile, nsplit0 = plan.nsplit;
     g_last_tile = tile;
     const int kstep = tile == 128 ? SPK : SPK2;
@@ -1437,7 +1443,10 @@ static int launch_split(const void* A, int64_t lda, const void* B, int64_t ldb, 
     }
     if (tile == 160) {
         if constexpr (!AK)
-            k_gemm_split_n160<BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+            k_gemm_split_n160<160, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
+    } else if (tile == 192) {
+        if constexpr (!AK)
+            k_gemm_split_n160<192, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn);
     } else if (tile == 256)
         k_gemm_split256<AK, BKM><<<grid, 512, 0, s>>>((const float*)A, lda, (const float*)B, ldb, dst, M, N, Kdim, kps, mn, 0);
     else

@@ -337,12 +337,13 @@ def test_dense_products_on_the_bf16_split_kernel(T, I, O):
         assert not np.array_equal(got128, got_f32) or e0 == 0.0         # the kernels really differ
 
 
-@pytest.mark.parametrize("T,I,O", [(256, 320, 128), (512, 320, 640), (768, 128, 160), (1024, 640, 320)])
-def test_dense_products_on_the_256_by_160_tile(T, I, O):
+@pytest.mark.parametrize("T,I,O,tile", [(256, 320, 128, 160), (512, 320, 640, 160), (768, 128, 160, 160), (1024, 640, 320, 160),
+                                        (256, 192, 128, 192), (512, 384, 768, 192), (768, 64, 192, 192), (1024, 768, 576, 192)])
+def test_dense_products_on_the_narrow_workgroup_tiles(T, I, O, tile):
     """Forward (output O wide) and input gradient (output I wide) of a dense layer pinned to the
-    256 x 160 workgroup tile of the split kernel where the output width is a multiple of 160
-    (the other product falls back to the 128 tile), against the oracle."""
-    print("case", T, I, O, flush=True)
+    256 x 160 or the 256 x 192 workgroup tile of the split kernel where the output width is a
+    multiple of it (the other product falls back to another tile), against the oracle."""
+    print("case", T, I, O, tile, flush=True)
     X, dY = synth.make_activations(45, 2, T, I, O)
     X = (X * np.exp2(synth.normal(45, 7, X.shape) * 3)).astype(np.float32)
     W = synth.normal(45, 3, (O, I), 0.02)
@@ -351,7 +352,7 @@ def test_dense_products_on_the_256_by_160_tile(T, I, O):
     rig.layer.set_path(mst.MST_PATH_DENSE)
     tiles = {}
     try:
-        mst.mst_gemm_force_fp32_mfma(160)
+        mst.mst_gemm_force_fp32_mfma(tile)
         Y = rig.fwd(X)
         tiles["Y"] = mst.mst_gemm_last_tile()
         dX = rig.bwd_input(dY)
@@ -365,8 +366,8 @@ def test_dense_products_on_the_256_by_160_tile(T, I, O):
         e = rel_err(got, ref)
         print(name, "width", width, "tile", tiles[name], "err %.3g" % e, flush=True)
         assert e <= 2e-5
-        if width % 160 == 0 and depth % 64 == 0:
-            assert tiles[name] == 160                    # the pinned tile really ran
+        if width % tile == 0 and depth % 64 == 0:
+            assert tiles[name] == tile                   # the pinned tile really ran
             if width % 128 == 0:
                 np.testing.assert_array_equal(got, got128)   # every tile adds a result's terms in the same order
 
