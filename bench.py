@@ -13,7 +13,9 @@ Default run (what `python bench.py --gpus 1 --steps K --warmup W` prints as ONE 
     density and then one update per layer that moves it to the next density of the cycle;
   * `per_config`: the other four workloads (single layer, GPT-2-small block at density 0.10,
     the same block at 0.02 with power-law rows, GPT-2-medium block with bfloat16 activations),
-    K steps each with a topology update every `--update-interval` steps.
+    K steps each with a topology update every `--update-interval` steps, and the step between two
+    updates replayed from a HIP graph (`graph_replay`: no host launch time, checked bit for bit
+    against the same step issued call by call).
 `--config Cx` runs one workload alone.  Inputs are synthetic, seeded, and resident in HBM
 before the timed region.  Every library call of the timed region is bracketed by events on
 the launch stream.
@@ -451,10 +453,76 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
                           mfma_peak=r["peak"], mfma_frac=r["frac"], mfma_dtype=r["mfma_dtype"])
     out["dense_grad_gemm"] = dict(operands="bf16" if act == "bf16" else "f32", layers=dg)
 
+    out["graph_replay"] = graph_replay_block(args, mst, torch, layers, T, products)
     if with_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_block(layers, T)
     free_layers(torch, layers)
     return out
+
+
+def graph_replay_block(args, mst, torch, layers, T, products):
+    """Everything a step does between two topology updates (the products, the caller's SGD, the value
+    hand-over, for every layer) recorded ONCE into a HIP graph and replayed: the step without the
+    host's per-launch time, which is what a training loop pays while the topology stands still (the
+    update itself sizes its launches on the host and stays outside; after it the graph is recorded
+    again).  The first replay is compared bit for bit with the same step issued call by call."""
+    main = torch.cuda.current_stream()
+
+    def step(s):
+        for L in layers:
+            for kind in products:
+                if kind == "fwd":
+                    mst.mst_sparse_fc_fwd(L.layer, L.X, L.Y, T, L.act, s)
+                elif kind == "bwd":
+                    mst.mst_sparse_fc_bwd(L.layer, L.dY, L.X, L.dX, L.dW, T, L.ws, L.act, s)
+                elif kind == "bwd_input":
+                    mst.mst_sparse_fc_bwd_input(L.layer, L.dY, L.dX, T, L.act, s)
+                else:
+                    mst.mst_sparse_fc_bwd_weight(L.layer, L.dY, L.X, L.dW, T, L.ws, L.act, s)
+            if args.lr:
+                L.sgd(args.lr)
+            L.layer.sync_values(s)
+
+    def outputs():
+        return [t.clone() for L in layers for t in (L.Y, L.dX, L.dW[:L.layer.nnz], L.layer.values())]
+
+    start = [L.layer.values().clone() for L in layers]
+
+    def rewind():
+        for L, v in zip(layers, start):
+            L.layer.values().copy_(v)
+            L.layer.sync_values(main)
+
+    step(main)
+    torch.cuda.synchronize()
+    eager = outputs()
+    rewind()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(main)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for L in layers:                              # (recording runs nothing: whatever a replay leaves is its own)
+        for t in (L.Y, L.dX, L.dW):
+            t.fill_(float("nan"))
+    graph.replay()
+    torch.cuda.synchronize()
+    same = all(torch.equal(a, b) for a, b in zip(eager, outputs()))
+    n = max(50, args.steps)
+    for _ in range(5):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / n
+    rewind()
+    torch.cuda.synchronize()
+    return dict(ms_per_step=round(ms, 4), replays=n, matches_call_by_call=bool(same),
+                holds="%s%s + value hand-over of every layer; no topology update" % (" + ".join(products), " + caller's SGD" if args.lr else ""))
 
 
 def pmc_probe_block(args, mst, torch, layers, T, stream):
@@ -937,7 +1005,7 @@ def compact(out, name):
                 hbm_frac=out["hbm_frac_step"], alu_frac=out["alu_frac_step"],
                 alu_frac_of_unpacked_peak=round(out["value"] / ALU_FP32_UNPACKED_TFLOPS, 4),
                 mask_updates_in_timed_region=out["config"]["mask_updates_in_timed_region"],
-                ms_per_mask_update=out["ms_per_mask_update"], ell_efficiency=out["config"]["ell_efficiency"],
+                ms_per_mask_update=out["ms_per_mask_update"], graph_replay=out["graph_replay"], ell_efficiency=out["config"]["ell_efficiency"],
                 slowest_call=dict(call=r["call"], avg_ms=r["avg_launch_ms"], bound=r["bound"], frac=r["frac"],
                                   hbm_frac=r.get("hbm_frac"), alu_frac=r.get("alu_frac"), lds_frac=r.get("lds_frac")),
                 path=out["config"]["path"],
