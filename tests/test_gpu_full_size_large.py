@@ -6,7 +6,8 @@ configuration the benchmark times (automatic path and launch shape); 0.1 runs a 
 pinned to the sparse kernels.  Outputs are compared
 with the oracle at >= 10^4 sampled positions per tensor (plus the longest / shortest rows
 and columns); the adjoint identities cover the complete outputs; masks after a fused
-Mixed-Growing update (Algorithm 1) are compared in full, bit for bit."""
+Mixed-Growing update (Algorithm 1) are compared in full, bit for bit; the update phase of the
+whole block runs as the benchmark issues it (one call for the four layers, a stream each)."""
 import numpy as np
 import pytest
 
@@ -116,3 +117,50 @@ def test_large_fc1_fused_updates_along_the_sweep_are_bit_exact():
     # the layer still computes with the topology it ended on
     Y = rig.fwd(X)
     sampled_check("fwd after the sweep", Y, lambda t, o: opr.fc_fwd_at(X, W, M, t, o), (T, O), n=2000, seed=6)
+
+
+def test_large_block_update_phase_as_the_benchmark_issues_it():
+    """The update phase of a sweep step in the benchmark's launch configuration: the four layers
+    of the block, per layer on a stream of its own the weight gradient read from the score
+    buffer, then ONE mst_mask_update_from_scores_multi call that runs the four updates side by
+    side (three side streams and the main one).  Ultra-sparse direction (0.1 -> 0.02) and back
+    (0.02 -> 0.1): every layer's mask, weights and index list equal the oracle's Algorithm 1."""
+    main = torch.cuda.current_stream()
+    streams = [torch.cuda.Stream() for _ in LARGE[:-1]] + [main]
+    rigs, Ws, Ms, Gs, Gd, seeds = [], [], [], [], [], []
+    for j, (name, I, O) in enumerate(LARGE):
+        W, M = synth.make_layer(4100 + j, 1, I, O, 0.10)
+        Ws.append(W); Ms.append(M)
+        Gs.append(synth.normal(4100 + j, 77, (O, I), 1.0))
+        Gd.append(dev(Gs[-1]))
+        rigs.append(Rig(W, M, T, cap=O * I))
+        seeds.append(2 ** 50 + 101 * j)
+    torch.cuda.synchronize()
+    for rnd, d in enumerate((0.02, 0.10)):
+        print("block update to density", d, flush=True)
+        dWs = []
+        for j, rig in enumerate(rigs):
+            dW = torch.full((rig.layer.nnz,), float("nan"), dtype=torch.float32, device=DEV)
+            streams[j].wait_stream(main)
+            mst.mst_gather_active(rig.layer, Gd[j], dW, streams[j])
+            dWs.append(dW)
+        sts = mst.mst_mask_update_from_scores_multi([r.layer for r in rigs], Gd, [d] * len(rigs), 0.3, 0.25,
+                                                    [s + rnd for s in seeds], [r.ws for r in rigs], streams)
+        torch.cuda.synchronize()
+        for j, rig in enumerate(rigs):
+            np.testing.assert_array_equal(dWs[j].cpu().numpy(), Gs[j].reshape(-1)[np.flatnonzero(Ms[j].reshape(-1))])
+            ref = omg.update(Ws[j], Ms[j], Gs[j], d, 0.3, 0.25, seeds[j] + rnd)
+            c = ref["counts"]
+            assert (sts[j]["n_prune"], sts[j]["n_grad"], sts[j]["n_rand"], sts[j]["nnz_after"]) == \
+                (c["n_prune"], c["n_grad"], c["n_rand"], c["nnz_target"])
+            We, Me = rig.export()
+            np.testing.assert_array_equal(Me, ref["M"], err_msg=LARGE[j][0])
+            np.testing.assert_array_equal(We, ref["W"], err_msg=LARGE[j][0])
+            np.testing.assert_array_equal(rig.indices(), np.flatnonzero(ref["M"].reshape(-1)))
+            Ws[j], Ms[j] = ref["W"], ref["M"]
+    # the layers compute with the topology they ended on (dense path at 0.1)
+    j = 1
+    X, _ = synth.make_activations(4100, 9, T, LARGE[j][1], LARGE[j][2])
+    Y = rigs[j].fwd(X)
+    sampled_check("fwd after the block updates", Y, lambda t, o: opr.fc_fwd_at(X, Ws[j], Ms[j], t, o),
+                  (T, LARGE[j][2]), n=2000, seed=8)
