@@ -68,25 +68,31 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
 
-    // lane q (0..QW) keeps the first pair of this wavefront's quad q of the current chunk
-    const int pl = fq + min(lane, QW);
-    int pv = ptr[pl];
+    // first pairs of this wavefront's quads 0 .. QW of the current chunk: the same for all lanes, so they
+    // come through scalar loads into scalar registers, one chunk ahead
+    const int* pw = ptr + fq;
+    int pb[QW + 1];
+#pragma unroll
+    for (int q = 0; q <= QW; ++q) pb[q] = pw[q];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
         load_tile<TIn, NW * 64>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
-        const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
-        int p = __builtin_amdgcn_readlane(pv, 0);
-        uint4 nxt = ent[(int64_t)p * 4 + eoff];               // (reads past the end stay in the tail)
+        int pb_next[QW + 1];
+        const int* pwn = pw + (int64_t)(c + 1 < nchunk ? c + 1 : c) * NBpad * 4;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
+        int p = pb[0];
+        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];               // (reads past the end stay in the tail)
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            const int pend = __builtin_amdgcn_readlane(pv, q + 1);
+            const int pend = pb[q + 1];
             while (p < pend) {
                 // batch = pairs p .. p+3 of this slice; the following batch starts at p + 4
                 // or, when the slice ends before that, at the first pair of the next slice
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = ent[(int64_t)pn * 4 + eoff];            // (at most 4 pairs past the end: next block or tail)
+                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];            // (at most 4 pairs past the end: next block or tail)
                 MST_PAIR(0, acc[q]);
                 if (p + 1 < pend) {
                     MST_PAIR(1, acc[q]);
@@ -98,7 +104,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
                 p = pn;
             }
         }
-        pv = pv_next;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb[q] = pb_next[q];
     }
 
     // rows of this lane's accumulators: place g of quad fq + q
@@ -180,13 +187,17 @@ template <typename TIn>
 __device__ inline void load_tile64(float* tile, const TIn* __restrict__ A, int64_t lda, int t0, int k0, int T,
                                    int K, bool vec_ok, int tid) {
     char* base = reinterpret_cast<char*>(tile);
+    asm volatile("" : "+v"(tid));                     // (offsets worked out per tile, see load_tile)
     const int kq = tid & 31, h = (tid >> 5) & 1, tq = tid >> 6;
     const int row = t0 + 4 * tq + 2 * h, k = k0 + 4 * kq;
     float4 a, b;
     if (vec_ok && t0 + TT64 <= T && k0 + KC <= K) {       // uniform: tile wholly inside the matrix
-        const TIn* p = A + (int64_t)row * lda + k;
-        a = load_quad_fast<TIn>(p);
-        b = load_quad_fast<TIn>(p + lda);
+        const TIn* corner = A + (int64_t)t0 * lda + k0;     // scalar; the lane adds a 32-bit byte offset
+        const uint32_t ld = (uint32_t)lda * (uint32_t)sizeof(TIn);
+        const __amdgpu_buffer_rsrc_t rs = buffer_of(corner, (uint32_t)(TT64 - 1) * ld + (uint32_t)(KC * sizeof(TIn)));
+        const uint32_t o = (uint32_t)(4 * tq + 2 * h) * ld + (uint32_t)(4 * kq * sizeof(TIn));
+        a = buffer_quad<TIn>(rs, o);
+        b = buffer_quad<TIn>(rs, o + ld);
     } else {
         a = load_quad<TIn>(A, lda, row, k, T, K, vec_ok);
         b = load_quad<TIn>(A, lda, row + 1, k, T, K, vec_ok);
@@ -224,22 +235,27 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[q][e] = 0.f;
 
-    const int pl = fq + min(lane, QW);
-    int pv = ptr[pl];
+    const int* pw = ptr + fq;                         // (scalar loads, one chunk ahead, as in k_spmm)
+    int pb[QW + 1];
+#pragma unroll
+    for (int q = 0; q <= QW; ++q) pb[q] = pw[q];
     for (int c = 0; c < nchunk; ++c) {
         if (c > 0) __syncthreads();
         load_tile64<TIn>(tile, A, K, t0, c * KC, T, K, vec_ok != 0, tid);
-        const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
-        int p = __builtin_amdgcn_readlane(pv, 0);
-        uint4 nxt = ent[(int64_t)p * 4 + eoff];
+        int pb_next[QW + 1];
+        const int* pwn = pw + (int64_t)(c + 1 < nchunk ? c + 1 : c) * NBpad * 4;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
+        int p = pb[0];
+        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            const int pend = __builtin_amdgcn_readlane(pv, q + 1);
+            const int pend = pb[q + 1];
             while (p < pend) {
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = ent[(int64_t)pn * 4 + eoff];
+                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];
                 MST_PAIR64(0, acc[q]);
                 if (p + 1 < pend) {
                     MST_PAIR64(1, acc[q]);
@@ -251,7 +267,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
                 p = pn;
             }
         }
-        pv = pv_next;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb[q] = pb_next[q];
     }
 
     // ---- epilogue: through LDS in passes of 256 slab rows; as in the 128-token kernel a

@@ -61,6 +61,28 @@ __device__ inline float4 load_quad_fast<uint16_t>(const uint16_t* __restrict__ p
                        __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
 }
 
+// Four consecutive elements as fp32 through a buffer load: the address is the descriptor's base (scalar
+// registers) plus a 32-bit byte offset per lane, so no 64-bit lane address has to live across the walk.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <typename TIn>
+__device__ inline float4 buffer_quad(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off);
+template <>
+__device__ inline float4 buffer_quad<float>(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, 0);
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+template <>
+__device__ inline float4 buffer_quad<uint16_t>(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
+    const u32x2 u = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)byte_off, 0, 0);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u),
+                       __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
+}
+// descriptor of `bytes` bytes from p (raw buffer: no stride, offsets beyond `bytes` read zero)
+__device__ inline __amdgpu_buffer_rsrc_t buffer_of(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
 // All threads of the workgroup fill tile[KC][TT] from A[t0 .. t0+TT) x [k0 .. k0+KC).
 // Work item = (token quad tq, index quad kq): four 16-byte row reads (consecutive lanes
 // read consecutive 16 bytes of a row), transposed in registers, eight 8-byte LDS stores.
@@ -74,6 +96,10 @@ __device__ inline void load_tile(float* tile, const TIn* __restrict__ A, int64_t
     static_assert(ITEMS % NTHREADS == 0, "tile loader needs a thread count that divides 1024");
     char* base = reinterpret_cast<char*>(tile);
     const bool interior = vec_ok && t0 + TT <= T && k0 + KC <= K;     // uniform over the workgroup
+    // The lane's offsets are worked out again for every tile (a dozen VALU instructions): as values that
+    // do not change round the chunk loop they would be kept in registers across the walk, which has none
+    // to spare -- they ended up in scratch memory and were read back before every tile.
+    asm volatile("" : "+v"(tid));
 #pragma unroll
     for (int it = 0; it < ITEMS / NTHREADS; ++it) {
         const int item = it * NTHREADS + tid;
@@ -84,11 +110,16 @@ __device__ inline void load_tile(float* tile, const TIn* __restrict__ A, int64_t
         const uint32_t slot = ((uint32_t)(tq >> 4) << 8) | ((uint32_t)((tq & 15) ^ (kq & 15)) << 4);
         const uint32_t kl = 4u * kq;
         if (interior) {
-            const TIn* p = A + (int64_t)row * lda + k;
-            const float4 r0 = load_quad_fast<TIn>(p);
-            const float4 r1 = load_quad_fast<TIn>(p + lda);
-            const float4 r2 = load_quad_fast<TIn>(p + 2 * lda);
-            const float4 r3 = load_quad_fast<TIn>(p + 3 * lda);
+            // buffer loads from the tile's corner (the same for every lane: scalar registers) with a 32-bit
+            // lane offset, instead of a 64-bit address per lane and row kept alive round the chunk loop
+            const TIn* corner = A + (int64_t)t0 * lda + k0;
+            const uint32_t ld = (uint32_t)lda * (uint32_t)sizeof(TIn);
+            const __amdgpu_buffer_rsrc_t rs = buffer_of(corner, (uint32_t)(TT - 1) * ld + (uint32_t)(KC * sizeof(TIn)));
+            const uint32_t o = (uint32_t)(4 * tq) * ld + (uint32_t)(4 * kq * sizeof(TIn));
+            const float4 r0 = buffer_quad<TIn>(rs, o);
+            const float4 r1 = buffer_quad<TIn>(rs, o + ld);
+            const float4 r2 = buffer_quad<TIn>(rs, o + 2 * ld);
+            const float4 r3 = buffer_quad<TIn>(rs, o + 3 * ld);
             *reinterpret_cast<float4*>(base + (((kl + 0) << 9) | slot)) = make_float4(r0.x, r1.x, r2.x, r3.x);
             *reinterpret_cast<float4*>(base + (((kl + 1) << 9) | slot)) = make_float4(r0.y, r1.y, r2.y, r3.y);
             *reinterpret_cast<float4*>(base + (((kl + 2) << 9) | slot)) = make_float4(r0.z, r1.z, r2.z, r3.z);
