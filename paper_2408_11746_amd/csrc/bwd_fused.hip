@@ -124,22 +124,29 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
     const int c_begin = blockIdx.y * chunks_per_split;
     const int c_end = min(nchunk, c_begin + chunks_per_split);
     dX += (int64_t)blockIdx.y * T * R;
-    const int pl = fq + min(lane, QW);
-    int pv = ptr[(int64_t)c_begin * NBpad * 4 + pl];
+    // first pairs of this wavefront's quads 0 .. QW of a chunk: the same for all lanes, read by scalar
+    // loads one chunk ahead
+    const int* pw = ptr + fq;
+    int pb[QW + 1];
+#pragma unroll
+    for (int q = 0; q <= QW; ++q) pb[q] = (pw + (int64_t)c_begin * NBpad * 4)[q];
     for (int c = c_begin; c < c_end; ++c) {
         __syncthreads();
         load_tile<TIn, NWF * 64>(tile, dY, K, t0, c * KC, T, K, vec_ok != 0, tid);
-        const int pv_next = (c + 1 < c_end) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
-        int p = __builtin_amdgcn_readlane(pv, 0);
-        uint4 nxt = ent[(int64_t)p * 4 + eoff];
+        int pb_next[QW + 1];
+        const int* pwn = pw + (int64_t)(c + 1 < c_end ? c + 1 : c) * NBpad * 4;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
+        int p = pb[0];
+        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            const int pend = __builtin_amdgcn_readlane(pv, q + 1);
+            const int pend = pb[q + 1];
             while (p < pend) {
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = ent[(int64_t)pn * 4 + eoff];
+                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];
                 MSTF_PAIR(0, xr[q], acc[q], p);
                 if (p + 1 < pend) {
                     MSTF_PAIR(1, xr[q], acc[q], p + 1);
@@ -151,7 +158,8 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
                 p = pn;
             }
         }
-        pv = pv_next;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb[q] = pb_next[q];
     }
 
     // ---- input gradient out: through LDS, 64 tokens at a time (token tl owns 1 KB, the

@@ -128,22 +128,29 @@ __device__ __forceinline__ void sddmm_side(const SddmmSide<TIn>& a, float* __res
                 dy[q][4 * h + e] = stf[((4 * s + e) * 64 + ((rloc[q] >> 2) ^ s)) * 4 + (rloc[q] & 3)];
     }
 
-    const int pl = fq + min(lane, QW);
-    int pv = ptr[pl];
+    // first pairs of this wavefront's quads 0 .. QW of a chunk: the same for all lanes, read by scalar
+    // loads one chunk ahead
+    const int* pw = ptr + fq;
+    int pb[QW + 1];
+#pragma unroll
+    for (int q = 0; q <= QW; ++q) pb[q] = pw[q];
     for (int c = 0; c < nchunk; ++c) {
         __syncthreads();
         load_tile<TIn, NW * 64>(tile, X, K, t0, c * KC, T, K, vec_ok != 0, tid);
-        const int pv_next = (c + 1 < nchunk) ? ptr[(int64_t)(c + 1) * NBpad * 4 + pl] : 0;
-        int p = __builtin_amdgcn_readlane(pv, 0);
-        uint4 nxt = ent[(int64_t)p * 4 + eoff];
+        int pb_next[QW + 1];
+        const int* pwn = pw + (int64_t)(c + 1 < nchunk ? c + 1 : c) * NBpad * 4;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
+        int p = pb[0];
+        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
-            const int pend = __builtin_amdgcn_readlane(pv, q + 1);
+            const int pend = pb[q + 1];
             while (p < pend) {
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = ent[(int64_t)pn * 4 + eoff];
+                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];
                 MST_DOT_PAIR(0, dy[q], p);
                 if (p + 1 < pend) {
                     MST_DOT_PAIR(1, dy[q], p + 1);
@@ -155,7 +162,8 @@ __device__ __forceinline__ void sddmm_side(const SddmmSide<TIn>& a, float* __res
                 p = pn;
             }
         }
-        pv = pv_next;
+#pragma unroll
+        for (int q = 0; q <= QW; ++q) pb[q] = pb_next[q];
     }
 }
 
