@@ -68,7 +68,7 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
-    const int eoff = (lane & 3) * 4 + g;
+    const uint32_t ebyte = (uint32_t)((lane & 3) * 4 + g) * 16u;
     const bool upper = (s & 8) != 0;
     const bool storer = (s & 7) == 0;
     const int pslot = g * 2 + (s >> 3);
@@ -138,7 +138,7 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
 #pragma unroll
         for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
         int p = pb[0];
-        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];
+        uint4 nxt = load_batch(ent, p, ebyte);
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
@@ -146,7 +146,7 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
             while (p < pend) {
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];
+                nxt = load_batch(ent, pn, ebyte);
                 MSTF_PAIR(0, xr[q], acc[q], p);
                 if (p + 1 < pend) {
                     MSTF_PAIR(1, xr[q], acc[q], p + 1);

@@ -85,7 +85,7 @@ __device__ __forceinline__ void sddmm_side(const SddmmSide<TIn>& a, float* __res
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
-    const int eoff = (lane & 3) * 4 + g;              // this lane's 16 bytes of a batch of four pairs
+    const uint32_t ebyte = (uint32_t)((lane & 3) * 4 + g) * 16u;              // this lane's 16 bytes of a batch of four pairs
     const bool upper = (s & 8) != 0;
     const bool storer = (s & 7) == 0;
     const int pslot = g * 2 + (s >> 3);               // slot of this lane's sum inside a pair's eight
@@ -142,7 +142,7 @@ __device__ __forceinline__ void sddmm_side(const SddmmSide<TIn>& a, float* __res
 #pragma unroll
         for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
         int p = pb[0];
-        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];
+        uint4 nxt = load_batch(ent, p, ebyte);
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
@@ -150,7 +150,7 @@ __device__ __forceinline__ void sddmm_side(const SddmmSide<TIn>& a, float* __res
             while (p < pend) {
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];
+                nxt = load_batch(ent, pn, ebyte);
                 MST_DOT_PAIR(0, dy[q], p);
                 if (p + 1 < pend) {
                     MST_DOT_PAIR(1, dy[q], p + 1);

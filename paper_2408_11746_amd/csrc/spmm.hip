@@ -60,7 +60,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const char* tb = reinterpret_cast<const char*>(tile);
     // a batch is four consecutive pairs: lane (g, j = lane & 3) holds lane group g's
     // 16 bytes of pair j of the batch, the four lanes of a group of four hand them round
-    const int eoff = (lane & 3) * 4 + g;
+    const uint32_t ebyte = (uint32_t)((lane & 3) * 4 + g) * 16u;
 
     float acc[QW][8];
 #pragma unroll
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 #pragma unroll
         for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
         int p = pb[0];
-        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];               // (reads past the end stay in the tail)
+        uint4 nxt = load_batch(ent, p, ebyte);               // (reads past the end stay in the tail)
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
                 // or, when the slice ends before that, at the first pair of the next slice
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];            // (at most 4 pairs past the end: next block or tail)
+                nxt = load_batch(ent, pn, ebyte);            // (at most 4 pairs past the end: next block or tail)
                 MST_PAIR(0, acc[q]);
                 if (p + 1 < pend) {
                     MST_PAIR(1, acc[q]);
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const int g = lane >> 4, s = lane & 15;
     const uint32_t lane16 = (uint32_t)s << 4;
     const char* tb = reinterpret_cast<const char*>(tile);
-    const int eoff = (lane & 3) * 4 + g;
+    const uint32_t ebyte = (uint32_t)((lane & 3) * 4 + g) * 16u;
 
     float acc[QW][4];
 #pragma unroll
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 #pragma unroll
         for (int q = 0; q <= QW; ++q) pb_next[q] = pwn[q];
         int p = pb[0];
-        uint4 nxt = (ent + (int64_t)p * 4)[(uint32_t)eoff];
+        uint4 nxt = load_batch(ent, p, ebyte);
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
             while (p < pend) {
                 const uint4 cur = nxt;
                 const int pn = min(p + 4, pend);
-                nxt = (ent + (int64_t)pn * 4)[(uint32_t)eoff];
+                nxt = load_batch(ent, pn, ebyte);
                 MST_PAIR64(0, acc[q]);
                 if (p + 1 < pend) {
                     MST_PAIR64(1, acc[q]);

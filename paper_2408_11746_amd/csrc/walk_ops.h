@@ -6,6 +6,17 @@
 
 namespace mst {
 
+// A lane's 16 bytes of the batch of four pairs that starts at pair p (p the same in all lanes): a buffer
+// load from a 256-byte descriptor of the batch (scalar registers) at the lane's byte offset, so that no
+// 64-bit lane address of the entry array has to be kept or added to.
+typedef uint32_t walk_u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 load_batch(const uint4* __restrict__ ent, int p, uint32_t lane_byte) {
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(ent + (int64_t)p * 4), 0, 256, 0x00020000);
+    const walk_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)lane_byte, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // value of v in lane JJ of this lane's aligned group of four lanes
 template <int JJ>
 __device__ inline uint32_t quad_bcast(uint32_t v) {
