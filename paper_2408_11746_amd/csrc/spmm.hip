@@ -108,12 +108,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
         for (int q = 0; q <= QW; ++q) pb[q] = pb_next[q];
     }
 
+    // (the epilogue works its lane constants out again instead of keeping the prologue's alive --
+    // in scratch memory -- across the chunk loop)
+    int tid_e = threadIdx.x;
+    asm volatile("" : "+v"(tid_e));
+    const int g_e = (tid_e >> 4) & 3, s_e = tid_e & 15;
+
     // rows of this lane's accumulators: place g of quad fq + q
     int rloc[QW];
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
-        const int rm = rowmap[(fq + q) * 4 + g];
-        fold_spread(acc[q], rm & SPREAD_FLAG, g);
+        const int rm = rowmap[(fq + q) * 4 + g_e];
+        fold_spread(acc[q], rm & SPREAD_FLAG, g_e);
         rloc[q] = rm & ~SPREAD_FLAG;
     }
 
@@ -130,14 +136,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
         __syncthreads();                              // tile / previous half no longer read
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int tl = 4 * s + e;
+            const int tl = 4 * s_e + e;
 #pragma unroll
             for (int q = 0; q < QW; ++q)
-                stf[(tl * 64 + ((rloc[q] >> 2) ^ s)) * 4 + (rloc[q] & 3)] = acc[q][4 * h + e];
+                stf[(tl * 64 + ((rloc[q] >> 2) ^ s_e)) * 4 + (rloc[q] & 3)] = acc[q][4 * h + e];
         }
         __syncthreads();
         constexpr int NCH = SLAB_ROWS / 4;            // 16-byte chunks per token row of the slab
-        for (int item = tid; item < 64 * NCH; item += nthreads) {
+        for (int item = tid_e; item < 64 * NCH; item += nthreads) {
             const int tl = item / NCH, j = item % NCH;
             const int t = t0 + 64 * h + tl;
             const int row = row0 + 4 * j;
@@ -277,11 +283,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
     constexpr int SLAB_ROWS = NW * QW * 4;
     constexpr int NPASS = (SLAB_ROWS + 255) / 256;
     const int row0 = slab * SLAB_ROWS;
+    int tid_e = threadIdx.x;                          // (lane constants worked out again, as in k_spmm)
+    asm volatile("" : "+v"(tid_e));
+    const int g_e = (tid_e >> 4) & 3, s_e = tid_e & 15;
     int rloc[QW];
 #pragma unroll
     for (int q = 0; q < QW; ++q) {
-        const int rm = rowmap[(fq + q) * 4 + g];
-        fold_spread(acc[q], rm & SPREAD_FLAG, g);
+        const int rm = rowmap[(fq + q) * 4 + g_e];
+        fold_spread(acc[q], rm & SPREAD_FLAG, g_e);
         rloc[q] = (rm & ~SPREAD_FLAG) - row0;
     }
     float* stf = tile;
@@ -294,11 +303,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
             const int rl = rloc[q] - 256 * h;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                stf[((4 * s + e) * 64 + ((rl >> 2) ^ s)) * 4 + (rl & 3)] = acc[q][e];
+                stf[((4 * s_e + e) * 64 + ((rl >> 2) ^ s_e)) * 4 + (rl & 3)] = acc[q][e];
         }
         __syncthreads();
         const int NCH = (SLAB_ROWS - 256 * h < 256 ? SLAB_ROWS - 256 * h : 256) / 4;   // constant after unrolling
-        for (int item = tid; item < 64 * NCH; item += nthreads) {
+        for (int item = tid_e; item < 64 * NCH; item += nthreads) {
             const int tl = item / NCH, j = item % NCH;
             const int t = t0 + tl;
             const int row = row0 + 256 * h + 4 * j;
