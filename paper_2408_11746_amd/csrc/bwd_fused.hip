@@ -230,15 +230,15 @@ static void launch_fused(const View& v, const TIn* dY, const TIn* X, float* dX, 
         (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0, cps);
 }
 
-// Launch shapes: 8 wavefronts x 3 quads (96-row slabs, 128 registers per lane) or 16
-// wavefronts x 1 quad (64-row slabs, 64 registers per lane).  Both give the same results.
+// Launch shapes: 8 wavefronts x 3, 4 or 5 quads (96-, 128-, 160-row slabs, up to 128 registers per
+// lane) or 16 wavefronts x 1 quad (64-row slabs, 64 registers per lane).  All give the same results.
 struct FusedShape {
     int waves, quads;
 };
 static FusedShape g_forced_fused = {0, 0};
 
 int bwd_fused_force_shape(int waves, int quads) {
-    const bool ok = (waves == 0 && quads == 0) || (waves == 8 && quads == 3) || (waves == 16 && quads == 1);
+    const bool ok = (waves == 0 && quads == 0) || (waves == 8 && quads >= 3 && quads <= 5) || (waves == 16 && quads == 1);
     if (!ok) return MST_ERR_ARG;
     g_forced_fused = {waves, quads};
     return MST_OK;
@@ -261,9 +261,11 @@ static FusedShape pick_fused_shape(int T, int R, int K, double density) {
         double kWalk, kStage, kReg, kChunk, kLoneTail, kLoneOnly;
     };
     static const Cand cand[] = {{{8, 3}, 96, 4.87e-5, 1.10e-4, 6.01e-4, 1.95, 0.58, 0.69},
+                                {{8, 4}, 128, 4.87e-5, 1.10e-4, 6.01e-4, 1.95, 0.58, 0.69},
+                                {{8, 5}, 160, 4.87e-5, 1.10e-4, 6.01e-4, 1.95, 0.58, 0.69},
                                 {{16, 1}, 64, 4.14e-5, 5.34e-5, 7.73e-4, 1.97, 0.60, 0.64}};
     const int64_t nchunk = cdiv(K, KC), ntile = cdiv(T, TT);
-    FusedShape best = cand[1].sh;
+    FusedShape best = cand[3].sh;
     double best_cost = 0.0;
     for (const Cand& c : cand) {
         const int64_t nslab = cdiv(R, c.rows), nwg = ntile * nslab;
@@ -310,7 +312,9 @@ static int launch_fused_any(const View& v, const TIn* dY, const TIn* X, float* d
         return MST_OK;
     }
     const FusedShape sh = pick_fused_shape(T, v.R, v.K, density);
-    if (sh.waves == 8) launch_fused<TIn, 8, 3>(v, dY, X, dX, ws.partial, T, 1, s);
+    if (sh.waves == 8 && sh.quads == 5) launch_fused<TIn, 8, 5>(v, dY, X, dX, ws.partial, T, 1, s);
+    else if (sh.waves == 8 && sh.quads == 4) launch_fused<TIn, 8, 4>(v, dY, X, dX, ws.partial, T, 1, s);
+    else if (sh.waves == 8) launch_fused<TIn, 8, 3>(v, dY, X, dX, ws.partial, T, 1, s);
     else launch_fused<TIn, 16, 1>(v, dY, X, dX, ws.partial, T, 1, s);
     MST_LAUNCH_CHECK();
     return MST_OK;
