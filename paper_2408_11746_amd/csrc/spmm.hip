@@ -346,8 +346,8 @@ static void launch64(const View& v, const TIn* A, float* out, int T, hipStream_t
 // quad segment it walks (pointer and first entry batch, padding to an even step count), which
 // at densities of a few percent decides for few quads per wavefront.  The constants were fitted
 // to timings of 138 cases (GPT-2 small / medium / large layer shapes, T = 512 .. 16384, densities
-// 0.01 .. 0.10: the range the sparse kernels serve) on MI355X: the chosen shape is 1.9 % slower
-// than the best one on average, 19 % at worst.
+// 0.01 .. 0.10: the range the sparse kernels serve) on MI355X: the chosen shape is 1.6 % slower
+// than the best one on average, 12 % at worst (timed again on the present kernels).
 struct SpmmShape {
     int tt, qw;
 };
