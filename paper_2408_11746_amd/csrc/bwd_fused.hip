@@ -81,14 +81,11 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
     // ---- X of this lane's 8 tokens for the row of each of its quads, through LDS (the
     // staging layout of the epilogue below); a spread quad works on the row of lane group 0
     float xr[QW][8];
-    int rout[QW], spread[QW];
     {
         int rin[QW];
 #pragma unroll
         for (int q = 0; q < QW; ++q) {
             const int rm = rowmap[(fq + q) * 4 + g], rm0 = rowmap[(fq + q) * 4];
-            spread[q] = rm & SPREAD_FLAG;
-            rout[q] = (rm & ~SPREAD_FLAG) - row0;
             rin[q] = (((rm & SPREAD_FLAG) ? rm0 : rm) & ~SPREAD_FLAG) - row0;
         }
         float* stf = tile;
@@ -164,21 +161,31 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
 
     // ---- input gradient out: through LDS, 64 tokens at a time (token tl owns 1 KB, the
     // 16-byte chunk j of rows 4j..4j+3 of the slab at slot j ^ ((tl >> 2) & 15))
+    // (the rows of the accumulators are read from the row map again, and the lane constants worked out
+    // again, rather than kept in registers across the walk)
+    int tid_e = threadIdx.x;
+    asm volatile("" : "+v"(tid_e));
+    const int g_e = (tid_e >> 4) & 3, s_e = tid_e & 15;
+    int rout[QW];
 #pragma unroll
-    for (int q = 0; q < QW; ++q) fold_spread(acc[q], spread[q], g);
+    for (int q = 0; q < QW; ++q) {
+        const int rm = rowmap[(fq + q) * 4 + g_e];
+        fold_spread(acc[q], rm & SPREAD_FLAG, g_e);
+        rout[q] = (rm & ~SPREAD_FLAG) - row0;
+    }
     float* stf = tile;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         __syncthreads();
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int tl = 4 * s + e;
+            const int tl = 4 * s_e + e;
 #pragma unroll
             for (int q = 0; q < QW; ++q)
-                stf[(tl * 64 + ((rout[q] >> 2) ^ s)) * 4 + (rout[q] & 3)] = acc[q][4 * h + e];
+                stf[(tl * 64 + ((rout[q] >> 2) ^ s_e)) * 4 + (rout[q] & 3)] = acc[q][4 * h + e];
         }
         __syncthreads();
-        for (int item = tid; item < 64 * NCH; item += nthreads) {
+        for (int item = tid_e; item < 64 * NCH; item += nthreads) {
             const int tl = item / NCH, j = item % NCH;
             const int t = t0 + 64 * h + tl;
             const int row = row0 + 4 * j;
@@ -230,15 +237,15 @@ static void launch_fused(const View& v, const TIn* dY, const TIn* X, float* dX, 
         (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0, cps);
 }
 
-// Launch shapes: 8 wavefronts x 3, 4 or 5 quads (96-, 128-, 160-row slabs, up to 128 registers per
-// lane) or 16 wavefronts x 1 quad (64-row slabs, 64 registers per lane).  All give the same results.
+// Launch shapes: 8 wavefronts x 3 .. 6 quads (96- .. 192-row slabs, up to 128 registers per lane) or
+// 16 wavefronts x 1 or 2 quads (64- / 128-row slabs, 64 registers per lane).  All give the same results.
 struct FusedShape {
     int waves, quads;
 };
 static FusedShape g_forced_fused = {0, 0};
 
 int bwd_fused_force_shape(int waves, int quads) {
-    const bool ok = (waves == 0 && quads == 0) || (waves == 8 && quads >= 3 && quads <= 5) || (waves == 16 && quads == 1);
+    const bool ok = (waves == 0 && quads == 0) || (waves == 8 && quads >= 3 && quads <= 6) || (waves == 16 && quads <= 2 && quads >= 1);
     if (!ok) return MST_ERR_ARG;
     g_forced_fused = {waves, quads};
     return MST_OK;
@@ -249,29 +256,30 @@ int bwd_fused_force_shape(int waves, int quads) {
 // at 0.20 (uniform masks), and equals them on power-law masks at 0.02.
 bool bwd_fused_pays(const mst_layer*) { return true; }
 
-// Cost of one workgroup (walk, staging of dY, the X rows of the slab, per-chunk overhead)
-// times the rounds its grid needs on 256 CUs x 2 workgroups, as for the SpMM launch
-// shapes; constants fitted to timings of GPT-2 small / medium / large layer shapes at
-// densities 0.02 .. 0.20 and 2048 .. 16384 tokens on MI355X.
+// Cost of one workgroup (walk, staging of dY, the X rows of the slab, per-chunk overhead and a
+// fixed amount per quad segment a wavefront walks) times the rounds its grid needs on 256 CUs x 2
+// workgroups, as for the SpMM launch shapes; one set of constants for the shapes of 8 wavefronts,
+// one for those of 16, fitted to timings of the six shapes on twelve GPT-2 small / medium / large
+// layer shapes at densities 0.02 .. 0.10 and 4096 .. 16384 tokens on MI355X (144 cases: the choice
+// is 0.3 % slower than the best shape on average, 11 % at worst).
 static FusedShape pick_fused_shape(int T, int R, int K, double density) {
     if (g_forced_fused.waves != 0) return g_forced_fused;
-    struct Cand {
-        FusedShape sh;
-        int rows;
-        double kWalk, kStage, kReg, kChunk, kLoneTail, kLoneOnly;
+    struct Cls {
+        double kWalk, kStage, kReg, kChunk, kLoneTail, kLoneOnly, kSeg;
     };
-    static const Cand cand[] = {{{8, 3}, 96, 4.87e-5, 1.10e-4, 6.01e-4, 1.95, 0.58, 0.69},
-                                {{8, 4}, 128, 4.87e-5, 1.10e-4, 6.01e-4, 1.95, 0.58, 0.69},
-                                {{8, 5}, 160, 4.87e-5, 1.10e-4, 6.01e-4, 1.95, 0.58, 0.69},
-                                {{16, 1}, 64, 4.14e-5, 5.34e-5, 7.73e-4, 1.97, 0.60, 0.64}};
+    static const Cls cls[2] = {{5.649e-5, 5.6e-6, 7.765e-4, 1.725, 0.628, 0.747, 0.454},      // 8 wavefronts
+                               {4.821e-5, 4.1e-6, 7.994e-4, 1.578, 0.578, 0.690, 0.861}};     // 16 wavefronts
+    static const FusedShape cand[] = {{8, 3}, {8, 4}, {8, 5}, {8, 6}, {16, 1}, {16, 2}};
     const int64_t nchunk = cdiv(K, KC), ntile = cdiv(T, TT);
-    FusedShape best = cand[3].sh;
+    FusedShape best = cand[4];
     double best_cost = 0.0;
-    for (const Cand& c : cand) {
-        const int64_t nslab = cdiv(R, c.rows), nwg = ntile * nslab;
+    for (const FusedShape& sh : cand) {
+        const Cls& c = cls[sh.waves == 8 ? 0 : 1];
+        const int rows = sh.waves * sh.quads * 4;
+        const int64_t nslab = cdiv(R, rows), nwg = ntile * nslab;
         const double rows_eff = (double)R / (double)nslab;
-        const double wg = TT * (rows_eff * density * K * c.kWalk + (double)nchunk * KC * c.kStage + c.rows * c.kReg) +
-                          c.kChunk * (double)nchunk;
+        const double wg = TT * (rows_eff * density * K * c.kWalk + (double)nchunk * KC * c.kStage + rows * c.kReg) +
+                          c.kChunk * (double)nchunk + c.kSeg * (double)sh.quads * (double)nchunk;
         const int64_t full = nwg / 512, rest = nwg % 512;
         double rounds;
         if (full == 0) rounds = rest <= 256 ? c.kLoneOnly : 1.0;
@@ -279,7 +287,7 @@ static FusedShape pick_fused_shape(int T, int R, int K, double density) {
         const double cost = wg * rounds;
         if (best_cost == 0.0 || cost < best_cost) {
             best_cost = cost;
-            best = c.sh;
+            best = sh;
         }
     }
     return best;
@@ -312,7 +320,9 @@ static int launch_fused_any(const View& v, const TIn* dY, const TIn* X, float* d
         return MST_OK;
     }
     const FusedShape sh = pick_fused_shape(T, v.R, v.K, density);
-    if (sh.waves == 8 && sh.quads == 5) launch_fused<TIn, 8, 5>(v, dY, X, dX, ws.partial, T, 1, s);
+    if (sh.waves == 8 && sh.quads == 6) launch_fused<TIn, 8, 6>(v, dY, X, dX, ws.partial, T, 1, s);
+    else if (sh.waves == 16 && sh.quads == 2) launch_fused<TIn, 16, 2>(v, dY, X, dX, ws.partial, T, 1, s);
+    else if (sh.waves == 8 && sh.quads == 5) launch_fused<TIn, 8, 5>(v, dY, X, dX, ws.partial, T, 1, s);
     else if (sh.waves == 8 && sh.quads == 4) launch_fused<TIn, 8, 4>(v, dY, X, dX, ws.partial, T, 1, s);
     else if (sh.waves == 8) launch_fused<TIn, 8, 3>(v, dY, X, dX, ws.partial, T, 1, s);
     else launch_fused<TIn, 16, 1>(v, dY, X, dX, ws.partial, T, 1, s);

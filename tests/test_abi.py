@@ -99,7 +99,7 @@ def test_size_queries_and_argument_errors():
     assert L.mst_sparse_fc_bwd_weight_update(None, None, None, None, 4, 0, 0.1, 0.3, 0.25, 1, None, 0, None, None) == -1
     assert L.mst_strided_attention_mask(None, 8, 4, None) == -1
     assert L.mst_layer_set_prune_lambda(None, 0.5) == -1
-    assert L.mst_bwd_force_shape(8, 2) == -1 and L.mst_bwd_force_shape(0, 0) == 0
+    assert L.mst_bwd_force_shape(8, 2) == -1 and L.mst_bwd_force_shape(16, 3) == -1 and L.mst_bwd_force_shape(0, 0) == 0
     assert L.mst_spmm_force_shape(128, 6) == -1 and L.mst_spmm_force_shape(0, 0) == 0
     assert L.mst_heavy_rows(3) == -1 and L.mst_heavy_rows(-1) == -1 and L.mst_heavy_rows(2) == 0 and L.mst_heavy_rows(1) == 0
     # the several-layer update: a negative count or missing arrays; an empty set of layers is fine
