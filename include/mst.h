@@ -220,7 +220,7 @@ int mst_sparse_fc_bwd(const mst_layer_t* layer, const void* dY_dev, const void* 
                       void* ws_dev, size_t ws_bytes, mst_stream_t stream);
 
 /* Test hook like mst_spmm_force_shape for the shared walk of mst_sparse_fc_bwd:
- * (8, 3) .. (8, 6), (16, 1) or (16, 2) wavefronts per workgroup x quads per wavefront, (0, 0) = automatic.
+ * (8, 3) .. (8, 5), (16, 1) or (16, 2) wavefronts per workgroup x quads per wavefront, (0, 0) = automatic.
  * Every shape gives the same results. */
 int mst_bwd_force_shape(int wavefronts_per_workgroup, int quads_per_wavefront);
 

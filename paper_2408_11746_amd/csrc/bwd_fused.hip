@@ -42,7 +42,7 @@ namespace mst {
         MSTF_STEP(JJ, cur.x, cur.y, XR, ACC, r0);                                    \
         MSTF_STEP(JJ, cur.z, cur.w, XR, ACC, r1);                                    \
         const float r_ = row_sum_pair(r0, r1, upper);                                \
-        if (storer) pt[(int64_t)(P) * 8 + pslot] = r_;                               \
+        if (storer) store_pair_slot(pt + (int64_t)(P) * 8, pbyte, r_);                      \
     } while (0)
 
 // NWF wavefronts per workgroup, QW quads per wavefront (consecutive quads): the slab of a
@@ -71,7 +71,7 @@ void k_bwd_fused(const TIn* __restrict__ dY /* staged [T x K] */, const TIn* __r
     const uint32_t ebyte = (uint32_t)((lane & 3) * 4 + g) * 16u;
     const bool upper = (s & 8) != 0;
     const bool storer = (s & 7) == 0;
-    const int pslot = g * 2 + (s >> 3);
+    const uint32_t pbyte = (uint32_t)(g * 2 + (s >> 3)) * 4u;
     float* pt = partial + (int64_t)tile_id * slots_stride;
 
     constexpr int SLAB_ROWS = NWF * QW * 4;
@@ -237,15 +237,15 @@ static void launch_fused(const View& v, const TIn* dY, const TIn* X, float* dX, 
         (v.K % 4 == 0) ? 1 : 0, (v.R % 4 == 0) ? 1 : 0, cps);
 }
 
-// Launch shapes: 8 wavefronts x 3 .. 6 quads (96- .. 192-row slabs, up to 128 registers per lane) or
-// 16 wavefronts x 1 or 2 quads (64- / 128-row slabs, 64 registers per lane).  All give the same results.
+// Launch shapes: 8 wavefronts x 3, 4 or 5 quads (96-, 128-, 160-row slabs, up to 128 registers per lane)
+// or 16 wavefronts x 1 or 2 quads (64- / 128-row slabs, 64 registers per lane).  All give the same results.
 struct FusedShape {
     int waves, quads;
 };
 static FusedShape g_forced_fused = {0, 0};
 
 int bwd_fused_force_shape(int waves, int quads) {
-    const bool ok = (waves == 0 && quads == 0) || (waves == 8 && quads >= 3 && quads <= 6) || (waves == 16 && quads <= 2 && quads >= 1);
+    const bool ok = (waves == 0 && quads == 0) || (waves == 8 && quads >= 3 && quads <= 5) || (waves == 16 && quads <= 2 && quads >= 1);
     if (!ok) return MST_ERR_ARG;
     g_forced_fused = {waves, quads};
     return MST_OK;
@@ -259,19 +259,19 @@ bool bwd_fused_pays(const mst_layer*) { return true; }
 // Cost of one workgroup (walk, staging of dY, the X rows of the slab, per-chunk overhead and a
 // fixed amount per quad segment a wavefront walks) times the rounds its grid needs on 256 CUs x 2
 // workgroups, as for the SpMM launch shapes; one set of constants for the shapes of 8 wavefronts,
-// one for those of 16, fitted to timings of the six shapes on twelve GPT-2 small / medium / large
+// one for those of 16, fitted to timings of the five shapes on twelve GPT-2 small / medium / large
 // layer shapes at densities 0.02 .. 0.10 and 4096 .. 16384 tokens on MI355X (144 cases: the choice
-// is 0.3 % slower than the best shape on average, 11 % at worst).
+// is 0.2 % slower than the best shape on average, 7 % at worst; 16 x 2 is the best in two thirds).
 static FusedShape pick_fused_shape(int T, int R, int K, double density) {
     if (g_forced_fused.waves != 0) return g_forced_fused;
     struct Cls {
         double kWalk, kStage, kReg, kChunk, kLoneTail, kLoneOnly, kSeg;
     };
-    static const Cls cls[2] = {{5.649e-5, 5.6e-6, 7.765e-4, 1.725, 0.628, 0.747, 0.454},      // 8 wavefronts
-                               {4.821e-5, 4.1e-6, 7.994e-4, 1.578, 0.578, 0.690, 0.861}};     // 16 wavefronts
-    static const FusedShape cand[] = {{8, 3}, {8, 4}, {8, 5}, {8, 6}, {16, 1}, {16, 2}};
+    static const Cls cls[2] = {{5.675e-5, 6.23e-5, 7.598e-4, 1.352, 0.633, 0.762, 0.287},     // 8 wavefronts
+                               {4.706e-5, 5.52e-5, 7.846e-4, 1.225, 0.580, 0.698, 0.392}};    // 16 wavefronts
+    static const FusedShape cand[] = {{8, 3}, {8, 4}, {8, 5}, {16, 1}, {16, 2}};
     const int64_t nchunk = cdiv(K, KC), ntile = cdiv(T, TT);
-    FusedShape best = cand[4];
+    FusedShape best = cand[3];
     double best_cost = 0.0;
     for (const FusedShape& sh : cand) {
         const Cls& c = cls[sh.waves == 8 ? 0 : 1];
@@ -320,8 +320,7 @@ static int launch_fused_any(const View& v, const TIn* dY, const TIn* X, float* d
         return MST_OK;
     }
     const FusedShape sh = pick_fused_shape(T, v.R, v.K, density);
-    if (sh.waves == 8 && sh.quads == 6) launch_fused<TIn, 8, 6>(v, dY, X, dX, ws.partial, T, 1, s);
-    else if (sh.waves == 16 && sh.quads == 2) launch_fused<TIn, 16, 2>(v, dY, X, dX, ws.partial, T, 1, s);
+    if (sh.waves == 16 && sh.quads == 2) launch_fused<TIn, 16, 2>(v, dY, X, dX, ws.partial, T, 1, s);
     else if (sh.waves == 8 && sh.quads == 5) launch_fused<TIn, 8, 5>(v, dY, X, dX, ws.partial, T, 1, s);
     else if (sh.waves == 8 && sh.quads == 4) launch_fused<TIn, 8, 4>(v, dY, X, dX, ws.partial, T, 1, s);
     else if (sh.waves == 8) launch_fused<TIn, 8, 3>(v, dY, X, dX, ws.partial, T, 1, s);

@@ -41,7 +41,7 @@ namespace mst {
         MST_DOT(JJ, cur.x, DY, r0);                                                  \
         MST_DOT(JJ, cur.z, DY, r1);                                                  \
         const float r_ = row_sum_pair(r0, r1, upper);                                \
-        if (storer) pt[(int64_t)(P) * 8 + pslot] = r_;                               \
+        if (storer) store_pair_slot(pt + (int64_t)(P) * 8, pbyte, r_);                      \
     } while (0)
 
 constexpr int NW = 16;      // wavefronts per workgroup
@@ -88,7 +88,7 @@ __device__ __forceinline__ void sddmm_side(const SddmmSide<TIn>& a, float* __res
     const uint32_t ebyte = (uint32_t)((lane & 3) * 4 + g) * 16u;              // this lane's 16 bytes of a batch of four pairs
     const bool upper = (s & 8) != 0;
     const bool storer = (s & 7) == 0;
-    const int pslot = g * 2 + (s >> 3);               // slot of this lane's sum inside a pair's eight
+    const uint32_t pbyte = (uint32_t)(g * 2 + (s >> 3)) * 4u;               // slot of this lane's sum inside a pair's eight
     // partial sums of this token tile: eight per pair, (lane group, step of the pair)
     float* pt = partial + (int64_t)tile_id * slots_stride;
 

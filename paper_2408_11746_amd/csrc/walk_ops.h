@@ -17,6 +17,13 @@ __device__ inline uint4 load_batch(const uint4* __restrict__ ent, int p, uint32_
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// A pair's eight partial sums (32 bytes at `slots`, the same address in all lanes): the storing lanes
+// write theirs with a buffer store at their byte offset -- again no 64-bit lane address.
+__device__ inline void store_pair_slot(float* slots, uint32_t lane_byte, float v) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(slots, 0, 32, 0x00020000);
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, (int)lane_byte, 0, 0);
+}
+
 // value of v in lane JJ of this lane's aligned group of four lanes
 template <int JJ>
 __device__ inline uint32_t quad_bcast(uint32_t v) {

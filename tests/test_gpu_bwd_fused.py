@@ -23,7 +23,7 @@ CASES = [
     (2100, 200, 3850, 0.05, "uniform"),     # ragged everywhere, 31 chunks
     (700, 768, 768, 0.06, "powerlaw"),      # long rows spread over quads, empty rows
 ]
-SHAPES = [(0, 0), (8, 3), (8, 4), (8, 5), (8, 6), (16, 1), (16, 2)]
+SHAPES = [(0, 0), (8, 3), (8, 4), (8, 5), (16, 1), (16, 2)]
 
 
 def _run(rig, dYd, Xd, T, I, act):
