@@ -320,6 +320,7 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
     # which contraction serves each call (asked of the library, not re-derived here)
     dense_prod = {L.name: L.layer.uses_dense(L.act, T) for L in layers}
     dense_wgrad = {L.name: L.layer.uses_dense(L.act, T, True) for L in layers}
+    dense_bwd = {L.name: L.layer.uses_dense(L.act, T, 2) for L in layers}      # the one-call backward's own rule
 
     def path_of(L, kind):
         a, b = dense_prod[L.name], dense_wgrad[L.name]
@@ -327,8 +328,7 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
             return "dense-mfma" if a else "sparse"
         if kind == "bwd_weight":
             return "dense-mfma" if b else "sparse"
-        return "dense-mfma" if a and b else "sparse" if not (a or b) else \
-            "dX %s, dW %s" % ("dense-mfma" if a else "sparse", "dense-mfma" if b else "sparse")
+        return "dense-mfma" if dense_bwd[L.name] else "sparse"
 
     if args.pmc_probe:
         pmc_probe_block(args, mst, torch, layers, T, stream)
@@ -426,7 +426,7 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
 
     _, drow, dL = dominant
     # fwd / bwd_input are one SpMM launch or one masked dense product; bwd is the shared walk followed by its
-    # small second kernel unless a dense contraction serves one of the two gradients (then separate kernels)
+    # small second kernel, or the two dense contractions
     dp, dw = dense_prod[dL.name], dense_wgrad[dL.name]
     spmm_k = "k_spmm / k_spmm64 (launch shape chosen per call) + k_heavy_fwd after the forward (heavy rows as a dense product; returns at once without any)"
     gemm_k = "k_gemm_split256 / k_gemm_split_n160 / k_gemm_split (fp32 operands as bf16 hi + lo)" if act == "f32" else \
@@ -435,8 +435,8 @@ def run_block(args, name, mst, synth, torch, lds_peak, with_cpu_baseline):
     kernel = {"fwd": gemm_k if dp else spmm_k,
               "bwd_input": gemm_k if dp else spmm_k,
               "bwd_weight": wgrad_dense_k if dw else "k_sddmm + k_sddmm_reduce",
-              "bwd": "k_bwd_fused + k_bwd_fused_reduce" if not (dp or dw) else
-                     "%s, then %s" % (gemm_k if dp else spmm_k, wgrad_dense_k if dw else "k_sddmm + k_sddmm_reduce")}[drow["call"]]
+              "bwd": "k_bwd_fused + k_bwd_fused_reduce" if not dense_bwd[dL.name] else
+                     "%s, then %s" % (gemm_k, wgrad_dense_k)}[drow["call"]]
     if drow["path"] == "dense-mfma":
         # every leg of the call is a dense contraction: priced against the matrix cores
         legs = 2 if drow["call"] == "bwd" else 1

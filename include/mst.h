@@ -137,7 +137,8 @@ int mst_layer_set_path(mst_layer_t* layer, mst_path path);
 
 /* Which path a product call with these arguments takes on the layer as it stands: 1 = masked
  * dense MFMA contraction, 0 = sparse kernel; weight_gradient = 0 asks for Y and dX (Eq. (1) and
- * its input gradient), 1 for the gradient of the active weights.  Host only, no device work;
+ * its input gradient), 1 for the gradient of the active weights, 2 for mst_sparse_fc_bwd (both
+ * gradients from the shared walk, or both from dense contractions).  Host only, no device work;
  * MST_ERR_ARG on a null layer, an unknown type or T < 1. */
 int mst_layer_uses_dense(const mst_layer_t* layer, mst_dtype act, int T, int weight_gradient);
 

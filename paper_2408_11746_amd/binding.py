@@ -259,7 +259,8 @@ class Layer:
     def set_path(self, path: int):
         _check("mst_layer_set_path", lib().mst_layer_set_path(self.h, path))
 
-    def uses_dense(self, act: int, T: int, weight_gradient: bool = False) -> bool:
+    def uses_dense(self, act: int, T: int, weight_gradient=False) -> bool:
+        """weight_gradient: False / 0 = Y and dX, True / 1 = the weight gradient, 2 = mst_sparse_fc_bwd."""
         rc = lib().mst_layer_uses_dense(self.h, act, T, int(weight_gradient))
         _check("mst_layer_uses_dense", min(rc, 0))
         return rc == 1

@@ -197,27 +197,22 @@ int mst_sparse_fc_bwd(const mst_layer_t* L, const void* dY_dev, const void* X_de
     if (ws_bytes < ws.total) return MST_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     note_call(L, act, T);
-    if (!(use_dense_path(L, act, T) && use_dense_weight_grad(L, act, T))) {
-        const int rcv = ensure_views(L, ws, s);                   // a sparse kernel serves at least one of the two
+    if (use_fused_backward(L, act, T) && bwd_fused_pays(L)) {
+        const int rcv = ensure_views(L, ws, s);
         if (rcv != MST_OK) return rcv;
+        return bwd_fused(L, dY_dev, X_dev, dX_dev, dW_dev, T, act, ws, s);
     }
-    if (use_dense_path(L, act, T) || use_dense_weight_grad(L, act, T) || !bwd_fused_pays(L)) {
-        // a dense contraction serves at least one of the two, or the layer is so sparse that
-        // the separate kernels with their wider slabs are faster: the separate calls
-        // (the split area of the workspace serves dX first, then the weight gradient: same stream)
-        int rc = use_dense_path(L, act, T)
-                     ? dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s, ws.gemm, (int64_t)ws.gemm_floats)
-                     : spmm(L->col, dY_dev, dX_dev, T, L->nnz, act, s);
-        if (rc != MST_OK) return rc;
-        return use_dense_weight_grad(L, act, T) ? dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s)
-                                                : sddmm(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
-    }
-    return bwd_fused(L, dY_dev, X_dev, dX_dev, dW_dev, T, act, ws, s);
+    // the two dense contractions (the split area of the workspace serves dX first, then the weight
+    // gradient: same stream)
+    const int rc = dense_products_bwd_input(L, dY_dev, dX_dev, T, act, s, ws.gemm, (int64_t)ws.gemm_floats);
+    if (rc != MST_OK) return rc;
+    return dense_products_bwd_weight(L, dY_dev, X_dev, dW_dev, T, act, ws, s);
 }
 
 int mst_layer_uses_dense(const mst_layer_t* L, mst_dtype act, int T, int weight_gradient) {
     if (!L || !act_ok(act) || T < 1) return MST_ERR_ARG;
     // Y and dX have no workspace to build unbuilt views with: they then run dense whatever the density
+    if (weight_gradient == 2) return use_fused_backward(L, act, T) ? 0 : 1;
     return (weight_gradient ? use_dense_weight_grad(L, act, T) : (use_dense_path(L, act, T) || !L->views_valid)) ? 1 : 0;
 }
 

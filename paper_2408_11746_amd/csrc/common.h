@@ -128,6 +128,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // true when a layer of this density should run the masked dense MFMA kernels
 bool use_dense_path(const mst_layer* L, mst_dtype act, int T);
 bool use_dense_weight_grad(const mst_layer* L, mst_dtype act, int T);
+bool use_fused_backward(const mst_layer* L, mst_dtype act, int T);
 
 // ---- workspace carving (one place so that mst_workspace_bytes and the users agree) ----
 struct Workspace {

@@ -53,6 +53,25 @@ bool use_dense_path(const mst_layer* L, mst_dtype act, int T) {
     return (double)L->nnz > thr * (double)L->N;
 }
 
+// The one-call backward has a third choice, the shared walk, and it moves the cross-over: against the
+// two dense contractions it wins up to densities of 0.065-0.11 with fp32 activations (GPT-2 small /
+// large layer shapes, T >= 8192; a sparse dX beside a dense dW is never the fastest), and only up to
+// 0.03 with bfloat16 activations, whose dense weight gradient is a single bf16 product.  Elsewhere the
+// thresholds of the separate calls coincide and apply.
+bool use_fused_backward(const mst_layer* L, mst_dtype act, int T) {
+    if (L->path == MST_PATH_DENSE) return false;
+    if (L->path == MST_PATH_SPARSE) return true;
+    double thr;
+    if (act == MST_BF16) {
+        const bool tiles = T % 256 == 0 && L->O % 256 == 0 && L->I % 256 == 0;
+        thr = tiles && T >= 2048 ? 0.03 : 0.30;
+    } else {
+        const bool tiles = T % 128 == 0 && L->O % 128 == 0 && L->I % 128 == 0;
+        thr = !tiles ? 0.30 : T >= 2048 ? 0.07 : 0.15;
+    }
+    return (double)L->nnz <= thr * (double)L->N;
+}
+
 bool use_dense_weight_grad(const mst_layer* L, mst_dtype act, int T) {
     if (L->path == MST_PATH_DENSE) return true;
     if (L->path == MST_PATH_SPARSE) return false;
