@@ -110,3 +110,31 @@ def test_argument_errors():
     for bad in [(8, 2), (16, 3), (4, 4), (8, 0)]:
         with pytest.raises(mst.MstError):
             mst.mst_bwd_force_shape(*bad)
+
+
+@pytest.mark.parametrize("density,act,walk", [(0.045, "f32", True), (0.065, "f32", True), (0.09, "f32", False),
+                                              (0.025, "bf16", True), (0.04, "bf16", False)])
+def test_automatic_path_of_the_one_call_backward(density, act, walk):
+    """On the automatic path the one-call backward takes the shared walk below its own cross-over
+    density (0.07 with fp32, 0.03 with bfloat16 activations on whole tiles, T >= 2048) and the two
+    dense contractions above it, whatever the separate calls would choose; mst_layer_uses_dense(.., 2)
+    says which; both sides agree with the oracle."""
+    T, I, O = 2048, 256, 512
+    W, M = synth.make_layer(47, 3, I, O, density)
+    if act == "f32":
+        X, dY = synth.make_activations(47, 3, T, I, O)
+        Xd, dYd, a = dev(X), dev(dY), mst.MST_F32
+    else:
+        X, dY, xb, yb = synth.make_activations(47, 3, T, I, O, "bf16")
+        Xd, dYd, a = dev(xb.view(np.int16)), dev(yb.view(np.int16)), mst.MST_BF16
+    rig = Rig(W, M, T)
+    assert rig.layer.uses_dense(a, T, 2) == (not walk)
+    dX, dW = _run(rig, dYd, Xd, T, I, a)
+    assert rel_err(dX, opr.fc_bwd_input(dY, W, M)) <= TOL and rel_err(dW, opr.fc_bwd_weight(dY, X, M)) <= TOL
+    rig.layer.set_path(mst.MST_PATH_SPARSE)
+    sX, sW = _run(rig, dYd, Xd, T, I, a)
+    if walk:                                        # the same kernels: the same bits
+        np.testing.assert_array_equal(dX, sX)
+        np.testing.assert_array_equal(dW, sW)
+    else:
+        assert rel_err(dX, sX) <= TOL and rel_err(dW, sW) <= TOL
